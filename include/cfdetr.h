@@ -1,0 +1,225 @@
+/*
+ * cfdetr.h - C ABI of the MI355X coarse-to-fine detection-transformer encoder.
+ *
+ * The library computes the data-parallel part of CF-DETR (Sec. III-B of the
+ * paper, strategies A1-A3):
+ *   A1  coarse inference: every camera frame is cut into a coarse grid of
+ *       patches, each patch becomes one token, and the transformer encoder
+ *       (self-attention among all tokens of a frame, Sec. II-A) runs on an
+ *       image-level batch of frames;
+ *   A2  selective fine inference: only the regions of interest are
+ *       re-partitioned into finer patches; everywhere else the coarse-stage
+ *       tokens are reused, which yields a mixed-granularity token set;
+ *   A3  multi-level batch inference: the token sets of several frames, of
+ *       different lengths, go through the encoder together.  The paper pads
+ *       them to one length; this library keeps them as variable-length
+ *       sequences addressed by offsets, which computes the same thing without
+ *       the padding work.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer (gfx950) owned by the caller,
+ *     unless a parameter says "host".  The library never frees or keeps
+ *     ownership of caller memory.  Weights must outlive the context.
+ *   - Work space is allocated once in cfdetr_create from the max_* fields and
+ *     released in cfdetr_destroy; the encode calls allocate nothing.
+ *   - Calls enqueue work on the given hipStream_t (passed as void*; NULL is
+ *     the default stream) and return without waiting.  No call synchronises
+ *     the host except cfdetr_sync_status, cfdetr_profile_end and
+ *     cfdetr_create / cfdetr_destroy.
+ *   - One context serves one stream at a time; calls on one context must not
+ *     overlap.  Different contexts are independent.
+ *   - Host-detectable argument errors return a status at once and enqueue
+ *     nothing.  A token total that exceeds max_tokens_total is detected on the
+ *     device: the selection then reports zero tokens for every frame, raises a
+ *     sticky flag, and cfdetr_sync_status returns CFDETR_ECAPACITY.  Output is
+ *     never silently truncated.
+ *
+ * Token descriptor: one int32 per token, level<<28 | row<<14 | col, where
+ * (row, col) index the grid of that level (level 0 = coarsest).
+ * Token order: frames in batch order; inside a frame coarse level first, and
+ * row-major inside a level.
+ *
+ * Number formats: matrices are stored in act_dtype (bf16 bit patterns or
+ * fp32); bias and LayerNorm vectors are always fp32; frames are stored in
+ * image_dtype; the cached coarse tokens (x0_cache) and both encoder outputs are
+ * always fp32.  With act_dtype = CFDETR_BF16 all contractions run on bf16
+ * matrix cores with fp32 accumulation and fp32 softmax / LayerNorm / residual
+ * stream; CFDETR_FP32 is a slow all-fp32 check mode.
+ */
+#ifndef CFDETR_H
+#define CFDETR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CFDETR_API __attribute__((visibility("default")))
+
+typedef struct cfdetr_ctx cfdetr_ctx; /* opaque; owns work space only */
+
+typedef enum {
+  CFDETR_OK = 0,
+  CFDETR_EINVAL = 1,    /* null pointer, bad enum, bad field value             */
+  CFDETR_ESHAPE = 2,    /* shape constraint violated (see cfdetr_config)       */
+  CFDETR_ECAPACITY = 3, /* batch / token / box count beyond the configured max */
+  CFDETR_ENOMEM = 4,    /* device or host allocation failed                    */
+  CFDETR_EDEVICE = 5    /* a HIP call failed; see cfdetr_last_error            */
+} cfdetr_status;
+
+typedef enum { CFDETR_BF16 = 0, CFDETR_FP32 = 1 } cfdetr_dtype;
+
+#define CFDETR_MAX_LEVELS 3
+
+/*
+ * Shape of the model and capacity of the work space.
+ * Constraints (else CFDETR_ESHAPE): n_levels in {1,2,3}; patch[l] = patch[l-1]/2;
+ * patch[n_levels-1] >= 8; img_h, img_w multiples of patch[0]; every grid at
+ * most 16384 cells per side; d_model a multiple of 64 and of n_heads;
+ * d_model / n_heads in {32, 64}; d_ffn a multiple of 64; n_layers >= 1;
+ * 1 <= max_batch <= 64; max_tokens_total >= max_batch * (coarse cells).
+ */
+typedef struct {
+  int32_t n_levels;
+  int32_t patch[CFDETR_MAX_LEVELS]; /* coarse -> fine, in pixels */
+  int32_t img_h, img_w;
+  int32_t d_model, n_heads, n_layers, d_ffn;
+  int32_t max_batch;        /* frames per call                                  */
+  int32_t max_tokens_total; /* tokens per call over all frames (fine pass)      */
+  cfdetr_dtype image_dtype; /* element type of the frames                       */
+  cfdetr_dtype act_dtype;   /* element type of weight matrices and contractions */
+  float ln_eps;             /* LayerNorm epsilon, e.g. 1e-5                     */
+} cfdetr_config;
+
+/*
+ * Encoder weights (device pointers).  Layouts, all row-major:
+ *   w_embed[l] [d_model, 3*patch[l]^2]  patch flattened (channel, row, column)
+ *   b_embed[l] [d_model]
+ *   per layer, stacked over layers in the leading dimension:
+ *   ln1_g, ln1_b [L, d]      w_qkv [L, 3d, d] (query rows, key rows, value rows;
+ *   b_qkv [L, 3d]            head h owns rows h*dh..(h+1)*dh of each third)
+ *   w_o [L, d, d]  b_o [L, d]  ln2_g, ln2_b [L, d]
+ *   w_ff1 [L, d_ffn, d]  b_ff1 [L, d_ffn]  w_ff2 [L, d, d_ffn]  b_ff2 [L, d]
+ *   lnf_g, lnf_b [d]         final LayerNorm
+ * Each layer is pre-LN: x += Wo.MHA(LN1 x); x += W2.GELU(W1.LN2 x); the output
+ * is LNf(x) after the last layer.
+ */
+typedef struct {
+  const void* w_embed[CFDETR_MAX_LEVELS];
+  const float* b_embed[CFDETR_MAX_LEVELS];
+  const float *ln1_g, *ln1_b;
+  const void* w_qkv;
+  const float* b_qkv;
+  const void* w_o;
+  const float* b_o;
+  const float *ln2_g, *ln2_b;
+  const void* w_ff1;
+  const float* b_ff1;
+  const void* w_ff2;
+  const float* b_ff2;
+  const float *lnf_g, *lnf_b;
+} cfdetr_weights;
+
+/* Kernel families, for cfdetr_profile_end. */
+typedef enum {
+  CFDETR_K_SELECT = 0, /* A2 cell tests, compaction, offsets                   */
+  CFDETR_K_PLAN = 1,   /* attention work list from the sequence offsets        */
+  CFDETR_K_EMBED = 2,  /* patch gather + projection + position                 */
+  CFDETR_K_GATHER = 3, /* reuse of cached coarse tokens                        */
+  CFDETR_K_LN = 4,     /* LayerNorm                                            */
+  CFDETR_K_QKV = 5,    /* query/key/value projection                           */
+  CFDETR_K_ATTN = 6,   /* variable-length self-attention                       */
+  CFDETR_K_OUT = 7,    /* output projection + residual                         */
+  CFDETR_K_FF1 = 8,    /* first FFN projection + GELU                          */
+  CFDETR_K_FF2 = 9,    /* second FFN projection + residual                     */
+  CFDETR_K_COUNT = 10
+} cfdetr_kernel_id;
+
+/* Host-side.  Validates cfg, copies it, keeps the weight POINTERS, allocates
+ * the work space on the current device and builds the position tables there.
+ * On failure *out is NULL. */
+CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_weights* w,
+                            cfdetr_ctx** out);
+/* Waits for the device, frees the work space.  NULL is allowed. */
+CFDETR_API void cfdetr_destroy(cfdetr_ctx* ctx);
+/* Host string describing the last error on this context ("" if none).  With
+ * ctx == NULL: the reason the calling thread's last cfdetr_create failed.  The
+ * pointer stays valid until the next failing call. */
+CFDETR_API const char* cfdetr_last_error(const cfdetr_ctx* ctx);
+/* Bytes of device work space the context holds. */
+CFDETR_API uint64_t cfdetr_workspace_bytes(const cfdetr_ctx* ctx);
+/* Waits for `hip_stream`, then reports and clears the device-side sticky flag:
+ * CFDETR_OK, or CFDETR_ECAPACITY if a selection overflowed max_tokens_total. */
+CFDETR_API cfdetr_status cfdetr_sync_status(cfdetr_ctx* ctx, void* hip_stream);
+
+/*
+ * A1, coarse inference on an image-level batch (Sec. III-B, A1).
+ *   images   [B, 3, img_h, img_w] in image_dtype, planar
+ *   x0_cache [B*N0, d] fp32 out: the coarse tokens as they enter the encoder
+ *            (patch projection + position); may be NULL if not wanted
+ *   y_coarse [B*N0, d] fp32 out: encoder output, frame after frame, row-major grid
+ * N0 = (img_h/patch[0]) * (img_w/patch[0]).  1 <= B <= max_batch.
+ */
+CFDETR_API cfdetr_status cfdetr_coarse_encode(cfdetr_ctx* ctx, const void* images, int32_t B,
+                                   float* x0_cache, float* y_coarse, void* hip_stream);
+
+/*
+ * A2, selective patch split as integer work only (Sec. III-B, A2).
+ *   boxes       [n_boxes, 4] int32 (x0, y0, x1, y1), half-open pixel rectangles;
+ *               clipped to the frame; empty ones select nothing
+ *   tier        [n_boxes] uint8: finest level this box asks for (0 = not
+ *               critical, n_levels-1 = finest); larger values act as finest
+ *   box_offsets [B+1] int32: boxes of frame i are box_offsets[i]..box_offsets[i+1]
+ * A cell of a non-finest level l is replaced by its four children iff a box of
+ * the same frame with tier > l overlaps it; the unsplit cells are the tokens.
+ * Outputs:
+ *   tok_desc     [max_tokens_total] int32; entries past the total are untouched
+ *   cu_seqlens   [B+1] int32: token offsets of the frames, cu_seqlens[0] = 0
+ *   level_counts [B, n_levels] int32: tokens of frame i at each level; may be NULL
+ */
+CFDETR_API cfdetr_status cfdetr_select_fine(cfdetr_ctx* ctx, const int32_t* boxes, const uint8_t* tier,
+                                 const int32_t* box_offsets, int32_t B, int32_t* tok_desc,
+                                 int32_t* cu_seqlens, int32_t* level_counts,
+                                 void* hip_stream);
+
+/*
+ * A2 + A3, encoder over the mixed-granularity token sets as one variable-length
+ * batch (Sec. III-B, A2 "reuse the coarse-stage tokens", A3 patch-level batch).
+ *   images, B    as in cfdetr_coarse_encode
+ *   tok_desc, cu_seqlens  as written by cfdetr_select_fine (device)
+ *   x0_cache     [B*N0, d] fp32 from cfdetr_coarse_encode on the same frames:
+ *                level-0 tokens are copied from it; NULL embeds them again
+ *   y_mixed      [max_tokens_total, d] fp32 out; rows past cu_seqlens[B] untouched
+ * Attention stays inside [cu_seqlens[i], cu_seqlens[i+1]) for every frame i.
+ */
+CFDETR_API cfdetr_status cfdetr_fine_encode(cfdetr_ctx* ctx, const void* images, int32_t B,
+                                 const int32_t* tok_desc, const int32_t* cu_seqlens,
+                                 const float* x0_cache, float* y_mixed, void* hip_stream);
+
+/*
+ * A1 -> A2 -> A3 in one call with no host synchronisation in between: coarse
+ * encode, selection, then the fine encode reusing the coarse tokens
+ * (Sec. III-B, A1-A3).  Arguments as in the three calls above; level_counts
+ * may be NULL.
+ */
+CFDETR_API cfdetr_status cfdetr_multilevel_batch(cfdetr_ctx* ctx, const void* images, int32_t B,
+                                      const int32_t* boxes, const uint8_t* tier,
+                                      const int32_t* box_offsets, float* y_coarse,
+                                      float* y_mixed, int32_t* tok_desc, int32_t* cu_seqlens,
+                                      int32_t* level_counts, void* hip_stream);
+
+/*
+ * Per-kernel timing with HIP events on the stream the kernels run on.
+ * Between begin and end every launch is bracketed by an event pair (this costs
+ * a few microseconds per launch, so timed throughput runs leave it off).
+ * cfdetr_profile_end waits for the stream and fills two host arrays of
+ * CFDETR_K_COUNT entries: summed milliseconds and launch counts per family.
+ */
+CFDETR_API cfdetr_status cfdetr_profile_begin(cfdetr_ctx* ctx);
+CFDETR_API cfdetr_status cfdetr_profile_end(cfdetr_ctx* ctx, float* total_ms, int32_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CFDETR_H */

@@ -1,0 +1,479 @@
+// C ABI of the library: context, validation, and the launch sequences of
+// A1 (coarse encode), A2 (selection), A2+A3 (mixed-granularity varlen encode).
+#include "../../include/cfdetr.h"
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace cfdetr;
+
+struct cfdetr_ctx {
+  cfdetr_config cfg;
+  cfdetr_weights w;
+  Pyramid pyr;
+  int device = 0;
+  int n0 = 0;          // coarse cells per frame
+  int nonfinest = 0;   // cells of all levels but the finest, per frame
+  bool bf16 = true;
+  size_t esz = 2;      // bytes per activation element
+
+  // one device allocation, carved up
+  void* arena = nullptr;
+  uint64_t arena_bytes = 0;
+  float* x = nullptr;      // residual stream [Tm, d] fp32
+  void* a = nullptr;       // LayerNorm output [Tm, d]
+  void* qkv = nullptr;     // [Tm, 3d]
+  void* o = nullptr;       // attention output [Tm, d]
+  void* h = nullptr;       // FFN hidden [Tm, F]
+  float* x0 = nullptr;     // coarse-token cache of cfdetr_multilevel_batch [Bmax*N0, d]
+  float* pe_row[kMaxLevels] = {};
+  float* pe_col[kMaxLevels] = {};
+  int32_t* coarse_desc = nullptr;  // static token table of the coarse grid, Bmax frames
+  int32_t* coarse_cu = nullptr;    // i * N0
+  uint8_t* hit = nullptr;
+  int32_t* split[2] = {};
+  int parity = 0;
+  int32_t* tiles = nullptr;
+  int32_t* n_tiles = nullptr;
+  int tile_cap = 0;
+  int block_q = 0;
+  int32_t* err_flag = nullptr;
+
+  std::string err;
+
+  bool prof = false;
+  std::vector<hipEvent_t> ev;   // pairs
+  std::vector<int> ev_kind;
+  size_t ev_used = 0;
+};
+
+namespace {
+
+// Error text of the last failed cfdetr_create of this thread (no context exists then).
+thread_local std::string g_create_err;
+
+cfdetr_status fail(cfdetr_ctx* c, cfdetr_status st, const std::string& msg) {
+  if (c) c->err = msg;
+  return st;
+}
+
+cfdetr_status fail_create(cfdetr_status st, const std::string& msg) {
+  g_create_err = msg;
+  return st;
+}
+
+cfdetr_status fail_hip(cfdetr_ctx* c, const char* what, hipError_t e) {
+  return fail(c, CFDETR_EDEVICE, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+const char* check_config(const cfdetr_config& c) {
+  if (c.n_levels < 1 || c.n_levels > kMaxLevels) return "n_levels must be 1..3";
+  for (int l = 0; l < c.n_levels; ++l) {
+    if (!is_pow2(c.patch[l]) || c.patch[l] < 8) return "patch sizes must be powers of two >= 8";
+    if (l > 0 && c.patch[l] * 2 != c.patch[l - 1]) return "each patch size must halve the previous";
+  }
+  if (c.img_h <= 0 || c.img_w <= 0 || c.img_h % c.patch[0] || c.img_w % c.patch[0])
+    return "frame sides must be positive multiples of patch[0]";
+  if (c.img_h / c.patch[c.n_levels - 1] > 16384 || c.img_w / c.patch[c.n_levels - 1] > 16384)
+    return "a grid has more than 16384 cells per side";
+  if (c.d_model <= 0 || c.d_model % 64 || c.d_model > 1024) return "d_model must be a multiple of 64, at most 1024";
+  if (c.n_heads <= 0 || c.d_model % c.n_heads) return "d_model must be a multiple of n_heads";
+  if (c.d_model / c.n_heads != 32 && c.d_model / c.n_heads != 64) return "head width must be 32 or 64";
+  if (c.d_ffn <= 0 || c.d_ffn % 64) return "d_ffn must be a multiple of 64";
+  if (c.n_layers < 1) return "n_layers must be >= 1";
+  if (c.max_batch < 1 || c.max_batch > kMaxBatch) return "max_batch must be 1..64";
+  const long n0 = (long)(c.img_h / c.patch[0]) * (c.img_w / c.patch[0]);
+  if ((long)c.max_tokens_total < (long)c.max_batch * n0)
+    return "max_tokens_total must hold the coarse grids of max_batch frames";
+  if ((long)c.max_tokens_total > (1L << 24) * 64) return "max_tokens_total too large";
+  return nullptr;
+}
+
+struct Carver {
+  uint64_t off = 0;
+  uint64_t take(uint64_t bytes) {
+    uint64_t at = off;
+    off += (bytes + 255) & ~uint64_t(255);
+    return at;
+  }
+};
+
+// --- profiling ---------------------------------------------------------------
+void prof_open(cfdetr_ctx* c, int kind, hipStream_t s) {
+  if (!c->prof || c->ev_used + 2 > c->ev.size()) return;
+  hipEventRecord(c->ev[c->ev_used], s);
+  c->ev_kind[c->ev_used / 2] = kind;
+}
+void prof_close(cfdetr_ctx* c, hipStream_t s) {
+  if (!c->prof || c->ev_used + 2 > c->ev.size()) return;
+  hipEventRecord(c->ev[c->ev_used + 1], s);
+  c->ev_used += 2;
+}
+
+#define CF_LAUNCH(kind, expr)                                       \
+  do {                                                              \
+    prof_open(ctx, (kind), s);                                      \
+    hipError_t e__ = (expr);                                        \
+    prof_close(ctx, s);                                             \
+    if (e__ != hipSuccess) return fail_hip(ctx, #expr, e__);        \
+  } while (0)
+
+cfdetr_status check_call(cfdetr_ctx* ctx, int B) {
+  if (!ctx) return CFDETR_EINVAL;
+  if (B < 1) return fail(ctx, CFDETR_EINVAL, "B must be >= 1");
+  if (B > ctx->cfg.max_batch) return fail(ctx, CFDETR_ECAPACITY, "B exceeds max_batch");
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(ctx, "hipGetDevice", e);
+  if (dev != ctx->device) return fail(ctx, CFDETR_EINVAL, "context belongs to another device");
+  return CFDETR_OK;
+}
+
+// Patch embedding of the tokens of one level into ctx->x (and optionally out2).
+cfdetr_status embed_level(cfdetr_ctx* ctx, const void* images, int level,
+                          const int32_t* tok_desc, const int32_t* cu, int B, float* out2,
+                          const int32_t* m_ptr, int m_host, int m_cap, hipStream_t s) {
+  EmbedArgs a;
+  a.images = images;
+  a.image_is_bf16 = ctx->cfg.image_dtype == CFDETR_BF16;
+  a.level = level;
+  a.patch = ctx->cfg.patch[level];
+  a.img_h = ctx->cfg.img_h;
+  a.img_w = ctx->cfg.img_w;
+  a.tok_desc = tok_desc;
+  a.cu_seqlens = cu;
+  a.B = B;
+  a.pe_row = ctx->pe_row[level];
+  a.pe_col = ctx->pe_col[level];
+  a.out = ctx->x;
+  a.out2 = out2;
+  CF_LAUNCH(CFDETR_K_EMBED, launch_embed(a, ctx->w.w_embed[level], ctx->w.b_embed[level],
+                                         ctx->cfg.d_model, ctx->bf16, m_ptr, m_host, m_cap, s));
+  return CFDETR_OK;
+}
+
+// All layers + final LayerNorm over ctx->x; sequences given by cu[0..B].
+cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, const int32_t* m_ptr,
+                          int m_host, int m_cap, float* y, hipStream_t s) {
+  const cfdetr_config& c = ctx->cfg;
+  const cfdetr_weights& w = ctx->w;
+  const int d = c.d_model, F = c.d_ffn;
+  const size_t es = ctx->esz;
+  const float eps = c.ln_eps;
+  const bool bf = ctx->bf16;
+  CF_LAUNCH(CFDETR_K_PLAN,
+            launch_plan(cu, B, ctx->block_q, ctx->tiles, ctx->n_tiles, ctx->tile_cap, s));
+  for (int l = 0; l < c.n_layers; ++l) {
+    const char* wqkv = static_cast<const char*>(w.w_qkv) + (size_t)l * 3 * d * d * es;
+    const char* wo = static_cast<const char*>(w.w_o) + (size_t)l * d * d * es;
+    const char* w1 = static_cast<const char*>(w.w_ff1) + (size_t)l * F * d * es;
+    const char* w2 = static_cast<const char*>(w.w_ff2) + (size_t)l * d * F * es;
+    CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->x, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d,
+                                            ctx->a, bf, d, eps, m_ptr, m_host, m_cap, s));
+    CF_LAUNCH(CFDETR_K_QKV, launch_gemm(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, 3 * d, d,
+                                        Epilogue::kBias, ctx->qkv, nullptr, bf, m_ptr, m_host,
+                                        m_cap, s));
+    CF_LAUNCH(CFDETR_K_ATTN, launch_attention(ctx->qkv, ctx->o, cu, B, d, c.n_heads, ctx->tiles,
+                                              ctx->n_tiles, ctx->tile_cap, ctx->block_q, bf, s));
+    CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->o, wo, w.b_o + (size_t)l * d, d, d,
+                                        Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr,
+                                        m_host, m_cap, s));
+    CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->x, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d,
+                                            ctx->a, bf, d, eps, m_ptr, m_host, m_cap, s));
+    CF_LAUNCH(CFDETR_K_FF1, launch_gemm(ctx->a, w1, w.b_ff1 + (size_t)l * F, F, d,
+                                        Epilogue::kBiasGelu, ctx->h, nullptr, bf, m_ptr, m_host,
+                                        m_cap, s));
+    CF_LAUNCH(CFDETR_K_FF2, launch_gemm(ctx->h, w2, w.b_ff2 + (size_t)l * d, d, F,
+                                        Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr,
+                                        m_host, m_cap, s));
+  }
+  CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->x, w.lnf_g, w.lnf_b, y, false, d, eps, m_ptr,
+                                          m_host, m_cap, s));
+  return CFDETR_OK;
+}
+
+cfdetr_status coarse_impl(cfdetr_ctx* ctx, const void* images, int B, float* x0_out,
+                          float* y_coarse, hipStream_t s) {
+  const int M = B * ctx->n0;
+  cfdetr_status st = embed_level(ctx, images, 0, ctx->coarse_desc, ctx->coarse_cu, B, x0_out,
+                                 nullptr, M, M, s);
+  if (st != CFDETR_OK) return st;
+  return run_encoder(ctx, ctx->coarse_cu, B, nullptr, M, M, y_coarse, s);
+}
+
+cfdetr_status select_impl(cfdetr_ctx* ctx, const int32_t* boxes, const uint8_t* tier,
+                          const int32_t* box_offsets, int B, int32_t* tok_desc,
+                          int32_t* cu_seqlens, int32_t* level_counts, hipStream_t s) {
+  int32_t* cur = ctx->split[ctx->parity];
+  int32_t* next = ctx->split[ctx->parity ^ 1];
+  ctx->parity ^= 1;
+  CF_LAUNCH(CFDETR_K_SELECT,
+            launch_select(ctx->pyr, boxes, tier, box_offsets, B, ctx->nonfinest, ctx->hit, cur,
+                          next, ctx->cfg.max_tokens_total, tok_desc, cu_seqlens, level_counts,
+                          ctx->err_flag, s));
+  return CFDETR_OK;
+}
+
+cfdetr_status fine_impl(cfdetr_ctx* ctx, const void* images, int B, const int32_t* tok_desc,
+                        const int32_t* cu, const float* x0_cache, float* y_mixed,
+                        hipStream_t s) {
+  const int cap = ctx->cfg.max_tokens_total;
+  const int32_t* m_ptr = cu + B;
+  int first = 0;
+  if (x0_cache) {
+    CF_LAUNCH(CFDETR_K_GATHER,
+              launch_gather_coarse(tok_desc, cu, B, x0_cache, ctx->n0, ctx->pyr.cols[0],
+                                   ctx->cfg.d_model, ctx->x, cap, s));
+    first = 1;
+  }
+  for (int l = first; l < ctx->cfg.n_levels; ++l) {
+    cfdetr_status st = embed_level(ctx, images, l, tok_desc, cu, B, nullptr, m_ptr, 0, cap, s);
+    if (st != CFDETR_OK) return st;
+  }
+  return run_encoder(ctx, cu, B, m_ptr, 0, cap, y_mixed, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_weights* w, cfdetr_ctx** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !w || !out) return fail_create(CFDETR_EINVAL, "null argument");
+  if (const char* why = check_config(*cfg)) return fail_create(CFDETR_ESHAPE, why);
+  if ((cfg->image_dtype != CFDETR_BF16 && cfg->image_dtype != CFDETR_FP32) ||
+      (cfg->act_dtype != CFDETR_BF16 && cfg->act_dtype != CFDETR_FP32) || !(cfg->ln_eps > 0.f))
+    return fail_create(CFDETR_EINVAL, "bad dtype or ln_eps");
+  for (int l = 0; l < cfg->n_levels; ++l)
+    if (!w->w_embed[l] || !w->b_embed[l] || !aligned16(w->w_embed[l]))
+      return fail_create(CFDETR_EINVAL, "null or misaligned embedding weight");
+  const void* ptrs[] = {w->ln1_g, w->ln1_b, w->w_qkv, w->b_qkv, w->w_o,   w->b_o,   w->ln2_g,
+                        w->ln2_b, w->w_ff1, w->b_ff1, w->w_ff2, w->b_ff2, w->lnf_g, w->lnf_b};
+  for (const void* p : ptrs)
+    if (!p || !aligned16(p)) return fail_create(CFDETR_EINVAL, "null or misaligned weight");
+
+  cfdetr_ctx* c = new (std::nothrow) cfdetr_ctx();
+  if (!c) return fail_create(CFDETR_ENOMEM, "host allocation failed");
+  c->cfg = *cfg;
+  c->w = *w;
+  c->bf16 = cfg->act_dtype == CFDETR_BF16;
+  c->esz = c->bf16 ? 2 : 4;
+  hipError_t e = hipGetDevice(&c->device);
+  if (e != hipSuccess) {
+    delete c;
+    return fail_create(CFDETR_EDEVICE, std::string("hipGetDevice: ") + hipGetErrorString(e));
+  }
+  Pyramid& p = c->pyr;
+  p.n_levels = cfg->n_levels;
+  p.img_h = cfg->img_h;
+  p.img_w = cfg->img_w;
+  for (int l = 0; l < kMaxLevels; ++l) {
+    p.patch[l] = l < cfg->n_levels ? cfg->patch[l] : 1;
+    p.rows[l] = l < cfg->n_levels ? cfg->img_h / cfg->patch[l] : 0;
+    p.cols[l] = l < cfg->n_levels ? cfg->img_w / cfg->patch[l] : 0;
+  }
+  c->n0 = p.rows[0] * p.cols[0];
+  c->nonfinest = 0;
+  for (int l = 0; l + 1 < cfg->n_levels; ++l) c->nonfinest += p.rows[l] * p.cols[l];
+  c->block_q = attention_block_q(cfg->d_model / cfg->n_heads, c->bf16);
+  c->tile_cap = (cfg->max_tokens_total + c->block_q - 1) / c->block_q + cfg->max_batch;
+
+  const uint64_t Tm = cfg->max_tokens_total, d = cfg->d_model, F = cfg->d_ffn;
+  const uint64_t Bm = cfg->max_batch, D = d / 2;
+  Carver cv;
+  const uint64_t o_x = cv.take(Tm * d * 4), o_a = cv.take(Tm * d * c->esz);
+  const uint64_t o_qkv = cv.take(Tm * 3 * d * c->esz), o_o = cv.take(Tm * d * c->esz);
+  const uint64_t o_h = cv.take(Tm * F * c->esz), o_x0 = cv.take(Bm * c->n0 * d * 4);
+  uint64_t o_per[kMaxLevels], o_pec[kMaxLevels];
+  for (int l = 0; l < cfg->n_levels; ++l) {
+    o_per[l] = cv.take((uint64_t)p.rows[l] * D * 4);
+    o_pec[l] = cv.take((uint64_t)p.cols[l] * D * 4);
+  }
+  const uint64_t o_cd = cv.take(Bm * c->n0 * 4), o_cc = cv.take((Bm + 1) * 4);
+  const uint64_t o_hit = cv.take(Bm * (uint64_t)(c->nonfinest > 0 ? c->nonfinest : 1));
+  const uint64_t o_s0 = cv.take(kMaxBatch * kMaxLevels * 4), o_s1 = cv.take(kMaxBatch * kMaxLevels * 4);
+  const uint64_t o_tiles = cv.take((uint64_t)c->tile_cap * 4), o_nt = cv.take(4), o_err = cv.take(4);
+  c->arena_bytes = cv.off;
+  e = hipMalloc(&c->arena, c->arena_bytes);
+  if (e != hipSuccess) {
+    delete c;
+    return fail_create(CFDETR_ENOMEM, std::string("hipMalloc of the work space: ") +
+                                          hipGetErrorString(e));
+  }
+  char* base = static_cast<char*>(c->arena);
+  c->x = reinterpret_cast<float*>(base + o_x);
+  c->a = base + o_a;
+  c->qkv = base + o_qkv;
+  c->o = base + o_o;
+  c->h = base + o_h;
+  c->x0 = reinterpret_cast<float*>(base + o_x0);
+  for (int l = 0; l < cfg->n_levels; ++l) {
+    c->pe_row[l] = reinterpret_cast<float*>(base + o_per[l]);
+    c->pe_col[l] = reinterpret_cast<float*>(base + o_pec[l]);
+  }
+  c->coarse_desc = reinterpret_cast<int32_t*>(base + o_cd);
+  c->coarse_cu = reinterpret_cast<int32_t*>(base + o_cc);
+  c->hit = reinterpret_cast<uint8_t*>(base + o_hit);
+  c->split[0] = reinterpret_cast<int32_t*>(base + o_s0);
+  c->split[1] = reinterpret_cast<int32_t*>(base + o_s1);
+  c->tiles = reinterpret_cast<int32_t*>(base + o_tiles);
+  c->n_tiles = reinterpret_cast<int32_t*>(base + o_nt);
+  c->err_flag = reinterpret_cast<int32_t*>(base + o_err);
+
+  // static tables: coarse grid descriptors, zeroed counters, position tables
+  std::vector<int32_t> desc(Bm * c->n0), cu(Bm + 1);
+  for (uint64_t b = 0; b < Bm; ++b)
+    for (int r = 0; r < p.rows[0]; ++r)
+      for (int q = 0; q < p.cols[0]; ++q) desc[b * c->n0 + r * p.cols[0] + q] = (r << 14) | q;
+  for (uint64_t b = 0; b <= Bm; ++b) cu[b] = (int32_t)(b * c->n0);
+  e = hipMemcpy(c->coarse_desc, desc.data(), desc.size() * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(c->coarse_cu, cu.data(), cu.size() * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemset(c->split[0], 0, kMaxBatch * kMaxLevels * 4);
+  if (e == hipSuccess) e = hipMemset(c->split[1], 0, kMaxBatch * kMaxLevels * 4);
+  if (e == hipSuccess) e = hipMemset(c->n_tiles, 0, 4);
+  if (e == hipSuccess) e = hipMemset(c->err_flag, 0, 4);
+  for (int l = 0; l < cfg->n_levels && e == hipSuccess; ++l)
+    e = launch_pe_tables(p.patch[l], p.rows[l], p.cols[l], p.img_h, p.img_w, (int)d, c->pe_row[l],
+                         c->pe_col[l], nullptr);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    hipFree(c->arena);
+    delete c;
+    return fail_create(CFDETR_EDEVICE, std::string("context set-up: ") + hipGetErrorString(e));
+  }
+  *out = c;
+  return CFDETR_OK;
+}
+
+CFDETR_API void cfdetr_destroy(cfdetr_ctx* ctx) {
+  if (!ctx) return;
+  hipDeviceSynchronize();
+  for (hipEvent_t ev : ctx->ev) hipEventDestroy(ev);
+  if (ctx->arena) hipFree(ctx->arena);
+  delete ctx;
+}
+
+CFDETR_API const char* cfdetr_last_error(const cfdetr_ctx* ctx) {
+  return ctx ? ctx->err.c_str() : g_create_err.c_str();
+}
+
+CFDETR_API uint64_t cfdetr_workspace_bytes(const cfdetr_ctx* ctx) { return ctx ? ctx->arena_bytes : 0; }
+
+CFDETR_API cfdetr_status cfdetr_sync_status(cfdetr_ctx* ctx, void* hip_stream) {
+  if (!ctx) return CFDETR_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return fail_hip(ctx, "hipStreamSynchronize", e);
+  int32_t flag = 0;
+  e = hipMemcpy(&flag, ctx->err_flag, 4, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return fail_hip(ctx, "hipMemcpy", e);
+  if (flag) {
+    e = hipMemset(ctx->err_flag, 0, 4);
+    if (e != hipSuccess) return fail_hip(ctx, "hipMemset", e);
+    return fail(ctx, CFDETR_ECAPACITY, "selection produced more tokens than max_tokens_total");
+  }
+  return CFDETR_OK;
+}
+
+CFDETR_API cfdetr_status cfdetr_coarse_encode(cfdetr_ctx* ctx, const void* images, int32_t B,
+                                   float* x0_cache, float* y_coarse, void* hip_stream) {
+  cfdetr_status st = check_call(ctx, B);
+  if (st != CFDETR_OK) return st;
+  if (!images || !y_coarse) return fail(ctx, CFDETR_EINVAL, "null pointer");
+  if (!aligned16(images) || !aligned16(y_coarse) || !aligned16(x0_cache))
+    return fail(ctx, CFDETR_EINVAL, "pointers must be 16-byte aligned");
+  return coarse_impl(ctx, images, B, x0_cache, y_coarse, static_cast<hipStream_t>(hip_stream));
+}
+
+CFDETR_API cfdetr_status cfdetr_select_fine(cfdetr_ctx* ctx, const int32_t* boxes, const uint8_t* tier,
+                                 const int32_t* box_offsets, int32_t B, int32_t* tok_desc,
+                                 int32_t* cu_seqlens, int32_t* level_counts, void* hip_stream) {
+  cfdetr_status st = check_call(ctx, B);
+  if (st != CFDETR_OK) return st;
+  if (!boxes || !tier || !box_offsets || !tok_desc || !cu_seqlens)
+    return fail(ctx, CFDETR_EINVAL, "null pointer");
+  return select_impl(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts,
+                     static_cast<hipStream_t>(hip_stream));
+}
+
+CFDETR_API cfdetr_status cfdetr_fine_encode(cfdetr_ctx* ctx, const void* images, int32_t B,
+                                 const int32_t* tok_desc, const int32_t* cu_seqlens,
+                                 const float* x0_cache, float* y_mixed, void* hip_stream) {
+  cfdetr_status st = check_call(ctx, B);
+  if (st != CFDETR_OK) return st;
+  if (!images || !tok_desc || !cu_seqlens || !y_mixed) return fail(ctx, CFDETR_EINVAL, "null pointer");
+  if (!aligned16(images) || !aligned16(y_mixed) || !aligned16(x0_cache))
+    return fail(ctx, CFDETR_EINVAL, "pointers must be 16-byte aligned");
+  return fine_impl(ctx, images, B, tok_desc, cu_seqlens, x0_cache, y_mixed,
+                   static_cast<hipStream_t>(hip_stream));
+}
+
+CFDETR_API cfdetr_status cfdetr_multilevel_batch(cfdetr_ctx* ctx, const void* images, int32_t B,
+                                      const int32_t* boxes, const uint8_t* tier,
+                                      const int32_t* box_offsets, float* y_coarse, float* y_mixed,
+                                      int32_t* tok_desc, int32_t* cu_seqlens,
+                                      int32_t* level_counts, void* hip_stream) {
+  cfdetr_status st = check_call(ctx, B);
+  if (st != CFDETR_OK) return st;
+  if (!images || !boxes || !tier || !box_offsets || !y_coarse || !y_mixed || !tok_desc ||
+      !cu_seqlens)
+    return fail(ctx, CFDETR_EINVAL, "null pointer");
+  if (!aligned16(images) || !aligned16(y_coarse) || !aligned16(y_mixed))
+    return fail(ctx, CFDETR_EINVAL, "pointers must be 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  st = coarse_impl(ctx, images, B, ctx->x0, y_coarse, s);
+  if (st != CFDETR_OK) return st;
+  st = select_impl(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts, s);
+  if (st != CFDETR_OK) return st;
+  return fine_impl(ctx, images, B, tok_desc, cu_seqlens, ctx->x0, y_mixed, s);
+}
+
+CFDETR_API cfdetr_status cfdetr_profile_begin(cfdetr_ctx* ctx) {
+  if (!ctx) return CFDETR_EINVAL;
+  if (ctx->ev.empty()) {
+    const size_t want = 2 * 8192;
+    ctx->ev.reserve(want);
+    for (size_t i = 0; i < want; ++i) {
+      hipEvent_t ev;
+      hipError_t e = hipEventCreate(&ev);
+      if (e != hipSuccess) return fail_hip(ctx, "hipEventCreate", e);
+      ctx->ev.push_back(ev);
+    }
+    ctx->ev_kind.assign(want / 2, 0);
+  }
+  ctx->ev_used = 0;
+  ctx->prof = true;
+  return CFDETR_OK;
+}
+
+CFDETR_API cfdetr_status cfdetr_profile_end(cfdetr_ctx* ctx, float* total_ms, int32_t* launches) {
+  if (!ctx || !total_ms || !launches) return CFDETR_EINVAL;
+  ctx->prof = false;
+  for (int k = 0; k < CFDETR_K_COUNT; ++k) {
+    total_ms[k] = 0.f;
+    launches[k] = 0;
+  }
+  if (ctx->ev_used == 0) return CFDETR_OK;
+  hipError_t e = hipEventSynchronize(ctx->ev[ctx->ev_used - 1]);
+  if (e != hipSuccess) return fail_hip(ctx, "hipEventSynchronize", e);
+  for (size_t i = 0; i < ctx->ev_used; i += 2) {
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, ctx->ev[i], ctx->ev[i + 1]);
+    if (e != hipSuccess) return fail_hip(ctx, "hipEventElapsedTime", e);
+    int k = ctx->ev_kind[i / 2];
+    total_ms[k] += ms;
+    launches[k] += 1;
+  }
+  ctx->ev_used = 0;
+  return CFDETR_OK;
+}
+
+}  // extern "C"

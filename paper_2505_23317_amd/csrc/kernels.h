@@ -1,0 +1,76 @@
+// Host-side launchers of the cfdetr kernels.  Every launcher enqueues on the
+// given stream and returns the hipGetLastError() of its launches; none of them
+// synchronises or allocates.
+#pragma once
+#include "common.h"
+
+namespace cfdetr {
+
+// ---- A2 selection (select.hip) -------------------------------------------
+// hit        [B, nonfinest] bytes: cell (levels < n-1, level-major) overlapped by a
+//            box asking for a finer level
+// split_cur  [kMaxBatch * kMaxLevels] int32, zero on entry: receives the number of hit
+//            cells per (frame, level); split_next is zeroed for the following call.
+hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t* tier,
+                         const int32_t* box_offsets, int B, int nonfinest, uint8_t* hit,
+                         int32_t* split_cur, int32_t* split_next, int max_tokens,
+                         int32_t* tok_desc, int32_t* cu_seqlens, int32_t* level_counts,
+                         int32_t* err_flag, hipStream_t s);
+
+// Attention work list: tiles[i] = frame<<24 | query-tile index, longest frame first.
+hipError_t launch_plan(const int32_t* cu_seqlens, int B, int block_q, int32_t* tiles,
+                       int32_t* n_tiles, int tile_capacity, hipStream_t s);
+
+// ---- row-wise kernels (rowwise.hip) ----------------------------------------
+// Position tables of one level: pe_row [rows, d/2], pe_col [cols, d/2] (fp32).
+hipError_t launch_pe_tables(int patch, int rows, int cols, int img_h, int img_w, int d,
+                            float* pe_row, float* pe_col, hipStream_t s);
+// out = LayerNorm(x) * g + b for rows < M, M = *m_ptr if m_ptr else m_host.
+// out_is_bf16 selects bf16 bit patterns or fp32 for `out`.
+hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* out,
+                            bool out_is_bf16, int d, float eps, const int32_t* m_ptr,
+                            int m_host, int m_capacity, hipStream_t s);
+// x[t] = x0[frame(t)*n0 + row*cols0 + col] for every level-0 token t < *m_ptr.
+hipError_t launch_gather_coarse(const int32_t* tok_desc, const int32_t* cu_seqlens, int B,
+                                const float* x0, int n0, int cols0, int d, float* x,
+                                int m_capacity, hipStream_t s);
+
+// ---- contractions (gemm.hip) -----------------------------------------------
+struct EmbedArgs {
+  const void* images;     // [B,3,H,W]
+  bool image_is_bf16;
+  int level;              // tokens of this level only; other rows are left untouched
+  int patch;              // pixels per side at this level
+  int img_h, img_w;
+  const int32_t* tok_desc;
+  const int32_t* cu_seqlens;
+  int B;
+  const float* pe_row;    // [rows, d/2]
+  const float* pe_col;    // [cols, d/2]
+  float* out;             // [M, d] fp32
+  float* out2;            // optional second copy (may be nullptr)
+};
+// Patch gather + projection + bias + position for the tokens of one level.
+// w [d, 3*patch^2] in bf16 (use_bf16) or fp32.
+hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, int d,
+                        bool use_bf16, const int32_t* m_ptr, int m_host, int m_capacity,
+                        hipStream_t s);
+
+enum class Epilogue { kBias, kBiasGelu, kBiasResidual };
+// C = A[M,K] . W[N,K]^T + bias, then per `epi`:
+//   kBias         -> out_act (activation dtype)
+//   kBiasGelu     -> GELU, out_act
+//   kBiasResidual -> resid[M,N] (fp32) += result, in place
+hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, int K,
+                       Epilogue epi, void* out_act, float* resid, bool use_bf16,
+                       const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s);
+
+// ---- attention (attention.hip) -----------------------------------------------
+// qkv [M, 3d] (q | k | v, head h at columns h*dh), out [M, d], both in the activation
+// dtype.  Softmax over the keys of the same frame only.
+hipError_t launch_attention(const void* qkv, void* out, const int32_t* cu_seqlens, int B,
+                            int d, int heads, const int32_t* tiles, const int32_t* n_tiles,
+                            int tile_capacity, int block_q, bool use_bf16, hipStream_t s);
+int attention_block_q(int d_head, bool use_bf16);
+
+}  // namespace cfdetr

@@ -1,0 +1,122 @@
+// Row-wise kernels: position tables, LayerNorm, reuse of cached coarse tokens.
+#include "kernels.h"
+
+namespace cfdetr {
+
+namespace {
+
+// Centre-based 2-D sinusoidal position, separable: the first half of a token's
+// vector depends on its row only, the second half on its column only.  With
+// D = d/2 and pair index j = i/2 < D/2 the frequency is 10000^(-2j/D); even i
+// holds sin, odd i holds cos of 2*pi*coord*frequency, coord = (index+0.5)*P/extent.
+// Evaluated once, in double, at context creation.
+__global__ void pe_table_kernel(int patch, int count, int extent, int D,
+                                float* __restrict__ table) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= count * D) return;
+  int cell = idx / D, i = idx - cell * D;
+  double coord = (cell + 0.5) * (double)patch / (double)extent;
+  double omega = pow(10000.0, -2.0 * (double)(i >> 1) / (double)D);
+  double arg = 2.0 * 3.14159265358979323846 * coord * omega;
+  table[idx] = (float)((i & 1) ? cos(arg) : sin(arg));
+}
+
+constexpr int kLnMaxPerLane = 16;  // d <= 1024
+
+template <typename TOut>
+__device__ __forceinline__ void store_out(TOut* p, float v);
+template <>
+__device__ __forceinline__ void store_out<float>(float* p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store_out<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// One wavefront per row; the row lives in registers between the two passes.
+template <typename TOut>
+__global__ __launch_bounds__(256) void layernorm_kernel(
+    const float* __restrict__ x, const float* __restrict__ g, const float* __restrict__ b,
+    TOut* __restrict__ out, int d, float eps, const int32_t* __restrict__ m_ptr, int m_host) {
+  const int M = m_ptr ? *m_ptr : m_host;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  const int lane = threadIdx.x & 63;
+  const int per = d >> 6;
+  const float* xr = x + (size_t)row * d;
+  float v[kLnMaxPerLane];
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < kLnMaxPerLane; ++j) {
+    if (j < per) {
+      v[j] = xr[lane + 64 * j];
+      sum += v[j];
+    }
+  }
+  const float mean = wave_sum(sum) / (float)d;
+  float sq = 0.f;
+#pragma unroll
+  for (int j = 0; j < kLnMaxPerLane; ++j) {
+    if (j < per) {
+      float c = v[j] - mean;
+      sq += c * c;
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)d + eps);
+  TOut* orow = out + (size_t)row * d;
+#pragma unroll
+  for (int j = 0; j < kLnMaxPerLane; ++j) {
+    if (j < per) {
+      int e = lane + 64 * j;
+      store_out<TOut>(orow + e, (v[j] - mean) * rstd * g[e] + b[e]);
+    }
+  }
+}
+
+// One wavefront per token: level-0 tokens take their row of the coarse cache.
+__global__ __launch_bounds__(256) void gather_coarse_kernel(
+    const int32_t* __restrict__ tok_desc, const int32_t* __restrict__ cu, int B,
+    const float* __restrict__ x0, int n0, int cols0, int d, float* __restrict__ x) {
+  const int M = cu[B];
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= M) return;
+  const int32_t desc = tok_desc[t];
+  if (tok_level(desc) != 0) return;
+  const int frame = frame_of_token(cu, B, t);
+  const float* src = x0 + ((size_t)frame * n0 + tok_row(desc) * cols0 + tok_col(desc)) * d;
+  float* dst = x + (size_t)t * d;
+  for (int e = (threadIdx.x & 63) * 4; e < d; e += 256)
+    *reinterpret_cast<float4*>(dst + e) = *reinterpret_cast<const float4*>(src + e);
+}
+
+}  // namespace
+
+hipError_t launch_pe_tables(int patch, int rows, int cols, int img_h, int img_w, int d,
+                            float* pe_row, float* pe_col, hipStream_t s) {
+  const int D = d / 2;
+  hipLaunchKernelGGL(pe_table_kernel, dim3((rows * D + 255) / 256), dim3(256), 0, s, patch,
+                     rows, img_h, D, pe_row);
+  hipLaunchKernelGGL(pe_table_kernel, dim3((cols * D + 255) / 256), dim3(256), 0, s, patch,
+                     cols, img_w, D, pe_col);
+  return hipGetLastError();
+}
+
+hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* out,
+                            bool out_is_bf16, int d, float eps, const int32_t* m_ptr,
+                            int m_host, int m_capacity, hipStream_t s) {
+  dim3 grid((m_capacity + 3) / 4);
+  if (out_is_bf16)
+    hipLaunchKernelGGL(layernorm_kernel<bf16_t>, grid, dim3(256), 0, s, x, g, b,
+                       static_cast<bf16_t*>(out), d, eps, m_ptr, m_host);
+  else
+    hipLaunchKernelGGL(layernorm_kernel<float>, grid, dim3(256), 0, s, x, g, b,
+                       static_cast<float*>(out), d, eps, m_ptr, m_host);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_coarse(const int32_t* tok_desc, const int32_t* cu_seqlens, int B,
+                                const float* x0, int n0, int cols0, int d, float* x,
+                                int m_capacity, hipStream_t s) {
+  hipLaunchKernelGGL(gather_coarse_kernel, dim3((m_capacity + 3) / 4), dim3(256), 0, s,
+                     tok_desc, cu_seqlens, B, x0, n0, cols0, d, x);
+  return hipGetLastError();
+}
+
+}  // namespace cfdetr

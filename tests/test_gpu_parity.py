@@ -1,0 +1,332 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle.
+
+Bars: token tables, offsets and counts bit-exact; activations within
+max|gpu - ref| / max|ref| <= 2e-2 with bf16 contractions and <= 1e-4 in the
+all-fp32 check mode.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import cfdetr_oracle as O
+from paper_2505_23317_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "fp32": 1e-4}
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def rel_err(g, r):
+    return float(np.abs(np.asarray(g, np.float64) - r).max() / np.abs(r).max())
+
+
+@pytest.fixture(scope="module")
+def K():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2505_23317_amd import cfdetr
+    cfdetr.load_library()
+    return cfdetr
+
+
+def gpu_multilevel(K, cfg, wl, act, max_tokens=None):
+    import torch
+    enc = K.Encoder(cfg, wl["weights"], act_dtype=act, max_tokens_total=max_tokens)
+    img = enc.upload_images(wl["images"])
+    b, t, o = enc.upload_boxes(wl["boxes"], wl["tier"], wl["box_offsets"])
+    out = enc.alloc_outputs(cfg.B)
+    enc.multilevel_batch(img, cfg.B, b, t, o, out)
+    enc.sync_status()
+    torch.cuda.synchronize()
+    res = {k: v.cpu().numpy() for k, v in out.items()}
+    enc.close()
+    return res
+
+
+def oracle_multilevel(cfg, wl):
+    yc, ym, tok, cu, counts = O.multilevel_batch(wl["images"], wl["boxes"], wl["tier"],
+                                                 wl["box_offsets"], cfg.patch, wl["weights"],
+                                                 cfg.heads)
+    return {"y_coarse": yc, "y_mixed": ym, "tok_desc": O.pack_tok_desc(tok),
+            "cu_seqlens": cu, "level_counts": counts}
+
+
+def check_all(got, ref, act, label):
+    T = int(ref["cu_seqlens"][-1])
+    np.testing.assert_array_equal(got["cu_seqlens"], ref["cu_seqlens"])
+    np.testing.assert_array_equal(got["level_counts"], ref["level_counts"])
+    np.testing.assert_array_equal(got["tok_desc"][:T], ref["tok_desc"])
+    ec = rel_err(got["y_coarse"], ref["y_coarse"])
+    em = rel_err(got["y_mixed"][:T], ref["y_mixed"])
+    _say(f"[parity] {label} {act}: T={T} coarse {ec:.2e} mixed {em:.2e} (bar {TOL[act]:.0e})")
+    assert np.isfinite(got["y_mixed"][:T]).all()
+    assert ec <= TOL[act], (label, act, ec)
+    assert em <= TOL[act], (label, act, em)
+    # rows past the token total stay as the caller left them (zero-filled here)
+    assert not got["y_mixed"][T:].any()
+
+
+# ------------------------------------------------------------------ selection
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
+def test_selection_is_bit_exact_on_every_config(K, cfg_id):
+    import torch
+    cfg = synth.config(cfg_id)
+    _say(f"[case] selection cfg{cfg_id}")
+    images, boxes, tier, offs, _ = synth.make_frames(synth.replace(cfg, H=cfg.H, W=cfg.W), cfg_id)
+    w = synth.make_weights(synth.replace(cfg, layers=1), 1)
+    enc = K.Encoder(synth.replace(cfg, layers=1), w)
+    b, t, o = enc.upload_boxes(boxes, tier, offs)
+    out = enc.alloc_outputs(cfg.B)
+    enc.select_fine(b, t, o, cfg.B, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
+    enc.sync_status()
+    tok, cu, counts = O.select_fine(boxes, tier, offs, cfg.B, cfg.H, cfg.W, cfg.patch)
+    T = int(cu[-1])
+    np.testing.assert_array_equal(out["cu_seqlens"].cpu().numpy(), cu)
+    np.testing.assert_array_equal(out["level_counts"].cpu().numpy(), counts)
+    np.testing.assert_array_equal(out["tok_desc"].cpu().numpy()[:T], O.pack_tok_desc(tok))
+    # a second call on the same context starts from clean counters
+    enc.select_fine(b, t, o, cfg.B, out["tok_desc"], out["cu_seqlens"], None)
+    enc.sync_status()
+    np.testing.assert_array_equal(out["cu_seqlens"].cpu().numpy(), cu)
+    enc.close()
+
+
+def test_selection_edge_cases(K):
+    cfg = synth.Config("edge", 4, 128, 192, (64, 32, 16), 64, 2, 1, 128, "f32")
+    w = synth.make_weights(cfg, 2)
+    enc = K.Encoder(cfg, w)
+    # frame 0: no box; 1: everything at finest; 2: clipped / empty / outside boxes and
+    # a mid-tier box; 3: tier above the finest level acts as finest
+    boxes = np.asarray([[0, 0, 192, 128],
+                        [-50, -50, 1, 1], [40, 40, 40, 90], [500, 0, 600, 50], [100, 70, 130, 100],
+                        [191, 127, 4000, 4000],
+                        [10, 10, 20, 20]], np.int32)
+    tier = np.asarray([2, 2, 2, 2, 1, 2, 9], np.uint8)
+    offs = np.asarray([0, 0, 1, 6, 7], np.int32)
+    b, t, o = enc.upload_boxes(boxes, tier, offs)
+    out = enc.alloc_outputs(cfg.B)
+    enc.select_fine(b, t, o, cfg.B, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
+    enc.sync_status()
+    tok, cu, counts = O.select_fine(boxes, np.minimum(tier, 2), offs, cfg.B, cfg.H, cfg.W, cfg.patch)
+    np.testing.assert_array_equal(out["cu_seqlens"].cpu().numpy(), cu)
+    np.testing.assert_array_equal(out["level_counts"].cpu().numpy(), counts)
+    np.testing.assert_array_equal(out["tok_desc"].cpu().numpy()[:cu[-1]], O.pack_tok_desc(tok))
+    assert counts[0].tolist() == [6, 0, 0] and counts[1].tolist() == [0, 0, 96]
+    enc.close()
+
+
+def test_selection_overflow_is_reported_not_truncated(K):
+    cfg = synth.Config("ovf", 2, 128, 128, (32, 16), 64, 2, 1, 128, "f32")
+    enc = K.Encoder(cfg, synth.make_weights(cfg, 3), max_tokens_total=40)
+    boxes = np.asarray([[0, 0, 128, 128]], np.int32)      # frame 1 alone needs 64 tokens
+    b, t, o = enc.upload_boxes(boxes, np.asarray([1], np.uint8), np.asarray([0, 0, 1], np.int32))
+    out = enc.alloc_outputs(cfg.B)
+    out["tok_desc"].fill_(-7)
+    enc.select_fine(b, t, o, cfg.B, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
+    with pytest.raises(K.CfdetrError) as ei:
+        enc.sync_status()
+    assert ei.value.status == K.CFDETR_ECAPACITY
+    assert out["cu_seqlens"].cpu().tolist() == [0, 0, 0]
+    assert (out["tok_desc"].cpu().numpy() == -7).all()
+    enc.sync_status()                                       # flag is cleared once reported
+    # the context keeps working afterwards
+    b, t, o = enc.upload_boxes(np.zeros((0, 4)), np.zeros(0), np.asarray([0, 0, 0], np.int32))
+    enc.select_fine(b, t, o, cfg.B, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
+    enc.sync_status()
+    assert out["cu_seqlens"].cpu().tolist() == [0, 16, 32]
+    enc.close()
+
+
+def test_host_side_argument_errors(K):
+    import torch
+    cfg = synth.config(1)
+    wl = synth.make_workload(1)
+    enc = K.Encoder(cfg, wl["weights"])
+    img = enc.upload_images(wl["images"])
+    out = enc.alloc_outputs(1)
+    with pytest.raises(K.CfdetrError) as ei:
+        enc.coarse_encode(img, 2, out["x0_cache"], out["y_coarse"])
+    assert ei.value.status == K.CFDETR_ECAPACITY
+    with pytest.raises(K.CfdetrError) as ei:
+        enc.coarse_encode(img, 0, out["x0_cache"], out["y_coarse"])
+    assert ei.value.status == K.CFDETR_EINVAL
+    with pytest.raises(K.CfdetrError) as ei:
+        K.cfdetr_coarse_encode(enc.ctx, img.data_ptr(), 1, None, out["y_coarse"].data_ptr() + 4, 0)
+    assert ei.value.status == K.CFDETR_EINVAL
+    with pytest.raises(K.CfdetrError) as ei:
+        K.cfdetr_fine_encode(enc.ctx, img.data_ptr(), 1, None, out["cu_seqlens"].data_ptr(), None,
+                             out["y_mixed"].data_ptr(), 0)
+    assert ei.value.status == K.CFDETR_EINVAL
+    assert "null" in K.cfdetr_last_error(enc.ctx)
+    assert K.cfdetr_workspace_bytes(enc.ctx) > 0
+    enc.close()
+
+
+# ------------------------------------------------------------------ whole path
+@pytest.mark.parametrize("act", ["fp32", "bf16"])
+@pytest.mark.parametrize("seed", [1, 2, 5])
+def test_cfg1_tiny_frame(K, act, seed):
+    cfg = synth.config(1)
+    _say(f"[case] cfg1 seed {seed} {act}")
+    wl = synth.make_workload(cfg, seed=seed)
+    check_all(gpu_multilevel(K, cfg, wl, act), oracle_multilevel(cfg, wl), act, f"cfg1/s{seed}")
+
+
+@pytest.mark.parametrize("act", ["fp32", "bf16"])
+@pytest.mark.parametrize("cfg_id", [2, 3])
+def test_cfg2_cfg3_full_size(K, act, cfg_id):
+    cfg = synth.config(cfg_id)
+    _say(f"[case] cfg{cfg_id} {act}")
+    wl = synth.make_workload(cfg_id)
+    check_all(gpu_multilevel(K, cfg, wl, act), oracle_multilevel(cfg, wl), act, f"cfg{cfg_id}")
+
+
+REDUCED = {
+    # head width 64, d=384: the shape family of the high-resolution config, ragged lengths
+    "cfg4_reduced": synth.Config("cfg4r", 3, 512, 384, (32, 16), 384, 6, 2, 1536, "bf16",
+                                 frac_lo=0.0, frac_hi=1.0, box_rule="fraction"),
+    # three levels, d=768, 12 heads
+    "cfg5_reduced": synth.Config("cfg5r", 3, 256, 384, (64, 32, 16), 768, 12, 2, 3072, "bf16",
+                                 box_rule="tiered", box_lambda=3.0, side_lo=16, side_hi=96),
+}
+
+
+@pytest.mark.parametrize("act", ["fp32", "bf16"])
+@pytest.mark.parametrize("name", sorted(REDUCED))
+def test_reduced_large_shapes(K, act, name):
+    cfg = REDUCED[name]
+    _say(f"[case] {name} {act}")
+    wl = synth.make_workload(cfg, seed=17)
+    ref = oracle_multilevel(cfg, wl)
+    lens = np.diff(ref["cu_seqlens"])
+    assert len(set(lens.tolist())) > 1 and (lens % 64 != 0).any()     # ragged tails
+    check_all(gpu_multilevel(K, cfg, wl, act), ref, act, name)
+
+
+@pytest.mark.parametrize("act", ["fp32", "bf16"])
+def test_sharp_attention_weights(K, act):
+    # random N(0,0.02) weights give nearly uniform attention; this set has logits of a
+    # few units so that scale, mask and max-subtraction mistakes would show
+    cfg = synth.replace(synth.config(3), B=3, layers=2)
+    _say(f"[case] sharp {act}")
+    wl = synth.make_workload(cfg, seed=23, sharp=True)
+    check_all(gpu_multilevel(K, cfg, wl, act), oracle_multilevel(cfg, wl), act, "sharp")
+
+
+@pytest.mark.parametrize("cfg_id", [4, 5])
+def test_full_size_against_stored_oracle_rows(K, cfg_id):
+    path = os.path.join(GOLDEN, f"cfg{cfg_id}_oracle.npz")
+    ref = np.load(path)
+    cfg = synth.config(cfg_id)
+    _say(f"[case] cfg{cfg_id} full size bf16 vs stored oracle rows")
+    wl = synth.make_workload(cfg_id)
+    got = gpu_multilevel(K, cfg, wl, "bf16")
+    T = int(ref["cu_seqlens"][-1])
+    np.testing.assert_array_equal(got["cu_seqlens"], ref["cu_seqlens"])
+    np.testing.assert_array_equal(got["level_counts"], ref["level_counts"])
+    np.testing.assert_array_equal(got["tok_desc"][:T], ref["tok_desc"])
+    ec = np.abs(got["y_coarse"][ref["rows_coarse"]] - ref["y_coarse"]).max() / ref["max_abs_coarse"]
+    em = np.abs(got["y_mixed"][ref["rows_mixed"]] - ref["y_mixed"]).max() / ref["max_abs_mixed"]
+    _say(f"[parity] cfg{cfg_id} full: T={T} coarse {ec:.2e} mixed {em:.2e}")
+    assert np.isfinite(got["y_mixed"][:T]).all() and np.isfinite(got["y_coarse"]).all()
+    assert ec <= TOL["bf16"] and em <= TOL["bf16"]
+
+
+# ------------------------------------------------------------------ invariants on the GPU
+def _calls_separately(K, cfg, wl, act, use_cache=True, boxes=None):
+    import torch
+    enc = K.Encoder(cfg, wl["weights"], act_dtype=act)
+    img = enc.upload_images(wl["images"])
+    bx = wl if boxes is None else boxes
+    b, t, o = enc.upload_boxes(bx["boxes"], bx["tier"], bx["box_offsets"])
+    out = enc.alloc_outputs(cfg.B)
+    enc.coarse_encode(img, cfg.B, out["x0_cache"], out["y_coarse"])
+    enc.select_fine(b, t, o, cfg.B, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
+    enc.fine_encode(img, cfg.B, out["tok_desc"], out["cu_seqlens"],
+                    out["x0_cache"] if use_cache else None, out["y_mixed"])
+    enc.sync_status()
+    res = {k: v.cpu().numpy() for k, v in out.items()}
+    enc.close()
+    return res
+
+
+@pytest.mark.parametrize("act", ["fp32", "bf16"])
+def test_one_call_equals_three_calls_and_cache_equals_recompute(K, act):
+    cfg = synth.replace(synth.config(3), B=3, layers=2)
+    wl = synth.make_workload(cfg, seed=31)
+    one = gpu_multilevel(K, cfg, wl, act)
+    three = _calls_separately(K, cfg, wl, act, use_cache=True)
+    fresh = _calls_separately(K, cfg, wl, act, use_cache=False)
+    T = int(one["cu_seqlens"][-1])
+    for k in ("y_coarse", "tok_desc", "cu_seqlens", "level_counts"):
+        np.testing.assert_array_equal(one[k], three[k])
+    np.testing.assert_array_equal(one["y_mixed"][:T], three["y_mixed"][:T])
+    # same kernel, same arithmetic order for a coarse token whether cached or re-embedded
+    np.testing.assert_array_equal(three["y_mixed"][:T], fresh["y_mixed"][:T])
+    x0_ref, _ = O.coarse_encode(wl["images"], cfg.patch, wl["weights"], cfg.heads)
+    assert rel_err(three["x0_cache"], x0_ref) <= TOL[act]
+
+
+def test_no_roi_gives_the_coarse_result(K):
+    cfg = synth.replace(synth.config(3), B=2, layers=2)
+    wl = synth.make_workload(cfg, seed=37)
+    none = {"boxes": np.zeros((0, 4), np.int32), "tier": np.zeros(0, np.uint8),
+            "box_offsets": np.zeros(cfg.B + 1, np.int32)}
+    got = _calls_separately(K, cfg, wl, "bf16", boxes=none)
+    n0 = cfg.n_cells(0)
+    assert got["cu_seqlens"].tolist() == [0, n0, 2 * n0]
+    # the mixed pass over coarse-only token sets runs the same kernels on the same rows
+    np.testing.assert_array_equal(got["y_mixed"][:2 * n0], got["y_coarse"])
+
+
+def test_batched_equals_frame_by_frame(K):
+    cfg = synth.replace(synth.config(3), B=3, layers=2)
+    wl = synth.make_workload(cfg, seed=41, sharp=True)
+    full = gpu_multilevel(K, cfg, wl, "bf16")
+    cu = full["cu_seqlens"]
+    n0 = cfg.n_cells(0)
+    for i in range(cfg.B):
+        lo, hi = wl["box_offsets"][i], wl["box_offsets"][i + 1]
+        one_cfg = synth.replace(cfg, B=1)
+        one = dict(wl, images=wl["images"][i:i + 1], boxes=wl["boxes"][lo:hi],
+                   tier=wl["tier"][lo:hi], box_offsets=np.asarray([0, hi - lo], np.int32))
+        got = gpu_multilevel(K, one_cfg, one, "bf16")
+        np.testing.assert_array_equal(got["y_mixed"][:cu[i + 1] - cu[i]],
+                                      full["y_mixed"][cu[i]:cu[i + 1]])
+        np.testing.assert_array_equal(got["y_coarse"], full["y_coarse"][i * n0:(i + 1) * n0])
+
+
+def test_two_runs_are_bit_identical(K):
+    cfg = synth.replace(synth.config(3), layers=2)
+    wl = synth.make_workload(cfg, seed=43)
+    a = gpu_multilevel(K, cfg, wl, "bf16")
+    b = gpu_multilevel(K, cfg, wl, "bf16")
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
+
+
+def test_profile_interface_counts_launches(K):
+    cfg = synth.replace(synth.config(2), layers=2)
+    wl = synth.make_workload(cfg, seed=47)
+    enc = K.Encoder(cfg, wl["weights"])
+    img = enc.upload_images(wl["images"])
+    b, t, o = enc.upload_boxes(wl["boxes"], wl["tier"], wl["box_offsets"])
+    out = enc.alloc_outputs(cfg.B)
+    K.cfdetr_profile_begin(enc.ctx)
+    enc.multilevel_batch(img, cfg.B, b, t, o, out)
+    prof = K.cfdetr_profile_end(enc.ctx)
+    assert prof["attention"]["launches"] == 2 * cfg.layers
+    assert prof["layernorm"]["launches"] == 2 * (2 * cfg.layers + 1)
+    assert prof["select"]["launches"] == 1 and prof["gather"]["launches"] == 1
+    assert prof["embed"]["launches"] == 2
+    assert all(v["ms"] >= 0 for v in prof.values())
+    enc.close()
