@@ -40,8 +40,8 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
   constexpr int LDV = kBlockKV + 8;   // sVt row stride
   constexpr int KS = DH / 16;         // k-steps of Q.K^T
   constexpr int MO = DH / 32;         // 32-row blocks of O^T
-  __shared__ __attribute__((aligned(16))) bf16_t sK[kBlockKV * LDK];
-  __shared__ __attribute__((aligned(16))) bf16_t sVt[DH * LDV];
+  __shared__ __attribute__((aligned(16))) bf16_t sK[2 * kBlockKV * LDK];   // double buffer
+  __shared__ __attribute__((aligned(16))) bf16_t sVt[2 * DH * LDV];
 
   if ((int)blockIdx.x >= *n_tiles) return;
   const int32_t tile = tiles[blockIdx.x];
@@ -73,38 +73,43 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
   const bool v_active = tid < V_UNITS;
   const int v_pair = tid & 31, v_piece = tid >> 5;
 
-  uint4 rk[K_PASSES], rv0, rv1;
-  auto fetch = [&](int kv0) {
-#pragma unroll
-    for (int p = 0; p < K_PASSES; ++p) {
-      int key = min(kv0 + k_row + p * K_ROWS_PER_PASS, T - 1);
-      rk[p] = *reinterpret_cast<const uint4*>(kbase + (size_t)key * ld + k_piece * 8);
-    }
-    if (v_active) {
-      int key0 = min(kv0 + 2 * v_pair, T - 1), key1 = min(kv0 + 2 * v_pair + 1, T - 1);
-      rv0 = *reinterpret_cast<const uint4*>(vbase + (size_t)key0 * ld + v_piece * 8);
-      rv1 = *reinterpret_cast<const uint4*>(vbase + (size_t)key1 * ld + v_piece * 8);
-    }
-  };
-  auto stage = [&]() {
-#pragma unroll
-    for (int p = 0; p < K_PASSES; ++p) {
-      int r = k_row + p * K_ROWS_PER_PASS;
-      int rr = (r & 32) | swap_bits_2_3(r & 31);
-      *reinterpret_cast<uint4*>(&sK[rr * LDK + k_piece * 8]) = rk[p];
-    }
-    if (v_active) {
-      const uint32_t a[4] = {rv0.x, rv0.y, rv0.z, rv0.w};
-      const uint32_t b[4] = {rv1.x, rv1.y, rv1.z, rv1.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        uint32_t lo = (a[e] & 0xFFFFu) | (b[e] << 16);          // dh 2e  : (key0, key1)
-        uint32_t hi = (a[e] >> 16) | (b[e] & 0xFFFF0000u);      // dh 2e+1
-        *reinterpret_cast<uint32_t*>(&sVt[(v_piece * 8 + 2 * e) * LDV + 2 * v_pair]) = lo;
-        *reinterpret_cast<uint32_t*>(&sVt[(v_piece * 8 + 2 * e + 1) * LDV + 2 * v_pair]) = hi;
-      }
-    }
-  };
+  // Global -> register fetch of one K/V tile and its (permuted / transposed) store to
+  // LDS, written out twice below without closures so the registers stay registers.
+  uint4 rk[K_PASSES], rv0 = make_uint4(0, 0, 0, 0), rv1 = make_uint4(0, 0, 0, 0);
+#define CFDETR_ATTN_FETCH(kv0_)                                                              \
+  do {                                                                                       \
+    _Pragma("unroll") for (int p = 0; p < K_PASSES; ++p) {                                   \
+      int key = min((kv0_) + k_row + p * K_ROWS_PER_PASS, T - 1);                            \
+      rk[p] = *reinterpret_cast<const uint4*>(kbase + (size_t)key * ld + k_piece * 8);       \
+    }                                                                                        \
+    if (v_active) {                                                                          \
+      int key0 = min((kv0_) + 2 * v_pair, T - 1), key1 = min((kv0_) + 2 * v_pair + 1, T - 1); \
+      rv0 = *reinterpret_cast<const uint4*>(vbase + (size_t)key0 * ld + v_piece * 8);        \
+      rv1 = *reinterpret_cast<const uint4*>(vbase + (size_t)key1 * ld + v_piece * 8);        \
+    }                                                                                        \
+  } while (0)
+#define CFDETR_ATTN_STAGE(sk_, sv_)                                                          \
+  do {                                                                                       \
+    _Pragma("unroll") for (int p = 0; p < K_PASSES; ++p) {                                   \
+      int r = k_row + p * K_ROWS_PER_PASS;                                                   \
+      int rr = (r & 32) | swap_bits_2_3(r & 31);                                             \
+      *reinterpret_cast<uint4*>((sk_) + rr * LDK + k_piece * 8) = rk[p];                     \
+    }                                                                                        \
+    if (v_active) {                                                                          \
+      const uint32_t a0 = rv0.x, a1 = rv0.y, a2 = rv0.z, a3 = rv0.w;                         \
+      const uint32_t b0 = rv1.x, b1 = rv1.y, b2 = rv1.z, b3 = rv1.w;                         \
+      bf16_t* vd = (sv_) + (v_piece * 8) * LDV + 2 * v_pair;                                 \
+      /* dh 2e: (key0,key1) from the low halves; dh 2e+1 from the high halves */             \
+      *reinterpret_cast<uint32_t*>(vd + 0 * LDV) = (a0 & 0xFFFFu) | (b0 << 16);              \
+      *reinterpret_cast<uint32_t*>(vd + 1 * LDV) = (a0 >> 16) | (b0 & 0xFFFF0000u);          \
+      *reinterpret_cast<uint32_t*>(vd + 2 * LDV) = (a1 & 0xFFFFu) | (b1 << 16);              \
+      *reinterpret_cast<uint32_t*>(vd + 3 * LDV) = (a1 >> 16) | (b1 & 0xFFFF0000u);          \
+      *reinterpret_cast<uint32_t*>(vd + 4 * LDV) = (a2 & 0xFFFFu) | (b2 << 16);              \
+      *reinterpret_cast<uint32_t*>(vd + 5 * LDV) = (a2 >> 16) | (b2 & 0xFFFF0000u);          \
+      *reinterpret_cast<uint32_t*>(vd + 6 * LDV) = (a3 & 0xFFFFu) | (b3 << 16);              \
+      *reinterpret_cast<uint32_t*>(vd + 7 * LDV) = (a3 >> 16) | (b3 & 0xFFFF0000u);          \
+    }                                                                                        \
+  } while (0)
 
   f32x16 acc_o[MO];
 #pragma unroll
@@ -113,12 +118,17 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  fetch(0);
-  stage();
+  CFDETR_ATTN_FETCH(0);
+  CFDETR_ATTN_STAGE(sK, sVt);
   __syncthreads();
-  for (int kv0 = 0; kv0 < T; kv0 += kBlockKV) {
-    const bool more = (kv0 + kBlockKV) < T;
-    if (more) fetch(kv0 + kBlockKV);
+  const int n_kv = (T + kBlockKV - 1) / kBlockKV;
+  for (int it = 0; it < n_kv; ++it) {
+    const int kv0 = it * kBlockKV;
+    // the last pass refetches its own tile (unused): no conditionals around the registers
+    const int kv_next = min(it + 1, n_kv - 1) * kBlockKV;
+    CFDETR_ATTN_FETCH(kv_next);
+    const bf16_t* cK = sK + (it & 1) * (kBlockKV * LDK);
+    const bf16_t* cV = sVt + (it & 1) * (DH * LDV);
 
     // S^T for the two 32-key sub-tiles
     f32x16 s[2];
@@ -128,7 +138,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
       for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 kf = *reinterpret_cast<const bf16x8*>(&sK[(sub * 32 + l32) * LDK + ks * 16 + g * 8]);
+        bf16x8 kf = *reinterpret_cast<const bf16x8*>(cK + (sub * 32 + l32) * LDK + ks * 16 + g * 8);
         s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[sub], 0, 0, 0);
       }
     }
@@ -181,16 +191,15 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          bf16x8 vf = *reinterpret_cast<const bf16x8*>(
-              &sVt[(i * 32 + l32) * LDV + sub * 32 + t * 16 + g * 8]);
+          bf16x8 vf = *reinterpret_cast<const bf16x8*>(cV + (i * 32 + l32) * LDV + sub * 32 +
+                                                       t * 16 + g * 8);
           acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sub][t], acc_o[i], 0, 0, 0);
         }
+    CFDETR_ATTN_STAGE(sK + ((it + 1) & 1) * (kBlockKV * LDK), sVt + ((it + 1) & 1) * (DH * LDV));
     __syncthreads();
-    if (more) {
-      stage();
-      __syncthreads();
-    }
   }
+#undef CFDETR_ATTN_FETCH
+#undef CFDETR_ATTN_STAGE
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
   const float inv = 1.0f / l_tot;

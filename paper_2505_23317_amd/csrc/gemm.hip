@@ -167,39 +167,60 @@ __device__ __forceinline__ auto prepare_row(const AL& al, int m, bool& valid, in
 }
 
 // ---------------------------------------------------------------------------
-// bf16 MFMA kernel.  256 threads = 4 wavefronts in a 2 x 2 arrangement.
+// bf16 MFMA kernel.  NWM x NWN wavefronts; each owns a (BM/NWM) x (BN/NWN) block
+// of 32x32 MFMA tiles.  LDS holds two K-slabs of A and W (double buffer): while the
+// MFMAs run on one, the next one travels global -> registers -> the other buffer,
+// with a single barrier per slab.  All per-thread staging state lives in fully
+// unrolled register arrays (no closures over them: those end up in scratch memory).
 // ---------------------------------------------------------------------------
-template <int BM, int BN, typename AL, typename EP>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(AL al, const bf16_t* __restrict__ W,
-                                                        int N, int K, EP ep,
-                                                        const int32_t* __restrict__ m_ptr,
-                                                        int m_host, const int32_t* tok_desc) {
-  constexpr int MT = BM / 64, NT = BN / 64;       // 32x32 tiles per wavefront, each way
-  constexpr int A_LOADS = BM / 32, B_LOADS = BN / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t sA[BM * LDS_LD];
-  __shared__ __attribute__((aligned(16))) bf16_t sB[BN * LDS_LD];
-  __shared__ int32_t s_desc[BM];
-  __shared__ int s_any;
+template <int BM, int BN>
+constexpr size_t gemm_lds_bytes() {
+  return (size_t)2 * (BM + BN) * LDS_LD * sizeof(bf16_t) + BM * sizeof(int32_t) + 16;
+}
+
+template <int BM, int BN, int NWM, int NWN, typename AL, typename EP>
+__global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
+    AL al, const bf16_t* __restrict__ W, int N, int K, EP ep, const int32_t* __restrict__ m_ptr,
+    int m_host, const int32_t* tok_desc) {
+  constexpr int THREADS = 64 * NWM * NWN;
+  constexpr int WTM = BM / NWM, WTN = BN / NWN;   // wavefront tile
+  constexpr int MT = WTM / 32, NT = WTN / 32;     // 32x32 tiles per wavefront, each way
+  constexpr int PASS_ROWS = THREADS / 8;          // rows staged per pass (8 x 16 B per row)
+  constexpr int A_LOADS = BM / PASS_ROWS, B_LOADS = BN / PASS_ROWS;
+  static_assert(BM % PASS_ROWS == 0 && BN % PASS_ROWS == 0, "tile / thread mismatch");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);          // [2][BM * LDS_LD]
+  bf16_t* sB = sA + 2 * BM * LDS_LD;                         // [2][BN * LDS_LD]
+  int32_t* s_desc = reinterpret_cast<int32_t*>(sB + 2 * BN * LDS_LD);   // [BM]
+  int32_t* s_any = s_desc + BM;
 
   const int M = m_ptr ? *m_ptr : m_host;
   const int n_blocks = N / BN;
-  const int m0 = (blockIdx.x / n_blocks) * BM;
-  const int n0 = (blockIdx.x % n_blocks) * BN;
-  if (m0 >= M) return;
+  const int total = ((M + BM - 1) / BM) * n_blocks;
+  int pid = blockIdx.x;
+  if (pid >= total) return;
+  // Workgroups are dealt round-robin to the 8 XCDs.  Give each XCD a contiguous run
+  // of tiles so that neighbours in tile order (same rows of A) share one L2.
+  {
+    const int per = total >> 3;
+    if (pid < (per << 3)) pid = (pid & 7) * per + (pid >> 3);
+  }
+  const int m0 = (pid / n_blocks) * BM;
+  const int n0 = (pid % n_blocks) * BN;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / NWN, wn = wave % NWN;
   const int chunk = tid & 7;     // which 8-element piece of a 64-wide slab row
-  const int srow = tid >> 3;     // staged row (plus 32*j)
+  const int srow = tid >> 3;     // staged row (plus PASS_ROWS * j)
 
-  if (tid == 0) s_any = 0;
+  if (tid == 0) *s_any = 0;
   __syncthreads();
   typename AL::Row arow[A_LOADS];
   bool any_valid = false;
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
-    int r = srow + 32 * j;
+    const int r = srow + PASS_ROWS * j;
     bool valid = (m0 + r) < M;
     arow[j] = prepare_row(al, m0 + r, valid, M);
     if (chunk == 0) {
@@ -210,13 +231,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(AL al, const bf16_t* __r
     any_valid |= valid;
   }
   if (IsPatch<AL>::value) {
-    if (any_valid) s_any = 1;
+    if (any_valid) *s_any = 1;
     __syncthreads();
-    if (!s_any) return;  // no token of this level in the tile
+    if (!*s_any) return;  // no token of this level in the tile
   }
   const bf16_t* wrow[B_LOADS];
 #pragma unroll
-  for (int j = 0; j < B_LOADS; ++j) wrow[j] = W + (size_t)(n0 + srow + 32 * j) * K + chunk * 8;
+  for (int j = 0; j < B_LOADS; ++j)
+    wrow[j] = W + (size_t)(n0 + srow + PASS_ROWS * j) * K + chunk * 8;
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -226,32 +248,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(AL al, const bf16_t* __r
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 ra[A_LOADS], rb[B_LOADS];
-  auto fetch = [&](int k0) {
-#pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) ra[j] = al.load8(arow[j], k0 + chunk * 8);
-#pragma unroll
-    for (int j = 0; j < B_LOADS; ++j) rb[j] = *reinterpret_cast<const uint4*>(wrow[j] + k0);
-  };
-  auto stage = [&]() {
-#pragma unroll
-    for (int j = 0; j < A_LOADS; ++j)
-      *reinterpret_cast<uint4*>(&sA[(srow + 32 * j) * LDS_LD + chunk * 8]) = ra[j];
-#pragma unroll
-    for (int j = 0; j < B_LOADS; ++j)
-      *reinterpret_cast<uint4*>(&sB[(srow + 32 * j) * LDS_LD + chunk * 8]) = rb[j];
-  };
-
   const int l32 = lane & 31, g = lane >> 5;
-  const bf16_t* pa = &sA[(wm * (BM / 2) + l32) * LDS_LD + g * 8];
-  const bf16_t* pb = &sB[(wn * (BN / 2) + l32) * LDS_LD + g * 8];
+  const int a_off = (wm * WTM + l32) * LDS_LD + g * 8;
+  const int b_off = (wn * WTN + l32) * LDS_LD + g * 8;
+  const int st_off = srow * LDS_LD + chunk * 8;
 
-  fetch(0);
-  stage();
+  uint4 ra[A_LOADS], rb[B_LOADS];
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j) ra[j] = al.load8(arow[j], chunk * 8);
+#pragma unroll
+  for (int j = 0; j < B_LOADS; ++j) rb[j] = *reinterpret_cast<const uint4*>(wrow[j]);
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j)
+    *reinterpret_cast<uint4*>(sA + st_off + PASS_ROWS * j * LDS_LD) = ra[j];
+#pragma unroll
+  for (int j = 0; j < B_LOADS; ++j)
+    *reinterpret_cast<uint4*>(sB + st_off + PASS_ROWS * j * LDS_LD) = rb[j];
   __syncthreads();
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    const bool more = (k0 + BK) < K;
-    if (more) fetch(k0 + BK);
+
+  const int nk = K / BK;
+  for (int it = 0; it < nk; ++it) {
+    // The last pass fetches its own slab again (unused) so that the loop body is
+    // free of conditionals around the register arrays.
+    const int kn = min(it + 1, nk - 1) * BK;
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j) ra[j] = al.load8(arow[j], kn + chunk * 8);
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j) rb[j] = *reinterpret_cast<const uint4*>(wrow[j] + kn);
+    const bf16_t* pa = sA + (it & 1) * BM * LDS_LD + a_off;
+    const bf16_t* pb = sB + (it & 1) * BN * LDS_LD + b_off;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 fa[MT], fb[NT];
@@ -267,11 +292,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(AL al, const bf16_t* __r
         for (int j = 0; j < NT; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
+    bf16_t* qa = sA + ((it + 1) & 1) * BM * LDS_LD + st_off;
+    bf16_t* qb = sB + ((it + 1) & 1) * BN * LDS_LD + st_off;
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j)
+      *reinterpret_cast<uint4*>(qa + PASS_ROWS * j * LDS_LD) = ra[j];
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j)
+      *reinterpret_cast<uint4*>(qb + PASS_ROWS * j * LDS_LD) = rb[j];
     __syncthreads();
-    if (more) {
-      stage();
-      __syncthreads();
-    }
   }
 
   // C layout of the 32x32 MFMA: lane -> column l32, register r -> row 8*(r/4)+4*g+(r%4).
@@ -279,12 +308,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(AL al, const bf16_t* __r
   for (int i = 0; i < MT; ++i) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int ml = wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+      const int ml = wm * WTM + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
       const int32_t desc = s_desc[ml];
       if (desc < 0) continue;
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
-        const int n = n0 + wn * (BN / 2) + j * 32 + l32;
+        const int n = n0 + wn * WTN + j * 32 + l32;
         ep.store(m0 + ml, n, acc[i][j][r], desc);
       }
     }
@@ -367,29 +396,44 @@ int ilog2(int v) {
   return l;
 }
 
-template <typename AL, typename EP>
-void launch_bf16(const AL& al, const void* W, int N, int K, const EP& ep, const int32_t* m_ptr,
-                 int m_host, int m_capacity, const int32_t* tok_desc, hipStream_t s) {
-  const bf16_t* w = static_cast<const bf16_t*>(W);
-  // Large tiles when they still give every CU work, small tiles otherwise.
-  const long tiles128 = (long)((m_capacity + 127) / 128) * (N / 128);
-  if (N % 128 == 0 && tiles128 >= 512) {
-    dim3 grid(((m_capacity + 127) / 128) * (N / 128));
-    hipLaunchKernelGGL((gemm_bf16_kernel<128, 128, AL, EP>), grid, dim3(256), 0, s, al, w, N, K,
-                       ep, m_ptr, m_host, tok_desc);
-  } else {
-    dim3 grid(((m_capacity + 63) / 64) * (N / 64));
-    hipLaunchKernelGGL((gemm_bf16_kernel<64, 64, AL, EP>), grid, dim3(256), 0, s, al, w, N, K, ep,
-                       m_ptr, m_host, tok_desc);
+template <int BM, int BN, int NWM, int NWN, typename AL, typename EP>
+hipError_t launch_bf16_tile(const AL& al, const bf16_t* w, int N, int K, const EP& ep,
+                            const int32_t* m_ptr, int m_host, int m_capacity,
+                            const int32_t* tok_desc, hipStream_t s) {
+  auto kern = gemm_bf16_kernel<BM, BN, NWM, NWN, AL, EP>;
+  constexpr size_t lds = gemm_lds_bytes<BM, BN>();
+  static bool configured = false;   // per instantiation; the attribute is sticky
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
   }
+  dim3 grid(((m_capacity + BM - 1) / BM) * (N / BN));
+  hipLaunchKernelGGL(kern, grid, dim3(64 * NWM * NWN), lds, s, al, w, N, K, ep, m_ptr, m_host,
+                     tok_desc);
+  return hipSuccess;
 }
 
 template <typename AL, typename EP>
-void launch_f32(const AL& al, const void* W, int N, int K, const EP& ep, const int32_t* m_ptr,
+hipError_t launch_bf16(const AL& al, const void* W, int N, int K, const EP& ep,
+                       const int32_t* m_ptr, int m_host, int m_capacity,
+                       const int32_t* tok_desc, hipStream_t s) {
+  const bf16_t* w = static_cast<const bf16_t*>(W);
+  // Large tiles when they still give every CU work, small tiles otherwise.
+  const long tiles128 = (long)((m_capacity + 127) / 128) * (N / 128);
+  if (N % 128 == 0 && tiles128 >= 256)
+    return launch_bf16_tile<128, 128, 2, 2>(al, w, N, K, ep, m_ptr, m_host, m_capacity, tok_desc, s);
+  return launch_bf16_tile<64, 64, 2, 2>(al, w, N, K, ep, m_ptr, m_host, m_capacity, tok_desc, s);
+}
+
+template <typename AL, typename EP>
+hipError_t launch_f32(const AL& al, const void* W, int N, int K, const EP& ep, const int32_t* m_ptr,
                 int m_host, int m_capacity, const int32_t* tok_desc, hipStream_t s) {
   dim3 grid(((m_capacity + 63) / 64) * (N / 64));
   hipLaunchKernelGGL((gemm_f32_kernel<AL, EP>), grid, dim3(256), 0, s, al,
                      static_cast<const float*>(W), N, K, ep, m_ptr, m_host, tok_desc);
+  return hipSuccess;
 }
 
 }  // namespace
@@ -399,37 +443,40 @@ hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, in
                         hipStream_t s) {
   const int K = 3 * a.patch * a.patch;
   EpiEmbed ep{bias, a.pe_row, a.pe_col, a.out, a.out2, d};
+  hipError_t e = hipSuccess;
   if (a.image_is_bf16) {
     PatchRows<bf16_t> al{static_cast<const bf16_t*>(a.images), a.tok_desc, a.cu_seqlens, a.B,
                          a.level, ilog2(a.patch), a.img_h, a.img_w};
-    if (use_bf16) launch_bf16(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
-    else launch_f32(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
+    if (use_bf16) e = launch_bf16(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
+    else e = launch_f32(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
   } else {
     PatchRows<float> al{static_cast<const float*>(a.images), a.tok_desc, a.cu_seqlens, a.B,
                         a.level, ilog2(a.patch), a.img_h, a.img_w};
-    if (use_bf16) launch_bf16(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
-    else launch_f32(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
+    if (use_bf16) e = launch_bf16(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
+    else e = launch_f32(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
   }
+  if (e != hipSuccess) return e;
   return hipGetLastError();
 }
 
 hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, int K,
                        Epilogue epi, void* out_act, float* resid, bool use_bf16,
                        const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
+  hipError_t e = hipSuccess;
   if (use_bf16) {
     PlainBf16 al{static_cast<const bf16_t*>(A), K};
     bf16_t* o = static_cast<bf16_t*>(out_act);
     switch (epi) {
       case Epilogue::kBias:
-        launch_bf16(al, W, N, K, EpiAct<bf16_t, false>{bias, o, N}, m_ptr, m_host, m_capacity,
+        e = launch_bf16(al, W, N, K, EpiAct<bf16_t, false>{bias, o, N}, m_ptr, m_host, m_capacity,
                     nullptr, s);
         break;
       case Epilogue::kBiasGelu:
-        launch_bf16(al, W, N, K, EpiAct<bf16_t, true>{bias, o, N}, m_ptr, m_host, m_capacity,
+        e = launch_bf16(al, W, N, K, EpiAct<bf16_t, true>{bias, o, N}, m_ptr, m_host, m_capacity,
                     nullptr, s);
         break;
       case Epilogue::kBiasResidual:
-        launch_bf16(al, W, N, K, EpiResidual{bias, resid, N}, m_ptr, m_host, m_capacity, nullptr,
+        e = launch_bf16(al, W, N, K, EpiResidual{bias, resid, N}, m_ptr, m_host, m_capacity, nullptr,
                     s);
         break;
     }
@@ -438,19 +485,20 @@ hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, i
     float* o = static_cast<float*>(out_act);
     switch (epi) {
       case Epilogue::kBias:
-        launch_f32(al, W, N, K, EpiAct<float, false>{bias, o, N}, m_ptr, m_host, m_capacity,
+        e = launch_f32(al, W, N, K, EpiAct<float, false>{bias, o, N}, m_ptr, m_host, m_capacity,
                    nullptr, s);
         break;
       case Epilogue::kBiasGelu:
-        launch_f32(al, W, N, K, EpiAct<float, true>{bias, o, N}, m_ptr, m_host, m_capacity,
+        e = launch_f32(al, W, N, K, EpiAct<float, true>{bias, o, N}, m_ptr, m_host, m_capacity,
                    nullptr, s);
         break;
       case Epilogue::kBiasResidual:
-        launch_f32(al, W, N, K, EpiResidual{bias, resid, N}, m_ptr, m_host, m_capacity, nullptr,
+        e = launch_f32(al, W, N, K, EpiResidual{bias, resid, N}, m_ptr, m_host, m_capacity, nullptr,
                    s);
         break;
     }
   }
+  if (e != hipSuccess) return e;
   return hipGetLastError();
 }
 
