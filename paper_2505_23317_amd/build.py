@@ -12,6 +12,10 @@ LIB = os.path.join(HERE, "libcfdetr.so")
 SOURCES = ["api.hip", "select.hip", "rowwise.hip", "gemm.hip", "attention.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# Per-source extras.  The attention kernel reads every MFMA result back for the
+# softmax, so its accumulators should live in ordinary VGPRs (no AGPR copies); the
+# GEMMs only read theirs in the epilogue and are faster with AGPR accumulators.
+EXTRA_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _hipcc() -> str:
@@ -29,7 +33,7 @@ def build(verbose: bool = True) -> str:
 
     def compile_one(src: str) -> str:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{res.stdout}\n{res.stderr}")

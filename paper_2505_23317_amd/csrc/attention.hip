@@ -159,8 +159,9 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
       for (int r = 0; r < 16; ++r) m_tile = fmaxf(m_tile, s[sub][r]);
     m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, kWave));
     const float m_new = fmaxf(m_run, m_tile);
-    const float alpha = exp2f((m_run - m_new) * scale_log2e);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
     const float mc = m_new * scale_log2e;
+    const bool grew = m_new > m_run;
     m_run = m_new;
     float psum = 0.f;
     bf16x8 pf[2][2];
@@ -171,8 +172,8 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
         uint32_t w[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          float p0 = exp2f(fmaf(s[sub][8 * t + 2 * e], scale_log2e, -mc));
-          float p1 = exp2f(fmaf(s[sub][8 * t + 2 * e + 1], scale_log2e, -mc));
+          float p0 = __builtin_amdgcn_exp2f(fmaf(s[sub][8 * t + 2 * e], scale_log2e, -mc));
+          float p1 = __builtin_amdgcn_exp2f(fmaf(s[sub][8 * t + 2 * e + 1], scale_log2e, -mc));
           psum += p0 + p1;
           w[e] = pack_bf16x2(p0, p1);
         }
@@ -180,10 +181,14 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
         pf[sub][t] = *reinterpret_cast<bf16x8*>(&packed);
       }
     l_run = l_run * alpha + psum;
+    // Rescale the accumulators only when some query of the wavefront saw a new
+    // maximum (alpha is exactly 1 otherwise); after the first tiles that is rare.
+    if (__any(grew)) {
 #pragma unroll
-    for (int i = 0; i < MO; ++i)
+      for (int i = 0; i < MO; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+        for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+    }
     // O^T += V^T . P^T
 #pragma unroll
     for (int i = 0; i < MO; ++i)
