@@ -1,22 +1,27 @@
 // Contractions of the encoder: C[M,N] = A[M,K] . W[N,K]^T with fused epilogues.
 //
 // Both operands have K innermost, which is what the 32x32x16 bf16 MFMA wants: a
-// lane supplies 8 consecutive k of one row.  A workgroup of four wavefronts
-// (2 x 2) owns a BM x BN tile of C; K is walked in slabs of 64 that are staged
-// through LDS (rows padded by 8 elements so that the 16-byte operand reads of
-// eight consecutive rows fall into disjoint banks) while the next slab is
-// already in flight from global memory into registers.
+// lane supplies 8 consecutive k of one row.  The product is computed TRANSPOSED
+// (MFMA A-operand = rows of W, B-operand = rows of the activations), so that in
+// the result layout a lane owns one output ROW (token) and its registers hold runs
+// of four consecutive output columns: the epilogue then works on 8- or 16-byte
+// pieces (bias as float4, residual read-modify-write as float4, bf16 output as
+// 4 packed values) and row validity is a per-lane question.
 //
-// The A operand comes from a loader: either a plain row-major activation matrix
-// or the pixels of a frame gathered patch by patch (patch embedding as an
-// implicit-im2col GEMM).  The epilogue is a functor as well: bias, bias+GELU,
-// bias+residual, or bias+position for the embedding.
-//
-// M may live on the device (the token total after selection): the grid is sized
-// for the capacity and workgroups beyond the real M leave at once.
-//
-// An all-fp32 variant of the same contractions (no matrix cores) serves the
-// check mode.
+// Two bf16 kernels share that orientation:
+//  * gemm_bf16_direct_kernel: activations x weights.  K-slabs of 64 go from global
+//    memory straight into LDS (global_load_lds, 16 bytes per lane, no VGPR round
+//    trip), double-buffered, one barrier per slab.  LDS rows are 128 bytes,
+//    unpadded; the 16-byte chunks of row r are stored at position chunk ^ (r & 7),
+//    which keeps the operand reads of 8 consecutive rows on disjoint banks.  The
+//    swizzle costs nothing: the lane that fills LDS position p of row r simply
+//    fetches logical chunk p ^ (r & 7) from global memory.
+//  * gemm_bf16_gather_kernel: the patch embedding as an implicit-im2col GEMM.  The
+//    A rows are pixels gathered patch by patch (bf16 or fp32 frames), staged through
+//    registers into padded LDS rows.
+// A workgroup -> tile mapping that gives each XCD (own L2) a contiguous run of tiles,
+// M read from device memory (grids are sized for the capacity; surplus workgroups
+// leave at once), and an all-fp32 kernel for the check mode complete the file.
 #include "kernels.h"
 
 namespace cfdetr {
@@ -24,105 +29,60 @@ namespace cfdetr {
 namespace {
 
 constexpr int BK = 64;
-constexpr int LDS_LD = BK + 8;  // bf16 elements per staged row
+constexpr int LDS_LD = BK + 8;  // padded row (elements) of the register-staged kernel
 
 // ---------------------------------------------------------------------------
-// A loaders.  prepare(m, valid) is called once per staged row by the thread that
-// stages it; load8(ctx, k) returns 8 consecutive k as bf16; load1 serves fp32 mode.
+// Epilogues: store4(m, n, v, desc) receives four consecutive columns n..n+3 of row m.
 // ---------------------------------------------------------------------------
-struct PlainBf16 {
-  const bf16_t* A;
-  int lda;
-  struct Row { const bf16_t* p; };
-  __device__ Row prepare(int m) const { return Row{A + (size_t)m * lda}; }
-  __device__ uint4 load8(const Row& r, int k) const {
-    return *reinterpret_cast<const uint4*>(r.p + k);
-  }
-};
-
-struct PlainF32 {
-  const float* A;
-  int lda;
-  struct Row { const float* p; };
-  __device__ Row prepare(int m) const { return Row{A + (size_t)m * lda}; }
-  __device__ float load1(const Row& r, int k) const { return r.p[k]; }
-};
-
-// Pixels of one patch, flattened (channel, row, column).  P is a power of two.
-template <typename TPix>
-struct PatchRows {
-  const TPix* images;
-  const int32_t* tok_desc;
-  const int32_t* cu;
-  int B, level, log2p, img_h, img_w;
-  struct Row { const TPix* p; };
-  // Rows that are not tokens of this level read frame 0's first patch (in bounds,
-  // result discarded).
-  __device__ Row prepare(int m, bool& valid) const {
-    size_t off = 0;
-    if (valid) {
-      int32_t desc = tok_desc[m];
-      valid = tok_level(desc) == level;
-      if (valid) {
-        int frame = frame_of_token(cu, B, m);
-        off = ((size_t)frame * 3 * img_h + ((size_t)tok_row(desc) << log2p)) * img_w +
-              ((size_t)tok_col(desc) << log2p);
-      }
-    }
-    return Row{images + off};
-  }
-  __device__ size_t pix_off(int k) const {
-    int c = k >> (2 * log2p);
-    int r = (k >> log2p) & ((1 << log2p) - 1);
-    int x = k & ((1 << log2p) - 1);
-    return ((size_t)c * img_h + r) * img_w + x;
-  }
-  __device__ uint4 load8(const Row& row, int k) const;
-  __device__ float load1(const Row& row, int k) const;
-};
-template <>
-__device__ uint4 PatchRows<bf16_t>::load8(const Row& row, int k) const {
-  return *reinterpret_cast<const uint4*>(row.p + pix_off(k));
-}
-template <>
-__device__ uint4 PatchRows<float>::load8(const Row& row, int k) const {
-  const float4* p = reinterpret_cast<const float4*>(row.p + pix_off(k));
-  float4 a = p[0], b = p[1];
-  return make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(b.x, b.y),
-                    pack_bf16x2(b.z, b.w));
-}
-template <>
-__device__ float PatchRows<bf16_t>::load1(const Row& row, int k) const {
-  return bf16_to_f32(row.p[pix_off(k)]);
-}
-template <>
-__device__ float PatchRows<float>::load1(const Row& row, int k) const {
-  return row.p[pix_off(k)];
-}
-
-// ---------------------------------------------------------------------------
-// Epilogues.  store(m, n, v, info) with info = the staged row's descriptor.
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ float gelu_exact(float x) {
+__device__ __forceinline__ float gelu_erf(float x) {
   return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
 }
 
-template <typename TAct>
-__device__ __forceinline__ void store_act(TAct* p, float v);
-template <>
-__device__ __forceinline__ void store_act<float>(float* p, float v) { *p = v; }
-template <>
-__device__ __forceinline__ void store_act<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+// x * Phi(x) with erfc from the five-term rational approximation of Abramowitz &
+// Stegun 7.1.26 (absolute error 1.5e-7, far below bf16 resolution).
+__device__ __forceinline__ float gelu_fast(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float half_erfc = 0.5f * p * t * __builtin_amdgcn_exp2f(-1.4426950408889634f * z * z);
+  return x * (x >= 0.f ? 1.0f - half_erfc : half_erfc);
+}
 
 template <typename TAct, bool kGelu>
-struct EpiAct {
+struct EpiAct;
+
+template <bool kGelu>
+struct EpiAct<bf16_t, kGelu> {
   const float* bias;
-  TAct* out;
+  bf16_t* out;
   int ldc;
-  __device__ void store(int m, int n, float v, int32_t) const {
-    v += bias[n];
-    if (kGelu) v = gelu_exact(v);
-    store_act<TAct>(out + (size_t)m * ldc + n, v);
+  __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t) const {
+    const float4 b = *reinterpret_cast<const float4*>(bias + n);
+    float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
+    if (kGelu) {
+      r0 = gelu_fast(r0);
+      r1 = gelu_fast(r1);
+      r2 = gelu_fast(r2);
+      r3 = gelu_fast(r3);
+    }
+    uint2 w = make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+    *reinterpret_cast<uint2*>(out + (size_t)m * ldc + n) = w;
+  }
+};
+
+template <bool kGelu>
+struct EpiAct<float, kGelu> {
+  const float* bias;
+  float* out;
+  int ldc;
+  __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t) const {
+    const float4 b = *reinterpret_cast<const float4*>(bias + n);
+    float4 r = make_float4(v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w);
+    if (kGelu) r = make_float4(gelu_erf(r.x), gelu_erf(r.y), gelu_erf(r.z), gelu_erf(r.w));
+    *reinterpret_cast<float4*>(out + (size_t)m * ldc + n) = r;
   }
 };
 
@@ -130,9 +90,15 @@ struct EpiResidual {
   const float* bias;
   float* resid;
   int ldc;
-  __device__ void store(int m, int n, float v, int32_t) const {
-    float* p = resid + (size_t)m * ldc + n;
-    *p = *p + (v + bias[n]);
+  __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t) const {
+    const float4 b = *reinterpret_cast<const float4*>(bias + n);
+    float4* p = reinterpret_cast<float4*>(resid + (size_t)m * ldc + n);
+    float4 x = *p;
+    x.x += v[0] + b.x;
+    x.y += v[1] + b.y;
+    x.z += v[2] + b.z;
+    x.w += v[3] + b.w;
+    *p = x;
   }
 };
 
@@ -143,98 +109,247 @@ struct EpiEmbed {
   float* out;
   float* out2;
   int d;
-  __device__ void store(int m, int n, float v, int32_t desc) const {
-    const int D = d >> 1;
-    float pe = (n < D) ? pe_row[tok_row(desc) * D + n] : pe_col[tok_col(desc) * D + (n - D)];
-    v += bias[n] + pe;
-    out[(size_t)m * d + n] = v;
-    if (out2) out2[(size_t)m * d + n] = v;
+  __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t desc) const {
+    const int D = d >> 1;  // a multiple of 32: a run of four never straddles the halves
+    const float* pe = (n < D) ? pe_row + tok_row(desc) * D + n : pe_col + tok_col(desc) * D + (n - D);
+    const float4 e = *reinterpret_cast<const float4*>(pe);
+    const float4 b = *reinterpret_cast<const float4*>(bias + n);
+    const float4 r = make_float4(v[0] + b.x + e.x, v[1] + b.y + e.y, v[2] + b.z + e.z,
+                                 v[3] + b.w + e.w);
+    *reinterpret_cast<float4*>(out + (size_t)m * d + n) = r;
+    if (out2) *reinterpret_cast<float4*>(out2 + (size_t)m * d + n) = r;
   }
 };
 
-template <typename AL>
-struct IsPatch { static constexpr bool value = false; };
-template <typename T>
-struct IsPatch<PatchRows<T>> { static constexpr bool value = true; };
+// Maps a workgroup id to a tile id such that each of the 8 XCDs (workgroups are dealt
+// to them round-robin) works on a contiguous run of tiles and its L2 sees the same
+// activation rows again and again.
+__device__ __forceinline__ int xcd_tile_order(int pid, int total) {
+  const int per = total >> 3;
+  return (pid < (per << 3)) ? (pid & 7) * per + (pid >> 3) : pid;
+}
 
-template <typename AL>
-__device__ __forceinline__ auto prepare_row(const AL& al, int m, bool& valid, int M) {
-  if constexpr (IsPatch<AL>::value) {
-    return al.prepare(m, valid);
-  } else {
-    return al.prepare(valid ? m : (M - 1));
+// ---------------------------------------------------------------------------
+// Activations x weights, direct global -> LDS.
+// ---------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
+
+template <int BM, int BN, int NWM, int NWN, typename EP>
+__global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int N, int K, EP ep,
+    const int32_t* __restrict__ m_ptr, int m_host) {
+  constexpr int NW = NWM * NWN;
+  constexpr int WTM = BM / NWM, WTN = BN / NWN;      // wavefront tile
+  constexpr int MT = WTM / 32, NT = WTN / 32;        // 32x32 MFMA tiles, each way
+  constexpr int A_INST = BM / (8 * NW), B_INST = BN / (8 * NW);  // 8 rows per wave instruction
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile / wavefront mismatch");
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_direct[];
+  unsigned char* sA = smem_direct;                   // [2][BM * 128]
+  unsigned char* sB = smem_direct + 2 * BM * 128;    // [2][BN * 128]
+
+  const int M = m_ptr ? *m_ptr : m_host;
+  const int n_blocks = N / BN;
+  const int total = ((M + BM - 1) / BM) * n_blocks;
+  if ((int)blockIdx.x >= total) return;
+  const int pid = xcd_tile_order(blockIdx.x, total);
+  const int m0 = (pid / n_blocks) * BM;
+  const int n0 = (pid % n_blocks) * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / NWN, wn = wave % NWN;
+  // Loader role: a wave instruction fills 8 consecutive LDS rows (1 KB).  Lane ->
+  // (row lane/8 of the group, LDS chunk position lane%8) and fetches the logical chunk
+  // position ^ row (groups start at multiples of 8, so row & 7 == lane / 8).
+  const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;
+  const bf16_t* ag[A_INST];
+  const bf16_t* wg[B_INST];
+#pragma unroll
+  for (int j = 0; j < A_INST; ++j) {
+    const int r = min(m0 + (wave * A_INST + j) * 8 + lrow, M - 1);   // rows past M: any valid row
+    ag[j] = A + (size_t)r * K + lchunk * 8;
+  }
+#pragma unroll
+  for (int j = 0; j < B_INST; ++j)
+    wg[j] = W + (size_t)(n0 + (wave * B_INST + j) * 8 + lrow) * K + lchunk * 8;
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int l32 = lane & 31, g = lane >> 5;
+  const int nk = K / BK;
+
+#define CFDETR_ISSUE_SLAB(k0_, buf_)                                                          \
+  do {                                                                                        \
+    _Pragma("unroll") for (int j = 0; j < A_INST; ++j) __builtin_amdgcn_global_load_lds(      \
+        (global_void_ptr)(ag[j] + (k0_)),                                                     \
+        (lds_void_ptr)(sA + (buf_) * (BM * 128) + (wave * A_INST + j) * 1024), 16, 0, 0);     \
+    _Pragma("unroll") for (int j = 0; j < B_INST; ++j) __builtin_amdgcn_global_load_lds(      \
+        (global_void_ptr)(wg[j] + (k0_)),                                                     \
+        (lds_void_ptr)(sB + (buf_) * (BN * 128) + (wave * B_INST + j) * 1024), 16, 0, 0);     \
+  } while (0)
+
+  CFDETR_ISSUE_SLAB(0, 0);
+  for (int it = 0; it < nk; ++it) {
+    // vmcnt(0): this wavefront's LDS writes of slab `it` have landed; the barrier then
+    // makes every wavefront's part visible and retires all reads of the other buffer.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (it + 1 < nk) CFDETR_ISSUE_SLAB((it + 1) * BK, (it + 1) & 1);
+    const unsigned char* pa = sA + (it & 1) * (BM * 128);
+    const unsigned char* pb = sB + (it & 1) * (BN * 128);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const int c = 2 * ks + g;  // logical 16-byte chunk of this lane's 8 k
+      bf16x8 fa[MT], fb[NT];
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        const int r = wm * WTM + i * 32 + l32;
+        fa[i] = *reinterpret_cast<const bf16x8*>(pa + r * 128 + ((c ^ (r & 7)) << 4));
+      }
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int r = wn * WTN + j * 32 + l32;
+        fb[j] = *reinterpret_cast<const bf16x8*>(pb + r * 128 + ((c ^ (r & 7)) << 4));
+      }
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+  }
+#undef CFDETR_ISSUE_SLAB
+
+  // Result layout (transposed product): lane -> row m = l32, register r -> column
+  // 8*(r/4) + 4*g + (r%4).
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const int m = m0 + wm * WTM + i * 32 + l32;
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn * WTN + j * 32 + 8 * q + 4 * g;
+        const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                            acc[i][j][4 * q + 3]};
+        ep.store4(m, n, v, 0);
+      }
+    }
   }
 }
 
 // ---------------------------------------------------------------------------
-// bf16 MFMA kernel.  NWM x NWN wavefronts; each owns a (BM/NWM) x (BN/NWN) block
-// of 32x32 MFMA tiles.  LDS holds two K-slabs of A and W (double buffer): while the
-// MFMAs run on one, the next one travels global -> registers -> the other buffer,
-// with a single barrier per slab.  All per-thread staging state lives in fully
-// unrolled register arrays (no closures over them: those end up in scratch memory).
+// Patch embedding: rows of A are gathered pixels.
 // ---------------------------------------------------------------------------
+// Pixels of one patch, flattened (channel, row, column).  P is a power of two.
+template <typename TPix>
+struct PatchRows {
+  const TPix* images;
+  const int32_t* tok_desc;
+  const int32_t* cu;
+  int B, level, log2p, img_h, img_w;
+  // Pixel offset of the patch of token m, or 0 (frame 0's first patch: in bounds,
+  // result discarded) with valid = false when m is not a token of this level.
+  __device__ size_t prepare(int m, bool& valid) const {
+    size_t off = 0;
+    if (valid) {
+      const int32_t desc = tok_desc[m];
+      valid = tok_level(desc) == level;
+      if (valid) {
+        const int frame = frame_of_token(cu, B, m);
+        off = ((size_t)frame * 3 * img_h + ((size_t)tok_row(desc) << log2p)) * img_w +
+              ((size_t)tok_col(desc) << log2p);
+      }
+    }
+    return off;
+  }
+  __device__ size_t pix_off(int k) const {
+    const int c = k >> (2 * log2p);
+    const int r = (k >> log2p) & ((1 << log2p) - 1);
+    const int x = k & ((1 << log2p) - 1);
+    return ((size_t)c * img_h + r) * img_w + x;
+  }
+  __device__ uint4 load8(size_t row_off, int k) const;
+  __device__ float load1(size_t row_off, int k) const;
+};
+template <>
+__device__ uint4 PatchRows<bf16_t>::load8(size_t row_off, int k) const {
+  return *reinterpret_cast<const uint4*>(images + row_off + pix_off(k));
+}
+template <>
+__device__ uint4 PatchRows<float>::load8(size_t row_off, int k) const {
+  const float4* p = reinterpret_cast<const float4*>(images + row_off + pix_off(k));
+  const float4 a = p[0], b = p[1];
+  return make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(b.x, b.y),
+                    pack_bf16x2(b.z, b.w));
+}
+template <>
+__device__ float PatchRows<bf16_t>::load1(size_t row_off, int k) const {
+  return bf16_to_f32(images[row_off + pix_off(k)]);
+}
+template <>
+__device__ float PatchRows<float>::load1(size_t row_off, int k) const {
+  return images[row_off + pix_off(k)];
+}
+
 template <int BM, int BN>
-constexpr size_t gemm_lds_bytes() {
+constexpr size_t gather_lds_bytes() {
   return (size_t)2 * (BM + BN) * LDS_LD * sizeof(bf16_t) + BM * sizeof(int32_t) + 16;
 }
 
-template <int BM, int BN, int NWM, int NWN, typename AL, typename EP>
-__global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
-    AL al, const bf16_t* __restrict__ W, int N, int K, EP ep, const int32_t* __restrict__ m_ptr,
-    int m_host, const int32_t* tok_desc) {
+// Register-staged, double-buffered (global -> registers -> padded LDS rows, one
+// barrier per slab).  The staging registers are plain unrolled arrays; closures over
+// them would push them into scratch memory.
+template <int BM, int BN, int NWM, int NWN, typename TPix>
+__global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_gather_kernel(
+    PatchRows<TPix> al, const bf16_t* __restrict__ W, int N, int K, EpiEmbed ep,
+    const int32_t* __restrict__ m_ptr, int m_host) {
   constexpr int THREADS = 64 * NWM * NWN;
-  constexpr int WTM = BM / NWM, WTN = BN / NWN;   // wavefront tile
-  constexpr int MT = WTM / 32, NT = WTN / 32;     // 32x32 tiles per wavefront, each way
-  constexpr int PASS_ROWS = THREADS / 8;          // rows staged per pass (8 x 16 B per row)
+  constexpr int WTM = BM / NWM, WTN = BN / NWN;
+  constexpr int MT = WTM / 32, NT = WTN / 32;
+  constexpr int PASS_ROWS = THREADS / 8;  // rows staged per pass (8 x 16 B per row)
   constexpr int A_LOADS = BM / PASS_ROWS, B_LOADS = BN / PASS_ROWS;
   static_assert(BM % PASS_ROWS == 0 && BN % PASS_ROWS == 0, "tile / thread mismatch");
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);          // [2][BM * LDS_LD]
-  bf16_t* sB = sA + 2 * BM * LDS_LD;                         // [2][BN * LDS_LD]
-  int32_t* s_desc = reinterpret_cast<int32_t*>(sB + 2 * BN * LDS_LD);   // [BM]
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_gather[];
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_gather);                 // [2][BM * LDS_LD]
+  bf16_t* sB = sA + 2 * BM * LDS_LD;                                   // [2][BN * LDS_LD]
+  int32_t* s_desc = reinterpret_cast<int32_t*>(sB + 2 * BN * LDS_LD);  // [BM], -1 = not ours
   int32_t* s_any = s_desc + BM;
 
   const int M = m_ptr ? *m_ptr : m_host;
   const int n_blocks = N / BN;
   const int total = ((M + BM - 1) / BM) * n_blocks;
-  int pid = blockIdx.x;
-  if (pid >= total) return;
-  // Workgroups are dealt round-robin to the 8 XCDs.  Give each XCD a contiguous run
-  // of tiles so that neighbours in tile order (same rows of A) share one L2.
-  {
-    const int per = total >> 3;
-    if (pid < (per << 3)) pid = (pid & 7) * per + (pid >> 3);
-  }
+  if ((int)blockIdx.x >= total) return;
+  const int pid = xcd_tile_order(blockIdx.x, total);
   const int m0 = (pid / n_blocks) * BM;
   const int n0 = (pid % n_blocks) * BN;
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / NWN, wn = wave % NWN;
-  const int chunk = tid & 7;     // which 8-element piece of a 64-wide slab row
-  const int srow = tid >> 3;     // staged row (plus PASS_ROWS * j)
+  const int chunk = tid & 7, srow = tid >> 3;
 
   if (tid == 0) *s_any = 0;
   __syncthreads();
-  typename AL::Row arow[A_LOADS];
+  size_t arow[A_LOADS];
   bool any_valid = false;
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
     const int r = srow + PASS_ROWS * j;
     bool valid = (m0 + r) < M;
-    arow[j] = prepare_row(al, m0 + r, valid, M);
-    if (chunk == 0) {
-      int32_t desc = -1;
-      if (valid) desc = IsPatch<AL>::value ? tok_desc[m0 + r] : 0;
-      s_desc[r] = desc;
-    }
+    arow[j] = al.prepare(m0 + r, valid);
+    if (chunk == 0) s_desc[r] = valid ? al.tok_desc[m0 + r] : -1;
     any_valid |= valid;
   }
-  if (IsPatch<AL>::value) {
-    if (any_valid) *s_any = 1;
-    __syncthreads();
-    if (!*s_any) return;  // no token of this level in the tile
-  }
+  if (any_valid) *s_any = 1;
+  __syncthreads();
+  if (!*s_any) return;  // no token of this level in the tile
   const bf16_t* wrow[B_LOADS];
 #pragma unroll
   for (int j = 0; j < B_LOADS; ++j)
@@ -290,7 +405,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
       for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
     }
     bf16_t* qa = sA + ((it + 1) & 1) * BM * LDS_LD + st_off;
     bf16_t* qb = sB + ((it + 1) & 1) * BN * LDS_LD + st_off;
@@ -303,18 +418,19 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
     __syncthreads();
   }
 
-  // C layout of the 32x32 MFMA: lane -> column l32, register r -> row 8*(r/4)+4*g+(r%4).
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
+    const int ml = wm * WTM + i * 32 + l32;
+    const int32_t desc = s_desc[ml];
+    if (desc < 0) continue;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int ml = wm * WTM + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-      const int32_t desc = s_desc[ml];
-      if (desc < 0) continue;
+    for (int j = 0; j < NT; ++j) {
 #pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const int n = n0 + wn * WTN + j * 32 + l32;
-        ep.store(m0 + ml, n, acc[i][j][r], desc);
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn * WTN + j * 32 + 8 * q + 4 * g;
+        const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                            acc[i][j][4 * q + 3]};
+        ep.store4(m0 + ml, n, v, desc);
       }
     }
   }
@@ -323,6 +439,18 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_kernel(
 // ---------------------------------------------------------------------------
 // fp32 check-mode kernel: 64x64 tile, 256 threads, 4x4 outputs per thread.
 // ---------------------------------------------------------------------------
+struct PlainF32 {
+  const float* A;
+  int lda;
+  __device__ size_t prepare(int m, bool&) const { return (size_t)m * lda; }
+  __device__ float load1(size_t row_off, int k) const { return A[row_off + k]; }
+};
+
+template <typename AL>
+struct IsPatch { static constexpr bool value = false; };
+template <typename T>
+struct IsPatch<PatchRows<T>> { static constexpr bool value = true; };
+
 template <typename AL, typename EP>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(AL al, const float* __restrict__ W, int N,
                                                        int K, EP ep,
@@ -339,22 +467,20 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(AL al, const float* __res
   const int n0 = (blockIdx.x % n_blocks) * T;
   if (m0 >= M) return;
   const int tid = threadIdx.x;
-  const int lrow = tid >> 2;        // staged row 0..63
-  const int lk = (tid & 3) * 4;     // 4 consecutive k of a 16-wide slab
+  const int lrow = tid >> 2;     // staged row 0..63
+  const int lk = (tid & 3) * 4;  // 4 consecutive k of a 16-wide slab
   if (tid == 0) s_any = 0;
   __syncthreads();
   bool valid = (m0 + lrow) < M;
-  typename AL::Row arow = prepare_row(al, m0 + lrow, valid, M);
+  const size_t arow = al.prepare(valid ? m0 + lrow : M - 1, valid);
   if ((tid & 3) == 0) {
     int32_t desc = -1;
     if (valid) desc = IsPatch<AL>::value ? tok_desc[m0 + lrow] : 0;
     s_desc[lrow] = desc;
   }
-  if (IsPatch<AL>::value) {
-    if (valid) s_any = 1;
-    __syncthreads();
-    if (!s_any) return;
-  }
+  if (valid) s_any = 1;
+  __syncthreads();
+  if (!s_any) return;
   const float* wrow = W + (size_t)(n0 + lrow) * K;
   const int ty = tid >> 4, tx = tid & 15;
   float acc[4][4] = {};
@@ -385,8 +511,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(AL al, const float* __res
     const int ml = ty * 4 + p;
     const int32_t desc = s_desc[ml];
     if (desc < 0) continue;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) ep.store(m0 + ml, n0 + tx * 4 + q, acc[p][q], desc);
+    ep.store4(m0 + ml, n0 + tx * 4, acc[p], desc);
   }
 }
 
@@ -396,40 +521,73 @@ int ilog2(int v) {
   return l;
 }
 
-template <int BM, int BN, int NWM, int NWN, typename AL, typename EP>
-hipError_t launch_bf16_tile(const AL& al, const bf16_t* w, int N, int K, const EP& ep,
-                            const int32_t* m_ptr, int m_host, int m_capacity,
-                            const int32_t* tok_desc, hipStream_t s) {
-  auto kern = gemm_bf16_kernel<BM, BN, NWM, NWN, AL, EP>;
-  constexpr size_t lds = gemm_lds_bytes<BM, BN>();
-  static bool configured = false;   // per instantiation; the attribute is sticky
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+template <typename Kern>
+hipError_t allow_lds(Kern kern, size_t bytes, bool* configured) {
+  if (*configured) return hipSuccess;   // the attribute is sticky
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) *configured = true;
+  return e;
+}
+
+template <int BM, int BN, int NWM, int NWN, typename EP>
+hipError_t launch_direct_tile(const bf16_t* A, const bf16_t* w, int N, int K, const EP& ep,
+                              const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
+  auto kern = gemm_bf16_direct_kernel<BM, BN, NWM, NWN, EP>;
+  constexpr size_t lds = (size_t)2 * (BM + BN) * 128;
+  static bool configured = false;
+  hipError_t e = allow_lds(kern, lds, &configured);
+  if (e != hipSuccess) return e;
   dim3 grid(((m_capacity + BM - 1) / BM) * (N / BN));
-  hipLaunchKernelGGL(kern, grid, dim3(64 * NWM * NWN), lds, s, al, w, N, K, ep, m_ptr, m_host,
-                     tok_desc);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * NWM * NWN), lds, s, A, w, N, K, ep, m_ptr, m_host);
   return hipSuccess;
 }
 
-template <typename AL, typename EP>
-hipError_t launch_bf16(const AL& al, const void* W, int N, int K, const EP& ep,
-                       const int32_t* m_ptr, int m_host, int m_capacity,
-                       const int32_t* tok_desc, hipStream_t s) {
+// Tile choice by problem size: 256x256 (8 wavefronts, 128x64 each) for wide outputs
+// over many rows, 128x128 (4 wavefronts, 64x64 each) while that still yields a
+// workgroup per CU, else 64x64.
+template <typename EP>
+hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& ep,
+                         const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
+  const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* w = static_cast<const bf16_t*>(W);
-  // Large tiles when they still give every CU work, small tiles otherwise.
+  const long tiles128 = (long)((m_capacity + 127) / 128) * (N / 128);
+  if (N % 256 == 0 && N >= 2048 && m_capacity >= 16384)
+    return launch_direct_tile<256, 256, 2, 4>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+  if (N % 128 == 0 && tiles128 >= 256)
+    return launch_direct_tile<128, 128, 2, 2>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+  return launch_direct_tile<64, 64, 2, 2>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+}
+
+template <int BM, int BN, typename TPix>
+hipError_t launch_gather_tile(const PatchRows<TPix>& al, const bf16_t* w, int N, int K,
+                              const EpiEmbed& ep, const int32_t* m_ptr, int m_host,
+                              int m_capacity, hipStream_t s) {
+  auto kern = gemm_bf16_gather_kernel<BM, BN, 2, 2, TPix>;
+  constexpr size_t lds = gather_lds_bytes<BM, BN>();
+  static bool configured = false;
+  hipError_t e = allow_lds(kern, lds, &configured);
+  if (e != hipSuccess) return e;
+  dim3 grid(((m_capacity + BM - 1) / BM) * (N / BN));
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, al, w, N, K, ep, m_ptr, m_host);
+  return hipSuccess;
+}
+
+template <typename TPix>
+hipError_t launch_gather(const PatchRows<TPix>& al, const void* W, int N, int K,
+                         const EpiEmbed& ep, const int32_t* m_ptr, int m_host, int m_capacity,
+                         hipStream_t s) {
+  const bf16_t* w = static_cast<const bf16_t*>(W);
   const long tiles128 = (long)((m_capacity + 127) / 128) * (N / 128);
   if (N % 128 == 0 && tiles128 >= 256)
-    return launch_bf16_tile<128, 128, 2, 2>(al, w, N, K, ep, m_ptr, m_host, m_capacity, tok_desc, s);
-  return launch_bf16_tile<64, 64, 2, 2>(al, w, N, K, ep, m_ptr, m_host, m_capacity, tok_desc, s);
+    return launch_gather_tile<128, 128>(al, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+  return launch_gather_tile<64, 64>(al, w, N, K, ep, m_ptr, m_host, m_capacity, s);
 }
 
 template <typename AL, typename EP>
-hipError_t launch_f32(const AL& al, const void* W, int N, int K, const EP& ep, const int32_t* m_ptr,
-                int m_host, int m_capacity, const int32_t* tok_desc, hipStream_t s) {
+hipError_t launch_f32(const AL& al, const void* W, int N, int K, const EP& ep,
+                      const int32_t* m_ptr, int m_host, int m_capacity,
+                      const int32_t* tok_desc, hipStream_t s) {
   dim3 grid(((m_capacity + 63) / 64) * (N / 64));
   hipLaunchKernelGGL((gemm_f32_kernel<AL, EP>), grid, dim3(256), 0, s, al,
                      static_cast<const float*>(W), N, K, ep, m_ptr, m_host, tok_desc);
@@ -447,12 +605,12 @@ hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, in
   if (a.image_is_bf16) {
     PatchRows<bf16_t> al{static_cast<const bf16_t*>(a.images), a.tok_desc, a.cu_seqlens, a.B,
                          a.level, ilog2(a.patch), a.img_h, a.img_w};
-    if (use_bf16) e = launch_bf16(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
+    if (use_bf16) e = launch_gather(al, w, d, K, ep, m_ptr, m_host, m_capacity, s);
     else e = launch_f32(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
   } else {
     PatchRows<float> al{static_cast<const float*>(a.images), a.tok_desc, a.cu_seqlens, a.B,
                         a.level, ilog2(a.patch), a.img_h, a.img_w};
-    if (use_bf16) e = launch_bf16(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
+    if (use_bf16) e = launch_gather(al, w, d, K, ep, m_ptr, m_host, m_capacity, s);
     else e = launch_f32(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
   }
   if (e != hipSuccess) return e;
@@ -464,20 +622,18 @@ hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, i
                        const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
   hipError_t e = hipSuccess;
   if (use_bf16) {
-    PlainBf16 al{static_cast<const bf16_t*>(A), K};
     bf16_t* o = static_cast<bf16_t*>(out_act);
     switch (epi) {
       case Epilogue::kBias:
-        e = launch_bf16(al, W, N, K, EpiAct<bf16_t, false>{bias, o, N}, m_ptr, m_host, m_capacity,
-                    nullptr, s);
+        e = launch_direct(A, W, N, K, EpiAct<bf16_t, false>{bias, o, N}, m_ptr, m_host,
+                          m_capacity, s);
         break;
       case Epilogue::kBiasGelu:
-        e = launch_bf16(al, W, N, K, EpiAct<bf16_t, true>{bias, o, N}, m_ptr, m_host, m_capacity,
-                    nullptr, s);
+        e = launch_direct(A, W, N, K, EpiAct<bf16_t, true>{bias, o, N}, m_ptr, m_host,
+                          m_capacity, s);
         break;
       case Epilogue::kBiasResidual:
-        e = launch_bf16(al, W, N, K, EpiResidual{bias, resid, N}, m_ptr, m_host, m_capacity, nullptr,
-                    s);
+        e = launch_direct(A, W, N, K, EpiResidual{bias, resid, N}, m_ptr, m_host, m_capacity, s);
         break;
     }
   } else {
@@ -486,15 +642,15 @@ hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, i
     switch (epi) {
       case Epilogue::kBias:
         e = launch_f32(al, W, N, K, EpiAct<float, false>{bias, o, N}, m_ptr, m_host, m_capacity,
-                   nullptr, s);
+                       nullptr, s);
         break;
       case Epilogue::kBiasGelu:
         e = launch_f32(al, W, N, K, EpiAct<float, true>{bias, o, N}, m_ptr, m_host, m_capacity,
-                   nullptr, s);
+                       nullptr, s);
         break;
       case Epilogue::kBiasResidual:
         e = launch_f32(al, W, N, K, EpiResidual{bias, resid, N}, m_ptr, m_host, m_capacity, nullptr,
-                   s);
+                       s);
         break;
     }
   }
