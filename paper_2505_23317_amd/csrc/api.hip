@@ -30,6 +30,9 @@ struct cfdetr_ctx {
   void* qkv = nullptr;     // [Tm, 3d]
   void* o = nullptr;       // attention output [Tm, d]
   void* h = nullptr;       // FFN hidden [Tm, F]
+  void* vt = nullptr;      // bf16 mode: V feature-major [d, vt_ld], frames padded to 64
+  int vt_ld = 0;
+  int32_t* pcu = nullptr;  // padded frame offsets into vt
   float* x0 = nullptr;     // coarse-token cache of cfdetr_multilevel_batch [Bmax*N0, d]
   float* pe_row[kMaxLevels] = {};
   float* pe_col[kMaxLevels] = {};
@@ -169,8 +172,8 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, const int32
   const size_t es = ctx->esz;
   const float eps = c.ln_eps;
   const bool bf = ctx->bf16;
-  CF_LAUNCH(CFDETR_K_PLAN,
-            launch_plan(cu, B, ctx->block_q, ctx->tiles, ctx->n_tiles, ctx->tile_cap, s));
+  CF_LAUNCH(CFDETR_K_PLAN, launch_plan(cu, B, ctx->block_q, ctx->tiles, ctx->n_tiles,
+                                       ctx->tile_cap, ctx->pcu, s));
   for (int l = 0; l < c.n_layers; ++l) {
     const char* wqkv = static_cast<const char*>(w.w_qkv) + (size_t)l * 3 * d * d * es;
     const char* wo = static_cast<const char*>(w.w_o) + (size_t)l * d * d * es;
@@ -178,11 +181,17 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, const int32
     const char* w2 = static_cast<const char*>(w.w_ff2) + (size_t)l * d * F * es;
     CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->x, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d,
                                             ctx->a, bf, d, eps, m_ptr, m_host, m_cap, s));
-    CF_LAUNCH(CFDETR_K_QKV, launch_gemm(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, 3 * d, d,
-                                        Epilogue::kBias, ctx->qkv, nullptr, bf, m_ptr, m_host,
-                                        m_cap, s));
-    CF_LAUNCH(CFDETR_K_ATTN, launch_attention(ctx->qkv, ctx->o, cu, B, d, c.n_heads, ctx->tiles,
-                                              ctx->n_tiles, ctx->tile_cap, ctx->block_q, bf, s));
+    if (bf)
+      CF_LAUNCH(CFDETR_K_QKV,
+                launch_gemm_qkv(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, d, ctx->qkv, ctx->vt,
+                                ctx->vt_ld, cu, ctx->pcu, B, m_ptr, m_host, m_cap, s));
+    else
+      CF_LAUNCH(CFDETR_K_QKV, launch_gemm(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, 3 * d, d,
+                                          Epilogue::kBias, ctx->qkv, nullptr, bf, m_ptr, m_host,
+                                          m_cap, s));
+    CF_LAUNCH(CFDETR_K_ATTN,
+              launch_attention(ctx->qkv, ctx->vt, ctx->vt_ld, ctx->o, cu, ctx->pcu, d, c.n_heads,
+                               ctx->tiles, ctx->n_tiles, ctx->tile_cap, ctx->block_q, bf, s));
     CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->o, wo, w.b_o + (size_t)l * d, d, d,
                                         Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr,
                                         m_host, m_cap, s));
@@ -283,7 +292,8 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->n0 = p.rows[0] * p.cols[0];
   c->nonfinest = 0;
   for (int l = 0; l + 1 < cfg->n_levels; ++l) c->nonfinest += p.rows[l] * p.cols[l];
-  c->block_q = attention_block_q(cfg->d_model / cfg->n_heads, c->bf16);
+  c->block_q = attention_block_q(cfg->d_model / cfg->n_heads, c->bf16,
+                                 cfg->max_tokens_total / cfg->max_batch);
   c->tile_cap = (cfg->max_tokens_total + c->block_q - 1) / c->block_q + cfg->max_batch;
 
   const uint64_t Tm = cfg->max_tokens_total, d = cfg->d_model, F = cfg->d_ffn;
@@ -292,6 +302,9 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   const uint64_t o_x = cv.take(Tm * d * 4), o_a = cv.take(Tm * d * c->esz);
   const uint64_t o_qkv = cv.take(Tm * 3 * d * c->esz), o_o = cv.take(Tm * d * c->esz);
   const uint64_t o_h = cv.take(Tm * F * c->esz), o_x0 = cv.take(Bm * c->n0 * d * 4);
+  c->vt_ld = (int)((Tm + 64 * Bm + 63) & ~uint64_t(63));
+  const uint64_t vt_bytes = c->bf16 ? d * (uint64_t)c->vt_ld * 2 : 256;
+  const uint64_t o_vt = cv.take(vt_bytes), o_pcu = cv.take((Bm + 1) * 4);
   uint64_t o_per[kMaxLevels], o_pec[kMaxLevels];
   for (int l = 0; l < cfg->n_levels; ++l) {
     o_per[l] = cv.take((uint64_t)p.rows[l] * D * 4);
@@ -315,6 +328,8 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->o = base + o_o;
   c->h = base + o_h;
   c->x0 = reinterpret_cast<float*>(base + o_x0);
+  c->vt = base + o_vt;
+  c->pcu = reinterpret_cast<int32_t*>(base + o_pcu);
   for (int l = 0; l < cfg->n_levels; ++l) {
     c->pe_row[l] = reinterpret_cast<float*>(base + o_per[l]);
     c->pe_col[l] = reinterpret_cast<float*>(base + o_pec[l]);
@@ -338,6 +353,10 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   if (e == hipSuccess) e = hipMemcpy(c->coarse_cu, cu.data(), cu.size() * 4, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemset(c->split[0], 0, kMaxBatch * kMaxLevels * 4);
   if (e == hipSuccess) e = hipMemset(c->split[1], 0, kMaxBatch * kMaxLevels * 4);
+  // Padding positions of vt are read (with probability 0) by the attention kernel:
+  // they must hold finite numbers.  Everything ever written there is finite, so
+  // zeroing once is enough.
+  if (e == hipSuccess) e = hipMemset(c->vt, 0, vt_bytes);
   if (e == hipSuccess) e = hipMemset(c->n_tiles, 0, 4);
   if (e == hipSuccess) e = hipMemset(c->err_flag, 0, 4);
   for (int l = 0; l < cfg->n_levels && e == hipSuccess; ++l)

@@ -59,6 +59,7 @@ struct EpiAct<bf16_t, kGelu> {
   const float* bias;
   bf16_t* out;
   int ldc;
+  __device__ __forceinline__ int32_t row_info(int) const { return 0; }
   __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t) const {
     const float4 b = *reinterpret_cast<const float4*>(bias + n);
     float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
@@ -90,6 +91,7 @@ struct EpiResidual {
   const float* bias;
   float* resid;
   int ldc;
+  __device__ __forceinline__ int32_t row_info(int) const { return 0; }
   __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t) const {
     const float4 b = *reinterpret_cast<const float4*>(bias + n);
     float4* p = reinterpret_cast<float4*>(resid + (size_t)m * ldc + n);
@@ -99,6 +101,39 @@ struct EpiResidual {
     x.z += v[2] + b.z;
     x.w += v[3] + b.w;
     *p = x;
+  }
+};
+
+// Query/key/value projection: q and k columns (n < 2d) go token-major to qk [M, 3d];
+// v columns go feature-major to vt [d, vt_ld], token m of frame f at position
+// pcu[f] + (m - cu[f]).  row_info(m) is that position.
+struct EpiQkv {
+  const float* bias;
+  bf16_t* qk;
+  int ldc;    // 3d
+  int d2;     // 2d: first v column
+  bf16_t* vt;
+  int vt_ld;
+  const int32_t* cu;
+  const int32_t* pcu;
+  int B;
+  __device__ __forceinline__ int32_t row_info(int m) const {
+    const int f = frame_of_token(cu, B, m);
+    return pcu[f] + (m - cu[f]);
+  }
+  __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t pos) const {
+    const float4 b = *reinterpret_cast<const float4*>(bias + n);
+    const float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
+    if (n < d2) {
+      *reinterpret_cast<uint2*>(qk + (size_t)m * ldc + n) =
+          make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+    } else {
+      bf16_t* p = vt + (size_t)(n - d2) * vt_ld + pos;
+      p[0] = f32_to_bf16(r0);
+      p[(size_t)vt_ld] = f32_to_bf16(r1);
+      p[(size_t)2 * vt_ld] = f32_to_bf16(r2);
+      p[(size_t)3 * vt_ld] = f32_to_bf16(r3);
+    }
   }
 };
 
@@ -232,6 +267,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   for (int i = 0; i < MT; ++i) {
     const int m = m0 + wm * WTM + i * 32 + l32;
     if (m >= M) continue;
+    const int32_t info = ep.row_info(m);
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
 #pragma unroll
@@ -239,7 +275,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
         const int n = n0 + wn * WTN + j * 32 + 8 * q + 4 * g;
         const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
                             acc[i][j][4 * q + 3]};
-        ep.store4(m, n, v, 0);
+        ep.store4(m, n, v, info);
       }
     }
   }
@@ -613,6 +649,17 @@ hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, in
     if (use_bf16) e = launch_gather(al, w, d, K, ep, m_ptr, m_host, m_capacity, s);
     else e = launch_f32(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
   }
+  if (e != hipSuccess) return e;
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_qkv(const void* A, const void* W, const float* bias, int d, void* qk,
+                           void* vt, int vt_ld, const int32_t* cu_seqlens, const int32_t* pcu,
+                           int B, const int32_t* m_ptr, int m_host, int m_capacity,
+                           hipStream_t s) {
+  EpiQkv ep{bias, static_cast<bf16_t*>(qk), 3 * d, 2 * d, static_cast<bf16_t*>(vt), vt_ld,
+            cu_seqlens, pcu, B};
+  hipError_t e = launch_direct(A, W, 3 * d, d, ep, m_ptr, m_host, m_capacity, s);
   if (e != hipSuccess) return e;
   return hipGetLastError();
 }

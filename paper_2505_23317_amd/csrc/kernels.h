@@ -18,8 +18,10 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
                          int32_t* err_flag, hipStream_t s);
 
 // Attention work list: tiles[i] = frame<<24 | query-tile index, longest frame first.
+// Also pcu[0..B]: frame offsets when every frame is padded to a multiple of 64
+// positions (the layout of the feature-major copy of V).
 hipError_t launch_plan(const int32_t* cu_seqlens, int B, int block_q, int32_t* tiles,
-                       int32_t* n_tiles, int tile_capacity, hipStream_t s);
+                       int32_t* n_tiles, int tile_capacity, int32_t* pcu, hipStream_t s);
 
 // ---- row-wise kernels (rowwise.hip) ----------------------------------------
 // Position tables of one level: pe_row [rows, d/2], pe_col [cols, d/2] (fp32).
@@ -65,12 +67,22 @@ hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, i
                        Epilogue epi, void* out_act, float* resid, bool use_bf16,
                        const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s);
 
+// bf16 query/key/value projection: q and k go to qk [M, 3d] (columns 0..2d, bias added);
+// v goes feature-major to vt [d, vt_ld] at position pcu[frame] + (token - cu[frame]).
+hipError_t launch_gemm_qkv(const void* A, const void* W, const float* bias, int d, void* qk,
+                           void* vt, int vt_ld, const int32_t* cu_seqlens, const int32_t* pcu,
+                           int B, const int32_t* m_ptr, int m_host, int m_capacity,
+                           hipStream_t s);
+
 // ---- attention (attention.hip) -----------------------------------------------
 // qkv [M, 3d] (q | k | v, head h at columns h*dh), out [M, d], both in the activation
-// dtype.  Softmax over the keys of the same frame only.
-hipError_t launch_attention(const void* qkv, void* out, const int32_t* cu_seqlens, int B,
-                            int d, int heads, const int32_t* tiles, const int32_t* n_tiles,
-                            int tile_capacity, int block_q, bool use_bf16, hipStream_t s);
-int attention_block_q(int d_head, bool use_bf16);
+// dtype.  The bf16 kernel takes v from vt (see launch_gemm_qkv) instead of the last
+// third of qkv.  Softmax over the keys of the same frame only.
+hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* out,
+                            const int32_t* cu_seqlens, const int32_t* pcu, int d, int heads,
+                            const int32_t* tiles, const int32_t* n_tiles, int tile_capacity,
+                            int block_q, bool use_bf16, hipStream_t s);
+// Queries per workgroup (128 or 256) for a given head width and typical frame length.
+int attention_block_q(int d_head, bool use_bf16, int tokens_per_frame);
 
 }  // namespace cfdetr

@@ -136,7 +136,8 @@ __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
 
 __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ cu, int B,
                                                    int block_q, int32_t* __restrict__ tiles,
-                                                   int32_t* __restrict__ n_tiles, int capacity) {
+                                                   int32_t* __restrict__ n_tiles, int capacity,
+                                                   int32_t* __restrict__ pcu) {
   __shared__ int s_order[kMaxBatch];
   __shared__ int s_start[kMaxBatch + 1];
   const int tid = threadIdx.x;
@@ -159,6 +160,12 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
     }
     s_start[B] = acc;
     *n_tiles = min(acc, capacity);
+    int pos = 0;
+    for (int i = 0; i < B; ++i) {
+      pcu[i] = pos;
+      pos += (cu[i + 1] - cu[i] + 63) & ~63;
+    }
+    pcu[B] = pos;
   }
   __syncthreads();
   for (int k = 0; k < B; ++k) {
@@ -190,9 +197,9 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
 }
 
 hipError_t launch_plan(const int32_t* cu_seqlens, int B, int block_q, int32_t* tiles,
-                       int32_t* n_tiles, int tile_capacity, hipStream_t s) {
+                       int32_t* n_tiles, int tile_capacity, int32_t* pcu, hipStream_t s) {
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, cu_seqlens, B, block_q, tiles,
-                     n_tiles, tile_capacity);
+                     n_tiles, tile_capacity, pcu);
   return hipGetLastError();
 }
 
