@@ -32,7 +32,10 @@ struct cfdetr_ctx {
   void* h = nullptr;       // FFN hidden [Tm, F]
   void* vt = nullptr;      // bf16 mode: V feature-major [d, vt_ld], frames padded to 64
   int vt_ld = 0;
-  int32_t* pcu = nullptr;  // padded frame offsets into vt
+  int32_t* pcu = nullptr;  // padded sequence offsets into vt
+  int32_t* cu_all = nullptr;  // sequence offsets of the encoder run in flight
+  int32_t* m_all = nullptr;   // its token total
+  uint64_t tok_cap = 0;       // rows of the activation buffers
   float* x0 = nullptr;     // coarse-token cache of cfdetr_multilevel_batch [Bmax*N0, d]
   float* pe_row[kMaxLevels] = {};
   float* pe_col[kMaxLevels] = {};
@@ -142,8 +145,9 @@ cfdetr_status check_call(cfdetr_ctx* ctx, int B) {
 
 // Patch embedding of the tokens of one level into ctx->x (and optionally out2).
 cfdetr_status embed_level(cfdetr_ctx* ctx, const void* images, int level,
-                          const int32_t* tok_desc, const int32_t* cu, int B, float* out2,
-                          const int32_t* m_ptr, int m_host, int m_cap, hipStream_t s) {
+                          const int32_t* tok_desc, const int32_t* cu, int B, float* out,
+                          float* out2, const int32_t* m_ptr, int m_host, int m_cap,
+                          hipStream_t s) {
   EmbedArgs a;
   a.images = images;
   a.image_is_bf16 = ctx->cfg.image_dtype == CFDETR_BF16;
@@ -156,66 +160,76 @@ cfdetr_status embed_level(cfdetr_ctx* ctx, const void* images, int level,
   a.B = B;
   a.pe_row = ctx->pe_row[level];
   a.pe_col = ctx->pe_col[level];
-  a.out = ctx->x;
+  a.out = out;
   a.out2 = out2;
   CF_LAUNCH(CFDETR_K_EMBED, launch_embed(a, ctx->w.w_embed[level], ctx->w.b_embed[level],
                                          ctx->cfg.d_model, ctx->bf16, m_ptr, m_host, m_cap, s));
   return CFDETR_OK;
 }
 
-// All layers + final LayerNorm over ctx->x; sequences given by cu[0..B].
-cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, const int32_t* m_ptr,
-                          int m_host, int m_cap, float* y, hipStream_t s) {
+// All layers + final LayerNorm over the tokens in ctx->x.  The sequences are
+// n_prefix coarse grids (n0 tokens each) followed by the B sequences of cu; the
+// plan kernel turns that into ctx->cu_all / ctx->m_all, which every kernel reads
+// on the device.  Output rows below split_row go to y0, the others to y1.
+cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefix, int m_cap,
+                          float* y0, int split_row, float* y1, hipStream_t s) {
   const cfdetr_config& c = ctx->cfg;
   const cfdetr_weights& w = ctx->w;
   const int d = c.d_model, F = c.d_ffn;
   const size_t es = ctx->esz;
   const float eps = c.ln_eps;
   const bool bf = ctx->bf16;
-  CF_LAUNCH(CFDETR_K_PLAN, launch_plan(cu, B, ctx->block_q, ctx->tiles, ctx->n_tiles,
-                                       ctx->tile_cap, ctx->pcu, s));
+  const int nseq = n_prefix + B;
+  const int32_t* cu_all = ctx->cu_all;
+  const int32_t* m_ptr = ctx->m_all;
+  CF_LAUNCH(CFDETR_K_PLAN,
+            launch_plan(cu, B, n_prefix, ctx->n0, ctx->block_q, ctx->tiles, ctx->n_tiles,
+                        ctx->tile_cap, ctx->cu_all, ctx->m_all, ctx->pcu, s));
   for (int l = 0; l < c.n_layers; ++l) {
     const char* wqkv = static_cast<const char*>(w.w_qkv) + (size_t)l * 3 * d * d * es;
     const char* wo = static_cast<const char*>(w.w_o) + (size_t)l * d * d * es;
     const char* w1 = static_cast<const char*>(w.w_ff1) + (size_t)l * F * d * es;
     const char* w2 = static_cast<const char*>(w.w_ff2) + (size_t)l * d * F * es;
-    CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->x, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d,
-                                            ctx->a, bf, d, eps, m_ptr, m_host, m_cap, s));
+    CF_LAUNCH(CFDETR_K_LN,
+              launch_layernorm(ctx->x, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d, ctx->a, bf,
+                               d, eps, m_ptr, 0, m_cap, 0, nullptr, s));
     if (bf)
       CF_LAUNCH(CFDETR_K_QKV,
                 launch_gemm_qkv(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, d, ctx->qkv, ctx->vt,
-                                ctx->vt_ld, cu, ctx->pcu, B, m_ptr, m_host, m_cap, s));
+                                ctx->vt_ld, cu_all, ctx->pcu, nseq, m_ptr, 0, m_cap, s));
     else
       CF_LAUNCH(CFDETR_K_QKV, launch_gemm(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, 3 * d, d,
-                                          Epilogue::kBias, ctx->qkv, nullptr, bf, m_ptr, m_host,
-                                          m_cap, s));
+                                          Epilogue::kBias, ctx->qkv, nullptr, bf, m_ptr, 0, m_cap,
+                                          s));
     CF_LAUNCH(CFDETR_K_ATTN,
-              launch_attention(ctx->qkv, ctx->vt, ctx->vt_ld, ctx->o, cu, ctx->pcu, d, c.n_heads,
-                               ctx->tiles, ctx->n_tiles, ctx->tile_cap, ctx->block_q, bf, s));
+              launch_attention(ctx->qkv, ctx->vt, ctx->vt_ld, ctx->o, cu_all, ctx->pcu, d,
+                               c.n_heads, ctx->tiles, ctx->n_tiles, ctx->tile_cap, ctx->block_q, bf,
+                               s));
     CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->o, wo, w.b_o + (size_t)l * d, d, d,
-                                        Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr,
-                                        m_host, m_cap, s));
-    CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->x, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d,
-                                            ctx->a, bf, d, eps, m_ptr, m_host, m_cap, s));
-    CF_LAUNCH(CFDETR_K_FF1, launch_gemm(ctx->a, w1, w.b_ff1 + (size_t)l * F, F, d,
-                                        Epilogue::kBiasGelu, ctx->h, nullptr, bf, m_ptr, m_host,
+                                        Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, 0,
                                         m_cap, s));
+    CF_LAUNCH(CFDETR_K_LN,
+              launch_layernorm(ctx->x, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d, ctx->a, bf,
+                               d, eps, m_ptr, 0, m_cap, 0, nullptr, s));
+    CF_LAUNCH(CFDETR_K_FF1, launch_gemm(ctx->a, w1, w.b_ff1 + (size_t)l * F, F, d,
+                                        Epilogue::kBiasGelu, ctx->h, nullptr, bf, m_ptr, 0, m_cap,
+                                        s));
     CF_LAUNCH(CFDETR_K_FF2, launch_gemm(ctx->h, w2, w.b_ff2 + (size_t)l * d, d, F,
-                                        Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr,
-                                        m_host, m_cap, s));
+                                        Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, 0,
+                                        m_cap, s));
   }
-  CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->x, w.lnf_g, w.lnf_b, y, false, d, eps, m_ptr,
-                                          m_host, m_cap, s));
+  CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->x, w.lnf_g, w.lnf_b, y0, false, d, eps, m_ptr, 0,
+                                          m_cap, split_row, y1, s));
   return CFDETR_OK;
 }
 
 cfdetr_status coarse_impl(cfdetr_ctx* ctx, const void* images, int B, float* x0_out,
                           float* y_coarse, hipStream_t s) {
   const int M = B * ctx->n0;
-  cfdetr_status st = embed_level(ctx, images, 0, ctx->coarse_desc, ctx->coarse_cu, B, x0_out,
-                                 nullptr, M, M, s);
+  cfdetr_status st = embed_level(ctx, images, 0, ctx->coarse_desc, ctx->coarse_cu, B, ctx->x,
+                                 x0_out, nullptr, M, M, s);
   if (st != CFDETR_OK) return st;
-  return run_encoder(ctx, ctx->coarse_cu, B, nullptr, M, M, y_coarse, s);
+  return run_encoder(ctx, ctx->coarse_cu, B, 0, M, y_coarse, 0, nullptr, s);
 }
 
 cfdetr_status select_impl(cfdetr_ctx* ctx, const int32_t* boxes, const uint8_t* tier,
@@ -231,23 +245,53 @@ cfdetr_status select_impl(cfdetr_ctx* ctx, const int32_t* boxes, const uint8_t* 
   return CFDETR_OK;
 }
 
-cfdetr_status fine_impl(cfdetr_ctx* ctx, const void* images, int B, const int32_t* tok_desc,
-                        const int32_t* cu, const float* x0_cache, float* y_mixed,
-                        hipStream_t s) {
+// Tokens of the mixed-granularity sets into rows [row0, row0 + cu[B]) of ctx->x.
+cfdetr_status fine_embed(cfdetr_ctx* ctx, const void* images, int B, const int32_t* tok_desc,
+                         const int32_t* cu, const float* x0_cache, int row0, hipStream_t s) {
   const int cap = ctx->cfg.max_tokens_total;
   const int32_t* m_ptr = cu + B;
+  float* dst = ctx->x + (size_t)row0 * ctx->cfg.d_model;
   int first = 0;
   if (x0_cache) {
     CF_LAUNCH(CFDETR_K_GATHER,
               launch_gather_coarse(tok_desc, cu, B, x0_cache, ctx->n0, ctx->pyr.cols[0],
-                                   ctx->cfg.d_model, ctx->x, cap, s));
+                                   ctx->cfg.d_model, dst, cap, s));
     first = 1;
   }
   for (int l = first; l < ctx->cfg.n_levels; ++l) {
-    cfdetr_status st = embed_level(ctx, images, l, tok_desc, cu, B, nullptr, m_ptr, 0, cap, s);
+    cfdetr_status st =
+        embed_level(ctx, images, l, tok_desc, cu, B, dst, nullptr, m_ptr, 0, cap, s);
     if (st != CFDETR_OK) return st;
   }
-  return run_encoder(ctx, cu, B, m_ptr, 0, cap, y_mixed, s);
+  return CFDETR_OK;
+}
+
+cfdetr_status fine_impl(cfdetr_ctx* ctx, const void* images, int B, const int32_t* tok_desc,
+                        const int32_t* cu, const float* x0_cache, float* y_mixed,
+                        hipStream_t s) {
+  cfdetr_status st = fine_embed(ctx, images, B, tok_desc, cu, x0_cache, 0, s);
+  if (st != CFDETR_OK) return st;
+  return run_encoder(ctx, cu, B, 0, ctx->cfg.max_tokens_total, y_mixed, 0, nullptr, s);
+}
+
+// A1 -> A2 -> A3 with ONE encoder run: the B coarse grids and the B mixed token sets
+// are 2B independent sequences of the same variable-length batch (same weights), so
+// every layer kernel is launched once for both.  Only the coarse embedding has to
+// come first (the mixed sets reuse its tokens); the selection needs the boxes only.
+cfdetr_status merged_impl(cfdetr_ctx* ctx, const void* images, int B, const int32_t* boxes,
+                          const uint8_t* tier, const int32_t* box_offsets, float* y_coarse,
+                          float* y_mixed, int32_t* tok_desc, int32_t* cu_seqlens,
+                          int32_t* level_counts, hipStream_t s) {
+  const int Mc = B * ctx->n0;
+  cfdetr_status st = embed_level(ctx, images, 0, ctx->coarse_desc, ctx->coarse_cu, B, ctx->x,
+                                 ctx->x0, nullptr, Mc, Mc, s);
+  if (st != CFDETR_OK) return st;
+  st = select_impl(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts, s);
+  if (st != CFDETR_OK) return st;
+  st = fine_embed(ctx, images, B, tok_desc, cu_seqlens, ctx->x0, Mc, s);
+  if (st != CFDETR_OK) return st;
+  return run_encoder(ctx, cu_seqlens, B, B, Mc + ctx->cfg.max_tokens_total, y_coarse, Mc,
+                     y_mixed, s);
 }
 
 }  // namespace
@@ -294,17 +338,20 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   for (int l = 0; l + 1 < cfg->n_levels; ++l) c->nonfinest += p.rows[l] * p.cols[l];
   c->block_q = attention_block_q(cfg->d_model / cfg->n_heads, c->bf16,
                                  cfg->max_tokens_total / cfg->max_batch);
-  c->tile_cap = (cfg->max_tokens_total + c->block_q - 1) / c->block_q + cfg->max_batch;
+  // Activation buffers hold one merged run: max_batch coarse grids + the mixed sets.
+  c->tok_cap = (uint64_t)cfg->max_tokens_total + (uint64_t)cfg->max_batch * c->n0;
+  c->tile_cap = (int)((c->tok_cap + c->block_q - 1) / c->block_q) + 2 * cfg->max_batch;
 
-  const uint64_t Tm = cfg->max_tokens_total, d = cfg->d_model, F = cfg->d_ffn;
+  const uint64_t Tm = c->tok_cap, d = cfg->d_model, F = cfg->d_ffn;
   const uint64_t Bm = cfg->max_batch, D = d / 2;
   Carver cv;
   const uint64_t o_x = cv.take(Tm * d * 4), o_a = cv.take(Tm * d * c->esz);
   const uint64_t o_qkv = cv.take(Tm * 3 * d * c->esz), o_o = cv.take(Tm * d * c->esz);
   const uint64_t o_h = cv.take(Tm * F * c->esz), o_x0 = cv.take(Bm * c->n0 * d * 4);
-  c->vt_ld = (int)((Tm + 64 * Bm + 63) & ~uint64_t(63));
+  c->vt_ld = (int)((Tm + 64 * 2 * Bm + 63) & ~uint64_t(63));
   const uint64_t vt_bytes = c->bf16 ? d * (uint64_t)c->vt_ld * 2 : 256;
-  const uint64_t o_vt = cv.take(vt_bytes), o_pcu = cv.take((Bm + 1) * 4);
+  const uint64_t o_vt = cv.take(vt_bytes), o_pcu = cv.take((2 * Bm + 1) * 4);
+  const uint64_t o_cua = cv.take((2 * Bm + 1) * 4), o_mall = cv.take(4);
   uint64_t o_per[kMaxLevels], o_pec[kMaxLevels];
   for (int l = 0; l < cfg->n_levels; ++l) {
     o_per[l] = cv.take((uint64_t)p.rows[l] * D * 4);
@@ -330,6 +377,8 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->x0 = reinterpret_cast<float*>(base + o_x0);
   c->vt = base + o_vt;
   c->pcu = reinterpret_cast<int32_t*>(base + o_pcu);
+  c->cu_all = reinterpret_cast<int32_t*>(base + o_cua);
+  c->m_all = reinterpret_cast<int32_t*>(base + o_mall);
   for (int l = 0; l < cfg->n_levels; ++l) {
     c->pe_row[l] = reinterpret_cast<float*>(base + o_per[l]);
     c->pe_col[l] = reinterpret_cast<float*>(base + o_pec[l]);
@@ -447,12 +496,8 @@ CFDETR_API cfdetr_status cfdetr_multilevel_batch(cfdetr_ctx* ctx, const void* im
     return fail(ctx, CFDETR_EINVAL, "null pointer");
   if (!aligned16(images) || !aligned16(y_coarse) || !aligned16(y_mixed))
     return fail(ctx, CFDETR_EINVAL, "pointers must be 16-byte aligned");
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  st = coarse_impl(ctx, images, B, ctx->x0, y_coarse, s);
-  if (st != CFDETR_OK) return st;
-  st = select_impl(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts, s);
-  if (st != CFDETR_OK) return st;
-  return fine_impl(ctx, images, B, tok_desc, cu_seqlens, ctx->x0, y_mixed, s);
+  return merged_impl(ctx, images, B, boxes, tier, box_offsets, y_coarse, y_mixed, tok_desc,
+                     cu_seqlens, level_counts, static_cast<hipStream_t>(hip_stream));
 }
 
 CFDETR_API cfdetr_status cfdetr_profile_begin(cfdetr_ctx* ctx) {

@@ -136,12 +136,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     // every wavefront's part and retires all reads of the other buffer.
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-#if defined(ATTN_ABLATE_NOLOAD)
-#elif defined(ATTN_ABLATE_SAMETILE)
-    if (it + 1 < n_kv) CFDETR_ATTN_ISSUE(0, (it + 1) & 1);
-#else
     if (it + 1 < n_kv) CFDETR_ATTN_ISSUE(kv0 + kBlockKV, (it + 1) & 1);
-#endif
     const unsigned char* cK = sK + (it & 1) * KBYTES;
     const unsigned char* cV = sV + (it & 1) * VBYTES;
 

@@ -12,10 +12,10 @@
 //  * gemm_bf16_direct_kernel: activations x weights.  K-slabs of 64 go from global
 //    memory straight into LDS (global_load_lds, 16 bytes per lane, no VGPR round
 //    trip), double-buffered, one barrier per slab.  LDS rows are 128 bytes,
-//    unpadded; the 16-byte chunks of row r are stored at position chunk ^ (r & 7),
-//    which keeps the operand reads of 8 consecutive rows on disjoint banks.  The
-//    swizzle costs nothing: the lane that fills LDS position p of row r simply
-//    fetches logical chunk p ^ (r & 7) from global memory.
+//    unpadded; the 16-byte chunks of row r are stored at position chunk ^ ((r/2) & 7),
+//    which keeps the operand reads of 16 consecutive rows (what one LDS cycle serves)
+//    on disjoint banks.  The swizzle costs nothing: the lane that fills LDS position
+//    p of row r simply fetches logical chunk p ^ ((r/2) & 7) from global memory.
 //  * gemm_bf16_gather_kernel: the patch embedding as an implicit-im2col GEMM.  The
 //    A rows are pixels gathered patch by patch (bf16 or fp32 frames), staged through
 //    registers into padded LDS rows.
@@ -195,18 +195,21 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   const int wm = wave / NWN, wn = wave % NWN;
   // Loader role: a wave instruction fills 8 consecutive LDS rows (1 KB).  Lane ->
   // (row lane/8 of the group, LDS chunk position lane%8) and fetches the logical chunk
-  // position ^ row (groups start at multiples of 8, so row & 7 == lane / 8).
-  const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;
+  // position ^ swizzle key of that row.
+  const int lrow = lane >> 3, lpos = lane & 7;
   const bf16_t* ag[A_INST];
   const bf16_t* wg[B_INST];
 #pragma unroll
   for (int j = 0; j < A_INST; ++j) {
-    const int r = min(m0 + (wave * A_INST + j) * 8 + lrow, M - 1);   // rows past M: any valid row
-    ag[j] = A + (size_t)r * K + lchunk * 8;
+    const int rt = (wave * A_INST + j) * 8 + lrow;        // row inside the tile
+    const int r = min(m0 + rt, M - 1);                    // rows past M: any valid row
+    ag[j] = A + (size_t)r * K + (lpos ^ ((rt >> 1) & 7)) * 8;
   }
 #pragma unroll
-  for (int j = 0; j < B_INST; ++j)
-    wg[j] = W + (size_t)(n0 + (wave * B_INST + j) * 8 + lrow) * K + lchunk * 8;
+  for (int j = 0; j < B_INST; ++j) {
+    const int rt = (wave * B_INST + j) * 8 + lrow;
+    wg[j] = W + (size_t)(n0 + rt) * K + (lpos ^ ((rt >> 1) & 7)) * 8;
+  }
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -245,12 +248,12 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
         const int r = wm * WTM + i * 32 + l32;
-        fa[i] = *reinterpret_cast<const bf16x8*>(pa + r * 128 + ((c ^ (r & 7)) << 4));
+        fa[i] = *reinterpret_cast<const bf16x8*>(pa + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
       }
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const int r = wn * WTN + j * 32 + l32;
-        fb[j] = *reinterpret_cast<const bf16x8*>(pb + r * 128 + ((c ^ (r & 7)) << 4));
+        fb[j] = *reinterpret_cast<const bf16x8*>(pb + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
       }
 #pragma unroll
       for (int i = 0; i < MT; ++i)

@@ -17,22 +17,28 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
                          int32_t* tok_desc, int32_t* cu_seqlens, int32_t* level_counts,
                          int32_t* err_flag, hipStream_t s);
 
-// Attention work list: tiles[i] = frame<<24 | query-tile index, longest frame first.
-// Also pcu[0..B]: frame offsets when every frame is padded to a multiple of 64
-// positions (the layout of the feature-major copy of V).
-hipError_t launch_plan(const int32_t* cu_seqlens, int B, int block_q, int32_t* tiles,
-                       int32_t* n_tiles, int tile_capacity, int32_t* pcu, hipStream_t s);
+// Sequence list and attention work list of one encoder run.  The sequences are
+// n_prefix sequences of prefix_len tokens (coarse grids of a merged run; may be 0)
+// followed by the B sequences delimited by cu_seqlens.  Writes cu_all[0..nseq] and
+// m_all (offsets and total), pcu[0..nseq] (offsets with every sequence padded to a
+// multiple of 64: the layout of the feature-major copy of V), and
+// tiles[i] = sequence<<24 | query-tile index, longest sequence first.
+hipError_t launch_plan(const int32_t* cu_seqlens, int B, int n_prefix, int prefix_len,
+                       int block_q, int32_t* tiles, int32_t* n_tiles, int tile_capacity,
+                       int32_t* cu_all, int32_t* m_all, int32_t* pcu, hipStream_t s);
 
 // ---- row-wise kernels (rowwise.hip) ----------------------------------------
 // Position tables of one level: pe_row [rows, d/2], pe_col [cols, d/2] (fp32).
 hipError_t launch_pe_tables(int patch, int rows, int cols, int img_h, int img_w, int d,
                             float* pe_row, float* pe_col, hipStream_t s);
 // out = LayerNorm(x) * g + b for rows < M, M = *m_ptr if m_ptr else m_host.
-// out_is_bf16 selects bf16 bit patterns or fp32 for `out`.
+// out_is_bf16 selects bf16 bit patterns or fp32 for `out`.  Rows >= split_row go to
+// out2 (row - split_row) instead, when out2 is given.
 hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* out,
                             bool out_is_bf16, int d, float eps, const int32_t* m_ptr,
-                            int m_host, int m_capacity, hipStream_t s);
-// x[t] = x0[frame(t)*n0 + row*cols0 + col] for every level-0 token t < *m_ptr.
+                            int m_host, int m_capacity, int split_row, void* out2,
+                            hipStream_t s);
+// x[t] = x0[frame(t)*n0 + row*cols0 + col] for every level-0 token t < cu[B].
 hipError_t launch_gather_coarse(const int32_t* tok_desc, const int32_t* cu_seqlens, int B,
                                 const float* x0, int n0, int cols0, int d, float* x,
                                 int m_capacity, hipStream_t s);

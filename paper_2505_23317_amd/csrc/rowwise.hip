@@ -34,7 +34,8 @@ __device__ __forceinline__ void store_out<bf16_t>(bf16_t* p, float v) { *p = f32
 template <typename TOut>
 __global__ __launch_bounds__(256) void layernorm_kernel(
     const float* __restrict__ x, const float* __restrict__ g, const float* __restrict__ b,
-    TOut* __restrict__ out, int d, float eps, const int32_t* __restrict__ m_ptr, int m_host) {
+    TOut* __restrict__ out, int d, float eps, const int32_t* __restrict__ m_ptr, int m_host,
+    int split_row, TOut* __restrict__ out2) {
   const int M = m_ptr ? *m_ptr : m_host;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= M) return;
@@ -60,7 +61,8 @@ __global__ __launch_bounds__(256) void layernorm_kernel(
     }
   }
   const float rstd = rsqrtf(wave_sum(sq) / (float)d + eps);
-  TOut* orow = out + (size_t)row * d;
+  TOut* orow = (out2 != nullptr && row >= split_row) ? out2 + (size_t)(row - split_row) * d
+                                                     : out + (size_t)row * d;
 #pragma unroll
   for (int j = 0; j < kLnMaxPerLane; ++j) {
     if (j < per) {
@@ -100,14 +102,17 @@ hipError_t launch_pe_tables(int patch, int rows, int cols, int img_h, int img_w,
 
 hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* out,
                             bool out_is_bf16, int d, float eps, const int32_t* m_ptr,
-                            int m_host, int m_capacity, hipStream_t s) {
+                            int m_host, int m_capacity, int split_row, void* out2,
+                            hipStream_t s) {
   dim3 grid((m_capacity + 3) / 4);
   if (out_is_bf16)
     hipLaunchKernelGGL(layernorm_kernel<bf16_t>, grid, dim3(256), 0, s, x, g, b,
-                       static_cast<bf16_t*>(out), d, eps, m_ptr, m_host);
+                       static_cast<bf16_t*>(out), d, eps, m_ptr, m_host, split_row,
+                       static_cast<bf16_t*>(out2));
   else
     hipLaunchKernelGGL(layernorm_kernel<float>, grid, dim3(256), 0, s, x, g, b,
-                       static_cast<float*>(out), d, eps, m_ptr, m_host);
+                       static_cast<float*>(out), d, eps, m_ptr, m_host, split_row,
+                       static_cast<float*>(out2));
   return hipGetLastError();
 }
 

@@ -134,18 +134,32 @@ __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
   }
 }
 
+// Sequence list of one encoder run, and the attention work list over it.
+// The sequences are `n_prefix` sequences of `prefix_len` tokens each (the coarse grids
+// of a merged coarse+mixed run; n_prefix may be 0) followed by the B sequences that
+// cu[0..B] delimits.  Outputs:
+//   cu_all[0..nseq]  offsets of all sequences, m_all = their total
+//   pcu[0..nseq]     offsets when every sequence is padded to a multiple of 64
+//   tiles[i] = sequence<<24 | query-tile index, longest sequence first; n_tiles
 __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ cu, int B,
-                                                   int block_q, int32_t* __restrict__ tiles,
+                                                   int n_prefix, int prefix_len, int block_q,
+                                                   int32_t* __restrict__ tiles,
                                                    int32_t* __restrict__ n_tiles, int capacity,
+                                                   int32_t* __restrict__ cu_all,
+                                                   int32_t* __restrict__ m_all,
                                                    int32_t* __restrict__ pcu) {
-  __shared__ int s_order[kMaxBatch];
-  __shared__ int s_start[kMaxBatch + 1];
+  __shared__ int s_len[2 * kMaxBatch];
+  __shared__ int s_order[2 * kMaxBatch];
+  __shared__ int s_start[2 * kMaxBatch + 1];
   const int tid = threadIdx.x;
-  if (tid < B) {
-    int len = cu[tid + 1] - cu[tid];
+  const int nseq = n_prefix + B;
+  if (tid < nseq) s_len[tid] = tid < n_prefix ? prefix_len : cu[tid - n_prefix + 1] - cu[tid - n_prefix];
+  __syncthreads();
+  if (tid < nseq) {
+    const int len = s_len[tid];
     int rank = 0;
-    for (int j = 0; j < B; ++j) {
-      int lj = cu[j + 1] - cu[j];
+    for (int j = 0; j < nseq; ++j) {
+      const int lj = s_len[j];
       rank += (lj > len) || (lj == len && j < tid);
     }
     s_order[rank] = tid;
@@ -153,26 +167,29 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
   __syncthreads();
   if (tid == 0) {
     int acc = 0;
-    for (int k = 0; k < B; ++k) {
-      int f = s_order[k];
+    for (int k = 0; k < nseq; ++k) {
       s_start[k] = acc;
-      acc += (cu[f + 1] - cu[f] + block_q - 1) / block_q;
+      acc += (s_len[s_order[k]] + block_q - 1) / block_q;
     }
-    s_start[B] = acc;
+    s_start[nseq] = acc;
     *n_tiles = min(acc, capacity);
-    int pos = 0;
-    for (int i = 0; i < B; ++i) {
-      pcu[i] = pos;
-      pos += (cu[i + 1] - cu[i] + 63) & ~63;
+    int pos = 0, ppos = 0;
+    for (int i = 0; i < nseq; ++i) {
+      cu_all[i] = pos;
+      pcu[i] = ppos;
+      pos += s_len[i];
+      ppos += (s_len[i] + 63) & ~63;
     }
-    pcu[B] = pos;
+    cu_all[nseq] = pos;
+    pcu[nseq] = ppos;
+    *m_all = pos;
   }
   __syncthreads();
-  for (int k = 0; k < B; ++k) {
-    int f = s_order[k];
-    int nt = s_start[k + 1] - s_start[k];
+  for (int k = 0; k < nseq; ++k) {
+    const int f = s_order[k];
+    const int nt = s_start[k + 1] - s_start[k];
     for (int q = tid; q < nt; q += blockDim.x) {
-      int idx = s_start[k] + q;
+      const int idx = s_start[k] + q;
       if (idx < capacity) tiles[idx] = (f << 24) | q;
     }
   }
@@ -196,10 +213,11 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
   return hipGetLastError();
 }
 
-hipError_t launch_plan(const int32_t* cu_seqlens, int B, int block_q, int32_t* tiles,
-                       int32_t* n_tiles, int tile_capacity, int32_t* pcu, hipStream_t s) {
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, cu_seqlens, B, block_q, tiles,
-                     n_tiles, tile_capacity, pcu);
+hipError_t launch_plan(const int32_t* cu_seqlens, int B, int n_prefix, int prefix_len,
+                       int block_q, int32_t* tiles, int32_t* n_tiles, int tile_capacity,
+                       int32_t* cu_all, int32_t* m_all, int32_t* pcu, hipStream_t s) {
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, cu_seqlens, B, n_prefix, prefix_len,
+                     block_q, tiles, n_tiles, tile_capacity, cu_all, m_all, pcu);
   return hipGetLastError();
 }
 
