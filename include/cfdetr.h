@@ -18,7 +18,8 @@
  *
  * Conventions
  *   - Every data pointer is a DEVICE pointer (gfx950) owned by the caller,
- *     unless a parameter says "host".  The library never frees or keeps
+ *     unless a parameter says "host".  Frames, boxes, weights and the fp32
+ *     token/output buffers must be 16-byte aligned (else CFDETR_EINVAL).  The library never frees or keeps
  *     ownership of caller memory.  Weights must outlive the context.
  *   - Work space is allocated once in cfdetr_create from the max_* fields and
  *     released in cfdetr_destroy; the encode calls allocate nothing.

@@ -468,6 +468,7 @@ CFDETR_API cfdetr_status cfdetr_select_fine(cfdetr_ctx* ctx, const int32_t* boxe
   if (st != CFDETR_OK) return st;
   if (!boxes || !tier || !box_offsets || !tok_desc || !cu_seqlens)
     return fail(ctx, CFDETR_EINVAL, "null pointer");
+  if (!aligned16(boxes)) return fail(ctx, CFDETR_EINVAL, "boxes must be 16-byte aligned");
   return select_impl(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts,
                      static_cast<hipStream_t>(hip_stream));
 }
@@ -494,7 +495,7 @@ CFDETR_API cfdetr_status cfdetr_multilevel_batch(cfdetr_ctx* ctx, const void* im
   if (!images || !boxes || !tier || !box_offsets || !y_coarse || !y_mixed || !tok_desc ||
       !cu_seqlens)
     return fail(ctx, CFDETR_EINVAL, "null pointer");
-  if (!aligned16(images) || !aligned16(y_coarse) || !aligned16(y_mixed))
+  if (!aligned16(images) || !aligned16(y_coarse) || !aligned16(y_mixed) || !aligned16(boxes))
     return fail(ctx, CFDETR_EINVAL, "pointers must be 16-byte aligned");
   return merged_impl(ctx, images, B, boxes, tier, box_offsets, y_coarse, y_mixed, tok_desc,
                      cu_seqlens, level_counts, static_cast<hipStream_t>(hip_stream));

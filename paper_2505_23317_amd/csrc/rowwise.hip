@@ -21,16 +21,17 @@ __global__ void pe_table_kernel(int patch, int count, int extent, int D,
   table[idx] = (float)((i & 1) ? cos(arg) : sin(arg));
 }
 
-constexpr int kLnMaxPerLane = 16;  // d <= 1024
+constexpr int kLnMaxPairs = 8;  // pairs of elements per lane: d <= 1024
 
-template <typename TOut>
-__device__ __forceinline__ void store_out(TOut* p, float v);
-template <>
-__device__ __forceinline__ void store_out<float>(float* p, float v) { *p = v; }
-template <>
-__device__ __forceinline__ void store_out<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+__device__ __forceinline__ void store_pair(float* p, float a, float b) {
+  *reinterpret_cast<float2*>(p) = make_float2(a, b);
+}
+__device__ __forceinline__ void store_pair(bf16_t* p, float a, float b) {
+  *reinterpret_cast<uint32_t*>(p) = pack_bf16x2(a, b);
+}
 
-// One wavefront per row; the row lives in registers between the two passes.
+// One wavefront per row; the row lives in registers (two elements per lane and step)
+// between the two passes: mean first, then the variance of the centred values.
 template <typename TOut>
 __global__ __launch_bounds__(256) void layernorm_kernel(
     const float* __restrict__ x, const float* __restrict__ g, const float* __restrict__ b,
@@ -40,34 +41,37 @@ __global__ __launch_bounds__(256) void layernorm_kernel(
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= M) return;
   const int lane = threadIdx.x & 63;
-  const int per = d >> 6;
-  const float* xr = x + (size_t)row * d;
-  float v[kLnMaxPerLane];
+  const int pairs = d >> 1;
+  const float2* xr = reinterpret_cast<const float2*>(x + (size_t)row * d);
+  float2 v[kLnMaxPairs];
   float sum = 0.f;
 #pragma unroll
-  for (int j = 0; j < kLnMaxPerLane; ++j) {
-    if (j < per) {
-      v[j] = xr[lane + 64 * j];
-      sum += v[j];
-    }
+  for (int j = 0; j < kLnMaxPairs; ++j) {
+    const int i = lane + 64 * j;
+    v[j] = (i < pairs) ? xr[i] : make_float2(0.f, 0.f);
+    sum += v[j].x + v[j].y;
   }
   const float mean = wave_sum(sum) / (float)d;
   float sq = 0.f;
 #pragma unroll
-  for (int j = 0; j < kLnMaxPerLane; ++j) {
-    if (j < per) {
-      float c = v[j] - mean;
-      sq += c * c;
+  for (int j = 0; j < kLnMaxPairs; ++j) {
+    if (lane + 64 * j < pairs) {
+      const float cx = v[j].x - mean, cy = v[j].y - mean;
+      sq += cx * cx + cy * cy;
     }
   }
   const float rstd = rsqrtf(wave_sum(sq) / (float)d + eps);
   TOut* orow = (out2 != nullptr && row >= split_row) ? out2 + (size_t)(row - split_row) * d
                                                      : out + (size_t)row * d;
+  const float2* g2 = reinterpret_cast<const float2*>(g);
+  const float2* b2 = reinterpret_cast<const float2*>(b);
 #pragma unroll
-  for (int j = 0; j < kLnMaxPerLane; ++j) {
-    if (j < per) {
-      int e = lane + 64 * j;
-      store_out<TOut>(orow + e, (v[j] - mean) * rstd * g[e] + b[e]);
+  for (int j = 0; j < kLnMaxPairs; ++j) {
+    const int i = lane + 64 * j;
+    if (i < pairs) {
+      const float2 gg = g2[i], bb = b2[i];
+      store_pair(orow + 2 * i, (v[j].x - mean) * rstd * gg.x + bb.x,
+                 (v[j].y - mean) * rstd * gg.y + bb.y);
     }
   }
 }

@@ -21,10 +21,15 @@ namespace {
 constexpr int kHitThreads = 256;
 constexpr int kCompactThreads = 1024;
 
+// One thread per non-finest cell.  The boxes of the frame are clipped once and staged
+// through LDS in chunks (tier 0 marks an empty or non-critical box), so the inner loop
+// reads them as LDS broadcasts.
 __global__ __launch_bounds__(kHitThreads) void select_hit_kernel(
     Pyramid pyr, const int32_t* __restrict__ boxes, const uint8_t* __restrict__ tier,
     const int32_t* __restrict__ box_offsets, int nonfinest, uint8_t* __restrict__ hit,
     int32_t* __restrict__ split_count) {
+  __shared__ int4 s_box[kHitThreads];
+  __shared__ int s_tier[kHitThreads];
   const int frame = blockIdx.y;
   int id = blockIdx.x * kHitThreads + threadIdx.x;
   const bool valid = id < nonfinest;
@@ -42,12 +47,24 @@ __global__ __launch_bounds__(kHitThreads) void select_hit_kernel(
   const int cx0 = col * P, cx1 = cx0 + P, cy0 = row * P, cy1 = cy0 + P;
   const int lo = box_offsets[frame], hi = box_offsets[frame + 1];
   bool flag = false;
-  for (int b = lo; b < hi; ++b) {  // uniform over the block: box data are scalar loads
-    int x0 = max(boxes[4 * b + 0], 0), y0 = max(boxes[4 * b + 1], 0);
-    int x1 = min(boxes[4 * b + 2], pyr.img_w), y1 = min(boxes[4 * b + 3], pyr.img_h);
-    int t = tier[b];
-    bool nonempty = (x1 > x0) && (y1 > y0);
-    flag |= nonempty && (t > level) && (x0 < cx1) && (x1 > cx0) && (y0 < cy1) && (y1 > cy0);
+  for (int base = lo; base < hi; base += kHitThreads) {
+    const int b = base + threadIdx.x;
+    int4 bx = make_int4(0, 0, 0, 0);
+    int t = 0;
+    if (b < hi) {
+      const int4 raw = *reinterpret_cast<const int4*>(boxes + 4 * (size_t)b);
+      bx = make_int4(max(raw.x, 0), max(raw.y, 0), min(raw.z, pyr.img_w), min(raw.w, pyr.img_h));
+      t = (bx.z > bx.x && bx.w > bx.y) ? (int)tier[b] : 0;
+    }
+    __syncthreads();   // previous chunk fully consumed
+    s_box[threadIdx.x] = bx;
+    s_tier[threadIdx.x] = t;
+    __syncthreads();
+    const int n = min(kHitThreads, hi - base);
+    for (int k = 0; k < n; ++k) {
+      const int4 q = s_box[k];
+      flag |= (s_tier[k] > level) && (q.x < cx1) && (q.z > cx0) && (q.y < cy1) && (q.w > cy0);
+    }
   }
   flag = flag && valid;
   if (valid) hit[(size_t)frame * nonfinest + blockIdx.x * kHitThreads + threadIdx.x] = flag;
