@@ -41,8 +41,8 @@ struct cfdetr_ctx {
   float* pe_col[kMaxLevels] = {};
   int32_t* coarse_desc = nullptr;  // static token table of the coarse grid, Bmax frames
   int32_t* coarse_cu = nullptr;    // i * N0
-  uint8_t* hit = nullptr;
-  int32_t* split[2] = {};
+  uint8_t* hit[2] = {};   // selection flags; the two arrays alternate between calls
+  int hit_bytes = 0;
   int parity = 0;
   int32_t* tiles = nullptr;
   int32_t* n_tiles = nullptr;
@@ -235,12 +235,12 @@ cfdetr_status coarse_impl(cfdetr_ctx* ctx, const void* images, int B, float* x0_
 cfdetr_status select_impl(cfdetr_ctx* ctx, const int32_t* boxes, const uint8_t* tier,
                           const int32_t* box_offsets, int B, int32_t* tok_desc,
                           int32_t* cu_seqlens, int32_t* level_counts, hipStream_t s) {
-  int32_t* cur = ctx->split[ctx->parity];
-  int32_t* next = ctx->split[ctx->parity ^ 1];
+  uint8_t* cur = ctx->hit[ctx->parity];
+  uint8_t* next = ctx->hit[ctx->parity ^ 1];
   ctx->parity ^= 1;
   CF_LAUNCH(CFDETR_K_SELECT,
-            launch_select(ctx->pyr, boxes, tier, box_offsets, B, ctx->nonfinest, ctx->hit, cur,
-                          next, ctx->cfg.max_tokens_total, tok_desc, cu_seqlens, level_counts,
+            launch_select(ctx->pyr, boxes, tier, box_offsets, B, ctx->nonfinest, cur, next,
+                          ctx->hit_bytes, ctx->cfg.max_tokens_total, tok_desc, cu_seqlens, level_counts,
                           ctx->err_flag, s));
   return CFDETR_OK;
 }
@@ -358,8 +358,9 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
     o_pec[l] = cv.take((uint64_t)p.cols[l] * D * 4);
   }
   const uint64_t o_cd = cv.take(Bm * c->n0 * 4), o_cc = cv.take((Bm + 1) * 4);
-  const uint64_t o_hit = cv.take(Bm * (uint64_t)(c->nonfinest > 0 ? c->nonfinest : 1));
-  const uint64_t o_s0 = cv.take(kMaxBatch * kMaxLevels * 4), o_s1 = cv.take(kMaxBatch * kMaxLevels * 4);
+  const uint64_t hit_bytes = Bm * (uint64_t)(c->nonfinest > 0 ? c->nonfinest : 1);
+  const uint64_t o_hit0 = cv.take(hit_bytes), o_hit1 = cv.take(hit_bytes);
+  c->hit_bytes = (int)hit_bytes;
   const uint64_t o_tiles = cv.take((uint64_t)c->tile_cap * 4), o_nt = cv.take(4), o_err = cv.take(4);
   c->arena_bytes = cv.off;
   e = hipMalloc(&c->arena, c->arena_bytes);
@@ -385,9 +386,8 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   }
   c->coarse_desc = reinterpret_cast<int32_t*>(base + o_cd);
   c->coarse_cu = reinterpret_cast<int32_t*>(base + o_cc);
-  c->hit = reinterpret_cast<uint8_t*>(base + o_hit);
-  c->split[0] = reinterpret_cast<int32_t*>(base + o_s0);
-  c->split[1] = reinterpret_cast<int32_t*>(base + o_s1);
+  c->hit[0] = reinterpret_cast<uint8_t*>(base + o_hit0);
+  c->hit[1] = reinterpret_cast<uint8_t*>(base + o_hit1);
   c->tiles = reinterpret_cast<int32_t*>(base + o_tiles);
   c->n_tiles = reinterpret_cast<int32_t*>(base + o_nt);
   c->err_flag = reinterpret_cast<int32_t*>(base + o_err);
@@ -400,8 +400,8 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   for (uint64_t b = 0; b <= Bm; ++b) cu[b] = (int32_t)(b * c->n0);
   e = hipMemcpy(c->coarse_desc, desc.data(), desc.size() * 4, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(c->coarse_cu, cu.data(), cu.size() * 4, hipMemcpyHostToDevice);
-  if (e == hipSuccess) e = hipMemset(c->split[0], 0, kMaxBatch * kMaxLevels * 4);
-  if (e == hipSuccess) e = hipMemset(c->split[1], 0, kMaxBatch * kMaxLevels * 4);
+  if (e == hipSuccess) e = hipMemset(c->hit[0], 0, hit_bytes);
+  if (e == hipSuccess) e = hipMemset(c->hit[1], 0, hit_bytes);
   // Padding positions of vt are read (with probability 0) by the attention kernel:
   // they must hold finite numbers.  Everything ever written there is finite, so
   // zeroing once is enough.

@@ -7,15 +7,15 @@
 namespace cfdetr {
 
 // ---- A2 selection (select.hip) -------------------------------------------
-// hit        [B, nonfinest] bytes: cell (levels < n-1, level-major) overlapped by a
-//            box asking for a finer level
-// split_cur  [kMaxBatch * kMaxLevels] int32, zero on entry: receives the number of hit
-//            cells per (frame, level); split_next is zeroed for the following call.
+// hit        [B, nonfinest] bytes, all zero on entry: flag of every cell of the levels
+//            below the finest (level-major) that a box asking for a finer level
+//            overlaps; hit_next (hit_bytes long) is the array of the following call
+//            and is cleared.
 hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t* tier,
                          const int32_t* box_offsets, int B, int nonfinest, uint8_t* hit,
-                         int32_t* split_cur, int32_t* split_next, int max_tokens,
-                         int32_t* tok_desc, int32_t* cu_seqlens, int32_t* level_counts,
-                         int32_t* err_flag, hipStream_t s);
+                         uint8_t* hit_next, int hit_bytes, int max_tokens, int32_t* tok_desc,
+                         int32_t* cu_seqlens, int32_t* level_counts, int32_t* err_flag,
+                         hipStream_t s);
 
 // Sequence list and attention work list of one encoder run.  The sequences are
 // n_prefix sequences of prefix_len tokens (coarse grids of a merged run; may be 0)

@@ -7,11 +7,14 @@
 // cell always has split ancestors.  Two consequences used here:
 //   * a cell (l, r, c) is a token iff (l == 0 or its parent is hit) and
 //     (l == finest or it is not hit itself): no recursion needed;
-//   * the number of tokens of a frame at level l is 4*S(l-1) - S(l), with S(l)
-//     the number of hit cells at level l, S(finest) = 0 and 4*S(-1) := N0.
-// Kernel 1 tests every non-finest cell against the boxes of its frame and counts
-// hits per (frame, level); kernel 2 turns the counts into frame offsets and
-// compacts the tokens with wavefront ballots and popcount prefix sums.
+//   * a frame has N0 + 3 * (number of hit cells) tokens, and 4*S(l-1) - S(l) of them
+//     at level l, with S(l) the hit cells of level l, S(finest) = 0, 4*S(-1) := N0.
+// Kernel 1 tests every non-finest cell against the boxes of its frame (kBoxLanes
+// threads share a cell, each taking every kBoxLanes-th box) and raises the cell's
+// flag; kernel 2 counts the flags of all frames (offsets), then compacts the tokens
+// of its own frame with wavefront ballots and popcount prefix sums, and clears the
+// flag array that the NEXT call will use (two arrays alternate), so no memset is
+// ever needed.
 #include "kernels.h"
 
 namespace cfdetr {
@@ -19,105 +22,113 @@ namespace cfdetr {
 namespace {
 
 constexpr int kHitThreads = 256;
+constexpr int kBoxLanes = 8;
 constexpr int kCompactThreads = 1024;
 
-// One thread per non-finest cell.  The boxes of the frame are clipped once and staged
-// through LDS in chunks (tier 0 marks an empty or non-critical box), so the inner loop
-// reads them as LDS broadcasts.
 __global__ __launch_bounds__(kHitThreads) void select_hit_kernel(
     Pyramid pyr, const int32_t* __restrict__ boxes, const uint8_t* __restrict__ tier,
-    const int32_t* __restrict__ box_offsets, int nonfinest, uint8_t* __restrict__ hit,
-    int32_t* __restrict__ split_count) {
-  __shared__ int4 s_box[kHitThreads];
-  __shared__ int s_tier[kHitThreads];
+    const int32_t* __restrict__ box_offsets, int nonfinest, uint8_t* __restrict__ hit) {
   const int frame = blockIdx.y;
-  int id = blockIdx.x * kHitThreads + threadIdx.x;
-  const bool valid = id < nonfinest;
-  int level = 0;
-  if (valid) {
-    while (id >= pyr.rows[level] * pyr.cols[level]) {
-      id -= pyr.rows[level] * pyr.cols[level];
-      ++level;
-    }
-  } else {
-    id = 0;
+  const int cell = blockIdx.x * (kHitThreads / kBoxLanes) + threadIdx.x / kBoxLanes;
+  const int boxlane = threadIdx.x % kBoxLanes;
+  if (cell >= nonfinest) return;
+  int id = cell, level = 0;
+  while (id >= pyr.rows[level] * pyr.cols[level]) {
+    id -= pyr.rows[level] * pyr.cols[level];
+    ++level;
   }
   const int P = pyr.patch[level];
   const int row = id / pyr.cols[level], col = id % pyr.cols[level];
   const int cx0 = col * P, cx1 = cx0 + P, cy0 = row * P, cy1 = cy0 + P;
   const int lo = box_offsets[frame], hi = box_offsets[frame + 1];
   bool flag = false;
-  for (int base = lo; base < hi; base += kHitThreads) {
-    const int b = base + threadIdx.x;
-    int4 bx = make_int4(0, 0, 0, 0);
-    int t = 0;
-    if (b < hi) {
-      const int4 raw = *reinterpret_cast<const int4*>(boxes + 4 * (size_t)b);
-      bx = make_int4(max(raw.x, 0), max(raw.y, 0), min(raw.z, pyr.img_w), min(raw.w, pyr.img_h));
-      t = (bx.z > bx.x && bx.w > bx.y) ? (int)tier[b] : 0;
-    }
-    __syncthreads();   // previous chunk fully consumed
-    s_box[threadIdx.x] = bx;
-    s_tier[threadIdx.x] = t;
-    __syncthreads();
-    const int n = min(kHitThreads, hi - base);
-    for (int k = 0; k < n; ++k) {
-      const int4 q = s_box[k];
-      flag |= (s_tier[k] > level) && (q.x < cx1) && (q.z > cx0) && (q.y < cy1) && (q.w > cy0);
-    }
+  for (int b = lo + boxlane; b < hi; b += kBoxLanes) {
+    const int4 raw = *reinterpret_cast<const int4*>(boxes + 4 * (size_t)b);
+    const int x0 = max(raw.x, 0), y0 = max(raw.y, 0);
+    const int x1 = min(raw.z, pyr.img_w), y1 = min(raw.w, pyr.img_h);
+    const bool nonempty = (x1 > x0) && (y1 > y0);
+    flag |= nonempty && ((int)tier[b] > level) && (x0 < cx1) && (x1 > cx0) && (y0 < cy1) &&
+            (y1 > cy0);
   }
-  flag = flag && valid;
-  if (valid) hit[(size_t)frame * nonfinest + blockIdx.x * kHitThreads + threadIdx.x] = flag;
-  for (int l = 0; l + 1 < pyr.n_levels; ++l) {
-    unsigned long long m = __ballot(flag && level == l);
-    if ((threadIdx.x & (kWave - 1)) == 0 && m != 0)
-      atomicAdd(&split_count[frame * kMaxLevels + l], __popcll(m));
-  }
+  if (flag) hit[(size_t)frame * nonfinest + cell] = 1;   // several lanes may write the same 1
 }
 
 __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
     Pyramid pyr, int B, int nonfinest, const uint8_t* __restrict__ hit,
-    const int32_t* __restrict__ split_cur, int32_t* __restrict__ split_next, int max_tokens,
-    int32_t* __restrict__ tok_desc, int32_t* __restrict__ cu_seqlens,
-    int32_t* __restrict__ level_counts, int32_t* __restrict__ err_flag) {
-  __shared__ int s_cnt[kMaxBatch][kMaxLevels];
+    uint8_t* __restrict__ hit_next, int hit_bytes, int max_tokens,
+    int32_t* __restrict__ tok_desc,
+    int32_t* __restrict__ cu_seqlens, int32_t* __restrict__ level_counts,
+    int32_t* __restrict__ err_flag) {
+  __shared__ int s_split[kMaxBatch][kMaxLevels];   // hit cells per (frame, level)
   __shared__ int s_wave[kCompactThreads / kWave];
   const int frame = blockIdx.x;
   const int tid = threadIdx.x;
   const int n = pyr.n_levels;
-  if (tid < B) {
-    int prev4 = pyr.rows[0] * pyr.cols[0];  // 4 * S(-1) := N0
-    for (int l = 0; l < n; ++l) {
-      int s = (l + 1 < n) ? split_cur[tid * kMaxLevels + l] : 0;
-      s_cnt[tid][l] = prev4 - s;
-      prev4 = 4 * s;
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+
+  // hit cells of every frame and level (each workgroup needs all of them for its offset)
+  for (int i = tid; i < kMaxBatch * kMaxLevels; i += kCompactThreads) (&s_split[0][0])[i] = 0;
+  __syncthreads();
+  {
+    int bound[kMaxLevels];   // end of level l inside one frame's flag array
+    int acc = 0;
+    for (int l = 0; l < kMaxLevels; ++l) {
+      if (l + 1 < n) acc += pyr.rows[l] * pyr.cols[l];
+      bound[l] = acc;
+    }
+    const int total = B * nonfinest;
+    for (int start = 0; start < total; start += kCompactThreads) {
+      const int i = start + tid;
+      int f = 0, l = 0;
+      bool h = false;
+      if (i < total) {
+        f = i / nonfinest;
+        const int c = i - f * nonfinest;
+        while (c >= bound[l]) ++l;
+        h = hit[i] != 0;
+      }
+      // frames and levels change rarely inside a wavefront: vote per (frame, level) of lane 0
+      // and let the few stragglers add on their own
+      const int f0 = __shfl(f, 0, kWave), l0 = __shfl(l, 0, kWave);
+      const bool same = (f == f0) && (l == l0);
+      const unsigned long long m = __ballot(h && same);
+      if (lane == 0 && m != 0) atomicAdd(&s_split[f0][l0], __popcll(m));
+      if (h && !same) atomicAdd(&s_split[f][l], 1);
     }
   }
   __syncthreads();
-  long long total = 0;
+  long long total_tokens = 0;
   int base = 0;
   for (int j = 0; j < B; ++j) {
-    int tj = 0;
-    for (int l = 0; l < n; ++l) tj += s_cnt[j][l];
+    int sj = 0;
+    for (int l = 0; l + 1 < n; ++l) sj += s_split[j][l];
+    const int tj = pyr.rows[0] * pyr.cols[0] + 3 * sj;
     if (j < frame) base += tj;
-    total += tj;
+    total_tokens += tj;
   }
-  // counters of the call after this one start from zero
-  if (tid < kMaxLevels) split_next[frame * kMaxLevels + tid] = 0;
-  const bool overflow = total > (long long)max_tokens;
+  // The flag array of the call after this one starts from zero: all of it (that call
+  // may have more frames than this one), shared out among the workgroups.
+  {
+    const int share = (hit_bytes + B - 1) / B;
+    const int lo = frame * share, hi = min(lo + share, hit_bytes);
+    for (int i = lo + tid; i < hi; i += kCompactThreads) hit_next[i] = 0;
+  }
+  const bool overflow = total_tokens > (long long)max_tokens;
   if (tid == 0) {
     cu_seqlens[frame] = overflow ? 0 : base;
-    if (frame == B - 1) cu_seqlens[B] = overflow ? 0 : (int)total;
+    if (frame == B - 1) cu_seqlens[B] = overflow ? 0 : (int)total_tokens;
     if (overflow && frame == 0) *err_flag = 1;
   }
-  if (level_counts != nullptr && tid < n)
-    level_counts[frame * n + tid] = overflow ? 0 : s_cnt[frame][tid];
+  if (level_counts != nullptr && tid < n) {
+    const int prev4 = tid == 0 ? pyr.rows[0] * pyr.cols[0] : 4 * s_split[frame][tid - 1];
+    const int cur = (tid + 1 < n) ? s_split[frame][tid] : 0;
+    level_counts[frame * n + tid] = overflow ? 0 : prev4 - cur;
+  }
   if (overflow) return;
 
   const uint8_t* fhit = hit + (size_t)frame * nonfinest;
-  const int lane = tid & (kWave - 1), wave = tid / kWave;
   int running = base;
-  int off_prev = 0, off_cur = 0;  // start of level l-1 / level l inside the hit array
+  int off_prev = 0, off_cur = 0;  // start of level l-1 / level l inside the flag array
   for (int l = 0; l < n; ++l) {
     const int rows = pyr.rows[l], cols = pyr.cols[l], nl = rows * cols;
     const int pcols = (l > 0) ? pyr.cols[l - 1] : 0;
@@ -216,16 +227,17 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
 
 hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t* tier,
                          const int32_t* box_offsets, int B, int nonfinest, uint8_t* hit,
-                         int32_t* split_cur, int32_t* split_next, int max_tokens,
-                         int32_t* tok_desc, int32_t* cu_seqlens, int32_t* level_counts,
-                         int32_t* err_flag, hipStream_t s) {
+                         uint8_t* hit_next, int hit_bytes, int max_tokens, int32_t* tok_desc,
+                         int32_t* cu_seqlens, int32_t* level_counts, int32_t* err_flag,
+                         hipStream_t s) {
   if (nonfinest > 0) {
-    dim3 grid((nonfinest + kHitThreads - 1) / kHitThreads, B);
+    const int cells_per_block = kHitThreads / kBoxLanes;
+    dim3 grid((nonfinest + cells_per_block - 1) / cells_per_block, B);
     hipLaunchKernelGGL(select_hit_kernel, grid, dim3(kHitThreads), 0, s, pyr, boxes, tier,
-                       box_offsets, nonfinest, hit, split_cur);
+                       box_offsets, nonfinest, hit);
   }
   hipLaunchKernelGGL(select_compact_kernel, dim3(B), dim3(kCompactThreads), 0, s, pyr, B,
-                     nonfinest, hit, split_cur, split_next, max_tokens, tok_desc, cu_seqlens,
+                     nonfinest, hit, hit_next, hit_bytes, max_tokens, tok_desc, cu_seqlens,
                      level_counts, err_flag);
   return hipGetLastError();
 }

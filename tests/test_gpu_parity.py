@@ -124,6 +124,32 @@ def test_selection_edge_cases(K):
     enc.close()
 
 
+def test_selection_with_changing_batch_size_on_one_context(K):
+    # flags raised by a call with many frames must not leak into later, smaller or larger calls
+    cfg = synth.Config("varb", 4, 128, 128, (64, 32, 16), 64, 2, 1, 128, "f32")
+    enc = K.Encoder(cfg, synth.make_weights(cfg, 4))
+    rng = np.random.default_rng(5)
+    for B in (4, 2, 4, 1, 3, 4):
+        boxes, tier, offs = [], [], [0]
+        for _ in range(B):
+            for _ in range(int(rng.integers(0, 4))):
+                x0, y0 = int(rng.integers(0, 100)), int(rng.integers(0, 100))
+                boxes.append((x0, y0, x0 + int(rng.integers(1, 60)), y0 + int(rng.integers(1, 60))))
+                tier.append(int(rng.integers(0, 3)))
+            offs.append(len(boxes))
+        boxes = np.asarray(boxes, np.int32).reshape(-1, 4)
+        tier, offs = np.asarray(tier, np.uint8), np.asarray(offs, np.int32)
+        b, t, o = enc.upload_boxes(boxes, tier, offs)
+        out = enc.alloc_outputs(B)
+        enc.select_fine(b, t, o, B, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
+        enc.sync_status()
+        tok, cu, counts = O.select_fine(boxes, tier, offs, B, cfg.H, cfg.W, cfg.patch)
+        np.testing.assert_array_equal(out["cu_seqlens"].cpu().numpy(), cu)
+        np.testing.assert_array_equal(out["level_counts"].cpu().numpy(), counts)
+        np.testing.assert_array_equal(out["tok_desc"].cpu().numpy()[:cu[-1]], O.pack_tok_desc(tok))
+    enc.close()
+
+
 def test_selection_overflow_is_reported_not_truncated(K):
     cfg = synth.Config("ovf", 2, 128, 128, (32, 16), 64, 2, 1, 128, "f32")
     enc = K.Encoder(cfg, synth.make_weights(cfg, 3), max_tokens_total=40)
