@@ -2,6 +2,7 @@
 // A1 (coarse encode), A2 (selection), A2+A3 (mixed-granularity varlen encode).
 #include "../../include/cfdetr.h"
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -44,9 +45,8 @@ struct cfdetr_ctx {
   uint8_t* hit[2] = {};   // selection flags; the two arrays alternate between calls
   int hit_bytes = 0;
   int parity = 0;
-  int32_t* tiles = nullptr;
-  int32_t* n_tiles = nullptr;
-  int tile_cap = 0;
+  int32_t* items = nullptr;   // attention work items, 8 * cap8 entries
+  int cap8 = 0;               // workgroups per XCD the attention grid provides
   int block_q = 0;
   int32_t* err_flag = nullptr;
 
@@ -93,6 +93,7 @@ const char* check_config(const cfdetr_config& c) {
   if (c.d_model <= 0 || c.d_model % 64 || c.d_model > 1024) return "d_model must be a multiple of 64, at most 1024";
   if (c.n_heads <= 0 || c.d_model % c.n_heads) return "d_model must be a multiple of n_heads";
   if (c.d_model / c.n_heads != 32 && c.d_model / c.n_heads != 64) return "head width must be 32 or 64";
+  if (c.n_heads > 32) return "at most 32 heads";
   if (c.d_ffn <= 0 || c.d_ffn % 64) return "d_ffn must be a multiple of 64";
   if (c.n_layers < 1) return "n_layers must be >= 1";
   if (c.max_batch < 1 || c.max_batch > kMaxBatch) return "max_batch must be 1..64";
@@ -183,8 +184,8 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
   const int32_t* cu_all = ctx->cu_all;
   const int32_t* m_ptr = ctx->m_all;
   CF_LAUNCH(CFDETR_K_PLAN,
-            launch_plan(cu, B, n_prefix, ctx->n0, ctx->block_q, ctx->tiles, ctx->n_tiles,
-                        ctx->tile_cap, ctx->cu_all, ctx->m_all, ctx->pcu, s));
+            launch_plan(cu, B, n_prefix, ctx->n0, ctx->block_q, c.n_heads, ctx->items,
+                        ctx->cap8, ctx->cu_all, ctx->m_all, ctx->pcu, s));
   for (int l = 0; l < c.n_layers; ++l) {
     const char* wqkv = static_cast<const char*>(w.w_qkv) + (size_t)l * 3 * d * d * es;
     const char* wo = static_cast<const char*>(w.w_o) + (size_t)l * d * d * es;
@@ -203,8 +204,7 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
                                           s));
     CF_LAUNCH(CFDETR_K_ATTN,
               launch_attention(ctx->qkv, ctx->vt, ctx->vt_ld, ctx->o, cu_all, ctx->pcu, d,
-                               c.n_heads, ctx->tiles, ctx->n_tiles, ctx->tile_cap, ctx->block_q, bf,
-                               s));
+                               c.n_heads, ctx->items, ctx->cap8, ctx->block_q, bf, s));
     CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->o, wo, w.b_o + (size_t)l * d, d, d,
                                         Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, 0,
                                         m_cap, s));
@@ -340,7 +340,13 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
                                  cfg->max_tokens_total / cfg->max_batch);
   // Activation buffers hold one merged run: max_batch coarse grids + the mixed sets.
   c->tok_cap = (uint64_t)cfg->max_tokens_total + (uint64_t)cfg->max_batch * c->n0;
-  c->tile_cap = (int)((c->tok_cap + c->block_q - 1) / c->block_q) + 2 * cfg->max_batch;
+  {
+    // Query tiles of a whole run, and of its longest possible sequence; an XCD never
+    // gets more than (all items)/8 + (tiles of the longest sequence) work items.
+    const int tiles_all = (int)((c->tok_cap + c->block_q - 1) / c->block_q) + 2 * cfg->max_batch;
+    const int longest = std::max(cfg->max_tokens_total, c->n0);
+    c->cap8 = (tiles_all * cfg->n_heads + 7) / 8 + (longest + c->block_q - 1) / c->block_q;
+  }
 
   const uint64_t Tm = c->tok_cap, d = cfg->d_model, F = cfg->d_ffn;
   const uint64_t Bm = cfg->max_batch, D = d / 2;
@@ -361,7 +367,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   const uint64_t hit_bytes = Bm * (uint64_t)(c->nonfinest > 0 ? c->nonfinest : 1);
   const uint64_t o_hit0 = cv.take(hit_bytes), o_hit1 = cv.take(hit_bytes);
   c->hit_bytes = (int)hit_bytes;
-  const uint64_t o_tiles = cv.take((uint64_t)c->tile_cap * 4), o_nt = cv.take(4), o_err = cv.take(4);
+  const uint64_t o_items = cv.take((uint64_t)c->cap8 * 8 * 4), o_err = cv.take(4);
   c->arena_bytes = cv.off;
   e = hipMalloc(&c->arena, c->arena_bytes);
   if (e != hipSuccess) {
@@ -388,8 +394,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->coarse_cu = reinterpret_cast<int32_t*>(base + o_cc);
   c->hit[0] = reinterpret_cast<uint8_t*>(base + o_hit0);
   c->hit[1] = reinterpret_cast<uint8_t*>(base + o_hit1);
-  c->tiles = reinterpret_cast<int32_t*>(base + o_tiles);
-  c->n_tiles = reinterpret_cast<int32_t*>(base + o_nt);
+  c->items = reinterpret_cast<int32_t*>(base + o_items);
   c->err_flag = reinterpret_cast<int32_t*>(base + o_err);
 
   // static tables: coarse grid descriptors, zeroed counters, position tables
@@ -406,7 +411,6 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   // they must hold finite numbers.  Everything ever written there is finite, so
   // zeroing once is enough.
   if (e == hipSuccess) e = hipMemset(c->vt, 0, vt_bytes);
-  if (e == hipSuccess) e = hipMemset(c->n_tiles, 0, 4);
   if (e == hipSuccess) e = hipMemset(c->err_flag, 0, 4);
   for (int l = 0; l < cfg->n_levels && e == hipSuccess; ++l)
     e = launch_pe_tables(p.patch[l], p.rows[l], p.cols[l], p.img_h, p.img_w, (int)d, c->pe_row[l],

@@ -50,8 +50,7 @@ template <int DH, int QW>
 __global__ __launch_bounds__(256) void attention_bf16_kernel(
     const bf16_t* __restrict__ qk, const bf16_t* __restrict__ vt, int vt_ld,
     bf16_t* __restrict__ out, const int32_t* __restrict__ cu, const int32_t* __restrict__ pcu,
-    int d, const int32_t* __restrict__ tiles, const int32_t* __restrict__ n_tiles,
-    float scale_log2e) {
+    int d, const int32_t* __restrict__ items, float scale_log2e) {
   constexpr int BQ = 128 * QW;
   constexpr int KS = DH / 16;          // k-steps of Q.K^T
   constexpr int MO = DH / 32;          // 32-row blocks of O^T
@@ -64,10 +63,9 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
   __shared__ __attribute__((aligned(1024))) unsigned char sK[2 * KBYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char sV[2 * VBYTES];
 
-  if ((int)blockIdx.x >= *n_tiles) return;
-  const int32_t tile = tiles[blockIdx.x];
-  const int frame = tile >> 24, qt = tile & 0xFFFFFF;
-  const int head = blockIdx.y;
+  const int32_t item = items[blockIdx.x];
+  if (item < 0) return;
+  const int frame = item >> 24, head = (item >> 19) & 31, qt = item & 0x7FFFF;
   const int seq0 = cu[frame], T = cu[frame + 1] - seq0;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
@@ -256,14 +254,13 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 template <int DH>
 __global__ __launch_bounds__(256) void attention_f32_kernel(
     const float* __restrict__ qkv, float* __restrict__ out, const int32_t* __restrict__ cu, int d,
-    const int32_t* __restrict__ tiles, const int32_t* __restrict__ n_tiles, float scale) {
+    const int32_t* __restrict__ items, float scale) {
   constexpr int TK = 32;
   __shared__ float sK[TK][DH];
   __shared__ float sV[TK][DH];
-  if ((int)blockIdx.x >= *n_tiles) return;
-  const int32_t tile = tiles[blockIdx.x];
-  const int frame = tile >> 24, qt = tile & 0xFFFFFF;
-  const int head = blockIdx.y;
+  const int32_t item = items[blockIdx.x];
+  if (item < 0) return;
+  const int frame = item >> 24, head = (item >> 19) & 31, qt = item & 0x7FFFF;
   const int seq0 = cu[frame], T = cu[frame + 1] - seq0;
   const int ld = 3 * d;
   const float* qbase = qkv + (size_t)seq0 * ld + head * DH;
@@ -328,12 +325,12 @@ int attention_block_q(int d_head, bool use_bf16, int tokens_per_frame) {
 
 hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* out,
                             const int32_t* cu_seqlens, const int32_t* pcu, int d, int heads,
-                            const int32_t* tiles, const int32_t* n_tiles, int tile_capacity,
-                            int block_q, bool use_bf16, hipStream_t s) {
+                            const int32_t* items, int cap8, int block_q, bool use_bf16,
+                            hipStream_t s) {
   if (block_q != 128 && block_q != 256) return hipErrorInvalidValue;
   const int dh = d / heads;
   const float scale = 1.0f / sqrtf((float)dh);
-  dim3 grid(tile_capacity, heads);
+  dim3 grid(8 * cap8);
   if (use_bf16) {
     const float c = scale * 1.44269504088896340736f;
     const bf16_t* in = static_cast<const bf16_t*>(qkv);
@@ -341,7 +338,7 @@ hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* ou
     bf16_t* o = static_cast<bf16_t*>(out);
 #define CFDETR_LAUNCH_ATTN(DH_, QW_)                                                          \
   hipLaunchKernelGGL((attention_bf16_kernel<DH_, QW_>), grid, dim3(256), 0, s, in, v, vt_ld, o, \
-                     cu_seqlens, pcu, d, tiles, n_tiles, c)
+                     cu_seqlens, pcu, d, items, c)
     if (dh == 64 && block_q == 256) CFDETR_LAUNCH_ATTN(64, 2);
     else if (dh == 64) CFDETR_LAUNCH_ATTN(64, 1);
     else if (dh == 32 && block_q == 256) CFDETR_LAUNCH_ATTN(32, 2);
@@ -353,10 +350,10 @@ hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* ou
     float* o = static_cast<float*>(out);
     if (dh == 64)
       hipLaunchKernelGGL(attention_f32_kernel<64>, grid, dim3(block_q), 0, s, in, o, cu_seqlens, d,
-                         tiles, n_tiles, scale);
+                         items, scale);
     else if (dh == 32)
       hipLaunchKernelGGL(attention_f32_kernel<32>, grid, dim3(block_q), 0, s, in, o, cu_seqlens, d,
-                         tiles, n_tiles, scale);
+                         items, scale);
     else
       return hipErrorInvalidValue;
   }

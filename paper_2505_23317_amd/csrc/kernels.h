@@ -21,11 +21,12 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
 // n_prefix sequences of prefix_len tokens (coarse grids of a merged run; may be 0)
 // followed by the B sequences delimited by cu_seqlens.  Writes cu_all[0..nseq] and
 // m_all (offsets and total), pcu[0..nseq] (offsets with every sequence padded to a
-// multiple of 64: the layout of the feature-major copy of V), and
-// tiles[i] = sequence<<24 | query-tile index, longest sequence first.
+// multiple of 64: the layout of the feature-major copy of V), and items[0..8*cap8):
+// the attention work item of workgroup w (sequence<<24 | head<<19 | query tile, or
+// -1), arranged so that all tiles of one (sequence, head) run on the same XCD.
 hipError_t launch_plan(const int32_t* cu_seqlens, int B, int n_prefix, int prefix_len,
-                       int block_q, int32_t* tiles, int32_t* n_tiles, int tile_capacity,
-                       int32_t* cu_all, int32_t* m_all, int32_t* pcu, hipStream_t s);
+                       int block_q, int heads, int32_t* items, int cap8, int32_t* cu_all,
+                       int32_t* m_all, int32_t* pcu, hipStream_t s);
 
 // ---- row-wise kernels (rowwise.hip) ----------------------------------------
 // Position tables of one level: pe_row [rows, d/2], pe_col [cols, d/2] (fp32).
@@ -86,8 +87,8 @@ hipError_t launch_gemm_qkv(const void* A, const void* W, const float* bias, int 
 // third of qkv.  Softmax over the keys of the same frame only.
 hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* out,
                             const int32_t* cu_seqlens, const int32_t* pcu, int d, int heads,
-                            const int32_t* tiles, const int32_t* n_tiles, int tile_capacity,
-                            int block_q, bool use_bf16, hipStream_t s);
+                            const int32_t* items, int cap8, int block_q, bool use_bf16,
+                            hipStream_t s);
 // Queries per workgroup (128 or 256) for a given head width and typical frame length.
 int attention_block_q(int d_head, bool use_bf16, int tokens_per_frame);
 

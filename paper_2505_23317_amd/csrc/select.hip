@@ -168,17 +168,26 @@ __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
 // cu[0..B] delimits.  Outputs:
 //   cu_all[0..nseq]  offsets of all sequences, m_all = their total
 //   pcu[0..nseq]     offsets when every sequence is padded to a multiple of 64
-//   tiles[i] = sequence<<24 | query-tile index, longest sequence first; n_tiles
+//   items[0..8*cap8) attention work items, sequence<<24 | head<<19 | query tile, or -1.
+// Workgroups are dealt to the 8 XCDs round-robin (workgroup w runs on XCD w % 8), and
+// every XCD has its own L2.  All query tiles of one (sequence, head) read the same
+// keys and values, so a whole group goes to one XCD: groups are ordered longest
+// sequence first and dealt round-robin, group G to XCD G % 8, whose workgroups
+// 8*j + G%8 take its tiles in order.  Costs fall with G, so the XCD loads differ by at
+// most one group, and no XCD gets more than total/8 + (tiles of the longest sequence)
+// items, which is what cap8 provides.
+constexpr int kMaxHeads = 32;
+
 __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ cu, int B,
                                                    int n_prefix, int prefix_len, int block_q,
-                                                   int32_t* __restrict__ tiles,
-                                                   int32_t* __restrict__ n_tiles, int capacity,
-                                                   int32_t* __restrict__ cu_all,
+                                                   int heads, int32_t* __restrict__ items,
+                                                   int cap8, int32_t* __restrict__ cu_all,
                                                    int32_t* __restrict__ m_all,
                                                    int32_t* __restrict__ pcu) {
   __shared__ int s_len[2 * kMaxBatch];
   __shared__ int s_order[2 * kMaxBatch];
-  __shared__ int s_start[2 * kMaxBatch + 1];
+  __shared__ int s_gstart[2 * kMaxBatch * kMaxHeads];
+  __shared__ int s_count[8];
   const int tid = threadIdx.x;
   const int nseq = n_prefix + B;
   if (tid < nseq) s_len[tid] = tid < n_prefix ? prefix_len : cu[tid - n_prefix + 1] - cu[tid - n_prefix];
@@ -193,14 +202,16 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
     s_order[rank] = tid;
   }
   __syncthreads();
-  if (tid == 0) {
-    int acc = 0;
-    for (int k = 0; k < nseq; ++k) {
-      s_start[k] = acc;
-      acc += (s_len[s_order[k]] + block_q - 1) / block_q;
+  const int ngroups = nseq * heads;
+  if (tid < 8) {   // XCD tid: slots of its groups
+    int pos = 0;
+    for (int G = tid; G < ngroups; G += 8) {
+      s_gstart[G] = pos;
+      pos += (s_len[s_order[G / heads]] + block_q - 1) / block_q;
     }
-    s_start[nseq] = acc;
-    *n_tiles = min(acc, capacity);
+    s_count[tid] = min(pos, cap8);
+  }
+  if (tid == 8) {
     int pos = 0, ppos = 0;
     for (int i = 0; i < nseq; ++i) {
       cu_all[i] = pos;
@@ -213,14 +224,15 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
     *m_all = pos;
   }
   __syncthreads();
-  for (int k = 0; k < nseq; ++k) {
-    const int f = s_order[k];
-    const int nt = s_start[k + 1] - s_start[k];
-    for (int q = tid; q < nt; q += blockDim.x) {
-      const int idx = s_start[k] + q;
-      if (idx < capacity) tiles[idx] = (f << 24) | q;
-    }
+  for (int G = tid; G < ngroups; G += blockDim.x) {   // one thread per group
+    const int f = s_order[G / heads], h = G % heads, x = G & 7;
+    const int nt = (s_len[f] + block_q - 1) / block_q;
+    const int j0 = s_gstart[G];
+    for (int q = 0; q < nt && j0 + q < cap8; ++q)
+      items[8 * (j0 + q) + x] = (f << 24) | (h << 19) | q;
   }
+  for (int i = tid; i < 8 * cap8; i += blockDim.x)
+    if ((i >> 3) >= s_count[i & 7]) items[i] = -1;
 }
 
 }  // namespace
@@ -243,10 +255,10 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
 }
 
 hipError_t launch_plan(const int32_t* cu_seqlens, int B, int n_prefix, int prefix_len,
-                       int block_q, int32_t* tiles, int32_t* n_tiles, int tile_capacity,
-                       int32_t* cu_all, int32_t* m_all, int32_t* pcu, hipStream_t s) {
+                       int block_q, int heads, int32_t* items, int cap8, int32_t* cu_all,
+                       int32_t* m_all, int32_t* pcu, hipStream_t s) {
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, cu_seqlens, B, n_prefix, prefix_len,
-                     block_q, tiles, n_tiles, tile_capacity, cu_all, m_all, pcu);
+                     block_q, heads, items, cap8, cu_all, m_all, pcu);
   return hipGetLastError();
 }
 

@@ -1,0 +1,121 @@
+"""HBM traffic of the hot path from rocprofv3 counters.
+
+Two steps, both on the GPU machine:
+
+  rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d OUT/fetch -o t -- \
+      python3 -m paper_2505_23317_amd.hbm_probe run --config 3
+  rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d OUT/write -o t -- \
+      python3 -m paper_2505_23317_amd.hbm_probe run --config 3
+  python3 -m paper_2505_23317_amd.hbm_probe report OUT/fetch/t_counter_collection.csv \
+      OUT/write/t_counter_collection.csv --config 3 > profiles/<name>.txt
+
+`run` first copies a buffer of known size with a plain device-to-device copy kernel
+(the calibration: it reads and writes exactly COPY_BYTES), then runs a few
+cfdetr_multilevel_batch steps.  `report` scales each counter by what it read for the
+copy and prints bytes per launch for every kernel family.
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import re
+import sys
+
+COPY_BYTES = 1 << 30
+STEPS = 3
+
+FAMILIES = [
+    ("attention", r"attention_bf16_kernel"),
+    ("gemm_qkv", r"gemm_bf16_direct_kernel.*EpiQkv"),
+    ("gemm_ffn1_gelu", r"gemm_bf16_direct_kernel.*EpiAct<unsigned short, true>"),
+    ("gemm_residual", r"gemm_bf16_direct_kernel.*EpiResidual"),
+    ("embed", r"gemm_bf16_gather_kernel"),
+    ("layernorm", r"layernorm_kernel"),
+    ("select_hit", r"select_hit_kernel"),
+    ("select_compact", r"select_compact_kernel"),
+    ("gather_coarse", r"gather_coarse_kernel"),
+    ("plan", r"plan_kernel"),
+]
+
+
+def run(cfg_id: int) -> None:
+    import torch
+    from . import cfdetr, synth
+    src = torch.empty(COPY_BYTES, dtype=torch.uint8, device="cuda")
+    src.fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)                       # the calibration kernel (elementwise copy)
+    torch.cuda.synchronize()
+    cfg = synth.config(cfg_id)
+    wl = synth.make_workload(cfg_id)
+    enc = cfdetr.Encoder(cfg, wl["weights"])
+    img = enc.upload_images(wl["images"])
+    b, t, o = enc.upload_boxes(wl["boxes"], wl["tier"], wl["box_offsets"])
+    out = enc.alloc_outputs(cfg.B)
+    for _ in range(STEPS):
+        enc.multilevel_batch(img, cfg.B, b, t, o, out)
+    enc.sync_status()
+    enc.close()
+
+
+def _read(path: str):
+    """kernel name -> list of counter values (one per dispatch), and the counter's name."""
+    vals = collections.defaultdict(list)
+    name = None
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            name = r["Counter_Name"]
+            vals[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+    return vals, name
+
+
+def _copy_reading(vals):
+    """Counter value of the calibration copy: the largest single dispatch of a copy kernel."""
+    best = 0.0
+    for k, v in vals.items():
+        if "copy" in k.lower() or "elementwise" in k.lower():
+            best = max(best, max(v))
+    return best
+
+
+def report(fetch_csv: str, write_csv: str, cfg_id: int) -> None:
+    fetch, fname = _read(fetch_csv)
+    write, wname = _read(write_csv)
+    cf, cw = _copy_reading(fetch), _copy_reading(write)
+    if cf <= 0 or cw <= 0:
+        sys.exit("calibration copy not found in the counter files")
+    kf, kw = COPY_BYTES / cf, COPY_BYTES / cw        # bytes per counter unit
+    print(f"# HBM traffic per launch, cfdetr_multilevel_batch, config {cfg_id}")
+    print(f"# counters: {fname}, {wname}; calibration: a {COPY_BYTES} byte device copy read "
+          f"{cf:.1f} / {cw:.1f} counter units -> {kf:.1f} / {kw:.1f} bytes per unit "
+          f"(1024 would mean KiB)")
+    print("# family launches fetch_bytes_per_launch write_bytes_per_launch")
+    for fam, pat in FAMILIES:
+        rx = re.compile(pat)
+        f = [x for k, v in fetch.items() if rx.search(k) for x in v]
+        w = [x for k, v in write.items() if rx.search(k) for x in v]
+        if not f or not w:
+            continue
+        print(f"{fam} {len(f)} {kf * sum(f) / len(f):.0f} {kw * sum(w) / len(w):.0f}")
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    r = sub.add_parser("run")
+    r.add_argument("--config", type=int, default=3)
+    p = sub.add_parser("report")
+    p.add_argument("fetch_csv")
+    p.add_argument("write_csv")
+    p.add_argument("--config", type=int, default=3)
+    a = ap.parse_args()
+    if a.cmd == "run":
+        run(a.config)
+    else:
+        report(a.fetch_csv, a.write_csv, a.config)
+
+
+if __name__ == "__main__":
+    main()
