@@ -58,47 +58,55 @@ def cpu_baseline(cfg, wl, cfg_id):
         cores = os.cpu_count() or 1
     if cfg_id <= 3:
         frames = list(range(cfg.B))
-        sample = f"full {cfg.name} batch ({cfg.B} frames), one step"
+        sample = f"full {cfg.name} batch ({cfg.B} frames), coarse + mixed pass"
     else:
         frames = [0]
-        sample = f"frame 0 of {cfg.name} (all layers, coarse + mixed pass), one step"
+        sample = f"frame 0 of {cfg.name} (all layers, coarse + mixed pass)"
     lo, hi = int(wl["box_offsets"][frames[0]]), int(wl["box_offsets"][frames[-1] + 1])
     offs = wl["box_offsets"][frames[0]:frames[-1] + 2] - lo
+    # whole passes of the sample until about ten seconds of CPU work have been timed
     t0 = time.perf_counter()
-    yc, ym, tok, cu, counts = O.multilevel_batch(
-        wl["images"][frames], wl["boxes"][lo:hi], wl["tier"][lo:hi], offs, cfg.patch,
-        wl["weights"], cfg.heads)
-    dt = time.perf_counter() - t0
-    tokens = len(yc) + len(ym)
+    tokens, passes = 0, 0
+    while True:
+        yc, ym, tok, cu, counts = O.multilevel_batch(
+            wl["images"][frames], wl["boxes"][lo:hi], wl["tier"][lo:hi], offs, cfg.patch,
+            wl["weights"], cfg.heads)
+        tokens += len(yc) + len(ym)
+        passes += 1
+        dt = time.perf_counter() - t0
+        if dt >= 10.0:
+            break
     return {"value": tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": sample, "seconds": dt, "tokens": int(tokens)}
+            "sample": f"{sample}, repeated {passes} times", "seconds": dt, "tokens": int(tokens)}
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3)")
-    ap.add_argument("--profile-steps", type=int, default=5)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (cameras would shard across GPUs "
-              "with no exchange during the encoder; that path is not built). Use --gpus 1.",
-              file=sys.stderr)
-        return 2
+TRAFFIC_FAMILY = {"attention": "attention", "qkv": "gemm_qkv", "ffn1": "gemm_ffn1_gelu",
+                  "layernorm": "layernorm", "embed": "embed", "gather": "gather_coarse"}
 
+
+def hbm_traffic(cfg_id, family):
+    """HBM bytes per launch (fetch + write) of a kernel family from the committed
+    rocprofv3 counter summary of this workload, or None when there is none."""
+    path = os.path.join(ROOT, "profiles", f"multilevel_batch_cfg{cfg_id}_hbm_traffic.txt")
+    want = TRAFFIC_FAMILY.get(family)
+    if want is None or not os.path.exists(path):
+        return None
+    with open(path) as f:
+        for line in f:
+            parts = line.split()
+            if len(parts) == 4 and parts[0] == want:
+                return float(parts[2]) + float(parts[3])
+    return None
+
+
+def measure(cfg_id, steps, warmup, profile_steps):
+    """Time `steps` calls of cfdetr_multilevel_batch on one workload; returns the
+    throughput fields, the per-kernel table and the roofline object."""
     import torch
     from paper_2505_23317_amd import cfdetr, synth
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
-        return 2
-    cfdetr.load_library()
-
-    cfg = synth.config(args.config)
-    wl = synth.make_workload(args.config)
+    cfg = synth.config(cfg_id)
+    wl = synth.make_workload(cfg_id)
     enc = cfdetr.Encoder(cfg, wl["weights"], act_dtype="bf16")
     img = enc.upload_images(wl["images"])
     b, t, o = enc.upload_boxes(wl["boxes"], wl["tier"], wl["box_offsets"])
@@ -107,12 +115,12 @@ def main() -> int:
     def step():
         enc.multilevel_batch(img, cfg.B, b, t, o, out)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     enc.sync_status()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -122,21 +130,22 @@ def main() -> int:
     lens_fine = np.diff(cu).tolist()
     lens_coarse = [cfg.n_cells(0)] * cfg.B
     tokens_per_step = sum(lens_coarse) + sum(lens_fine)
-    ms_per_step = 1e3 * elapsed / args.steps
+    ms_per_step = 1e3 * elapsed / steps
 
     # per-kernel durations: HIP events recorded by the library around every launch, on
     # the stream the kernels run on
     cfdetr.cfdetr_profile_begin(enc.ctx)
-    for _ in range(args.profile_steps):
+    for _ in range(profile_steps):
         step()
     prof = cfdetr.cfdetr_profile_end(enc.ctx)
+    enc.close()
     work = family_work(cfg, lens_coarse, lens_fine, counts)
     kernels = {}
     for name, p in prof.items():
         if p["launches"] == 0:
             continue
-        ms_step = p["ms"] / args.profile_steps
-        row = {"ms_per_step": round(ms_step, 5), "launches_per_step": p["launches"] // args.profile_steps}
+        ms_step = p["ms"] / profile_steps
+        row = {"ms_per_step": round(ms_step, 5), "launches_per_step": p["launches"] // profile_steps}
         if name in work and ms_step > 0:
             kind, amount = work[name]
             if kind == "flop":
@@ -159,30 +168,82 @@ def main() -> int:
         roofline = {"bound": "hbm", "achieved": round(achieved, 2), "peak": PEAK_HBM_GBPS,
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 5)}
     roofline.update({"kernel": dom, "avg_launch_ms": round(avg_ms, 6),
-                     "launches_per_step": launches, "traffic": None})
+                     "launches_per_step": launches,
+                     "algorithmic_per_launch": round(amount / launches, 1),
+                     "traffic": hbm_traffic(cfg_id, dom)})
     total_flop = sum(a for k, a in work.values() if k == "flop")
-    enc.close()
+    return {
+        "cfg": cfg, "wl": wl, "elapsed": elapsed, "tokens_per_step": tokens_per_step,
+        "ms_per_step": ms_per_step, "lens_fine": lens_fine, "lens_coarse": lens_coarse,
+        "kernels": kernels, "roofline": roofline,
+        "whole_step_mfma_frac": round(total_flop / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 5),
+    }
 
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3)")
+    ap.add_argument("--profile-steps", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the short extra measurements of the two largest configs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (cameras would shard across GPUs "
+              "with no exchange during the encoder; that path is not built). Use --gpus 1.",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2505_23317_amd import cfdetr
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        return 2
+    cfdetr.load_library()
+
+    m = measure(args.config, args.steps, args.warmup, args.profile_steps)
+    cfg = m["cfg"]
     result = {
         "metric": "encoder tokens/sec + frames/sec (mixed coarse+fine batch); MFMA util vs peak",
-        "value": tokens_per_step * args.steps / elapsed,
+        "value": m["tokens_per_step"] * args.steps / m["elapsed"],
         "unit": "tokens/s",
-        "frames_per_s": cfg.B * args.steps / elapsed,
+        "frames_per_s": cfg.B * args.steps / m["elapsed"],
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}] {cfg.name}", "cameras": cfg.B,
                    "frame": [cfg.H, cfg.W], "patch": list(cfg.patch), "d_model": cfg.d,
                    "heads": cfg.heads, "layers": cfg.layers, "d_ffn": cfg.ffn,
-                   "tokens_coarse": int(sum(lens_coarse)), "tokens_mixed": int(sum(lens_fine)),
-                   "tokens_per_frame_mixed": lens_fine,
-                   "step": "cfdetr_multilevel_batch (A1 coarse encode + A2 select + A3 mixed varlen encode)"},
-        "whole_step_mfma_frac": round(total_flop / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 5),
-        "roofline": roofline,
-        "kernels": kernels,
+                   "tokens_coarse": int(sum(m["lens_coarse"])),
+                   "tokens_mixed": int(sum(m["lens_fine"])),
+                   "tokens_per_frame_mixed": m["lens_fine"],
+                   "step": "cfdetr_multilevel_batch (A1 coarse embed + A2 select + A3: coarse "
+                           "grids and mixed sets encoded as one varlen batch)"},
+        "whole_step_mfma_frac": m["whole_step_mfma_frac"],
+        "roofline": m["roofline"],
+        "kernels": m["kernels"],
     }
+    if not args.no_others:
+        # context only: the same step on the two largest configs, a few steps each
+        others = []
+        for cid in (4, 5):
+            if cid == args.config:
+                continue
+            mo = measure(cid, 10, 3, 3)
+            oc = mo["cfg"]
+            others.append({"workload": f"configs[{cid - 1}] {oc.name}",
+                           "tokens_per_s": mo["tokens_per_step"] * 10 / mo["elapsed"],
+                           "frames_per_s": oc.B * 10 / mo["elapsed"],
+                           "ms_per_step": mo["ms_per_step"],
+                           "whole_step_mfma_frac": mo["whole_step_mfma_frac"],
+                           "roofline": mo["roofline"]})
+        result["other_workloads"] = others
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, wl, args.config)
+        result["cpu_baseline"] = cpu_baseline(cfg, m["wl"], args.config)
     print(json.dumps(result))
     return 0
 

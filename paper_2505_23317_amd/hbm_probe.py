@@ -88,6 +88,12 @@ def report(fetch_csv: str, write_csv: str, cfg_id: int) -> None:
         sys.exit("calibration copy not found in the counter files")
     kf, kw = COPY_BYTES / cf, COPY_BYTES / cw        # bytes per counter unit
     print(f"# HBM traffic per launch, cfdetr_multilevel_batch, config {cfg_id}")
+    print("# commands, from the repository root on the MI355X box (OUT = any scratch folder):")
+    for c in ("FETCH_SIZE", "WRITE_SIZE"):
+        print(f"#   rocprofv3 --pmc {c} --kernel-trace --output-format csv -d OUT/{c.lower()} -o t "
+              f"-- python3 -m paper_2505_23317_amd.hbm_probe run --config {cfg_id}")
+    print(f"#   python3 -m paper_2505_23317_amd.hbm_probe report OUT/fetch_size/t_counter_collection.csv "
+          f"OUT/write_size/t_counter_collection.csv --config {cfg_id}")
     print(f"# counters: {fname}, {wname}; calibration: a {COPY_BYTES} byte device copy read "
           f"{cf:.1f} / {cw:.1f} counter units -> {kf:.1f} / {kw:.1f} bytes per unit "
           f"(1024 would mean KiB)")
