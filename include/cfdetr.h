@@ -199,10 +199,12 @@ CFDETR_API cfdetr_status cfdetr_fine_encode(cfdetr_ctx* ctx, const void* images,
                                  const float* x0_cache, float* y_mixed, void* hip_stream);
 
 /*
- * A1 -> A2 -> A3 in one call with no host synchronisation in between: coarse
- * encode, selection, then the fine encode reusing the coarse tokens
- * (Sec. III-B, A1-A3).  Arguments as in the three calls above; level_counts
- * may be NULL.
+ * A1 -> A2 -> A3 in one call with no host synchronisation in between
+ * (Sec. III-B, A1-A3).  Outputs are bit-identical to those of the three calls
+ * above, but the encoder runs once: the B coarse grids and the B mixed token
+ * sets form one variable-length batch of 2B sequences (multi-level batching,
+ * A3, across the coarse and the fine subtask).  Arguments as in the three
+ * calls above; level_counts may be NULL.
  */
 CFDETR_API cfdetr_status cfdetr_multilevel_batch(cfdetr_ctx* ctx, const void* images, int32_t B,
                                       const int32_t* boxes, const uint8_t* tier,
