@@ -46,7 +46,9 @@ struct cfdetr_ctx {
   int hit_bytes = 0;
   int parity = 0;
   int32_t* items = nullptr;   // attention work items, 8 * cap8 entries
-  int cap8 = 0;               // workgroups per XCD the attention grid provides
+  int cap8 = 0;               // entries per queue (one queue per XCD)
+  int32_t* queue_heads = nullptr;   // 8 fetch counters per layer, set by the plan kernel
+  int attn_grid = 0;                // workgroups of an attention launch
   int block_q = 0;
   int32_t* err_flag = nullptr;
 
@@ -185,7 +187,8 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
   const int32_t* m_ptr = ctx->m_all;
   CF_LAUNCH(CFDETR_K_PLAN,
             launch_plan(cu, B, n_prefix, ctx->n0, ctx->block_q, c.n_heads, ctx->items,
-                        ctx->cap8, ctx->cu_all, ctx->m_all, ctx->pcu, s));
+                        ctx->cap8, ctx->cu_all, ctx->m_all, ctx->pcu, ctx->queue_heads,
+                        8 * c.n_layers, ctx->attn_grid / 8, s));
   for (int l = 0; l < c.n_layers; ++l) {
     const char* wqkv = static_cast<const char*>(w.w_qkv) + (size_t)l * 3 * d * d * es;
     const char* wo = static_cast<const char*>(w.w_o) + (size_t)l * d * d * es;
@@ -196,7 +199,8 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
                                d, eps, m_ptr, 0, m_cap, 0, nullptr, s));
     if (bf)
       CF_LAUNCH(CFDETR_K_QKV,
-                launch_gemm_qkv(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, d, ctx->qkv, ctx->vt,
+                launch_gemm_qkv(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, d,
+                                attention_q_scale(d / c.n_heads), ctx->qkv, ctx->vt,
                                 ctx->vt_ld, cu_all, ctx->pcu, nseq, m_ptr, 0, m_cap, s));
     else
       CF_LAUNCH(CFDETR_K_QKV, launch_gemm(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, 3 * d, d,
@@ -204,7 +208,8 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
                                           s));
     CF_LAUNCH(CFDETR_K_ATTN,
               launch_attention(ctx->qkv, ctx->vt, ctx->vt_ld, ctx->o, cu_all, ctx->pcu, d,
-                               c.n_heads, ctx->items, ctx->cap8, ctx->block_q, bf, s));
+                               c.n_heads, ctx->items, ctx->cap8, ctx->queue_heads + 8 * l,
+                               ctx->attn_grid, ctx->block_q, bf, s));
     CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->o, wo, w.b_o + (size_t)l * d, d, d,
                                         Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, 0,
                                         m_cap, s));
@@ -347,6 +352,11 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
     const int longest = std::max(cfg->max_tokens_total, c->n0);
     c->cap8 = (tiles_all * cfg->n_heads + 7) / 8 + (longest + c->block_q - 1) / c->block_q;
   }
+  c->attn_grid = attention_grid(cfg->d_model / cfg->n_heads, c->bf16, c->cap8);
+  if (c->attn_grid < 8) {
+    delete c;
+    return fail_create(CFDETR_EDEVICE, "cannot size the attention grid for this device");
+  }
 
   const uint64_t Tm = c->tok_cap, d = cfg->d_model, F = cfg->d_ffn;
   const uint64_t Bm = cfg->max_batch, D = d / 2;
@@ -368,6 +378,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   const uint64_t o_hit0 = cv.take(hit_bytes), o_hit1 = cv.take(hit_bytes);
   c->hit_bytes = (int)hit_bytes;
   const uint64_t o_items = cv.take((uint64_t)c->cap8 * 8 * 4), o_err = cv.take(4);
+  const uint64_t o_qh = cv.take((uint64_t)cfg->n_layers * 8 * 4);
   c->arena_bytes = cv.off;
   e = hipMalloc(&c->arena, c->arena_bytes);
   if (e != hipSuccess) {
@@ -396,6 +407,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->hit[1] = reinterpret_cast<uint8_t*>(base + o_hit1);
   c->items = reinterpret_cast<int32_t*>(base + o_items);
   c->err_flag = reinterpret_cast<int32_t*>(base + o_err);
+  c->queue_heads = reinterpret_cast<int32_t*>(base + o_qh);
 
   // static tables: coarse grid descriptors, zeroed counters, position tables
   std::vector<int32_t> desc(Bm * c->n0), cu(Bm + 1);

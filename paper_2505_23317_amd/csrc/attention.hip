@@ -2,9 +2,9 @@
 // every token of its own frame; A3, Sec. III-B: several frames in one batch).
 // Frames are addressed by offsets, so no padding token is ever computed.
 //
-// bf16 kernel, flash style.  A workgroup owns 128*QW queries of one (frame, head);
-// each of its four wavefronts owns QW groups of 32 of them.  Keys/values are walked
-// in tiles of 64 that go from global memory straight into LDS (global_load_lds,
+// bf16 kernel, flash style.  A work item is 128 queries of one (frame, head); each of
+// the four wavefronts of a workgroup owns 32 of them.  Keys/values are walked in tiles
+// of 64 that go from global memory straight into LDS (global_load_lds,
 // double-buffered, one barrier per tile).  Everything is computed transposed so that
 // a query is a LANE:
 //   S^T[key, q] = K . Q^T          (MFMA A = K rows from LDS, B = Q rows in registers)
@@ -23,6 +23,24 @@
 // unpadded; 16-byte chunks are XOR-swizzled by row so that operand reads of 16
 // consecutive rows hit disjoint banks.
 //
+// Softmax arithmetic per element is one exp2, one add and half a convert:
+//  * q arrives multiplied by log2(e)/sqrt(dh), so S is a base-2 logit;
+//  * the first MFMA of S starts from an accumulator that holds -m (m: the reference
+//    maximum of the query) in all registers, so S leaves the matrix unit already shifted;
+//  * m is only a reference point, not the exact running maximum.  It starts at 0 and
+//    moves when a tile's probabilities sum above 2^12, or when it has never moved and
+//    the running sum is below 2^-20; the tile is then redone against the largest logit
+//    so far and the accumulators are rescaled.  Any reference gives the same quotient
+//    O / l; a bounded lag only shifts the fp32 exponents in use.
+//
+// Work distribution: sequences differ in length by 2-3x, so a fixed item -> workgroup
+// map leaves CUs idle while the longest items finish.  The grid is sized to what the
+// chip holds at once (a multiple of 8) and workgroup w serves queue w mod 8: it starts
+// with entry w/8 and fetches further entries (longest first) through an atomic counter
+// until the queue is empty.  Every queue has grid/8 workgroups whatever the hardware's
+// placement; with the usual round-robin placement those all sit on one XCD and share
+// its L2.
+//
 // The fp32 kernel (check mode) is the same online softmax with one query per thread.
 #include "kernels.h"
 
@@ -31,6 +49,8 @@ namespace cfdetr {
 namespace {
 
 constexpr int kBlockKV = 64;
+constexpr float kLazyLimit = 4096.0f;   // tile sum above which the reference maximum moves
+constexpr float kTinySum = 0x1p-20f;    // running sum below which an unanchored reference moves
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(1))) void* global_void_ptr;
@@ -46,12 +66,33 @@ __device__ __forceinline__ int swz(int r) {
   return ROWB == 128 ? ((r >> 1) & 7) : ((r >> 2) & 3);
 }
 
-template <int DH, int QW>
+// p = 2^s for the 32 logits of a lane, packed to bf16 MFMA operands; returns their sum.
+__device__ __forceinline__ float exp_tile(const f32x16 (&s)[2], bf16x8 (&pf)[2][2]) {
+  float psum = 0.f;
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      uint32_t w[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float p0 = __builtin_amdgcn_exp2f(s[sub][8 * t + 2 * e]);
+        const float p1 = __builtin_amdgcn_exp2f(s[sub][8 * t + 2 * e + 1]);
+        psum += p0 + p1;
+        w[e] = pack_bf16x2(p0, p1);
+      }
+      uint4 packed = make_uint4(w[0], w[1], w[2], w[3]);
+      pf[sub][t] = *reinterpret_cast<bf16x8*>(&packed);
+    }
+  return psum;
+}
+
+template <int DH>
 __global__ __launch_bounds__(256) void attention_bf16_kernel(
     const bf16_t* __restrict__ qk, const bf16_t* __restrict__ vt, int vt_ld,
     bf16_t* __restrict__ out, const int32_t* __restrict__ cu, const int32_t* __restrict__ pcu,
-    int d, const int32_t* __restrict__ items, float scale_log2e) {
-  constexpr int BQ = 128 * QW;
+    int d, const int32_t* __restrict__ items, int cap8, int32_t* __restrict__ queue_heads) {
+  constexpr int BQ = 128;
   constexpr int KS = DH / 16;          // k-steps of Q.K^T
   constexpr int MO = DH / 32;          // 32-row blocks of O^T
   constexpr int KROWB = DH * 2;        // bytes per K row in LDS
@@ -60,28 +101,19 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
   constexpr int KI = kBlockKV / KRPI / 4;   // K load instructions per wavefront
   constexpr int VI = DH / 8 / 4;            // V^T load instructions per wavefront (8 rows each)
   constexpr int KBYTES = kBlockKV * KROWB, VBYTES = DH * 128;
-  __shared__ __attribute__((aligned(1024))) unsigned char sK[2 * KBYTES];
-  __shared__ __attribute__((aligned(1024))) unsigned char sV[2 * VBYTES];
+  // One array per buffer and operand: the compiler then knows that a tile being
+  // filled is not the tile being read, and does not wait for the fill before the reads.
+  __shared__ __attribute__((aligned(1024))) unsigned char sK0[KBYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char sK1[KBYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char sV0[VBYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char sV1[VBYTES];
+  __shared__ int32_t s_item;
 
-  const int32_t item = items[blockIdx.x];
-  if (item < 0) return;
-  const int frame = item >> 24, head = (item >> 19) & 31, qt = item & 0x7FFFF;
-  const int seq0 = cu[frame], T = cu[frame + 1] - seq0;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int ld = 3 * d;
-  const bf16_t* qbase = qk + (size_t)seq0 * ld + head * DH;
-  const bf16_t* kbase = qbase + d;
-
-  // Q operands: lane = query, 8 consecutive dh per k-step.
-  bf16x8 qf[QW][KS];
-#pragma unroll
-  for (int qs = 0; qs < QW; ++qs) {
-    const int q_load = min(qt * BQ + (wave * QW + qs) * 32 + l32, T - 1);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-      qf[qs][ks] = *reinterpret_cast<const bf16x8*>(qbase + (size_t)q_load * ld + ks * 16 + g * 8);
-  }
+  const int home = blockIdx.x & 7;   // queue of this workgroup; w mod 8 is also its XCD
+  bool first = true;
 
   // Loader roles.  K: LDS row rho <- key (rho & 32) | swap23(rho & 31), chunk swizzled.
   int k_key[KI];
@@ -92,14 +124,42 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     k_key[j] = (rho & 32) | swap_bits_2_3(rho & 31);
     k_chunk[j] = (lane % KCPR) ^ swz<KROWB>(rho);
   }
-  // V^T: LDS row rho = dh index; 64 keys = 8 chunks of 8.
-  const bf16_t* v_src[VI];
+
+  for (;;) {
+    // every wavefront is done with the previous item's tiles and with s_item
+    __syncthreads();
+    if (tid == 0) {
+      // first item: entry blockIdx/8 of the home queue; later ones through the counter,
+      // which starts behind the entries handed out this way
+      const int j = first ? (int)(blockIdx.x >> 3) : atomicAdd(&queue_heads[home], 1);
+      s_item = j < cap8 ? items[home + 8 * j] : -1;
+    }
+    first = false;
+    __syncthreads();
+    const int32_t item = s_item;
+    if (item < 0) break;   // entries are in use from the front: the queue is empty
+
+    const int frame = item >> 24, head = (item >> 19) & 31, qt = item & 0x7FFFF;
+    const int seq0 = cu[frame], T = cu[frame + 1] - seq0;
+    const bf16_t* qbase = qk + (size_t)seq0 * ld + head * DH;
+    const bf16_t* kbase = qbase + d;
+
+    // Q operands: lane = query, 8 consecutive dh per k-step.
+    bf16x8 qf[KS];
+    {
+      const int q_load = min(qt * BQ + wave * 32 + l32, T - 1);
 #pragma unroll
-  for (int j = 0; j < VI; ++j) {
-    const int rho = (wave * VI + j) * 8 + (lane >> 3);
-    const int chunk = (lane & 7) ^ swz<128>(rho);
-    v_src[j] = vt + (size_t)(head * DH + rho) * vt_ld + pcu[frame] + chunk * 8;
-  }
+      for (int ks = 0; ks < KS; ++ks)
+        qf[ks] = *reinterpret_cast<const bf16x8*>(qbase + (size_t)q_load * ld + ks * 16 + g * 8);
+    }
+    // V^T: LDS row rho = dh index; 64 keys = 8 chunks of 8.
+    const bf16_t* v_src[VI];
+#pragma unroll
+    for (int j = 0; j < VI; ++j) {
+      const int rho = (wave * VI + j) * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ swz<128>(rho);
+      v_src[j] = vt + (size_t)(head * DH + rho) * vt_ld + pcu[frame] + chunk * 8;
+    }
 
 #define CFDETR_ATTN_ISSUE(kv0_, buf_)                                                        \
   do {                                                                                       \
@@ -107,133 +167,115 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
       const int key = min((kv0_) + k_key[j], T - 1);                                         \
       __builtin_amdgcn_global_load_lds(                                                      \
           (global_void_ptr)(kbase + (size_t)key * ld + k_chunk[j] * 8),                      \
-          (lds_void_ptr)(sK + (buf_) * KBYTES + (wave * KI + j) * 1024), 16, 0, 0);          \
+          (lds_void_ptr)(((buf_) ? sK1 : sK0) + (wave * KI + j) * 1024), 16, 0, 0);          \
     }                                                                                        \
     _Pragma("unroll") for (int j = 0; j < VI; ++j) __builtin_amdgcn_global_load_lds(         \
         (global_void_ptr)(v_src[j] + (kv0_)),                                                \
-        (lds_void_ptr)(sV + (buf_) * VBYTES + (wave * VI + j) * 1024), 16, 0, 0);            \
+        (lds_void_ptr)(((buf_) ? sV1 : sV0) + (wave * VI + j) * 1024), 16, 0, 0);            \
   } while (0)
 
-  f32x16 acc_o[QW][MO];
-  float m_run[QW], l_run[QW];
+    f32x16 acc_o[MO];
+    f32x16 negm;        // -m in every register: the start value of S
+    float l_run = 0.f;
+    bool anchored = false;   // wave-uniform: the reference has been moved at least once
 #pragma unroll
-  for (int qs = 0; qs < QW; ++qs) {
-    m_run[qs] = -INFINITY;
-    l_run[qs] = 0.f;
+    for (int r = 0; r < 16; ++r) negm[r] = 0.f;
 #pragma unroll
     for (int i = 0; i < MO; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc_o[qs][i][r] = 0.f;
-  }
+      for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
 
-  const int n_kv = (T + kBlockKV - 1) / kBlockKV;
-  CFDETR_ATTN_ISSUE(0, 0);
-  for (int it = 0; it < n_kv; ++it) {
-    const int kv0 = it * kBlockKV;
-    // vmcnt(0): this wavefront's part of tile `it` is in LDS; the barrier publishes
-    // every wavefront's part and retires all reads of the other buffer.
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-    if (it + 1 < n_kv) CFDETR_ATTN_ISSUE(kv0 + kBlockKV, (it + 1) & 1);
-    const unsigned char* cK = sK + (it & 1) * KBYTES;
-    const unsigned char* cV = sV + (it & 1) * VBYTES;
+    const int n_kv = (T + kBlockKV - 1) / kBlockKV;
+    CFDETR_ATTN_ISSUE(0, 0);
+    for (int it0 = 0; it0 < n_kv; it0 += 2) {
+#pragma unroll
+     for (int b = 0; b < 2; ++b) {   // buffer index: a constant after unrolling
+      const int it = it0 + b;
+      if (it >= n_kv) break;
+      const int kv0 = it * kBlockKV;
+      // vmcnt(0): this wavefront's part of tile `it` is in LDS; the barrier publishes
+      // every wavefront's part and retires all reads of the other buffer.
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+      if (it + 1 < n_kv) CFDETR_ATTN_ISSUE(kv0 + kBlockKV, b ^ 1);
+      const unsigned char* cK = b ? sK1 : sK0;
+      const unsigned char* cV = b ? sV1 : sV0;
 
-    // S^T for the two 32-key sub-tiles
-    f32x16 s[QW][2];
+      // S^T - m for the two 32-key sub-tiles; keys past the end of the frame (last tile
+      // only) get -inf.
+      f32x16 s[2];
+#define CFDETR_ATTN_LOGITS()                                                                  \
+  do {                                                                                        \
+    _Pragma("unroll") for (int sub = 0; sub < 2; ++sub) {                                     \
+      const int rho = sub * 32 + l32;                                                         \
+      _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                     \
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(                                   \
+            cK + rho * KROWB + (((2 * ks + g) ^ swz<KROWB>(rho)) << 4));                      \
+        s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? negm : s[sub], \
+                                                         0, 0, 0);                            \
+      }                                                                                       \
+    }                                                                                         \
+    if (kv0 + kBlockKV > T) {                                                                 \
+      _Pragma("unroll") for (int sub = 0; sub < 2; ++sub)                                     \
+      _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                        \
+        const int key = kv0 + sub * 32 + 16 * (r >> 3) + 8 * g + (r & 7);                     \
+        if (key >= T) s[sub][r] = -INFINITY;                                                  \
+      }                                                                                       \
+    }                                                                                         \
+  } while (0)
+      CFDETR_ATTN_LOGITS();
+      bf16x8 pf[2][2];
+      float psum = exp_tile(s, pf);
+      // Rare: some probability is far above 1, or nothing has anchored the reference yet
+      // and the sums are vanishing.  Move the reference to the largest logit so far
+      // (max of this tile's logits and log2 of the running sum) and redo the tile.
+      if (__any(!(psum <= kLazyLimit) || (!anchored && !(l_run + psum >= kTinySum)))) {
+        anchored = true;
+        CFDETR_ATTN_LOGITS();   // not kept across the exponentials
+        float mx = -INFINITY;
 #pragma unroll
-    for (int qs = 0; qs < QW; ++qs)
+        for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+        const float delta = fmaxf(mx, __builtin_amdgcn_logf(l_tot));   // log2; -inf for 0
+        const float alpha = fminf(__builtin_amdgcn_exp2f(-delta), 0x1p126f);
+        l_run *= alpha;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[qs][sub][r] = 0.f;
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      const int rho = sub * 32 + l32;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(
-            cK + rho * KROWB + (((2 * ks + g) ^ swz<KROWB>(rho)) << 4));
-#pragma unroll
-        for (int qs = 0; qs < QW; ++qs)
-          s[qs][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qs][ks], s[qs][sub], 0, 0, 0);
-      }
-    }
-    // mask keys past the end of the frame (last tile only)
-    if (kv0 + kBlockKV > T) {
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kv0 + sub * 32 + 16 * (r >> 3) + 8 * g + (r & 7);
-          if (key >= T) {
-#pragma unroll
-            for (int qs = 0; qs < QW; ++qs) s[qs][sub][r] = -INFINITY;
-          }
-        }
-    }
-    bf16x8 pf[QW][2][2];
-#pragma unroll
-    for (int qs = 0; qs < QW; ++qs) {
-      float m_tile = -INFINITY;
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) m_tile = fmaxf(m_tile, s[qs][sub][r]);
-      m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, kWave));
-      const float m_new = fmaxf(m_run[qs], m_tile);
-      const float alpha = __builtin_amdgcn_exp2f((m_run[qs] - m_new) * scale_log2e);
-      const float mc = m_new * scale_log2e;
-      const bool grew = m_new > m_run[qs];
-      m_run[qs] = m_new;
-      float psum = 0.f;
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          uint32_t w[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(s[qs][sub][8 * t + 2 * e], scale_log2e, -mc));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(s[qs][sub][8 * t + 2 * e + 1], scale_log2e, -mc));
-            psum += p0 + p1;
-            w[e] = pack_bf16x2(p0, p1);
-          }
-          uint4 packed = make_uint4(w[0], w[1], w[2], w[3]);
-          pf[qs][sub][t] = *reinterpret_cast<bf16x8*>(&packed);
-        }
-      l_run[qs] = l_run[qs] * alpha + psum;
-      // Rescale the accumulators only when some query of the wavefront saw a new
-      // maximum (alpha is exactly 1 otherwise); after the first tiles that is rare.
-      if (__any(grew)) {
+        for (int r = 0; r < 16; ++r) negm[r] -= delta;
 #pragma unroll
         for (int i = 0; i < MO; ++i)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) acc_o[qs][i][r] *= alpha;
+          for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[sub][r] -= delta;
+        psum = exp_tile(s, pf);
       }
+      l_run += psum;
+      // O^T += V^T . P^T
+#pragma unroll
+      for (int i = 0; i < MO; ++i) {
+        const int rho = i * 32 + l32;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const bf16x8 vf = *reinterpret_cast<const bf16x8*>(
+                cV + rho * 128 + (((4 * sub + 2 * t + g) ^ swz<128>(rho)) << 4));
+            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sub][t], acc_o[i], 0, 0, 0);
+          }
+      }
+     }
     }
-    // O^T += V^T . P^T
-#pragma unroll
-    for (int i = 0; i < MO; ++i) {
-      const int rho = i * 32 + l32;
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(
-              cV + rho * 128 + (((4 * sub + 2 * t + g) ^ swz<128>(rho)) << 4));
-#pragma unroll
-          for (int qs = 0; qs < QW; ++qs)
-            acc_o[qs][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qs][sub][t], acc_o[qs][i], 0, 0, 0);
-        }
-    }
-  }
 #undef CFDETR_ATTN_ISSUE
+#undef CFDETR_ATTN_LOGITS
 
-#pragma unroll
-  for (int qs = 0; qs < QW; ++qs) {
-    const float l_tot = l_run[qs] + __shfl_xor(l_run[qs], 32, kWave);
+    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     const float inv = 1.0f / l_tot;
-    const int q_local = qt * BQ + (wave * QW + qs) * 32 + l32;
+    const int q_local = qt * BQ + wave * 32 + l32;
     if (q_local < T) {
       bf16_t* orow = out + (size_t)(seq0 + q_local) * d + head * DH;
 #pragma unroll
@@ -242,8 +284,8 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
         for (int rq = 0; rq < 4; ++rq) {
           // registers 4*rq..4*rq+3 of lane group g are dh = 32*i + 8*rq + 4*g + 0..3
           uint2 w;
-          w.x = pack_bf16x2(acc_o[qs][i][4 * rq] * inv, acc_o[qs][i][4 * rq + 1] * inv);
-          w.y = pack_bf16x2(acc_o[qs][i][4 * rq + 2] * inv, acc_o[qs][i][4 * rq + 3] * inv);
+          w.x = pack_bf16x2(acc_o[i][4 * rq] * inv, acc_o[i][4 * rq + 1] * inv);
+          w.y = pack_bf16x2(acc_o[i][4 * rq + 2] * inv, acc_o[i][4 * rq + 3] * inv);
           *reinterpret_cast<uint2*>(orow + i * 32 + rq * 8 + g * 4) = w;
         }
     }
@@ -323,29 +365,58 @@ int attention_block_q(int d_head, bool use_bf16, int tokens_per_frame) {
   return 128;
 }
 
+float attention_q_scale(int d_head) {
+  return 1.44269504088896340736f / sqrtf((float)d_head);
+}
+
+namespace {
+
+// Workgroups the chip holds at once for a kernel: the size of a fetch-from-queue grid.
+template <typename K>
+int resident_grid(K kern) {
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, 0) != hipSuccess) return 0;
+  if (cus <= 0 || per_cu <= 0) return 0;
+  return (cus * per_cu + 7) & ~7;
+}
+
+}  // namespace
+
+int attention_grid(int d_head, bool use_bf16, int cap8) {
+  const long all = 8L * cap8;
+  if (!use_bf16) return (int)all;
+  int resident = 0;
+  if (d_head == 64) resident = resident_grid(attention_bf16_kernel<64>);
+  else if (d_head == 32) resident = resident_grid(attention_bf16_kernel<32>);
+  if (resident <= 0) return 0;
+  return (int)(all < resident ? all : resident);
+}
+
 hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* out,
                             const int32_t* cu_seqlens, const int32_t* pcu, int d, int heads,
-                            const int32_t* items, int cap8, int block_q, bool use_bf16,
-                            hipStream_t s) {
-  if (block_q != 128 && block_q != 256) return hipErrorInvalidValue;
+                            const int32_t* items, int cap8, int32_t* queue_heads, int grid_size,
+                            int block_q, bool use_bf16, hipStream_t s) {
+  if (block_q != 128 || grid_size < 8 || grid_size % 8 != 0 || grid_size > 8 * cap8)
+    return hipErrorInvalidValue;
   const int dh = d / heads;
-  const float scale = 1.0f / sqrtf((float)dh);
-  dim3 grid(8 * cap8);
   if (use_bf16) {
-    const float c = scale * 1.44269504088896340736f;
     const bf16_t* in = static_cast<const bf16_t*>(qkv);
     const bf16_t* v = static_cast<const bf16_t*>(vt);
     bf16_t* o = static_cast<bf16_t*>(out);
-#define CFDETR_LAUNCH_ATTN(DH_, QW_)                                                          \
-  hipLaunchKernelGGL((attention_bf16_kernel<DH_, QW_>), grid, dim3(256), 0, s, in, v, vt_ld, o, \
-                     cu_seqlens, pcu, d, items, c)
-    if (dh == 64 && block_q == 256) CFDETR_LAUNCH_ATTN(64, 2);
-    else if (dh == 64) CFDETR_LAUNCH_ATTN(64, 1);
-    else if (dh == 32 && block_q == 256) CFDETR_LAUNCH_ATTN(32, 2);
-    else if (dh == 32) CFDETR_LAUNCH_ATTN(32, 1);
-    else return hipErrorInvalidValue;
-#undef CFDETR_LAUNCH_ATTN
+    dim3 grid(grid_size);
+    if (dh == 64)
+      hipLaunchKernelGGL(attention_bf16_kernel<64>, grid, dim3(256), 0, s, in, v, vt_ld, o,
+                         cu_seqlens, pcu, d, items, cap8, queue_heads);
+    else if (dh == 32)
+      hipLaunchKernelGGL(attention_bf16_kernel<32>, grid, dim3(256), 0, s, in, v, vt_ld, o,
+                         cu_seqlens, pcu, d, items, cap8, queue_heads);
+    else
+      return hipErrorInvalidValue;
   } else {
+    const float scale = 1.0f / sqrtf((float)dh);
+    dim3 grid(8 * cap8);
     const float* in = static_cast<const float*>(qkv);
     float* o = static_cast<float*>(out);
     if (dh == 64)

@@ -112,6 +112,7 @@ struct EpiQkv {
   bf16_t* qk;
   int ldc;    // 3d
   int d2;     // 2d: first v column
+  float q_scale;   // queries (columns below d2/2) leave multiplied by this
   bf16_t* vt;
   int vt_ld;
   const int32_t* cu;
@@ -123,8 +124,14 @@ struct EpiQkv {
   }
   __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t pos) const {
     const float4 b = *reinterpret_cast<const float4*>(bias + n);
-    const float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
+    float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
     if (n < d2) {
+      if (2 * n < d2) {
+        r0 *= q_scale;
+        r1 *= q_scale;
+        r2 *= q_scale;
+        r3 *= q_scale;
+      }
       *reinterpret_cast<uint2*>(qk + (size_t)m * ldc + n) =
           make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
     } else {
@@ -656,11 +663,11 @@ hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, in
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_qkv(const void* A, const void* W, const float* bias, int d, void* qk,
-                           void* vt, int vt_ld, const int32_t* cu_seqlens, const int32_t* pcu,
+hipError_t launch_gemm_qkv(const void* A, const void* W, const float* bias, int d,
+                           float q_scale, void* qk, void* vt, int vt_ld, const int32_t* cu_seqlens, const int32_t* pcu,
                            int B, const int32_t* m_ptr, int m_host, int m_capacity,
                            hipStream_t s) {
-  EpiQkv ep{bias, static_cast<bf16_t*>(qk), 3 * d, 2 * d, static_cast<bf16_t*>(vt), vt_ld,
+  EpiQkv ep{bias, static_cast<bf16_t*>(qk), 3 * d, 2 * d, q_scale, static_cast<bf16_t*>(vt), vt_ld,
             cu_seqlens, pcu, B};
   hipError_t e = launch_direct(A, W, 3 * d, d, ep, m_ptr, m_host, m_capacity, s);
   if (e != hipSuccess) return e;

@@ -24,9 +24,13 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
 // multiple of 64: the layout of the feature-major copy of V), and items[0..8*cap8):
 // the attention work item of workgroup w (sequence<<24 | head<<19 | query tile, or
 // -1), arranged so that all tiles of one (sequence, head) run on the same XCD.
+// Also sets queue_heads[0..n_heads_q), the fetch counters of the attention launches
+// that follow (eight per launch), to queue_start = (attention grid) / 8: the entries
+// before that are handed out by workgroup index.
 hipError_t launch_plan(const int32_t* cu_seqlens, int B, int n_prefix, int prefix_len,
                        int block_q, int heads, int32_t* items, int cap8, int32_t* cu_all,
-                       int32_t* m_all, int32_t* pcu, hipStream_t s);
+                       int32_t* m_all, int32_t* pcu, int32_t* queue_heads, int n_heads_q,
+                       int queue_start, hipStream_t s);
 
 // ---- row-wise kernels (rowwise.hip) ----------------------------------------
 // Position tables of one level: pe_row [rows, d/2], pe_col [cols, d/2] (fp32).
@@ -74,21 +78,33 @@ hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, i
                        Epilogue epi, void* out_act, float* resid, bool use_bf16,
                        const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s);
 
-// bf16 query/key/value projection: q and k go to qk [M, 3d] (columns 0..2d, bias added);
-// v goes feature-major to vt [d, vt_ld] at position pcu[frame] + (token - cu[frame]).
-hipError_t launch_gemm_qkv(const void* A, const void* W, const float* bias, int d, void* qk,
-                           void* vt, int vt_ld, const int32_t* cu_seqlens, const int32_t* pcu,
-                           int B, const int32_t* m_ptr, int m_host, int m_capacity,
-                           hipStream_t s);
+// bf16 query/key/value projection: q and k go to qk [M, 3d] (columns 0..2d, bias added,
+// q multiplied by q_scale = attention_q_scale(d_head) so that the attention kernel gets
+// base-2 logits straight from its first MFMA); v goes feature-major to vt [d, vt_ld] at
+// position pcu[frame] + (token - cu[frame]).
+hipError_t launch_gemm_qkv(const void* A, const void* W, const float* bias, int d,
+                           float q_scale, void* qk, void* vt, int vt_ld,
+                           const int32_t* cu_seqlens, const int32_t* pcu, int B,
+                           const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s);
+// log2(e) / sqrt(d_head): the factor the bf16 attention kernel expects folded into q.
+float attention_q_scale(int d_head);
 
 // ---- attention (attention.hip) -----------------------------------------------
 // qkv [M, 3d] (q | k | v, head h at columns h*dh), out [M, d], both in the activation
 // dtype.  The bf16 kernel takes v from vt (see launch_gemm_qkv) instead of the last
-// third of qkv.  Softmax over the keys of the same frame only.
+// third of qkv and expects q pre-multiplied by attention_q_scale; its grid_size
+// (= attention_grid) workgroups serve eight queues (items[x + 8j], j = 0, 1, ... for
+// queue x): workgroup w takes entry w/8 of queue w%8 and then fetches through the
+// counter queue_heads[w%8], which must be grid_size/8 at launch and is used up by it.
+// The fp32 kernel maps workgroup w to entry w (grid_size = 8*cap8).
+// Softmax over the keys of the same frame only.
 hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* out,
                             const int32_t* cu_seqlens, const int32_t* pcu, int d, int heads,
-                            const int32_t* items, int cap8, int block_q, bool use_bf16,
-                            hipStream_t s);
+                            const int32_t* items, int cap8, int32_t* queue_heads, int grid_size,
+                            int block_q, bool use_bf16, hipStream_t s);
+// Grid of launch_attention on the current device: a multiple of 8, at most 8*cap8;
+// 0 if the device cannot be queried.
+int attention_grid(int d_head, bool use_bf16, int cap8);
 // Queries per workgroup (128 or 256) for a given head width and typical frame length.
 int attention_block_q(int d_head, bool use_bf16, int tokens_per_frame);
 

@@ -183,13 +183,16 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
                                                    int heads, int32_t* __restrict__ items,
                                                    int cap8, int32_t* __restrict__ cu_all,
                                                    int32_t* __restrict__ m_all,
-                                                   int32_t* __restrict__ pcu) {
+                                                   int32_t* __restrict__ pcu,
+                                                   int32_t* __restrict__ queue_heads,
+                                                   int n_heads_q, int queue_start) {
   __shared__ int s_len[2 * kMaxBatch];
   __shared__ int s_order[2 * kMaxBatch];
   __shared__ int s_gstart[2 * kMaxBatch * kMaxHeads];
   __shared__ int s_count[8];
   const int tid = threadIdx.x;
   const int nseq = n_prefix + B;
+  for (int i = tid; i < n_heads_q; i += blockDim.x) queue_heads[i] = queue_start;
   if (tid < nseq) s_len[tid] = tid < n_prefix ? prefix_len : cu[tid - n_prefix + 1] - cu[tid - n_prefix];
   __syncthreads();
   if (tid < nseq) {
@@ -256,9 +259,10 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
 
 hipError_t launch_plan(const int32_t* cu_seqlens, int B, int n_prefix, int prefix_len,
                        int block_q, int heads, int32_t* items, int cap8, int32_t* cu_all,
-                       int32_t* m_all, int32_t* pcu, hipStream_t s) {
+                       int32_t* m_all, int32_t* pcu, int32_t* queue_heads, int n_heads_q,
+                       int queue_start, hipStream_t s) {
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, cu_seqlens, B, n_prefix, prefix_len,
-                     block_q, heads, items, cap8, cu_all, m_all, pcu);
+                     block_q, heads, items, cap8, cu_all, m_all, pcu, queue_heads, n_heads_q, queue_start);
   return hipGetLastError();
 }
 
