@@ -42,8 +42,9 @@ def family_work(cfg, lens_coarse, lens_fine, level_counts):
         "out_proj": ("flop", L * 2.0 * tok * d * d),
         "ffn1": ("flop", L * 2.0 * tok * d * F),
         "ffn2": ("flop", L * 2.0 * tok * d * F),
-        # LayerNorm: read fp32 row, write bf16 row (final one writes fp32)
-        "layernorm": ("byte", (2 * L) * tok * d * 6.0 + tok * d * 8.0),
+        # LayerNorm, per stand-alone launch: read fp32 row, write bf16 row (scaled by the
+        # number of launches seen; the others run inside the residual contractions)
+        "layernorm": ("byte_per_launch", tok * d * 6.0),
         "gather": ("byte", float(level_counts[:, 0].sum()) * d * 8.0),
     }
 
@@ -148,6 +149,9 @@ def measure(cfg_id, steps, warmup, profile_steps):
         row = {"ms_per_step": round(ms_step, 5), "launches_per_step": p["launches"] // profile_steps}
         if name in work and ms_step > 0:
             kind, amount = work[name]
+            if kind == "byte_per_launch":
+                kind, amount = "byte", amount * row["launches_per_step"]
+                work[name] = (kind, amount)
             if kind == "flop":
                 row["tflops"] = round(amount / (ms_step * 1e-3) / 1e12, 3)
                 row["frac_of_bf16_mfma_peak"] = round(row["tflops"] / PEAK_BF16_TFLOPS, 5)

@@ -189,14 +189,19 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
             launch_plan(cu, B, n_prefix, ctx->n0, ctx->block_q, c.n_heads, ctx->items,
                         ctx->cap8, ctx->cu_all, ctx->m_all, ctx->pcu, ctx->queue_heads,
                         8 * c.n_layers, ctx->attn_grid / 8, s));
+  // Where a workgroup can own whole rows, the residual contractions also apply the
+  // LayerNorm that follows them, and only the very first one is a launch of its own.
+  const bool fused_ln = gemm_residual_ln_supported(d, bf);
   for (int l = 0; l < c.n_layers; ++l) {
     const char* wqkv = static_cast<const char*>(w.w_qkv) + (size_t)l * 3 * d * d * es;
     const char* wo = static_cast<const char*>(w.w_o) + (size_t)l * d * d * es;
     const char* w1 = static_cast<const char*>(w.w_ff1) + (size_t)l * F * d * es;
     const char* w2 = static_cast<const char*>(w.w_ff2) + (size_t)l * d * F * es;
-    CF_LAUNCH(CFDETR_K_LN,
-              launch_layernorm(ctx->x, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d, ctx->a, bf,
-                               d, eps, m_ptr, 0, m_cap, 0, nullptr, s));
+    const bool last = l + 1 == c.n_layers;
+    if (!fused_ln || l == 0)
+      CF_LAUNCH(CFDETR_K_LN,
+                launch_layernorm(ctx->x, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d, ctx->a,
+                                 bf, d, eps, m_ptr, 0, m_cap, 0, nullptr, s));
     if (bf)
       CF_LAUNCH(CFDETR_K_QKV,
                 launch_gemm_qkv(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, d,
@@ -210,21 +215,41 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
               launch_attention(ctx->qkv, ctx->vt, ctx->vt_ld, ctx->o, cu_all, ctx->pcu, d,
                                c.n_heads, ctx->items, ctx->cap8, ctx->queue_heads + 8 * l,
                                ctx->attn_grid, ctx->block_q, bf, s));
-    CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->o, wo, w.b_o + (size_t)l * d, d, d,
-                                        Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, 0,
-                                        m_cap, s));
-    CF_LAUNCH(CFDETR_K_LN,
-              launch_layernorm(ctx->x, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d, ctx->a, bf,
-                               d, eps, m_ptr, 0, m_cap, 0, nullptr, s));
+    if (fused_ln) {
+      CF_LAUNCH(CFDETR_K_OUT,
+                launch_gemm_residual_ln(ctx->o, wo, w.b_o + (size_t)l * d, d, d, ctx->x,
+                                        w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d, eps,
+                                        ctx->a, true, 0, nullptr, m_ptr, 0, m_cap, s));
+    } else {
+      CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->o, wo, w.b_o + (size_t)l * d, d, d,
+                                          Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, 0,
+                                          m_cap, s));
+      CF_LAUNCH(CFDETR_K_LN,
+                launch_layernorm(ctx->x, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d, ctx->a,
+                                 bf, d, eps, m_ptr, 0, m_cap, 0, nullptr, s));
+    }
     CF_LAUNCH(CFDETR_K_FF1, launch_gemm(ctx->a, w1, w.b_ff1 + (size_t)l * F, F, d,
                                         Epilogue::kBiasGelu, ctx->h, nullptr, bf, m_ptr, 0, m_cap,
                                         s));
-    CF_LAUNCH(CFDETR_K_FF2, launch_gemm(ctx->h, w2, w.b_ff2 + (size_t)l * d, d, F,
-                                        Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, 0,
-                                        m_cap, s));
+    if (fused_ln && !last)
+      CF_LAUNCH(CFDETR_K_FF2,
+                launch_gemm_residual_ln(ctx->h, w2, w.b_ff2 + (size_t)l * d, d, F, ctx->x,
+                                        w.ln1_g + (size_t)(l + 1) * d,
+                                        w.ln1_b + (size_t)(l + 1) * d, eps, ctx->a, true, 0,
+                                        nullptr, m_ptr, 0, m_cap, s));
+    else if (fused_ln)
+      CF_LAUNCH(CFDETR_K_FF2,
+                launch_gemm_residual_ln(ctx->h, w2, w.b_ff2 + (size_t)l * d, d, F, ctx->x, w.lnf_g,
+                                        w.lnf_b, eps, y0, false, split_row, y1, m_ptr, 0, m_cap,
+                                        s));
+    else
+      CF_LAUNCH(CFDETR_K_FF2, launch_gemm(ctx->h, w2, w.b_ff2 + (size_t)l * d, d, F,
+                                          Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, 0,
+                                          m_cap, s));
   }
-  CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->x, w.lnf_g, w.lnf_b, y0, false, d, eps, m_ptr, 0,
-                                          m_cap, split_row, y1, s));
+  if (!fused_ln)
+    CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->x, w.lnf_g, w.lnf_b, y0, false, d, eps, m_ptr, 0,
+                                            m_cap, split_row, y1, s));
   return CFDETR_OK;
 }
 

@@ -32,8 +32,19 @@ constexpr int BK = 64;
 constexpr int LDS_LD = BK + 8;  // padded row (elements) of the register-staged kernel
 
 // ---------------------------------------------------------------------------
-// Epilogues: store4(m, n, v, desc) receives four consecutive columns n..n+3 of row m.
+// Epilogues work on four consecutive columns n..n+3 of row m, in two steps:
+//   pre4(m, n, info)            loads what the result needs from memory (bias, residual,
+//                               position) and nothing else;
+//   store4(m, n, v, pre, info)  combines and stores.
+// A kernel calls pre4 for a whole batch of pieces before the first store4 of the batch:
+// loads and stores share one in-order counter on this hardware, so a load issued after a
+// store cannot be waited for without waiting for the store as well, and alternating them
+// costs a memory round trip per piece.
 // ---------------------------------------------------------------------------
+struct Pre4 {
+  float4 bias;
+  float4 extra;   // residual or position; unused by the plain epilogues
+};
 __device__ __forceinline__ float gelu_erf(float x) {
   return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
 }
@@ -60,8 +71,15 @@ struct EpiAct<bf16_t, kGelu> {
   bf16_t* out;
   int ldc;
   __device__ __forceinline__ int32_t row_info(int) const { return 0; }
-  __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t) const {
-    const float4 b = *reinterpret_cast<const float4*>(bias + n);
+  __device__ __forceinline__ Pre4 pre4(int, int n, int32_t) const {
+    Pre4 p;
+    p.bias = *reinterpret_cast<const float4*>(bias + n);
+    p.extra = make_float4(0.f, 0.f, 0.f, 0.f);
+    return p;
+  }
+  __device__ __forceinline__ void store4(int m, int n, const float* v, const Pre4& pre,
+                                         int32_t) const {
+    const float4 b = pre.bias;
     float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
     if (kGelu) {
       r0 = gelu_fast(r0);
@@ -79,8 +97,15 @@ struct EpiAct<float, kGelu> {
   const float* bias;
   float* out;
   int ldc;
-  __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t) const {
-    const float4 b = *reinterpret_cast<const float4*>(bias + n);
+  __device__ __forceinline__ Pre4 pre4(int, int n, int32_t) const {
+    Pre4 p;
+    p.bias = *reinterpret_cast<const float4*>(bias + n);
+    p.extra = make_float4(0.f, 0.f, 0.f, 0.f);
+    return p;
+  }
+  __device__ __forceinline__ void store4(int m, int n, const float* v, const Pre4& pre,
+                                         int32_t) const {
+    const float4 b = pre.bias;
     float4 r = make_float4(v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w);
     if (kGelu) r = make_float4(gelu_erf(r.x), gelu_erf(r.y), gelu_erf(r.z), gelu_erf(r.w));
     *reinterpret_cast<float4*>(out + (size_t)m * ldc + n) = r;
@@ -92,15 +117,21 @@ struct EpiResidual {
   float* resid;
   int ldc;
   __device__ __forceinline__ int32_t row_info(int) const { return 0; }
-  __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t) const {
-    const float4 b = *reinterpret_cast<const float4*>(bias + n);
-    float4* p = reinterpret_cast<float4*>(resid + (size_t)m * ldc + n);
-    float4 x = *p;
+  __device__ __forceinline__ Pre4 pre4(int m, int n, int32_t) const {
+    Pre4 p;
+    p.bias = *reinterpret_cast<const float4*>(bias + n);
+    p.extra = *reinterpret_cast<const float4*>(resid + (size_t)m * ldc + n);
+    return p;
+  }
+  __device__ __forceinline__ void store4(int m, int n, const float* v, const Pre4& pre,
+                                         int32_t) const {
+    const float4 b = pre.bias;
+    float4 x = pre.extra;
     x.x += v[0] + b.x;
     x.y += v[1] + b.y;
     x.z += v[2] + b.z;
     x.w += v[3] + b.w;
-    *p = x;
+    *reinterpret_cast<float4*>(resid + (size_t)m * ldc + n) = x;
   }
 };
 
@@ -122,8 +153,15 @@ struct EpiQkv {
     const int f = frame_of_token(cu, B, m);
     return pcu[f] + (m - cu[f]);
   }
-  __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t pos) const {
-    const float4 b = *reinterpret_cast<const float4*>(bias + n);
+  __device__ __forceinline__ Pre4 pre4(int, int n, int32_t) const {
+    Pre4 p;
+    p.bias = *reinterpret_cast<const float4*>(bias + n);
+    p.extra = make_float4(0.f, 0.f, 0.f, 0.f);
+    return p;
+  }
+  __device__ __forceinline__ void store4(int m, int n, const float* v, const Pre4& pre,
+                                         int32_t pos) const {
+    const float4 b = pre.bias;
     float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
     if (n < d2) {
       if (2 * n < d2) {
@@ -151,11 +189,18 @@ struct EpiEmbed {
   float* out;
   float* out2;
   int d;
-  __device__ __forceinline__ void store4(int m, int n, const float* v, int32_t desc) const {
+  __device__ __forceinline__ Pre4 pre4(int, int n, int32_t desc) const {
     const int D = d >> 1;  // a multiple of 32: a run of four never straddles the halves
     const float* pe = (n < D) ? pe_row + tok_row(desc) * D + n : pe_col + tok_col(desc) * D + (n - D);
-    const float4 e = *reinterpret_cast<const float4*>(pe);
-    const float4 b = *reinterpret_cast<const float4*>(bias + n);
+    Pre4 p;
+    p.extra = *reinterpret_cast<const float4*>(pe);
+    p.bias = *reinterpret_cast<const float4*>(bias + n);
+    return p;
+  }
+  __device__ __forceinline__ void store4(int m, int n, const float* v, const Pre4& pre,
+                                         int32_t) const {
+    const float4 e = pre.extra;
+    const float4 b = pre.bias;
     const float4 r = make_float4(v[0] + b.x + e.x, v[1] + b.y + e.y, v[2] + b.z + e.z,
                                  v[3] + b.w + e.w);
     *reinterpret_cast<float4*>(out + (size_t)m * d + n) = r;
@@ -176,6 +221,19 @@ __device__ __forceinline__ int xcd_tile_order(int pid, int total) {
 // ---------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(1))) void* global_void_ptr;
+
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16*lane
+// (lds_base wave-uniform), issued in a form the compiler does not track: it then adds
+// no wait of its own before LDS reads, and the caller orders fills and reads with
+// explicit vmcnt waits and barriers.
+__device__ __forceinline__ void dma16_untracked(const void* gptr, const unsigned char* lds_base) {
+  // the low half of a flat pointer into LDS is the LDS address
+  const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(m0v), "v"(gptr)
+               : "memory");   // M0 is reserved: the compiler keeps nothing in it
+}
 
 template <int BM, int BN, int NWM, int NWN, typename EP>
 __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
@@ -278,6 +336,12 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     const int m = m0 + wm * WTM + i * 32 + l32;
     if (m >= M) continue;
     const int32_t info = ep.row_info(m);
+    Pre4 pre[NT][4];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        pre[j][q] = ep.pre4(m, n0 + wn * WTN + j * 32 + 8 * q + 4 * g, info);
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
 #pragma unroll
@@ -285,9 +349,222 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
         const int n = n0 + wn * WTN + j * 32 + 8 * q + 4 * g;
         const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
                             acc[i][j][4 * q + 3]};
-        ep.store4(m, n, v, info);
+        ep.store4(m, n, v, pre[j][q], info);
       }
     }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Residual contraction + LayerNorm of the new residual rows in one kernel.
+// ---------------------------------------------------------------------------
+// x[m, :] += A[m, :] . W^T + bias;  out[m, :] = LayerNorm(x[m, :]) * g + b.
+// A workgroup owns BM complete rows (all D = N output columns), so the row statistics
+// are at hand in the epilogue: in-lane sums over the lane's registers, one exchange
+// between the two half-wavefronts, and one pass through LDS across the four
+// wavefronts (wavefront w owns columns [w*D/4, (w+1)*D/4)).  Mean first, then the
+// variance of the centred values, like the stand-alone kernel.
+//
+// Few rows per workgroup means one workgroup per CU and one wavefront per SIMD, so
+// latency is hidden by depth instead of occupancy: K-slabs of 64 run through a ring of
+// kStages (3 or 4) LDS buffers (one static array each, which lets the compiler see that the
+// slab being filled is not the slab being read), with kStages-1 slabs in flight, an
+// explicit vmcnt wait for the oldest one and a bare barrier per slab.
+template <int BM, int D, int kStages, bool kOutBf16>
+__global__ __launch_bounds__(256) void gemm_bf16_rowln_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int K,
+    const float* __restrict__ bias, float* __restrict__ resid, const float* __restrict__ ln_g,
+    const float* __restrict__ ln_b, float eps, void* __restrict__ out, int split_row,
+    void* __restrict__ out2, const int32_t* __restrict__ m_ptr, int m_host) {
+  constexpr int MT = BM / 32;                  // 32-row MFMA tiles per wavefront
+  constexpr int WTN = D / 4, NT = WTN / 32;    // columns per wavefront, 32-column tiles
+  constexpr int A_INST = BM / 32, B_INST = D / 32;   // 1 KB load instructions per wavefront
+  constexpr int LPW = A_INST + B_INST;         // loads a wavefront issues per slab
+  static_assert(BM % 32 == 0 && D % 128 == 0, "tile shape");
+  static_assert(kStages == 3 || kStages == 4, "ring of 3 or 4 buffers");
+  static_assert((kStages - 2) * LPW < 64, "vmcnt is a 6-bit counter");
+  __shared__ __attribute__((aligned(1024))) unsigned char sA0[BM * 128], sA1[BM * 128],
+      sA2[BM * 128], sA3[BM * 128];
+  __shared__ __attribute__((aligned(1024))) unsigned char sB0[D * 128], sB1[D * 128],
+      sB2[D * 128], sB3[D * 128];
+  __shared__ float s_red[2][4][BM];
+#define CFDETR_RING(arr_, s_) ((s_) == 0 ? arr_##0 : (s_) == 1 ? arr_##1 : (s_) == 2 ? arr_##2 : arr_##3)
+
+  const int M = m_ptr ? *m_ptr : m_host;
+  const int m0 = blockIdx.x * BM;
+  if (m0 >= M) return;   // surplus workgroup: the grid covers the capacity
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int lrow = lane >> 3, lpos = lane & 7;
+  const bf16_t* ag[A_INST];
+  const bf16_t* wg[B_INST];
+#pragma unroll
+  for (int j = 0; j < A_INST; ++j) {
+    const int rt = (wave * A_INST + j) * 8 + lrow;
+    const int r = min(m0 + rt, M - 1);   // rows past M: any valid row, never stored
+    ag[j] = A + (size_t)r * K + (lpos ^ ((rt >> 1) & 7)) * 8;
+  }
+#pragma unroll
+  for (int j = 0; j < B_INST; ++j) {
+    const int rt = (wave * B_INST + j) * 8 + lrow;
+    wg[j] = W + (size_t)rt * K + (lpos ^ ((rt >> 1) & 7)) * 8;
+  }
+
+#define CFDETR_ISSUE_RING(k0_, s_)                                                            \
+  do {                                                                                        \
+    _Pragma("unroll") for (int j = 0; j < A_INST; ++j)                                        \
+        dma16_untracked(ag[j] + (k0_), CFDETR_RING(sA, s_) + (wave * A_INST + j) * 1024);     \
+    _Pragma("unroll") for (int j = 0; j < B_INST; ++j)                                        \
+        dma16_untracked(wg[j] + (k0_), CFDETR_RING(sB, s_) + (wave * B_INST + j) * 1024);     \
+  } while (0)
+
+  const int nk = K / BK;
+#pragma unroll
+  for (int s = 0; s < kStages - 1; ++s)
+    if (s < nk) CFDETR_ISSUE_RING(s * BK, s);
+
+  // Everything the epilogue reads is requested now and arrives during the main loop.
+  // Lane -> row l32 of each 32-row tile; register r of tile j -> column
+  // wave*WTN + 32*j + 8*(r/4) + 4*g + r%4, i.e. piece q = r/4 starts at column
+  // wave*WTN + 32*j + 8*q + 4*g.
+  float4 bb[NT][4], gg[NT][4], be[NT][4], xx[MT][NT][4];
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int n = wave * WTN + j * 32 + 8 * q + 4 * g;
+      bb[j][q] = *reinterpret_cast<const float4*>(bias + n);
+      gg[j][q] = *reinterpret_cast<const float4*>(ln_g + n);
+      be[j][q] = *reinterpret_cast<const float4*>(ln_b + n);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        xx[i][j][q] = *reinterpret_cast<const float4*>(
+            resid + (size_t)min(m0 + i * 32 + l32, M - 1) * D + n);
+    }
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  for (int it0 = 0; it0 < nk; it0 += kStages) {
+#pragma unroll
+    for (int b = 0; b < kStages; ++b) {   // ring position: a constant after unrolling
+      const int it = it0 + b;
+      if (it >= nk) break;
+      // Slabs issued after slab `it` and still allowed in flight: up to kStages-2.
+      const int ahead = min(kStages - 2, nk - 1 - it);
+      if (kStages == 4 && ahead >= 2)
+        __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LPW) & 15) | (((2 * LPW) >> 4) << 14));
+      else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (LPW & 15) | ((LPW >> 4) << 14));
+      else __builtin_amdgcn_s_waitcnt(0x0F70);
+      // Everybody's part of slab `it` is in LDS, and everybody is done reading the
+      // buffer that the next issue overwrites (it was read in the previous step).
+      __builtin_amdgcn_s_barrier();
+      if (it + kStages - 1 < nk)
+        CFDETR_ISSUE_RING((it + kStages - 1) * BK, (b + kStages - 1) % kStages);
+      const unsigned char* pa = CFDETR_RING(sA, b);
+      const unsigned char* pb = CFDETR_RING(sB, b);
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        const int c = 2 * ks + g;
+        bf16x8 fa[MT], fb[NT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          const int r = i * 32 + l32;
+          fa[i] = *reinterpret_cast<const bf16x8*>(pa + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
+        }
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          const int r = wave * WTN + j * 32 + l32;
+          fb[j] = *reinterpret_cast<const bf16x8*>(pb + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
+        }
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+#undef CFDETR_ISSUE_RING
+#undef CFDETR_RING
+  // Epilogue: new residual rows, then their LayerNorm (mean first, then the variance of
+  // the centred values).
+  float mean[MT], rstd[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const int m = m0 + i * 32 + l32;
+    float* xrow = resid + (size_t)m * D;
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = wave * WTN + j * 32 + 8 * q + 4 * g;
+        float4 v;
+        v.x = acc[i][j][4 * q] + bb[j][q].x + xx[i][j][q].x;
+        v.y = acc[i][j][4 * q + 1] + bb[j][q].y + xx[i][j][q].y;
+        v.z = acc[i][j][4 * q + 2] + bb[j][q].z + xx[i][j][q].z;
+        v.w = acc[i][j][4 * q + 3] + bb[j][q].w + xx[i][j][q].w;
+        if (m < M) *reinterpret_cast<float4*>(xrow + n) = v;
+        acc[i][j][4 * q] = v.x;
+        acc[i][j][4 * q + 1] = v.y;
+        acc[i][j][4 * q + 2] = v.z;
+        acc[i][j][4 * q + 3] = v.w;
+        sum += (v.x + v.y) + (v.z + v.w);
+      }
+    sum += __shfl_xor(sum, 32, kWave);
+    if (g == 0) s_red[0][wave][i * 32 + l32] = sum;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const int rr = i * 32 + l32;
+    mean[i] = ((s_red[0][0][rr] + s_red[0][1][rr]) + (s_red[0][2][rr] + s_red[0][3][rr])) *
+              (1.0f / (float)D);
+    float sq = 0.f;
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float c = acc[i][j][r] - mean[i];
+        sq = fmaf(c, c, sq);
+      }
+    sq += __shfl_xor(sq, 32, kWave);
+    if (g == 0) s_red[1][wave][rr] = sq;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const int rr = i * 32 + l32;
+    const float var = ((s_red[1][0][rr] + s_red[1][1][rr]) + (s_red[1][2][rr] + s_red[1][3][rr])) *
+                      (1.0f / (float)D);
+    rstd[i] = rsqrtf(var + eps);
+    const int m = m0 + rr;
+    if (m >= M) continue;
+    const bool second = out2 != nullptr && m >= split_row;
+    const size_t row_off = (size_t)(second ? m - split_row : m) * D;
+    void* obase = second ? out2 : out;
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = wave * WTN + j * 32 + 8 * q + 4 * g;
+        const float r0 = (acc[i][j][4 * q] - mean[i]) * rstd[i] * gg[j][q].x + be[j][q].x;
+        const float r1 = (acc[i][j][4 * q + 1] - mean[i]) * rstd[i] * gg[j][q].y + be[j][q].y;
+        const float r2 = (acc[i][j][4 * q + 2] - mean[i]) * rstd[i] * gg[j][q].z + be[j][q].z;
+        const float r3 = (acc[i][j][4 * q + 3] - mean[i]) * rstd[i] * gg[j][q].w + be[j][q].w;
+        if (kOutBf16)
+          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(obase) + row_off + n) =
+              make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+        else
+          *reinterpret_cast<float4*>(static_cast<float*>(obase) + row_off + n) =
+              make_float4(r0, r1, r2, r3);
+      }
   }
 }
 
@@ -469,6 +746,12 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_gather_kernel(
     const int ml = wm * WTM + i * 32 + l32;
     const int32_t desc = s_desc[ml];
     if (desc < 0) continue;
+    Pre4 pre[NT][4];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        pre[j][q] = ep.pre4(m0 + ml, n0 + wn * WTN + j * 32 + 8 * q + 4 * g, desc);
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
 #pragma unroll
@@ -476,7 +759,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_gather_kernel(
         const int n = n0 + wn * WTN + j * 32 + 8 * q + 4 * g;
         const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
                             acc[i][j][4 * q + 3]};
-        ep.store4(m0 + ml, n, v, desc);
+        ep.store4(m0 + ml, n, v, pre[j][q], desc);
       }
     }
   }
@@ -557,7 +840,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(AL al, const float* __res
     const int ml = ty * 4 + p;
     const int32_t desc = s_desc[ml];
     if (desc < 0) continue;
-    ep.store4(m0 + ml, n0 + tx * 4, acc[p], desc);
+    ep.store4(m0 + ml, n0 + tx * 4, acc[p], ep.pre4(m0 + ml, n0 + tx * 4, desc), desc);
   }
 }
 
@@ -641,6 +924,27 @@ hipError_t launch_f32(const AL& al, const void* W, int N, int K, const EP& ep,
 }
 
 }  // namespace
+
+bool gemm_residual_ln_supported(int d, bool use_bf16) { return use_bf16 && d == 256; }
+
+hipError_t launch_gemm_residual_ln(const void* A, const void* W, const float* bias, int d, int K,
+                                   float* resid, const float* ln_g, const float* ln_b, float eps,
+                                   void* out, bool out_is_bf16, int split_row, void* out2,
+                                   const int32_t* m_ptr, int m_host, int m_capacity,
+                                   hipStream_t s) {
+  if (d != 256 || K % BK != 0) return hipErrorInvalidValue;
+  constexpr int BM = 32, S = 4;
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* w = static_cast<const bf16_t*>(W);
+  dim3 grid((m_capacity + BM - 1) / BM);
+  if (out_is_bf16)
+    hipLaunchKernelGGL((gemm_bf16_rowln_kernel<BM, 256, S, true>), grid, dim3(256), 0, s, a, w, K,
+                       bias, resid, ln_g, ln_b, eps, out, split_row, out2, m_ptr, m_host);
+  else
+    hipLaunchKernelGGL((gemm_bf16_rowln_kernel<BM, 256, S, false>), grid, dim3(256), 0, s, a, w, K,
+                       bias, resid, ln_g, ln_b, eps, out, split_row, out2, m_ptr, m_host);
+  return hipGetLastError();
+}
 
 hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, int d,
                         bool use_bf16, const int32_t* m_ptr, int m_host, int m_capacity,

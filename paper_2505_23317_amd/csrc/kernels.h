@@ -78,6 +78,18 @@ hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, i
                        Epilogue epi, void* out_act, float* resid, bool use_bf16,
                        const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s);
 
+// Residual contraction followed by LayerNorm of the updated rows, in one kernel (bf16
+// operands): resid[M,d] += A[M,K] . W[d,K]^T + bias, then
+// out = LayerNorm(resid) * ln_g + ln_b in bf16 (out_is_bf16) or fp32; rows >= split_row
+// go to out2 (row - split_row) when out2 is given.  Only for the widths
+// gemm_residual_ln_supported names.
+bool gemm_residual_ln_supported(int d, bool use_bf16);
+hipError_t launch_gemm_residual_ln(const void* A, const void* W, const float* bias, int d, int K,
+                                   float* resid, const float* ln_g, const float* ln_b, float eps,
+                                   void* out, bool out_is_bf16, int split_row, void* out2,
+                                   const int32_t* m_ptr, int m_host, int m_capacity,
+                                   hipStream_t s);
+
 // bf16 query/key/value projection: q and k go to qk [M, 3d] (columns 0..2d, bias added,
 // q multiplied by q_scale = attention_q_scale(d_head) so that the attention kernel gets
 // base-2 logits straight from its first MFMA); v goes feature-major to vt [d, vt_ld] at

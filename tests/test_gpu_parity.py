@@ -352,7 +352,10 @@ def test_profile_interface_counts_launches(K):
     prof = K.cfdetr_profile_end(enc.ctx)
     # the coarse grids and the mixed sets go through the layers as ONE varlen batch
     assert prof["attention"]["launches"] == cfg.layers
-    assert prof["layernorm"]["launches"] == 2 * cfg.layers + 1
+    # d_model 256: every LayerNorm but the first runs inside the residual contraction
+    # before it
+    assert cfg.d == 256 and prof["layernorm"]["launches"] == 1
+    assert prof["out_proj"]["launches"] == cfg.layers and prof["ffn2"]["launches"] == cfg.layers
     assert prof["plan"]["launches"] == 1
     assert prof["select"]["launches"] == 1 and prof["gather"]["launches"] == 1
     assert prof["embed"]["launches"] == 2
