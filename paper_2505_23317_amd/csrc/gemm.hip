@@ -32,34 +32,35 @@ constexpr int BK = 64;
 constexpr int LDS_LD = BK + 8;  // padded row (elements) of the register-staged kernel
 
 // ---------------------------------------------------------------------------
-// Epilogues work on four consecutive columns n..n+3 of row m, in two steps:
-//   pre4(m, n, info)            loads what the result needs from memory (bias, residual,
-//                               position) and nothing else;
-//   store4(m, n, v, pre, info)  combines and stores.
-// A kernel calls pre4 for a whole batch of pieces before the first store4 of the batch:
-// loads and stores share one in-order counter on this hardware, so a load issued after a
-// store cannot be waited for without waiting for the store as well, and alternating them
-// costs a memory round trip per piece.
+// Epilogues work on four consecutive columns n..n+3 of row m.  Loads and stores are
+// separate calls:
+//   row_info(m)                    per-row datum (position of the token, descriptor);
+//   bias4(n)                       per-column addend, the same for every row;
+//   extra4(m, n, info)             per-element addend (residual, position) or zero;
+//   store4(m, n, v, b, x, info)    combines and stores, and loads nothing.
+// Loads and stores share one in-order counter on this hardware: a load issued after a
+// store cannot be waited for without waiting for the store as well, so alternating them
+// costs a memory round trip per piece.  The kernels therefore fetch row_info and bias4
+// before their main loop and extra4 in one batch per 32-row tile, ahead of its stores.
 // ---------------------------------------------------------------------------
-struct Pre4 {
-  float4 bias;
-  float4 extra;   // residual or position; unused by the plain epilogues
-};
+constexpr bool kNoExtra = false, kHasExtra = true;
 __device__ __forceinline__ float gelu_erf(float x) {
   return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
 }
 
-// x * Phi(x) with erfc from the five-term rational approximation of Abramowitz &
-// Stegun 7.1.26 (absolute error 1.5e-7, far below bf16 resolution).
+// x * Phi(x) for the bf16 path, with Phi(x) ~ 1 / (1 + exp(-x (a + b x^2 + c x^4))),
+// coefficients fitted to the erf form (maximum absolute error of the product 2.6e-5 over
+// all x, two orders below the bf16 resolution of the values that matter); x is clamped
+// to [-8, 8] inside the exponent, where the quartic is still positive.  The epilogue of
+// the first FFN contraction evaluates this once per output element, and with K = d the
+// main loop is short: seven plain operations and two transcendental ones per element
+// keep it well below the cost of the MFMA loop.
 __device__ __forceinline__ float gelu_fast(float x) {
-  const float z = fabsf(x) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
-  const float half_erfc = 0.5f * p * t * __builtin_amdgcn_exp2f(-1.4426950408889634f * z * z);
-  return x * (x >= 0.f ? 1.0f - half_erfc : half_erfc);
+  const float xc = __builtin_amdgcn_fmed3f(x, -8.0f, 8.0f);
+  const float x2 = xc * xc;
+  // -log2(e) * (a, b, c)
+  const float t = fmaf(fmaf(1.0142780e-03f, x2, -1.0677580e-01f), x2, -2.3011212e+00f) * xc;
+  return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
 template <typename TAct, bool kGelu>
@@ -70,16 +71,16 @@ struct EpiAct<bf16_t, kGelu> {
   const float* bias;
   bf16_t* out;
   int ldc;
+  static constexpr bool kExtra = kNoExtra;
   __device__ __forceinline__ int32_t row_info(int) const { return 0; }
-  __device__ __forceinline__ Pre4 pre4(int, int n, int32_t) const {
-    Pre4 p;
-    p.bias = *reinterpret_cast<const float4*>(bias + n);
-    p.extra = make_float4(0.f, 0.f, 0.f, 0.f);
-    return p;
+  __device__ __forceinline__ float4 bias4(int n) const {
+    return *reinterpret_cast<const float4*>(bias + n);
   }
-  __device__ __forceinline__ void store4(int m, int n, const float* v, const Pre4& pre,
-                                         int32_t) const {
-    const float4 b = pre.bias;
+  __device__ __forceinline__ float4 extra4(int, int, int32_t) const {
+    return make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  __device__ __forceinline__ void store4(int m, int n, const float* v, const float4& b,
+                                         const float4&, int32_t) const {
     float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
     if (kGelu) {
       r0 = gelu_fast(r0);
@@ -90,6 +91,23 @@ struct EpiAct<bf16_t, kGelu> {
     uint2 w = make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
     *reinterpret_cast<uint2*>(out + (size_t)m * ldc + n) = w;
   }
+  // staged form: the finished bf16 values go to LDS, rows leave it 16 bytes per lane
+  static constexpr int kStageElem = 2;
+  __device__ __forceinline__ bool staged(int) const { return true; }
+  __device__ __forceinline__ void stage4(unsigned char* p, int, const float* v,
+                                         const float4& b) const {
+    float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
+    if (kGelu) {
+      r0 = gelu_fast(r0);
+      r1 = gelu_fast(r1);
+      r2 = gelu_fast(r2);
+      r3 = gelu_fast(r3);
+    }
+    *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+  }
+  __device__ __forceinline__ void copy16(int m, int n, const uint4& d, const float4&) const {
+    *reinterpret_cast<uint4*>(out + (size_t)m * ldc + n) = d;
+  }
 };
 
 template <bool kGelu>
@@ -97,15 +115,15 @@ struct EpiAct<float, kGelu> {
   const float* bias;
   float* out;
   int ldc;
-  __device__ __forceinline__ Pre4 pre4(int, int n, int32_t) const {
-    Pre4 p;
-    p.bias = *reinterpret_cast<const float4*>(bias + n);
-    p.extra = make_float4(0.f, 0.f, 0.f, 0.f);
-    return p;
+  static constexpr bool kExtra = kNoExtra;
+  __device__ __forceinline__ float4 bias4(int n) const {
+    return *reinterpret_cast<const float4*>(bias + n);
   }
-  __device__ __forceinline__ void store4(int m, int n, const float* v, const Pre4& pre,
-                                         int32_t) const {
-    const float4 b = pre.bias;
+  __device__ __forceinline__ float4 extra4(int, int, int32_t) const {
+    return make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  __device__ __forceinline__ void store4(int m, int n, const float* v, const float4& b,
+                                         const float4&, int32_t) const {
     float4 r = make_float4(v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w);
     if (kGelu) r = make_float4(gelu_erf(r.x), gelu_erf(r.y), gelu_erf(r.z), gelu_erf(r.w));
     *reinterpret_cast<float4*>(out + (size_t)m * ldc + n) = r;
@@ -116,21 +134,37 @@ struct EpiResidual {
   const float* bias;
   float* resid;
   int ldc;
+  static constexpr bool kExtra = kHasExtra;
   __device__ __forceinline__ int32_t row_info(int) const { return 0; }
-  __device__ __forceinline__ Pre4 pre4(int m, int n, int32_t) const {
-    Pre4 p;
-    p.bias = *reinterpret_cast<const float4*>(bias + n);
-    p.extra = *reinterpret_cast<const float4*>(resid + (size_t)m * ldc + n);
-    return p;
+  __device__ __forceinline__ float4 bias4(int n) const {
+    return *reinterpret_cast<const float4*>(bias + n);
   }
-  __device__ __forceinline__ void store4(int m, int n, const float* v, const Pre4& pre,
-                                         int32_t) const {
-    const float4 b = pre.bias;
-    float4 x = pre.extra;
+  __device__ __forceinline__ float4 extra4(int m, int n, int32_t) const {
+    return *reinterpret_cast<const float4*>(resid + (size_t)m * ldc + n);
+  }
+  __device__ __forceinline__ void store4(int m, int n, const float* v, const float4& b,
+                                         const float4& xin, int32_t) const {
+    float4 x = xin;
     x.x += v[0] + b.x;
     x.y += v[1] + b.y;
     x.z += v[2] + b.z;
     x.w += v[3] + b.w;
+    *reinterpret_cast<float4*>(resid + (size_t)m * ldc + n) = x;
+  }
+  // staged form: v + bias goes to LDS in fp32; the residual rows are then read, updated
+  // and written 16 bytes per lane (extra4 fetches the old values, same arithmetic)
+  static constexpr int kStageElem = 4;
+  __device__ __forceinline__ bool staged(int) const { return true; }
+  __device__ __forceinline__ void stage4(unsigned char* p, int, const float* v,
+                                         const float4& b) const {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w);
+  }
+  __device__ __forceinline__ void copy16(int m, int n, const uint4& d, const float4& xin) const {
+    float4 x = xin;
+    x.x += __uint_as_float(d.x);
+    x.y += __uint_as_float(d.y);
+    x.z += __uint_as_float(d.z);
+    x.w += __uint_as_float(d.w);
     *reinterpret_cast<float4*>(resid + (size_t)m * ldc + n) = x;
   }
 };
@@ -153,15 +187,15 @@ struct EpiQkv {
     const int f = frame_of_token(cu, B, m);
     return pcu[f] + (m - cu[f]);
   }
-  __device__ __forceinline__ Pre4 pre4(int, int n, int32_t) const {
-    Pre4 p;
-    p.bias = *reinterpret_cast<const float4*>(bias + n);
-    p.extra = make_float4(0.f, 0.f, 0.f, 0.f);
-    return p;
+  static constexpr bool kExtra = kNoExtra;
+  __device__ __forceinline__ float4 bias4(int n) const {
+    return *reinterpret_cast<const float4*>(bias + n);
   }
-  __device__ __forceinline__ void store4(int m, int n, const float* v, const Pre4& pre,
-                                         int32_t pos) const {
-    const float4 b = pre.bias;
+  __device__ __forceinline__ float4 extra4(int, int, int32_t) const {
+    return make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  __device__ __forceinline__ void store4(int m, int n, const float* v, const float4& b,
+                                         const float4&, int32_t pos) const {
     float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
     if (n < d2) {
       if (2 * n < d2) {
@@ -180,6 +214,25 @@ struct EpiQkv {
       p[(size_t)3 * vt_ld] = f32_to_bf16(r3);
     }
   }
+  // staged form for the q and k columns (a wavefront's columns are all on one side of
+  // 2d); the v columns keep store4: with a token per lane their feature-major stores are
+  // already runs of 32 consecutive positions
+  static constexpr int kStageElem = 2;
+  __device__ __forceinline__ bool staged(int n_first) const { return n_first < d2; }
+  __device__ __forceinline__ void stage4(unsigned char* p, int n, const float* v,
+                                         const float4& b) const {
+    float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
+    if (2 * n < d2) {
+      r0 *= q_scale;
+      r1 *= q_scale;
+      r2 *= q_scale;
+      r3 *= q_scale;
+    }
+    *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+  }
+  __device__ __forceinline__ void copy16(int m, int n, const uint4& d, const float4&) const {
+    *reinterpret_cast<uint4*>(qk + (size_t)m * ldc + n) = d;
+  }
 };
 
 struct EpiEmbed {
@@ -189,18 +242,17 @@ struct EpiEmbed {
   float* out;
   float* out2;
   int d;
-  __device__ __forceinline__ Pre4 pre4(int, int n, int32_t desc) const {
+  static constexpr bool kExtra = kHasExtra;
+  __device__ __forceinline__ float4 bias4(int n) const {
+    return *reinterpret_cast<const float4*>(bias + n);
+  }
+  __device__ __forceinline__ float4 extra4(int, int n, int32_t desc) const {
     const int D = d >> 1;  // a multiple of 32: a run of four never straddles the halves
     const float* pe = (n < D) ? pe_row + tok_row(desc) * D + n : pe_col + tok_col(desc) * D + (n - D);
-    Pre4 p;
-    p.extra = *reinterpret_cast<const float4*>(pe);
-    p.bias = *reinterpret_cast<const float4*>(bias + n);
-    return p;
+    return *reinterpret_cast<const float4*>(pe);
   }
-  __device__ __forceinline__ void store4(int m, int n, const float* v, const Pre4& pre,
-                                         int32_t) const {
-    const float4 e = pre.extra;
-    const float4 b = pre.bias;
+  __device__ __forceinline__ void store4(int m, int n, const float* v, const float4& b,
+                                         const float4& e, int32_t) const {
     const float4 r = make_float4(v[0] + b.x + e.x, v[1] + b.y + e.y, v[2] + b.z + e.z,
                                  v[3] + b.w + e.w);
     *reinterpret_cast<float4*>(out + (size_t)m * d + n) = r;
@@ -235,18 +287,31 @@ __device__ __forceinline__ void dma16_untracked(const void* gptr, const unsigned
                : "memory");   // M0 is reserved: the compiler keeps nothing in it
 }
 
-template <int BM, int BN, int NWM, int NWN, typename EP>
+// Swizzle key of LDS row r for rows of ROWB bytes: the 16-byte chunks of a row are
+// stored at position chunk ^ key, which keeps the operand reads of 16 consecutive rows
+// (what one LDS cycle serves) on disjoint banks.
+template <int ROWB>
+__device__ __forceinline__ int lds_row_key(int r) {
+  return ROWB == 128 ? ((r >> 1) & 7) : ((r >> 2) & 3);
+}
+
+template <int BM, int BN, int NWM, int NWN, int kStages, int BKT, typename EP>
 __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int N, int K, EP ep,
     const int32_t* __restrict__ m_ptr, int m_host) {
   constexpr int NW = NWM * NWN;
   constexpr int WTM = BM / NWM, WTN = BN / NWN;      // wavefront tile
   constexpr int MT = WTM / 32, NT = WTN / 32;        // 32x32 MFMA tiles, each way
-  constexpr int A_INST = BM / (8 * NW), B_INST = BN / (8 * NW);  // 8 rows per wave instruction
-  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile / wavefront mismatch");
+  constexpr int ROWB = BKT * 2;                      // bytes of an LDS row (one K-slab of a row)
+  constexpr int CPR = ROWB / 16;                     // 16-byte chunks per row
+  constexpr int RPI = 64 / CPR;                      // rows one wave instruction fills (1 KB)
+  constexpr int A_INST = BM / (RPI * NW), B_INST = BN / (RPI * NW);
+  constexpr int LPW = A_INST + B_INST;               // loads a wavefront issues per slab
+  constexpr int STAGE = (BM + BN) * ROWB;            // bytes of one ring buffer (A rows, then W rows)
+  static_assert(BKT == 32 || BKT == 64, "slab width");
+  static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile / wavefront mismatch");
+  static_assert(kStages >= 2 && kStages <= 4 && (kStages - 2) * LPW < 64, "ring depth");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_direct[];
-  unsigned char* sA = smem_direct;                   // [2][BM * 128]
-  unsigned char* sB = smem_direct + 2 * BM * 128;    // [2][BN * 128]
 
   const int M = m_ptr ? *m_ptr : m_host;
   const int n_blocks = N / BN;
@@ -258,22 +323,22 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / NWN, wn = wave % NWN;
-  // Loader role: a wave instruction fills 8 consecutive LDS rows (1 KB).  Lane ->
-  // (row lane/8 of the group, LDS chunk position lane%8) and fetches the logical chunk
-  // position ^ swizzle key of that row.
-  const int lrow = lane >> 3, lpos = lane & 7;
+  // Loader role: a wave instruction fills RPI consecutive LDS rows (1 KB).  Lane ->
+  // (row lane/CPR of the group, LDS chunk position lane%CPR) and fetches the logical
+  // chunk position ^ swizzle key of that row.
+  const int lrow = lane / CPR, lpos = lane % CPR;
   const bf16_t* ag[A_INST];
   const bf16_t* wg[B_INST];
 #pragma unroll
   for (int j = 0; j < A_INST; ++j) {
-    const int rt = (wave * A_INST + j) * 8 + lrow;        // row inside the tile
+    const int rt = (wave * A_INST + j) * RPI + lrow;      // row inside the tile
     const int r = min(m0 + rt, M - 1);                    // rows past M: any valid row
-    ag[j] = A + (size_t)r * K + (lpos ^ ((rt >> 1) & 7)) * 8;
+    ag[j] = A + (size_t)r * K + (lpos ^ lds_row_key<ROWB>(rt)) * 8;
   }
 #pragma unroll
   for (int j = 0; j < B_INST; ++j) {
-    const int rt = (wave * B_INST + j) * 8 + lrow;
-    wg[j] = W + (size_t)(n0 + rt) * K + (lpos ^ ((rt >> 1) & 7)) * 8;
+    const int rt = (wave * B_INST + j) * RPI + lrow;
+    wg[j] = W + (size_t)(n0 + rt) * K + (lpos ^ lds_row_key<ROWB>(rt)) * 8;
   }
 
   f32x16 acc[MT][NT];
@@ -285,40 +350,68 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int l32 = lane & 31, g = lane >> 5;
-  const int nk = K / BK;
+  const int nk = K / BKT;
 
+  // What the epilogue needs per row and per column is requested now and arrives while
+  // the main loop runs.  Result layout (transposed product): lane -> row l32 of each
+  // 32-row tile, register r -> column 8*(r/4) + 4*g + (r%4) of each 32-column tile.
+  int32_t info[MT];
+  float4 bias_r[NT][4];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) info[i] = ep.row_info(min(m0 + wm * WTM + i * 32 + l32, M - 1));
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) bias_r[j][q] = ep.bias4(n0 + wn * WTN + j * 32 + 8 * q + 4 * g);
+
+  // K-slabs run through a ring of kStages buffers with kStages-1 slabs in flight: a slab
+  // takes its transfer time plus the memory latency to arrive, which is more than one
+  // slab of MFMA work, so a ring of two would wait on every slab.  The loads are issued
+  // in a form the compiler does not track, so the only waits are the explicit ones: vmcnt
+  // for the oldest slab, then a bare barrier that publishes it and retires every
+  // wavefront's reads of the buffer the next issue overwrites.
 #define CFDETR_ISSUE_SLAB(k0_, buf_)                                                          \
   do {                                                                                        \
-    _Pragma("unroll") for (int j = 0; j < A_INST; ++j) __builtin_amdgcn_global_load_lds(      \
-        (global_void_ptr)(ag[j] + (k0_)),                                                     \
-        (lds_void_ptr)(sA + (buf_) * (BM * 128) + (wave * A_INST + j) * 1024), 16, 0, 0);     \
-    _Pragma("unroll") for (int j = 0; j < B_INST; ++j) __builtin_amdgcn_global_load_lds(      \
-        (global_void_ptr)(wg[j] + (k0_)),                                                     \
-        (lds_void_ptr)(sB + (buf_) * (BN * 128) + (wave * B_INST + j) * 1024), 16, 0, 0);     \
+    unsigned char* st_ = smem_direct + (buf_) * STAGE;                                        \
+    _Pragma("unroll") for (int j = 0; j < A_INST; ++j)                                        \
+        dma16_untracked(ag[j] + (k0_), st_ + (wave * A_INST + j) * 1024);                     \
+    _Pragma("unroll") for (int j = 0; j < B_INST; ++j)                                        \
+        dma16_untracked(wg[j] + (k0_), st_ + BM * ROWB + (wave * B_INST + j) * 1024);         \
   } while (0)
 
-  CFDETR_ISSUE_SLAB(0, 0);
-  for (int it = 0; it < nk; ++it) {
-    // vmcnt(0): this wavefront's LDS writes of slab `it` have landed; the barrier then
-    // makes every wavefront's part visible and retires all reads of the other buffer.
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-    if (it + 1 < nk) CFDETR_ISSUE_SLAB((it + 1) * BK, (it + 1) & 1);
-    const unsigned char* pa = sA + (it & 1) * (BM * 128);
-    const unsigned char* pb = sB + (it & 1) * (BN * 128);
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+  for (int s = 0; s < kStages - 1; ++s)
+    if (s < nk) CFDETR_ISSUE_SLAB(s * BKT, s);
+  int buf = 0;   // ring position of slab `it`
+  for (int it = 0; it < nk; ++it) {
+    const int ahead = min(kStages - 2, nk - 1 - it);   // later slabs that may stay in flight
+    if (kStages == 4 && ahead >= 2)
+      __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LPW) & 15) | (((2 * LPW) >> 4) << 14));
+    else if (kStages >= 3 && ahead >= 1)
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (LPW & 15) | ((LPW >> 4) << 14));
+    else
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+    if (it + kStages - 1 < nk) {
+      const int nb = buf == 0 ? kStages - 1 : buf - 1;   // (buf + kStages - 1) % kStages
+      CFDETR_ISSUE_SLAB((it + kStages - 1) * BKT, nb);
+    }
+    const unsigned char* pa = smem_direct + buf * STAGE;
+    const unsigned char* pb = pa + BM * ROWB;
+    buf = buf + 1 == kStages ? 0 : buf + 1;
+#pragma unroll
+    for (int ks = 0; ks < BKT / 16; ++ks) {
       const int c = 2 * ks + g;  // logical 16-byte chunk of this lane's 8 k
       bf16x8 fa[MT], fb[NT];
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
         const int r = wm * WTM + i * 32 + l32;
-        fa[i] = *reinterpret_cast<const bf16x8*>(pa + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
+        fa[i] = *reinterpret_cast<const bf16x8*>(pa + r * ROWB + ((c ^ lds_row_key<ROWB>(r)) << 4));
       }
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const int r = wn * WTN + j * 32 + l32;
-        fb[j] = *reinterpret_cast<const bf16x8*>(pb + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
+        fb[j] = *reinterpret_cast<const bf16x8*>(pb + r * ROWB + ((c ^ lds_row_key<ROWB>(r)) << 4));
       }
 #pragma unroll
       for (int i = 0; i < MT; ++i)
@@ -329,19 +422,63 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   }
 #undef CFDETR_ISSUE_SLAB
 
-  // Result layout (transposed product): lane -> row m = l32, register r -> column
-  // 8*(r/4) + 4*g + (r%4).
+  // Epilogue, one 32-row tile of the wavefront at a time.  With a row per lane a store
+  // instruction would touch 32 rows with 16 bytes each; instead the finished values
+  // pass through a small LDS area of the wavefront's own (the ring is free now), from
+  // which rows leave as runs of 128 bytes and more, 16 bytes per lane.  LDS serves a
+  // wavefront's instructions in order, so its reads see its earlier writes.
+  constexpr int ES = EP::kStageElem;                    // bytes per staged element
+  constexpr int ROWBYTES = WTN * ES;
+  constexpr int STRIDE = ROWBYTES + 16;   // keeps the 16-byte reads aligned; the 8-byte bf16
+                                          // writes of rows r and r+16 share banks (2-way)
+  constexpr int LPR = ROWBYTES / 16;                    // lanes that copy one row
+  constexpr int RPC = 64 / LPR;                         // rows per copy instruction
+  constexpr int NCOPY = 32 / RPC;
+  static_assert(NW * 32 * STRIDE <= kStages * STAGE, "staging area exceeds the ring");
+  const int nw0 = n0 + wn * WTN;
+  __builtin_amdgcn_s_barrier();   // every wavefront is done reading the ring
+  if (ep.staged(nw0)) {
+    unsigned char* stg = smem_direct + wave * (32 * STRIDE);
+    const int crow = lane / LPR, cchunk = lane % LPR;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const int mb = m0 + wm * WTM + i * 32;
+      if (mb >= M) break;
+      float4 xin[NCOPY];
+      if (EP::kExtra) {
+#pragma unroll
+        for (int t = 0; t < NCOPY; ++t)
+          xin[t] = ep.extra4(min(mb + t * RPC + crow, M - 1), nw0 + cchunk * (16 / ES), info[i]);
+      }
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int nl = j * 32 + 8 * q + 4 * g;
+          const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                              acc[i][j][4 * q + 3]};
+          ep.stage4(stg + l32 * STRIDE + nl * ES, nw0 + nl, v, bias_r[j][q]);
+        }
+#pragma unroll
+      for (int t = 0; t < NCOPY; ++t) {
+        const int row = t * RPC + crow;
+        const uint4 d = *reinterpret_cast<const uint4*>(stg + row * STRIDE + cchunk * 16);
+        if (mb + row < M) ep.copy16(mb + row, nw0 + cchunk * (16 / ES), d, xin[t]);
+      }
+    }
+    return;
+  }
+  // direct form: the per-element addends of the tile in one batch, then its stores
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
     const int m = m0 + wm * WTM + i * 32 + l32;
     if (m >= M) continue;
-    const int32_t info = ep.row_info(m);
-    Pre4 pre[NT][4];
+    float4 extra[NT][4];
 #pragma unroll
     for (int j = 0; j < NT; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q)
-        pre[j][q] = ep.pre4(m, n0 + wn * WTN + j * 32 + 8 * q + 4 * g, info);
+        extra[j][q] = ep.extra4(m, n0 + wn * WTN + j * 32 + 8 * q + 4 * g, info[i]);
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
 #pragma unroll
@@ -349,7 +486,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
         const int n = n0 + wn * WTN + j * 32 + 8 * q + 4 * g;
         const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
                             acc[i][j][4 * q + 3]};
-        ep.store4(m, n, v, pre[j][q], info);
+        ep.store4(m, n, v, bias_r[j][q], extra[j][q], info[i]);
       }
     }
   }
@@ -380,7 +517,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_rowln_kernel(
   constexpr int WTN = D / 4, NT = WTN / 32;    // columns per wavefront, 32-column tiles
   constexpr int A_INST = BM / 32, B_INST = D / 32;   // 1 KB load instructions per wavefront
   constexpr int LPW = A_INST + B_INST;         // loads a wavefront issues per slab
-  static_assert(BM % 32 == 0 && D % 128 == 0, "tile shape");
+  static_assert(BM % 32 == 0 && D % 128 == 0, "tile shape");   // 32 columns per MFMA tile, 4 wavefronts
   static_assert(kStages == 3 || kStages == 4, "ring of 3 or 4 buffers");
   static_assert((kStages - 2) * LPW < 64, "vmcnt is a 6-bit counter");
   __shared__ __attribute__((aligned(1024))) unsigned char sA0[BM * 128], sA1[BM * 128],
@@ -746,12 +883,15 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_gather_kernel(
     const int ml = wm * WTM + i * 32 + l32;
     const int32_t desc = s_desc[ml];
     if (desc < 0) continue;
-    Pre4 pre[NT][4];
+    float4 bias_r[NT][4], extra[NT][4];
 #pragma unroll
     for (int j = 0; j < NT; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        pre[j][q] = ep.pre4(m0 + ml, n0 + wn * WTN + j * 32 + 8 * q + 4 * g, desc);
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn * WTN + j * 32 + 8 * q + 4 * g;
+        bias_r[j][q] = ep.bias4(n);
+        extra[j][q] = ep.extra4(m0 + ml, n, desc);
+      }
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
 #pragma unroll
@@ -759,7 +899,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_gather_kernel(
         const int n = n0 + wn * WTN + j * 32 + 8 * q + 4 * g;
         const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
                             acc[i][j][4 * q + 3]};
-        ep.store4(m0 + ml, n, v, pre[j][q], desc);
+        ep.store4(m0 + ml, n, v, bias_r[j][q], extra[j][q], desc);
       }
     }
   }
@@ -840,7 +980,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(AL al, const float* __res
     const int ml = ty * 4 + p;
     const int32_t desc = s_desc[ml];
     if (desc < 0) continue;
-    ep.store4(m0 + ml, n0 + tx * 4, acc[p], ep.pre4(m0 + ml, n0 + tx * 4, desc), desc);
+    ep.store4(m0 + ml, n0 + tx * 4, acc[p], ep.bias4(n0 + tx * 4),
+              ep.extra4(m0 + ml, n0 + tx * 4, desc), desc);
   }
 }
 
@@ -859,11 +1000,12 @@ hipError_t allow_lds(Kern kern, size_t bytes, bool* configured) {
   return e;
 }
 
-template <int BM, int BN, int NWM, int NWN, typename EP>
+template <int BM, int BN, int NWM, int NWN, int S, int BKT, typename EP>
 hipError_t launch_direct_tile(const bf16_t* A, const bf16_t* w, int N, int K, const EP& ep,
                               const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
-  auto kern = gemm_bf16_direct_kernel<BM, BN, NWM, NWN, EP>;
-  constexpr size_t lds = (size_t)2 * (BM + BN) * 128;
+  auto kern = gemm_bf16_direct_kernel<BM, BN, NWM, NWN, S, BKT, EP>;
+  constexpr size_t lds = (size_t)S * (BM + BN) * BKT * 2;
+  static_assert(lds <= 160 * 1024, "ring exceeds the LDS");
   static bool configured = false;
   hipError_t e = allow_lds(kern, lds, &configured);
   if (e != hipSuccess) return e;
@@ -881,11 +1023,13 @@ hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& e
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* w = static_cast<const bf16_t*>(W);
   const long tiles128 = (long)((m_capacity + 127) / 128) * (N / 128);
+  // A deeper ring (3 or 4 buffers, also with slabs of 32) measured no faster for these
+  // tiles: their main loops are bound by LDS traffic, not by the latency of the loads.
   if (N % 256 == 0 && N >= 2048 && m_capacity >= 16384)
-    return launch_direct_tile<256, 256, 2, 4>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+    return launch_direct_tile<256, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
   if (N % 128 == 0 && tiles128 >= 256)
-    return launch_direct_tile<128, 128, 2, 2>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
-  return launch_direct_tile<64, 64, 2, 2>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+    return launch_direct_tile<128, 128, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+  return launch_direct_tile<64, 64, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
 }
 
 template <int BM, int BN, typename TPix>
@@ -925,25 +1069,43 @@ hipError_t launch_f32(const AL& al, const void* W, int N, int K, const EP& ep,
 
 }  // namespace
 
+// Width 384 would fit too (three ring buffers), but a workgroup then streams 48 KB of
+// weights per 32 rows and slab, and the pair of separate kernels is faster (measured).
 bool gemm_residual_ln_supported(int d, bool use_bf16) { return use_bf16 && d == 256; }
 
+namespace {
+
+template <int D, int S>
+hipError_t launch_rowln(const bf16_t* a, const bf16_t* w, const float* bias, int K, float* resid,
+                        const float* ln_g, const float* ln_b, float eps, void* out,
+                        bool out_is_bf16, int split_row, void* out2, const int32_t* m_ptr,
+                        int m_host, int m_capacity, hipStream_t s) {
+  constexpr int BM = 32;
+  dim3 grid((m_capacity + BM - 1) / BM);
+  if (out_is_bf16)
+    hipLaunchKernelGGL((gemm_bf16_rowln_kernel<BM, D, S, true>), grid, dim3(256), 0, s, a, w, K,
+                       bias, resid, ln_g, ln_b, eps, out, split_row, out2, m_ptr, m_host);
+  else
+    hipLaunchKernelGGL((gemm_bf16_rowln_kernel<BM, D, S, false>), grid, dim3(256), 0, s, a, w, K,
+                       bias, resid, ln_g, ln_b, eps, out, split_row, out2, m_ptr, m_host);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// The ring takes as many buffers of (32 + d) rows x 128 bytes as the 160 KB of LDS hold.
 hipError_t launch_gemm_residual_ln(const void* A, const void* W, const float* bias, int d, int K,
                                    float* resid, const float* ln_g, const float* ln_b, float eps,
                                    void* out, bool out_is_bf16, int split_row, void* out2,
                                    const int32_t* m_ptr, int m_host, int m_capacity,
                                    hipStream_t s) {
-  if (d != 256 || K % BK != 0) return hipErrorInvalidValue;
-  constexpr int BM = 32, S = 4;
+  if (K % BK != 0) return hipErrorInvalidValue;
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* w = static_cast<const bf16_t*>(W);
-  dim3 grid((m_capacity + BM - 1) / BM);
-  if (out_is_bf16)
-    hipLaunchKernelGGL((gemm_bf16_rowln_kernel<BM, 256, S, true>), grid, dim3(256), 0, s, a, w, K,
-                       bias, resid, ln_g, ln_b, eps, out, split_row, out2, m_ptr, m_host);
-  else
-    hipLaunchKernelGGL((gemm_bf16_rowln_kernel<BM, 256, S, false>), grid, dim3(256), 0, s, a, w, K,
-                       bias, resid, ln_g, ln_b, eps, out, split_row, out2, m_ptr, m_host);
-  return hipGetLastError();
+  if (d == 256)
+    return launch_rowln<256, 4>(a, w, bias, K, resid, ln_g, ln_b, eps, out, out_is_bf16, split_row,
+                                out2, m_ptr, m_host, m_capacity, s);
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, int d,
