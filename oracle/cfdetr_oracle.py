@@ -18,7 +18,11 @@ What it computes, and where the paper states it:
   else, so each frame gets a mixed-granularity token set;
 * multi-level batching (A3, Sec. III-B) runs several frames' token sets, of
   different lengths, through the encoder together; batching is a latency
-  device and must not change any frame's result.
+  device and must not change any frame's result;
+* the coarse stage's object queries decide whether a frame is easy or hard
+  (A1: average confidence of the queries that are not already certain) and,
+  for hard frames, propose the regions to refine (A2: the boxes of the
+  queries of intermediate confidence).
 
 The paper fixes the structure only.  Every numerical choice below that it is
 silent on (linear patch projection, quadtree split rule, level-major token
@@ -117,6 +121,74 @@ def select_fine(boxes: np.ndarray, tier: np.ndarray, box_offsets: np.ndarray,
         cu.append(len(toks))
     return (np.asarray(toks, dtype=np.int64).reshape(-1, 3),
             np.asarray(cu, dtype=np.int64), counts)
+
+
+# --------------------------------------------------------------------------
+# A1 (difficulty of a frame) and A2 (regions of interest) from the coarse
+# stage's object queries
+# --------------------------------------------------------------------------
+def frame_hardness(conf: np.ndarray, tau_hi: float, tau_lo: float) -> Tuple[bool, float]:
+    """Difficulty of one frame from its query confidences (Sec. III-B, A1).
+
+    Queries above ``tau_hi`` are the prominent, already certain objects and are
+    left out; the confidences of all the others are averaged; a frame whose
+    average is below ``tau_lo`` is easy, any other frame is hard.  Reading
+    where the paper is silent: with no query left the average is 0 (easy).
+    Returns (hard, average)."""
+    c = np.asarray(conf, dtype=np.float64)
+    rest = c[~(c > tau_hi)]
+    mean = float(rest.sum() / len(rest)) if len(rest) else 0.0
+    return (not mean < tau_lo), mean
+
+
+def roi_box(cx: float, cy: float, w: float, h: float, H: int, W: int,
+            scale: float = 1.0, min_side: float = 0.0) -> Tuple[int, int, int, int]:
+    """Pixel rectangle of one query box (Sec. III-B, A2: regions are proposed from
+    the location and size of the queries).
+
+    Readings: (cx, cy, w, h) are the centre and the size as fractions of the frame;
+    the region is the box scaled by ``scale`` about its centre and at least
+    ``min_side`` pixels wide and high (the adjustable region size of the paper's
+    draft); the half-open pixel rectangle is the smallest one that covers it
+    (lower edges rounded down, upper edges up), clipped to the frame.  The
+    arithmetic is float64 in this order: half = max(0.5*scale*size*extent,
+    0.5*min_side); edges = centre*extent -/+ half."""
+    half_w = max(0.5 * scale * w * W, 0.5 * min_side)
+    half_h = max(0.5 * scale * h * H, 0.5 * min_side)
+    x0 = math.floor(cx * W - half_w)
+    x1 = math.ceil(cx * W + half_w)
+    y0 = math.floor(cy * H - half_h)
+    y1 = math.ceil(cy * H + half_h)
+    return (min(max(x0, 0), W), min(max(y0, 0), H), min(max(x1, 0), W), min(max(y1, 0), H))
+
+
+def propose_rois(queries: np.ndarray, H: int, W: int, tau_hi: float, tau_lo: float,
+                 tier: int, scale: float = 1.0, min_side: float = 0.0):
+    """A1 difficulty test and A2 region proposal for a batch (Sec. III-B).
+
+    queries [B, Q, 5] = (cx, cy, w, h, c).  An easy frame proposes nothing (its
+    fine pass is skipped or equals its coarse pass); a hard frame proposes one
+    region per query of intermediate confidence, tau_lo < c <= tau_hi, in query
+    order, all with the refinement level ``tier``.
+    Returns boxes int32 [n,4], tier uint8 [n], box_offsets int32 [B+1],
+    hard int32 [B], mean float64 [B]."""
+    q = np.asarray(queries, dtype=np.float64)
+    B = q.shape[0]
+    boxes: List[Tuple[int, int, int, int]] = []
+    offs = [0]
+    hard = np.zeros(B, dtype=np.int32)
+    mean = np.zeros(B, dtype=np.float64)
+    for f in range(B):
+        is_hard, mean[f] = frame_hardness(q[f, :, 4], tau_hi, tau_lo)
+        hard[f] = int(is_hard)
+        if is_hard:
+            for k in range(q.shape[1]):
+                cx, cy, w, h, c = q[f, k]
+                if tau_lo < c <= tau_hi:
+                    boxes.append(roi_box(cx, cy, w, h, H, W, scale, min_side))
+        offs.append(len(boxes))
+    b = np.asarray(boxes, dtype=np.int32).reshape(-1, 4)
+    return (b, np.full(len(b), tier, dtype=np.uint8), np.asarray(offs, dtype=np.int32), hard, mean)
 
 
 def pack_tok_desc(tok: np.ndarray) -> np.ndarray:
