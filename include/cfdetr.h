@@ -134,7 +134,8 @@ typedef enum {
   CFDETR_K_OUT = 7,    /* output projection + residual                         */
   CFDETR_K_FF1 = 8,    /* first FFN projection + GELU                          */
   CFDETR_K_FF2 = 9,    /* second FFN projection + residual                     */
-  CFDETR_K_COUNT = 10
+  CFDETR_K_ROI = 10,   /* difficulty test and region proposal                  */
+  CFDETR_K_COUNT = 11
 } cfdetr_kernel_id;
 
 /* Host-side.  Validates cfg, copies it, keeps the weight POINTERS, allocates
@@ -164,6 +165,47 @@ CFDETR_API cfdetr_status cfdetr_sync_status(cfdetr_ctx* ctx, void* hip_stream);
  */
 CFDETR_API cfdetr_status cfdetr_coarse_encode(cfdetr_ctx* ctx, const void* images, int32_t B,
                                    float* x0_cache, float* y_coarse, void* hip_stream);
+
+/*
+ * Parameters of the difficulty test and the region proposal (host memory).
+ * Sec. III-B quotes tau_hi = 0.8 and tau_lo = 0.05 as examples.
+ */
+typedef struct {
+  float tau_hi;   /* a query with confidence above this is a certain, prominent object */
+  float tau_lo;   /* a frame is easy iff the average confidence of its other queries is
+                     below this; queries in (tau_lo, tau_hi] propose regions          */
+  float scale;    /* a region is the query's box scaled by this about its centre (1 = box) */
+  float min_side; /* least width and height of a region, in pixels (0 = none)          */
+  int32_t tier;   /* refinement level the regions ask for, 0..n_levels-1               */
+} cfdetr_roi_params;
+
+/*
+ * A1 difficulty test and A2 region proposal from the coarse stage's object queries
+ * (Sec. III-B, A1: queries above tau_hi are left out, the confidences of the others
+ * are averaged, a frame whose average is below tau_lo is easy and skips the fine
+ * stage; A2: the regions of a hard frame come from the location and size of its
+ * queries of intermediate confidence).
+ *   queries     [B, Q, 5] fp32 (cx, cy, w, h, c): centre and size of the candidate
+ *               box as fractions of the frame, confidence in [0, 1]; finite values;
+ *               16-byte aligned; 1 <= Q <= 65536
+ *   params      host pointer; tau_lo <= tau_hi, scale >= 0, min_side >= 0
+ *   max_boxes   capacity of boxes / tier
+ * Outputs (device), in the form cfdetr_select_fine takes:
+ *   boxes       [max_boxes, 4] int32 half-open pixel rectangles, smallest cover of the
+ *               scaled box, clipped to the frame; frame after frame, query order
+ *   tier        [max_boxes] uint8, params->tier for every region
+ *   box_offsets [B+1] int32
+ *   hard        [B] int32: 1 = hard; an easy frame proposes no region
+ *   mean_conf   [B] fp32: the average that decided it (0 if no query was left)
+ * Decisions are taken in fp64 on the fp32 inputs.  More than max_boxes regions in
+ * total: nothing is proposed (all offsets 0), a sticky flag is raised and
+ * cfdetr_sync_status returns CFDETR_ECAPACITY.
+ */
+CFDETR_API cfdetr_status cfdetr_propose_rois(cfdetr_ctx* ctx, const float* queries, int32_t B,
+                                  int32_t Q, const cfdetr_roi_params* params,
+                                  int32_t max_boxes, int32_t* boxes, uint8_t* tier,
+                                  int32_t* box_offsets, int32_t* hard, float* mean_conf,
+                                  void* hip_stream);
 
 /*
  * A2, selective patch split as integer work only (Sec. III-B, A2).

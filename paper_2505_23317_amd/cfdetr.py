@@ -24,13 +24,14 @@ CFDETR_OK, CFDETR_EINVAL, CFDETR_ESHAPE, CFDETR_ECAPACITY, CFDETR_ENOMEM, CFDETR
 CFDETR_BF16, CFDETR_FP32 = 0, 1
 CFDETR_MAX_LEVELS = 3
 KERNEL_NAMES = ["select", "plan", "embed", "gather", "layernorm", "qkv", "attention",
-                "out_proj", "ffn1", "ffn2"]
+                "out_proj", "ffn1", "ffn2", "roi"]
 CFDETR_K_COUNT = len(KERNEL_NAMES)
 STATUS_NAMES = ["OK", "EINVAL", "ESHAPE", "ECAPACITY", "ENOMEM", "EDEVICE"]
 
 EXPORTS = [
     "cfdetr_create", "cfdetr_destroy", "cfdetr_last_error", "cfdetr_workspace_bytes",
-    "cfdetr_sync_status", "cfdetr_coarse_encode", "cfdetr_select_fine", "cfdetr_fine_encode",
+    "cfdetr_sync_status", "cfdetr_coarse_encode", "cfdetr_propose_rois", "cfdetr_select_fine",
+    "cfdetr_fine_encode",
     "cfdetr_multilevel_batch", "cfdetr_profile_begin", "cfdetr_profile_end",
 ]
 
@@ -46,6 +47,12 @@ class CfdetrConfig(ctypes.Structure):
         ("image_dtype", ctypes.c_int), ("act_dtype", ctypes.c_int),
         ("ln_eps", ctypes.c_float),
     ]
+
+
+class CfdetrRoiParams(ctypes.Structure):
+    _fields_ = [("tau_hi", ctypes.c_float), ("tau_lo", ctypes.c_float),
+                ("scale", ctypes.c_float), ("min_side", ctypes.c_float),
+                ("tier", ctypes.c_int32)]
 
 
 class CfdetrWeights(ctypes.Structure):
@@ -89,6 +96,9 @@ def load_library() -> ctypes.CDLL:
     lib.cfdetr_sync_status.restype = ctypes.c_int
     lib.cfdetr_coarse_encode.argtypes = [vp, vp, i32, vp, vp, vp]
     lib.cfdetr_coarse_encode.restype = ctypes.c_int
+    lib.cfdetr_propose_rois.argtypes = [vp, vp, i32, i32, ctypes.POINTER(CfdetrRoiParams), i32,
+                                        vp, vp, vp, vp, vp, vp]
+    lib.cfdetr_propose_rois.restype = ctypes.c_int
     lib.cfdetr_select_fine.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.cfdetr_select_fine.restype = ctypes.c_int
     lib.cfdetr_fine_encode.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
@@ -145,6 +155,13 @@ def cfdetr_sync_status(ctx: int, stream: int = 0) -> None:
 
 def cfdetr_coarse_encode(ctx, images, B, x0_cache, y_coarse, stream=0) -> None:
     _check(load_library().cfdetr_coarse_encode(ctx, images, B, x0_cache, y_coarse, stream), ctx)
+
+
+def cfdetr_propose_rois(ctx, queries, B, Q, params: CfdetrRoiParams, max_boxes, boxes, tier,
+                        box_offsets, hard, mean_conf, stream=0) -> None:
+    _check(load_library().cfdetr_propose_rois(ctx, queries, B, Q, ctypes.byref(params), max_boxes,
+                                              boxes, tier, box_offsets, hard, mean_conf, stream),
+           ctx)
 
 
 def cfdetr_select_fine(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts,
@@ -271,6 +288,14 @@ class Encoder:
         cfdetr_coarse_encode(self.ctx, images.data_ptr(), B,
                              x0_cache.data_ptr() if x0_cache is not None else None,
                              y_coarse.data_ptr(), self._stream())
+
+    def propose_rois(self, queries, params: CfdetrRoiParams, boxes, tier, box_offsets, hard,
+                     mean_conf):
+        """queries: float32 device tensor [B, Q, 5]; the other tensors are outputs."""
+        B, Q = int(queries.shape[0]), int(queries.shape[1])
+        cfdetr_propose_rois(self.ctx, queries.data_ptr(), B, Q, params, int(boxes.shape[0]),
+                            boxes.data_ptr(), tier.data_ptr(), box_offsets.data_ptr(),
+                            hard.data_ptr(), mean_conf.data_ptr(), self._stream())
 
     def select_fine(self, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts=None):
         cfdetr_select_fine(self.ctx, boxes.data_ptr(), tier.data_ptr(), box_offsets.data_ptr(), B,

@@ -49,6 +49,7 @@ struct cfdetr_ctx {
   int cap8 = 0;               // entries per queue (one queue per XCD)
   int32_t* queue_heads = nullptr;   // 8 fetch counters per layer, set by the plan kernel
   int attn_grid = 0;                // workgroups of an attention launch
+  int32_t* n_roi = nullptr;         // regions per frame (scratch of the region proposal)
   int block_q = 0;
   int32_t* err_flag = nullptr;
 
@@ -404,6 +405,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->hit_bytes = (int)hit_bytes;
   const uint64_t o_items = cv.take((uint64_t)c->cap8 * 8 * 4), o_err = cv.take(4);
   const uint64_t o_qh = cv.take((uint64_t)cfg->n_layers * 8 * 4);
+  const uint64_t o_nroi = cv.take((uint64_t)kMaxBatch * 4);
   c->arena_bytes = cv.off;
   e = hipMalloc(&c->arena, c->arena_bytes);
   if (e != hipSuccess) {
@@ -433,6 +435,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->items = reinterpret_cast<int32_t*>(base + o_items);
   c->err_flag = reinterpret_cast<int32_t*>(base + o_err);
   c->queue_heads = reinterpret_cast<int32_t*>(base + o_qh);
+  c->n_roi = reinterpret_cast<int32_t*>(base + o_nroi);
 
   // static tables: coarse grid descriptors, zeroed counters, position tables
   std::vector<int32_t> desc(Bm * c->n0), cu(Bm + 1);
@@ -500,6 +503,30 @@ CFDETR_API cfdetr_status cfdetr_coarse_encode(cfdetr_ctx* ctx, const void* image
   if (!aligned16(images) || !aligned16(y_coarse) || !aligned16(x0_cache))
     return fail(ctx, CFDETR_EINVAL, "pointers must be 16-byte aligned");
   return coarse_impl(ctx, images, B, x0_cache, y_coarse, static_cast<hipStream_t>(hip_stream));
+}
+
+CFDETR_API cfdetr_status cfdetr_propose_rois(cfdetr_ctx* ctx, const float* queries, int32_t B,
+                                  int32_t Q, const cfdetr_roi_params* params,
+                                  int32_t max_boxes, int32_t* boxes, uint8_t* tier,
+                                  int32_t* box_offsets, int32_t* hard, float* mean_conf,
+                                  void* hip_stream) {
+  cfdetr_status st = check_call(ctx, B);
+  if (st != CFDETR_OK) return st;
+  if (!queries || !params || !boxes || !tier || !box_offsets || !hard || !mean_conf)
+    return fail(ctx, CFDETR_EINVAL, "null pointer");
+  if (!aligned16(queries) || !aligned16(boxes))
+    return fail(ctx, CFDETR_EINVAL, "queries and boxes must be 16-byte aligned");
+  if (Q < 1 || Q > 65536 || max_boxes < 0) return fail(ctx, CFDETR_EINVAL, "bad query or box count");
+  if (!(params->tau_lo <= params->tau_hi) || !(params->scale >= 0.f) ||
+      !(params->min_side >= 0.f) || params->tier < 0 || params->tier >= ctx->cfg.n_levels)
+    return fail(ctx, CFDETR_EINVAL, "bad region parameters");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  CF_LAUNCH(CFDETR_K_ROI,
+            launch_propose_rois(queries, B, Q, ctx->cfg.img_h, ctx->cfg.img_w, params->tau_hi,
+                                params->tau_lo, params->scale, params->min_side, params->tier,
+                                ctx->n_roi, max_boxes, boxes, tier, box_offsets, hard, mean_conf,
+                                ctx->err_flag, s));
+  return CFDETR_OK;
 }
 
 CFDETR_API cfdetr_status cfdetr_select_fine(cfdetr_ctx* ctx, const int32_t* boxes, const uint8_t* tier,

@@ -17,6 +17,20 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
                          int32_t* cu_seqlens, int32_t* level_counts, int32_t* err_flag,
                          hipStream_t s);
 
+// ---- A1 difficulty test + A2 region proposal (roi.hip) ----------------------
+// queries [B, Q, 5] = (cx, cy, w, h, c), centre and size as fractions of the frame.
+// Frame f is hard unless the average of its confidences not above tau_hi is below
+// tau_lo; a hard frame proposes, in query order, the box of every query with
+// tau_lo < c <= tau_hi, scaled by `scale` about its centre, at least min_side pixels
+// wide and high, rounded outward to pixels and clipped, with refinement level
+// tier_value.  Writes hard[B], mean_conf[B], n_roi[B] (scratch), boxes/tier (at most
+// max_boxes; a larger total proposes nothing and raises *err_flag) and box_offsets[B+1].
+hipError_t launch_propose_rois(const float* queries, int B, int Q, int H, int W, float tau_hi,
+                               float tau_lo, float scale, float min_side, int tier_value,
+                               int32_t* n_roi, int max_boxes, int32_t* boxes, uint8_t* tier,
+                               int32_t* box_offsets, int32_t* hard, float* mean_conf,
+                               int32_t* err_flag, hipStream_t s);
+
 // Sequence list and attention work list of one encoder run.  The sequences are
 // n_prefix sequences of prefix_len tokens (coarse grids of a merged run; may be 0)
 // followed by the B sequences delimited by cu_seqlens.  Writes cu_all[0..nseq] and

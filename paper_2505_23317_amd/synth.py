@@ -20,7 +20,7 @@ import numpy as np
 
 __all__ = [
     "Config", "CONFIGS", "config", "bf16_round", "bf16_bits", "make_weights",
-    "make_frames", "make_workload", "replace",
+    "make_frames", "make_workload", "make_queries", "replace",
 ]
 
 
@@ -241,3 +241,32 @@ def make_workload(cfg_or_id, seed: Optional[int] = None, sharp: bool = False) ->
         "box_offsets": box_offsets, "frac": frac,
         "weights": make_weights(cfg, 7 + seed, sharp=sharp),
     }
+
+
+def make_queries(cfg: Config, seed: int, n_queries: int = 128, easy_frames=()) -> np.ndarray:
+    """Object queries of the coarse stage for every frame, float32 [B, Q, 5] =
+    (cx, cy, w, h, c) with centre and size as fractions of the frame.
+
+    Per frame: a few certain objects (c in (0.8, 1)), a Poisson number (mean 24 per 128 queries) of uncertain ones
+    (c in (0.05, 0.8)) with the side law of the critical boxes, and background queries
+    with c exponential around 0.01 (clipped to 0.05).  Frames listed in easy_frames get
+    no uncertain query.  The values only have the shape of a detector's output; no
+    detector was run."""
+    B = cfg.B
+    q = np.zeros((B, n_queries, 5), dtype=np.float32)
+    for f in range(B):
+        rng = np.random.default_rng(7000 * seed + f)
+        n_hi = int(rng.integers(1, 6))
+        n_mid = 0 if f in easy_frames else int(min(n_queries - n_hi, max(1, rng.poisson(24.0 * n_queries / 128))))
+        kinds = np.array([2] * n_hi + [1] * n_mid + [0] * (n_queries - n_hi - n_mid))
+        rng.shuffle(kinds)
+        side = rng.uniform(cfg.side_lo, cfg.side_hi, (n_queries, 2))
+        q[f, :, 0] = rng.uniform(0.0, 1.0, n_queries)
+        q[f, :, 1] = rng.uniform(0.0, 1.0, n_queries)
+        q[f, :, 2] = side[:, 0] / cfg.W
+        q[f, :, 3] = side[:, 1] / cfg.H
+        c = np.minimum(rng.exponential(0.01, n_queries), 0.05)
+        c = np.where(kinds == 1, rng.uniform(0.0501, 0.8, n_queries), c)
+        c = np.where(kinds == 2, rng.uniform(0.8001, 1.0, n_queries), c)
+        q[f, :, 4] = c
+    return q
