@@ -184,6 +184,46 @@ def measure(cfg_id, steps, warmup, profile_steps):
     }
 
 
+def padded_comparison(cfg_id, steps, warmup):
+    """Fine pass alone: variable-length form against the paper's padded form (every
+    frame's token set brought to the length of the longest), same token sets."""
+    import torch
+    from paper_2505_23317_amd import cfdetr, synth
+
+    cfg = synth.config(cfg_id)
+    wl = synth.make_workload(cfg_id)
+    enc = cfdetr.Encoder(cfg, wl["weights"], act_dtype="bf16")
+    img = enc.upload_images(wl["images"])
+    b, t, o = enc.upload_boxes(wl["boxes"], wl["tier"], wl["box_offsets"])
+    out = enc.alloc_outputs(cfg.B)
+    enc.coarse_encode(img, cfg.B, out["x0_cache"], out["y_coarse"])
+    enc.select_fine(b, t, o, cfg.B, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
+    torch.cuda.synchronize()
+    lens = np.diff(out["cu_seqlens"].cpu().numpy())
+    t_pad = int(lens.max())
+    y_pad = torch.zeros((cfg.B * t_pad, cfg.d), dtype=torch.float32, device="cuda")
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return 1e3 * (time.perf_counter() - t0) / steps
+
+    ms_var = timed(lambda: enc.fine_encode(img, cfg.B, out["tok_desc"], out["cu_seqlens"],
+                                           out["x0_cache"], out["y_mixed"]))
+    ms_pad = timed(lambda: enc.fine_encode_padded(img, cfg.B, out["tok_desc"], out["cu_seqlens"],
+                                                  out["x0_cache"], t_pad, y_pad))
+    enc.sync_status()
+    enc.close()
+    return {"workload": f"configs[{cfg_id - 1}] {cfg.name}", "step": "fine pass only",
+            "tokens_real": int(lens.sum()), "tokens_padded": int(cfg.B * t_pad),
+            "ms_varlen": ms_var, "ms_padded": ms_pad, "padded_over_varlen": ms_pad / ms_var}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -192,6 +232,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3)")
     ap.add_argument("--profile-steps", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--compare-padded", action="store_true",
+                    help="also time the fine pass in the paper's padded form against the "
+                         "variable-length form (adds padded_baseline to the line)")
     ap.add_argument("--no-others", action="store_true",
                     help="skip the short extra measurements of the two largest configs")
     args = ap.parse_args()
@@ -246,6 +289,9 @@ def main() -> int:
                            "whole_step_mfma_frac": mo["whole_step_mfma_frac"],
                            "roofline": mo["roofline"]})
         result["other_workloads"] = others
+    if args.compare_padded:
+        result["padded_baseline"] = [padded_comparison(c, 20, 3)
+                                     for c in sorted({args.config, 3, 4})]
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, m["wl"], args.config)
     print(json.dumps(result))

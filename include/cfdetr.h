@@ -241,6 +241,24 @@ CFDETR_API cfdetr_status cfdetr_fine_encode(cfdetr_ctx* ctx, const void* images,
                                  const float* x0_cache, float* y_mixed, void* hip_stream);
 
 /*
+ * The fine pass in the form the paper describes for A3 (Sec. III-B): the token sets of
+ * the batch are padded to one length and go through the encoder as a dense batch; this
+ * library masks the padded keys, so every real token gets exactly the result
+ * cfdetr_fine_encode gives it.  A measurement mode: it shows what the variable-length
+ * form saves.
+ *   t_pad     tokens per frame after padding (host value), at least the longest frame of
+ *             the batch and the coarse grid size; B * t_pad <= max_tokens_total
+ *   y_padded  [B * t_pad, d] fp32 out: row f*t_pad + j is token j of frame f; rows of
+ *             padding hold finite values without meaning
+ * A frame longer than t_pad raises the sticky capacity flag (cfdetr_sync_status) and its
+ * surplus tokens are ignored.  Other arguments as in cfdetr_fine_encode.
+ */
+CFDETR_API cfdetr_status cfdetr_fine_encode_padded(cfdetr_ctx* ctx, const void* images, int32_t B,
+                                        const int32_t* tok_desc, const int32_t* cu_seqlens,
+                                        const float* x0_cache, int32_t t_pad, float* y_padded,
+                                        void* hip_stream);
+
+/*
  * A1 -> A2 -> A3 in one call with no host synchronisation in between
  * (Sec. III-B, A1-A3).  Outputs are bit-identical to those of the three calls
  * above, but the encoder runs once: the B coarse grids and the B mixed token

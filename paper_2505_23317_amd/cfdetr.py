@@ -31,7 +31,7 @@ STATUS_NAMES = ["OK", "EINVAL", "ESHAPE", "ECAPACITY", "ENOMEM", "EDEVICE"]
 EXPORTS = [
     "cfdetr_create", "cfdetr_destroy", "cfdetr_last_error", "cfdetr_workspace_bytes",
     "cfdetr_sync_status", "cfdetr_coarse_encode", "cfdetr_propose_rois", "cfdetr_select_fine",
-    "cfdetr_fine_encode",
+    "cfdetr_fine_encode", "cfdetr_fine_encode_padded",
     "cfdetr_multilevel_batch", "cfdetr_profile_begin", "cfdetr_profile_end",
 ]
 
@@ -103,6 +103,8 @@ def load_library() -> ctypes.CDLL:
     lib.cfdetr_select_fine.restype = ctypes.c_int
     lib.cfdetr_fine_encode.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
     lib.cfdetr_fine_encode.restype = ctypes.c_int
+    lib.cfdetr_fine_encode_padded.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp, vp]
+    lib.cfdetr_fine_encode_padded.restype = ctypes.c_int
     lib.cfdetr_multilevel_batch.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.cfdetr_multilevel_batch.restype = ctypes.c_int
     lib.cfdetr_profile_begin.argtypes = [vp]
@@ -173,6 +175,12 @@ def cfdetr_select_fine(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, l
 def cfdetr_fine_encode(ctx, images, B, tok_desc, cu_seqlens, x0_cache, y_mixed, stream=0) -> None:
     _check(load_library().cfdetr_fine_encode(ctx, images, B, tok_desc, cu_seqlens, x0_cache,
                                              y_mixed, stream), ctx)
+
+
+def cfdetr_fine_encode_padded(ctx, images, B, tok_desc, cu_seqlens, x0_cache, t_pad, y_padded,
+                              stream=0) -> None:
+    _check(load_library().cfdetr_fine_encode_padded(ctx, images, B, tok_desc, cu_seqlens, x0_cache,
+                                                    t_pad, y_padded, stream), ctx)
 
 
 def cfdetr_multilevel_batch(ctx, images, B, boxes, tier, box_offsets, y_coarse, y_mixed,
@@ -308,6 +316,12 @@ class Encoder:
                            cu_seqlens.data_ptr(),
                            x0_cache.data_ptr() if x0_cache is not None else None,
                            y_mixed.data_ptr(), self._stream())
+
+    def fine_encode_padded(self, images, B, tok_desc, cu_seqlens, x0_cache, t_pad, y_padded):
+        cfdetr_fine_encode_padded(self.ctx, images.data_ptr(), B, tok_desc.data_ptr(),
+                                  cu_seqlens.data_ptr(),
+                                  x0_cache.data_ptr() if x0_cache is not None else None,
+                                  t_pad, y_padded.data_ptr(), self._stream())
 
     def multilevel_batch(self, images, B, boxes, tier, box_offsets, out):
         cfdetr_multilevel_batch(self.ctx, images.data_ptr(), B, boxes.data_ptr(), tier.data_ptr(),

@@ -50,6 +50,9 @@ struct cfdetr_ctx {
   int32_t* queue_heads = nullptr;   // 8 fetch counters per layer, set by the plan kernel
   int attn_grid = 0;                // workgroups of an attention launch
   int32_t* n_roi = nullptr;         // regions per frame (scratch of the region proposal)
+  int32_t* tok_pad = nullptr;       // padded token table, offsets and true lengths of the
+  int32_t* cu_pad = nullptr;        // padded form of the fine pass
+  int32_t* kv_len = nullptr;
   int block_q = 0;
   int32_t* err_flag = nullptr;
 
@@ -176,7 +179,8 @@ cfdetr_status embed_level(cfdetr_ctx* ctx, const void* images, int level,
 // plan kernel turns that into ctx->cu_all / ctx->m_all, which every kernel reads
 // on the device.  Output rows below split_row go to y0, the others to y1.
 cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefix, int m_cap,
-                          float* y0, int split_row, float* y1, hipStream_t s) {
+                          float* y0, int split_row, float* y1, hipStream_t s,
+                          const int32_t* kv_len = nullptr) {
   const cfdetr_config& c = ctx->cfg;
   const cfdetr_weights& w = ctx->w;
   const int d = c.d_model, F = c.d_ffn;
@@ -215,7 +219,7 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
     CF_LAUNCH(CFDETR_K_ATTN,
               launch_attention(ctx->qkv, ctx->vt, ctx->vt_ld, ctx->o, cu_all, ctx->pcu, d,
                                c.n_heads, ctx->items, ctx->cap8, ctx->queue_heads + 8 * l,
-                               ctx->attn_grid, ctx->block_q, bf, s));
+                               ctx->attn_grid, ctx->block_q, bf, kv_len, s));
     if (fused_ln) {
       CF_LAUNCH(CFDETR_K_OUT,
                 launch_gemm_residual_ln(ctx->o, wo, w.b_o + (size_t)l * d, d, d, ctx->x,
@@ -303,6 +307,19 @@ cfdetr_status fine_impl(cfdetr_ctx* ctx, const void* images, int B, const int32_
   cfdetr_status st = fine_embed(ctx, images, B, tok_desc, cu, x0_cache, 0, s);
   if (st != CFDETR_OK) return st;
   return run_encoder(ctx, cu, B, 0, ctx->cfg.max_tokens_total, y_mixed, 0, nullptr, s);
+}
+
+// A3 as the paper states it: every frame's token set brought to t_pad tokens (repeats of
+// its last token, which cost what any padding token costs), all B*t_pad rows through every
+// kernel, padded keys masked in the attention.  Row f*t_pad + j of y is token j of frame f.
+cfdetr_status padded_impl(cfdetr_ctx* ctx, const void* images, int B, const int32_t* tok_desc,
+                          const int32_t* cu, const float* x0_cache, int t_pad, float* y_padded,
+                          hipStream_t s) {
+  CF_LAUNCH(CFDETR_K_SELECT, launch_pad_tokens(tok_desc, cu, B, t_pad, ctx->tok_pad, ctx->cu_pad,
+                                               ctx->kv_len, ctx->err_flag, s));
+  cfdetr_status st = fine_embed(ctx, images, B, ctx->tok_pad, ctx->cu_pad, x0_cache, 0, s);
+  if (st != CFDETR_OK) return st;
+  return run_encoder(ctx, ctx->cu_pad, B, 0, B * t_pad, y_padded, 0, nullptr, s, ctx->kv_len);
 }
 
 // A1 -> A2 -> A3 with ONE encoder run: the B coarse grids and the B mixed token sets
@@ -406,6 +423,8 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   const uint64_t o_items = cv.take((uint64_t)c->cap8 * 8 * 4), o_err = cv.take(4);
   const uint64_t o_qh = cv.take((uint64_t)cfg->n_layers * 8 * 4);
   const uint64_t o_nroi = cv.take((uint64_t)kMaxBatch * 4);
+  const uint64_t o_tpad = cv.take((uint64_t)cfg->max_tokens_total * 4);
+  const uint64_t o_cupad = cv.take((uint64_t)(kMaxBatch + 1) * 4), o_kvlen = cv.take((uint64_t)kMaxBatch * 4);
   c->arena_bytes = cv.off;
   e = hipMalloc(&c->arena, c->arena_bytes);
   if (e != hipSuccess) {
@@ -436,6 +455,9 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->err_flag = reinterpret_cast<int32_t*>(base + o_err);
   c->queue_heads = reinterpret_cast<int32_t*>(base + o_qh);
   c->n_roi = reinterpret_cast<int32_t*>(base + o_nroi);
+  c->tok_pad = reinterpret_cast<int32_t*>(base + o_tpad);
+  c->cu_pad = reinterpret_cast<int32_t*>(base + o_cupad);
+  c->kv_len = reinterpret_cast<int32_t*>(base + o_kvlen);
 
   // static tables: coarse grid descriptors, zeroed counters, position tables
   std::vector<int32_t> desc(Bm * c->n0), cu(Bm + 1);
@@ -551,6 +573,22 @@ CFDETR_API cfdetr_status cfdetr_fine_encode(cfdetr_ctx* ctx, const void* images,
     return fail(ctx, CFDETR_EINVAL, "pointers must be 16-byte aligned");
   return fine_impl(ctx, images, B, tok_desc, cu_seqlens, x0_cache, y_mixed,
                    static_cast<hipStream_t>(hip_stream));
+}
+
+CFDETR_API cfdetr_status cfdetr_fine_encode_padded(cfdetr_ctx* ctx, const void* images, int32_t B,
+                                        const int32_t* tok_desc, const int32_t* cu_seqlens,
+                                        const float* x0_cache, int32_t t_pad, float* y_padded,
+                                        void* hip_stream) {
+  cfdetr_status st = check_call(ctx, B);
+  if (st != CFDETR_OK) return st;
+  if (!images || !tok_desc || !cu_seqlens || !y_padded) return fail(ctx, CFDETR_EINVAL, "null pointer");
+  if (!aligned16(images) || !aligned16(y_padded) || !aligned16(x0_cache))
+    return fail(ctx, CFDETR_EINVAL, "pointers must be 16-byte aligned");
+  if (t_pad < ctx->n0) return fail(ctx, CFDETR_EINVAL, "t_pad below the coarse grid size");
+  if ((int64_t)B * t_pad > ctx->cfg.max_tokens_total)
+    return fail(ctx, CFDETR_ECAPACITY, "B * t_pad exceeds max_tokens_total");
+  return padded_impl(ctx, images, B, tok_desc, cu_seqlens, x0_cache, t_pad, y_padded,
+                     static_cast<hipStream_t>(hip_stream));
 }
 
 CFDETR_API cfdetr_status cfdetr_multilevel_batch(cfdetr_ctx* ctx, const void* images, int32_t B,

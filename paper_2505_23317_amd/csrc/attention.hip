@@ -91,7 +91,8 @@ template <int DH>
 __global__ __launch_bounds__(256) void attention_bf16_kernel(
     const bf16_t* __restrict__ qk, const bf16_t* __restrict__ vt, int vt_ld,
     bf16_t* __restrict__ out, const int32_t* __restrict__ cu, const int32_t* __restrict__ pcu,
-    int d, const int32_t* __restrict__ items, int cap8, int32_t* __restrict__ queue_heads) {
+    int d, const int32_t* __restrict__ items, int cap8, int32_t* __restrict__ queue_heads,
+    const int32_t* __restrict__ kv_len) {
   constexpr int BQ = 128;
   constexpr int KS = DH / 16;          // k-steps of Q.K^T
   constexpr int MO = DH / 32;          // 32-row blocks of O^T
@@ -141,6 +142,8 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 
     const int frame = item >> 24, head = (item >> 19) & 31, qt = item & 0x7FFFF;
     const int seq0 = cu[frame], T = cu[frame + 1] - seq0;
+    // keys of the sequence that take part (all of them unless the caller padded it)
+    const int TK = kv_len ? min(kv_len[frame], T) : T;
     const bf16_t* qbase = qk + (size_t)seq0 * ld + head * DH;
     const bf16_t* kbase = qbase + d;
 
@@ -164,7 +167,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 #define CFDETR_ATTN_ISSUE(kv0_, buf_)                                                        \
   do {                                                                                       \
     _Pragma("unroll") for (int j = 0; j < KI; ++j) {                                         \
-      const int key = min((kv0_) + k_key[j], T - 1);                                         \
+      const int key = min((kv0_) + k_key[j], TK - 1);                                        \
       __builtin_amdgcn_global_load_lds(                                                      \
           (global_void_ptr)(kbase + (size_t)key * ld + k_chunk[j] * 8),                      \
           (lds_void_ptr)(((buf_) ? sK1 : sK0) + (wave * KI + j) * 1024), 16, 0, 0);          \
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
 
-    const int n_kv = (T + kBlockKV - 1) / kBlockKV;
+    const int n_kv = (TK + kBlockKV - 1) / kBlockKV;
     CFDETR_ATTN_ISSUE(0, 0);
     for (int it0 = 0; it0 < n_kv; it0 += 2) {
 #pragma unroll
@@ -215,11 +218,11 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
                                                          0, 0, 0);                            \
       }                                                                                       \
     }                                                                                         \
-    if (kv0 + kBlockKV > T) {                                                                 \
+    if (kv0 + kBlockKV > TK) {                                                                \
       _Pragma("unroll") for (int sub = 0; sub < 2; ++sub)                                     \
       _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                        \
         const int key = kv0 + sub * 32 + 16 * (r >> 3) + 8 * g + (r & 7);                     \
-        if (key >= T) s[sub][r] = -INFINITY;                                                  \
+        if (key >= TK) s[sub][r] = -INFINITY;                                                 \
       }                                                                                       \
     }                                                                                         \
   } while (0)
@@ -296,14 +299,15 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 template <int DH>
 __global__ __launch_bounds__(256) void attention_f32_kernel(
     const float* __restrict__ qkv, float* __restrict__ out, const int32_t* __restrict__ cu, int d,
-    const int32_t* __restrict__ items, float scale) {
-  constexpr int TK = 32;
-  __shared__ float sK[TK][DH];
-  __shared__ float sV[TK][DH];
+    const int32_t* __restrict__ items, float scale, const int32_t* __restrict__ kv_len) {
+  constexpr int TILE = 32;
+  __shared__ float sK[TILE][DH];
+  __shared__ float sV[TILE][DH];
   const int32_t item = items[blockIdx.x];
   if (item < 0) return;
   const int frame = item >> 24, head = (item >> 19) & 31, qt = item & 0x7FFFF;
   const int seq0 = cu[frame], T = cu[frame + 1] - seq0;
+  const int TK = kv_len ? min(kv_len[frame], T) : T;
   const int ld = 3 * d;
   const float* qbase = qkv + (size_t)seq0 * ld + head * DH;
   const int q_local = qt * (int)blockDim.x + threadIdx.x;   // block size = queries per tile
@@ -315,23 +319,23 @@ __global__ __launch_bounds__(256) void attention_f32_kernel(
     o[i] = 0.f;
   }
   float m_run = -INFINITY, l_run = 0.f;
-  for (int kv0 = 0; kv0 < T; kv0 += TK) {
+  for (int kv0 = 0; kv0 < TK; kv0 += TILE) {
     __syncthreads();
-    for (int e = threadIdx.x; e < TK * DH; e += blockDim.x) {
+    for (int e = threadIdx.x; e < TILE * DH; e += blockDim.x) {
       int r = e / DH, c = e - r * DH;
-      int key = min(kv0 + r, T - 1);
+      int key = min(kv0 + r, TK - 1);
       sK[r][c] = qbase[(size_t)key * ld + d + c];
       sV[r][c] = qbase[(size_t)key * ld + 2 * d + c];
     }
     __syncthreads();
-    float s[TK];
+    float s[TILE];
     float m_tile = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < TK; ++r) {
+    for (int r = 0; r < TILE; ++r) {
       float acc = 0.f;
 #pragma unroll
       for (int i = 0; i < DH; ++i) acc = fmaf(q[i], sK[r][i], acc);
-      s[r] = (kv0 + r < T) ? acc : -INFINITY;
+      s[r] = (kv0 + r < TK) ? acc : -INFINITY;
       m_tile = fmaxf(m_tile, s[r]);
     }
     const float m_new = fmaxf(m_run, m_tile);
@@ -341,7 +345,7 @@ __global__ __launch_bounds__(256) void attention_f32_kernel(
 #pragma unroll
     for (int i = 0; i < DH; ++i) o[i] *= alpha;
 #pragma unroll
-    for (int r = 0; r < TK; ++r) {
+    for (int r = 0; r < TILE; ++r) {
       float p = expf(s[r] - m_new);
       l_run += p;
 #pragma unroll
@@ -397,7 +401,7 @@ int attention_grid(int d_head, bool use_bf16, int cap8) {
 hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* out,
                             const int32_t* cu_seqlens, const int32_t* pcu, int d, int heads,
                             const int32_t* items, int cap8, int32_t* queue_heads, int grid_size,
-                            int block_q, bool use_bf16, hipStream_t s) {
+                            int block_q, bool use_bf16, const int32_t* kv_len, hipStream_t s) {
   if (block_q != 128 || grid_size < 8 || grid_size % 8 != 0 || grid_size > 8 * cap8)
     return hipErrorInvalidValue;
   const int dh = d / heads;
@@ -408,10 +412,10 @@ hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* ou
     dim3 grid(grid_size);
     if (dh == 64)
       hipLaunchKernelGGL(attention_bf16_kernel<64>, grid, dim3(256), 0, s, in, v, vt_ld, o,
-                         cu_seqlens, pcu, d, items, cap8, queue_heads);
+                         cu_seqlens, pcu, d, items, cap8, queue_heads, kv_len);
     else if (dh == 32)
       hipLaunchKernelGGL(attention_bf16_kernel<32>, grid, dim3(256), 0, s, in, v, vt_ld, o,
-                         cu_seqlens, pcu, d, items, cap8, queue_heads);
+                         cu_seqlens, pcu, d, items, cap8, queue_heads, kv_len);
     else
       return hipErrorInvalidValue;
   } else {
@@ -421,10 +425,10 @@ hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* ou
     float* o = static_cast<float*>(out);
     if (dh == 64)
       hipLaunchKernelGGL(attention_f32_kernel<64>, grid, dim3(block_q), 0, s, in, o, cu_seqlens, d,
-                         items, scale);
+                         items, scale, kv_len);
     else if (dh == 32)
       hipLaunchKernelGGL(attention_f32_kernel<32>, grid, dim3(block_q), 0, s, in, o, cu_seqlens, d,
-                         items, scale);
+                         items, scale, kv_len);
     else
       return hipErrorInvalidValue;
   }

@@ -31,6 +31,14 @@ hipError_t launch_propose_rois(const float* queries, int B, int Q, int H, int W,
                                int32_t* box_offsets, int32_t* hard, float* mean_conf,
                                int32_t* err_flag, hipStream_t s);
 
+// Padded copy of a token table (the paper's own form of A3: every frame's token set is
+// brought to one length).  Frame f gets rows f*t_pad .. (f+1)*t_pad of tok_pad: its own
+// tokens, then repeats of its last one.  cu_pad[f] = f*t_pad, kv_len[f] = its true
+// length (t_pad and *err_flag = 1 if that exceeds t_pad).
+hipError_t launch_pad_tokens(const int32_t* tok_desc, const int32_t* cu_seqlens, int B, int t_pad,
+                             int32_t* tok_pad, int32_t* cu_pad, int32_t* kv_len,
+                             int32_t* err_flag, hipStream_t s);
+
 // Sequence list and attention work list of one encoder run.  The sequences are
 // n_prefix sequences of prefix_len tokens (coarse grids of a merged run; may be 0)
 // followed by the B sequences delimited by cu_seqlens.  Writes cu_all[0..nseq] and
@@ -123,11 +131,12 @@ float attention_q_scale(int d_head);
 // queue x): workgroup w takes entry w/8 of queue w%8 and then fetches through the
 // counter queue_heads[w%8], which must be grid_size/8 at launch and is used up by it.
 // The fp32 kernel maps workgroup w to entry w (grid_size = 8*cap8).
-// Softmax over the keys of the same frame only.
+// Softmax over the keys of the same frame only; with kv_len (may be null) only over the
+// first kv_len[i] keys of sequence i, the rest being padding.
 hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* out,
                             const int32_t* cu_seqlens, const int32_t* pcu, int d, int heads,
                             const int32_t* items, int cap8, int32_t* queue_heads, int grid_size,
-                            int block_q, bool use_bf16, hipStream_t s);
+                            int block_q, bool use_bf16, const int32_t* kv_len, hipStream_t s);
 // Grid of launch_attention on the current device: a multiple of 8, at most 8*cap8;
 // 0 if the device cannot be queried.
 int attention_grid(int d_head, bool use_bf16, int cap8);

@@ -238,7 +238,33 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
     if ((i >> 3) >= s_count[i & 7]) items[i] = -1;
 }
 
+__global__ __launch_bounds__(256) void pad_tokens_kernel(const int32_t* __restrict__ tok_desc,
+                                                         const int32_t* __restrict__ cu, int B,
+                                                         int t_pad, int32_t* __restrict__ tok_pad,
+                                                         int32_t* __restrict__ cu_pad,
+                                                         int32_t* __restrict__ kv_len,
+                                                         int32_t* __restrict__ err_flag) {
+  const int f = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int t0 = cu[f], len = cu[f + 1] - t0;
+  if (j == 0) {
+    cu_pad[f] = f * t_pad;
+    if (f == B - 1) cu_pad[B] = B * t_pad;
+    kv_len[f] = min(len, t_pad);
+    if (len > t_pad) *err_flag = 1;
+  }
+  if (j < t_pad) tok_pad[(size_t)f * t_pad + j] = tok_desc[t0 + min(j, len - 1)];
+}
+
 }  // namespace
+
+hipError_t launch_pad_tokens(const int32_t* tok_desc, const int32_t* cu_seqlens, int B, int t_pad,
+                             int32_t* tok_pad, int32_t* cu_pad, int32_t* kv_len,
+                             int32_t* err_flag, hipStream_t s) {
+  hipLaunchKernelGGL(pad_tokens_kernel, dim3((t_pad + 255) / 256, B), dim3(256), 0, s, tok_desc,
+                     cu_seqlens, B, t_pad, tok_pad, cu_pad, kv_len, err_flag);
+  return hipGetLastError();
+}
 
 hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t* tier,
                          const int32_t* box_offsets, int B, int nonfinest, uint8_t* hit,
