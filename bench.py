@@ -82,6 +82,7 @@ def cpu_baseline(cfg, wl, cfg_id):
 
 
 TRAFFIC_FAMILY = {"attention": "attention", "qkv": "gemm_qkv", "ffn1": "gemm_ffn1_gelu",
+                  "out_proj": "gemm_out_proj", "ffn2": "gemm_ffn2",
                   "layernorm": "layernorm", "embed": "embed", "gather": "gather_coarse"}
 
 

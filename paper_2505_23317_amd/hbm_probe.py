@@ -29,7 +29,7 @@ FAMILIES = [
     ("attention", r"attention_bf16_kernel"),
     ("gemm_qkv", r"gemm_bf16_direct_kernel.*EpiQkv"),
     ("gemm_ffn1_gelu", r"gemm_bf16_direct_kernel.*EpiAct<unsigned short, true>"),
-    ("gemm_residual", r"gemm_bf16_direct_kernel.*EpiResidual"),
+    ("gemm_residual", r"gemm_bf16_direct_kernel.*EpiResidual|gemm_bf16_rowln_kernel"),
     ("embed", r"gemm_bf16_gather_kernel"),
     ("layernorm", r"layernorm_kernel"),
     ("select_hit", r"select_hit_kernel"),
@@ -61,13 +61,15 @@ def run(cfg_id: int) -> None:
 
 
 def _read(path: str):
-    """kernel name -> list of counter values (one per dispatch), and the counter's name."""
+    """kernel name -> list of counter values (one per dispatch, in dispatch order), and
+    the counter's name."""
     vals = collections.defaultdict(list)
     name = None
     with open(path) as f:
-        for r in csv.DictReader(f):
-            name = r["Counter_Name"]
-            vals[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+        rows = sorted(csv.DictReader(f), key=lambda r: int(r["Dispatch_Id"]))
+    for r in rows:
+        name = r["Counter_Name"]
+        vals[r["Kernel_Name"]].append(float(r["Counter_Value"]))
     return vals, name
 
 
@@ -78,6 +80,14 @@ def _copy_reading(vals):
         if "copy" in k.lower() or "elementwise" in k.lower():
             best = max(best, max(v))
     return best
+
+
+def _alternate(v, sel):
+    """Every second dispatch of one kernel name, restarting with each of the STEPS steps."""
+    per = len(v) // STEPS
+    if per == 1:   # the instantiation that ends a run (final LayerNorm): a second FFN projection
+        return list(v) if sel == 1 else []
+    return [x for s0 in range(0, per * STEPS, per) for x in v[s0:s0 + per][sel::2]]
 
 
 def report(fetch_csv: str, write_csv: str, cfg_id: int) -> None:
@@ -103,6 +113,16 @@ def report(fetch_csv: str, write_csv: str, cfg_id: int) -> None:
         f = [x for k, v in fetch.items() if rx.search(k) for x in v]
         w = [x for k, v in write.items() if rx.search(k) for x in v]
         if not f or not w:
+            continue
+        if fam == "gemm_residual":
+            # the two residual contractions of a layer alternate: output projection, then
+            # second FFN projection (the last one of a run may be another instantiation,
+            # which keeps the alternation per kernel name)
+            for part, sel in (("gemm_out_proj", 0), ("gemm_ffn2", 1)):
+                fp = [x for k, v in fetch.items() if rx.search(k) for x in _alternate(v, sel)]
+                wp = [x for k, v in write.items() if rx.search(k) for x in _alternate(v, sel)]
+                if fp and wp:
+                    print(f"{part} {len(fp)} {kf * sum(fp) / len(fp):.0f} {kw * sum(wp) / len(wp):.0f}")
             continue
         print(f"{fam} {len(f)} {kf * sum(f) / len(f):.0f} {kw * sum(w) / len(w):.0f}")
 
