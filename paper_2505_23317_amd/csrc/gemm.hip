@@ -73,6 +73,7 @@ struct EpiAct<bf16_t, kGelu> {
   int ldc;
   static constexpr bool kExtra = kNoExtra;
   __device__ __forceinline__ int32_t row_info(int) const { return 0; }
+  __device__ __forceinline__ bool row_ok(int32_t) const { return true; }
   __device__ __forceinline__ float4 bias4(int n) const {
     return *reinterpret_cast<const float4*>(bias + n);
   }
@@ -136,6 +137,7 @@ struct EpiResidual {
   int ldc;
   static constexpr bool kExtra = kHasExtra;
   __device__ __forceinline__ int32_t row_info(int) const { return 0; }
+  __device__ __forceinline__ bool row_ok(int32_t) const { return true; }
   __device__ __forceinline__ float4 bias4(int n) const {
     return *reinterpret_cast<const float4*>(bias + n);
   }
@@ -187,6 +189,7 @@ struct EpiQkv {
     const int f = frame_of_token(cu, B, m);
     return pcu[f] + (m - cu[f]);
   }
+  __device__ __forceinline__ bool row_ok(int32_t) const { return true; }
   static constexpr bool kExtra = kNoExtra;
   __device__ __forceinline__ float4 bias4(int n) const {
     return *reinterpret_cast<const float4*>(bias + n);
@@ -242,7 +245,16 @@ struct EpiEmbed {
   float* out;
   float* out2;
   int d;
+  const int32_t* tok_desc;   // for row_info (direct-load kernel); the other kernels pass
+  int level;                 // the descriptor themselves
   static constexpr bool kExtra = kHasExtra;
+  static constexpr int kStageElem = 0;   // rows of other levels lie in between: stores stay per row
+  // descriptor of token m if it is a token of `level`, else -1 (row not to be written)
+  __device__ __forceinline__ int32_t row_info(int m) const {
+    const int32_t desc = tok_desc[m];
+    return tok_level(desc) == level ? desc : -1;
+  }
+  __device__ __forceinline__ bool row_ok(int32_t info) const { return info >= 0; }
   __device__ __forceinline__ float4 bias4(int n) const {
     return *reinterpret_cast<const float4*>(bias + n);
   }
@@ -287,6 +299,52 @@ __device__ __forceinline__ void dma16_untracked(const void* gptr, const unsigned
                : "memory");   // M0 is reserved: the compiler keeps nothing in it
 }
 
+// Where the rows of the A operand come from.  row(r, M, ok) is the address of element 0
+// of row r (rows that are not to be computed get ok = false and any valid address);
+// col(k) is the offset of element k, for k a multiple of 8 (8 consecutive elements are
+// contiguous in memory).
+struct DenseRows {   // an activation matrix [M, K], K innermost
+  const bf16_t* A;
+  int K;
+  static constexpr bool kSparse = false;
+  __device__ __forceinline__ const bf16_t* row(int r, int M, bool& ok) const {
+    ok = r < M;
+    return A + (size_t)min(r, M - 1) * K;
+  }
+  __device__ __forceinline__ size_t col(int k) const { return (size_t)k; }
+};
+
+// Patch pixels of bf16 frames as rows (implicit im2col): row m is the patch of token m
+// flattened (channel, row, column), for the tokens of one level only.  8 consecutive
+// elements are 8 consecutive pixels of one patch row (patches are at least 8 wide).
+struct PatchPixelRows {
+  const bf16_t* images;
+  const int32_t* tok_desc;
+  const int32_t* cu;
+  int B, level, log2p, img_h, img_w;
+  static constexpr bool kSparse = true;
+  __device__ __forceinline__ const bf16_t* row(int r, int M, bool& ok) const {
+    size_t off = 0;
+    ok = r < M;
+    if (ok) {
+      const int32_t desc = tok_desc[r];
+      ok = tok_level(desc) == level;
+      if (ok) {
+        const int frame = frame_of_token(cu, B, r);
+        off = ((size_t)frame * 3 * img_h + ((size_t)tok_row(desc) << log2p)) * img_w +
+              ((size_t)tok_col(desc) << log2p);
+      }
+    }
+    return images + off;   // not ok: frame 0's first patch, in bounds, result discarded
+  }
+  __device__ __forceinline__ size_t col(int k) const {
+    const int c = k >> (2 * log2p);
+    const int r = (k >> log2p) & ((1 << log2p) - 1);
+    const int x = k & ((1 << log2p) - 1);
+    return ((size_t)c * img_h + r) * img_w + x;
+  }
+};
+
 // Swizzle key of LDS row r for rows of ROWB bytes: the 16-byte chunks of a row are
 // stored at position chunk ^ key, which keeps the operand reads of 16 consecutive rows
 // (what one LDS cycle serves) on disjoint banks.
@@ -295,9 +353,9 @@ __device__ __forceinline__ int lds_row_key(int r) {
   return ROWB == 128 ? ((r >> 1) & 7) : ((r >> 2) & 3);
 }
 
-template <int BM, int BN, int NWM, int NWN, int kStages, int BKT, typename EP>
+template <int BM, int BN, int NWM, int NWN, int kStages, int BKT, typename AROWS, typename EP>
 __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
-    const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int N, int K, EP ep,
+    AROWS arows, const bf16_t* __restrict__ W, int N, int K, EP ep,
     const int32_t* __restrict__ m_ptr, int m_host) {
   constexpr int NW = NWM * NWN;
   constexpr int WTM = BM / NWM, WTN = BN / NWN;      // wavefront tile
@@ -327,13 +385,21 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   // (row lane/CPR of the group, LDS chunk position lane%CPR) and fetches the logical
   // chunk position ^ swizzle key of that row.
   const int lrow = lane / CPR, lpos = lane % CPR;
-  const bf16_t* ag[A_INST];
+  const bf16_t* ag[A_INST];   // element 0 of the lane's row
+  int ac[A_INST];             // first of the lane's 8 elements inside a slab
   const bf16_t* wg[B_INST];
+  bool any_row = false;
 #pragma unroll
   for (int j = 0; j < A_INST; ++j) {
     const int rt = (wave * A_INST + j) * RPI + lrow;      // row inside the tile
-    const int r = min(m0 + rt, M - 1);                    // rows past M: any valid row
-    ag[j] = A + (size_t)r * K + (lpos ^ lds_row_key<ROWB>(rt)) * 8;
+    bool ok;
+    ag[j] = arows.row(m0 + rt, M, ok);                    // not ok: any valid row
+    ac[j] = (lpos ^ lds_row_key<ROWB>(rt)) * 8;
+    any_row |= ok;
+  }
+  if (AROWS::kSparse) {
+    // a tile without a single row to compute (no token of the level) leaves at once
+    if (!__syncthreads_or(any_row)) return;
   }
 #pragma unroll
   for (int j = 0; j < B_INST; ++j) {
@@ -374,7 +440,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   do {                                                                                        \
     unsigned char* st_ = smem_direct + (buf_) * STAGE;                                        \
     _Pragma("unroll") for (int j = 0; j < A_INST; ++j)                                        \
-        dma16_untracked(ag[j] + (k0_), st_ + (wave * A_INST + j) * 1024);                     \
+        dma16_untracked(ag[j] + arows.col((k0_) + ac[j]), st_ + (wave * A_INST + j) * 1024);  \
     _Pragma("unroll") for (int j = 0; j < B_INST; ++j)                                        \
         dma16_untracked(wg[j] + (k0_), st_ + BM * ROWB + (wave * B_INST + j) * 1024);         \
   } while (0)
@@ -427,52 +493,54 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   // pass through a small LDS area of the wavefront's own (the ring is free now), from
   // which rows leave as runs of 128 bytes and more, 16 bytes per lane.  LDS serves a
   // wavefront's instructions in order, so its reads see its earlier writes.
-  constexpr int ES = EP::kStageElem;                    // bytes per staged element
-  constexpr int ROWBYTES = WTN * ES;
-  constexpr int STRIDE = ROWBYTES + 16;   // keeps the 16-byte reads aligned; the 8-byte bf16
-                                          // writes of rows r and r+16 share banks (2-way)
-  constexpr int LPR = ROWBYTES / 16;                    // lanes that copy one row
-  constexpr int RPC = 64 / LPR;                         // rows per copy instruction
-  constexpr int NCOPY = 32 / RPC;
-  static_assert(NW * 32 * STRIDE <= kStages * STAGE, "staging area exceeds the ring");
   const int nw0 = n0 + wn * WTN;
-  __builtin_amdgcn_s_barrier();   // every wavefront is done reading the ring
-  if (ep.staged(nw0)) {
-    unsigned char* stg = smem_direct + wave * (32 * STRIDE);
-    const int crow = lane / LPR, cchunk = lane % LPR;
+  if constexpr (EP::kStageElem > 0) {
+    constexpr int ES = EP::kStageElem;                    // bytes per staged element
+    constexpr int ROWBYTES = WTN * ES;
+    constexpr int STRIDE = ROWBYTES + 16;   // keeps the 16-byte reads aligned; the 8-byte bf16
+                                            // writes of rows r and r+16 share banks (2-way)
+    constexpr int LPR = ROWBYTES / 16;                    // lanes that copy one row
+    constexpr int RPC = 64 / LPR;                         // rows per copy instruction
+    constexpr int NCOPY = 32 / RPC;
+    static_assert(NW * 32 * STRIDE <= kStages * STAGE, "staging area exceeds the ring");
+    __builtin_amdgcn_s_barrier();   // every wavefront is done reading the ring
+    if (ep.staged(nw0)) {
+      unsigned char* stg = smem_direct + wave * (32 * STRIDE);
+      const int crow = lane / LPR, cchunk = lane % LPR;
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      const int mb = m0 + wm * WTM + i * 32;
-      if (mb >= M) break;
-      float4 xin[NCOPY];
-      if (EP::kExtra) {
+      for (int i = 0; i < MT; ++i) {
+        const int mb = m0 + wm * WTM + i * 32;
+        if (mb >= M) break;
+        float4 xin[NCOPY];
+        if (EP::kExtra) {
 #pragma unroll
-        for (int t = 0; t < NCOPY; ++t)
-          xin[t] = ep.extra4(min(mb + t * RPC + crow, M - 1), nw0 + cchunk * (16 / ES), info[i]);
-      }
-#pragma unroll
-      for (int j = 0; j < NT; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int nl = j * 32 + 8 * q + 4 * g;
-          const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
-                              acc[i][j][4 * q + 3]};
-          ep.stage4(stg + l32 * STRIDE + nl * ES, nw0 + nl, v, bias_r[j][q]);
+          for (int t = 0; t < NCOPY; ++t)
+            xin[t] = ep.extra4(min(mb + t * RPC + crow, M - 1), nw0 + cchunk * (16 / ES), info[i]);
         }
 #pragma unroll
-      for (int t = 0; t < NCOPY; ++t) {
-        const int row = t * RPC + crow;
-        const uint4 d = *reinterpret_cast<const uint4*>(stg + row * STRIDE + cchunk * 16);
-        if (mb + row < M) ep.copy16(mb + row, nw0 + cchunk * (16 / ES), d, xin[t]);
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int nl = j * 32 + 8 * q + 4 * g;
+            const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                                acc[i][j][4 * q + 3]};
+            ep.stage4(stg + l32 * STRIDE + nl * ES, nw0 + nl, v, bias_r[j][q]);
+          }
+#pragma unroll
+        for (int t = 0; t < NCOPY; ++t) {
+          const int row = t * RPC + crow;
+          const uint4 d = *reinterpret_cast<const uint4*>(stg + row * STRIDE + cchunk * 16);
+          if (mb + row < M) ep.copy16(mb + row, nw0 + cchunk * (16 / ES), d, xin[t]);
+        }
       }
+      return;
     }
-    return;
   }
   // direct form: the per-element addends of the tile in one batch, then its stores
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
     const int m = m0 + wm * WTM + i * 32 + l32;
-    if (m >= M) continue;
+    if (m >= M || !ep.row_ok(info[i])) continue;
     float4 extra[NT][4];
 #pragma unroll
     for (int j = 0; j < NT; ++j)
@@ -1000,17 +1068,17 @@ hipError_t allow_lds(Kern kern, size_t bytes, bool* configured) {
   return e;
 }
 
-template <int BM, int BN, int NWM, int NWN, int S, int BKT, typename EP>
-hipError_t launch_direct_tile(const bf16_t* A, const bf16_t* w, int N, int K, const EP& ep,
+template <int BM, int BN, int NWM, int NWN, int S, int BKT, typename AROWS, typename EP>
+hipError_t launch_direct_tile(const AROWS& a, const bf16_t* w, int N, int K, const EP& ep,
                               const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
-  auto kern = gemm_bf16_direct_kernel<BM, BN, NWM, NWN, S, BKT, EP>;
+  auto kern = gemm_bf16_direct_kernel<BM, BN, NWM, NWN, S, BKT, AROWS, EP>;
   constexpr size_t lds = (size_t)S * (BM + BN) * BKT * 2;
   static_assert(lds <= 160 * 1024, "ring exceeds the LDS");
   static bool configured = false;
   hipError_t e = allow_lds(kern, lds, &configured);
   if (e != hipSuccess) return e;
   dim3 grid(((m_capacity + BM - 1) / BM) * (N / BN));
-  hipLaunchKernelGGL(kern, grid, dim3(64 * NWM * NWN), lds, s, A, w, N, K, ep, m_ptr, m_host);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * NWM * NWN), lds, s, a, w, N, K, ep, m_ptr, m_host);
   return hipSuccess;
 }
 
@@ -1020,7 +1088,7 @@ hipError_t launch_direct_tile(const bf16_t* A, const bf16_t* w, int N, int K, co
 template <typename EP>
 hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& ep,
                          const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
-  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const DenseRows a{static_cast<const bf16_t*>(A), K};
   const bf16_t* w = static_cast<const bf16_t*>(W);
   const long tiles128 = (long)((m_capacity + 127) / 128) * (N / 128);
   // A deeper ring (3 or 4 buffers, also with slabs of 32) measured no faster for these
@@ -1112,13 +1180,25 @@ hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, in
                         bool use_bf16, const int32_t* m_ptr, int m_host, int m_capacity,
                         hipStream_t s) {
   const int K = 3 * a.patch * a.patch;
-  EpiEmbed ep{bias, a.pe_row, a.pe_col, a.out, a.out2, d};
+  EpiEmbed ep{bias, a.pe_row, a.pe_col, a.out, a.out2, d, a.tok_desc, a.level};
   hipError_t e = hipSuccess;
-  if (a.image_is_bf16) {
+  if (a.image_is_bf16 && use_bf16) {
+    // bf16 pixels need no conversion: patch rows go straight from the frames into LDS,
+    // through a deep ring when the problem is too small to hide latency by occupancy
+    const PatchPixelRows rows{static_cast<const bf16_t*>(a.images), a.tok_desc, a.cu_seqlens, a.B,
+                              a.level, ilog2(a.patch), a.img_h, a.img_w};
+    const bf16_t* wb = static_cast<const bf16_t*>(w);
+    // the coarse grid has a row count the host knows; the finer levels only a capacity
+    const int m_likely = m_ptr ? m_capacity : m_host;
+    const long tiles128 = (long)((m_likely + 127) / 128) * (d / 128);
+    if (d % 128 == 0 && tiles128 >= 256)
+      e = launch_direct_tile<128, 128, 2, 2, 2, 64>(rows, wb, d, K, ep, m_ptr, m_host, m_capacity, s);
+    else
+      e = launch_direct_tile<64, 64, 2, 2, 4, 64>(rows, wb, d, K, ep, m_ptr, m_host, m_capacity, s);
+  } else if (a.image_is_bf16) {
     PatchRows<bf16_t> al{static_cast<const bf16_t*>(a.images), a.tok_desc, a.cu_seqlens, a.B,
                          a.level, ilog2(a.patch), a.img_h, a.img_w};
-    if (use_bf16) e = launch_gather(al, w, d, K, ep, m_ptr, m_host, m_capacity, s);
-    else e = launch_f32(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
+    e = launch_f32(al, w, d, K, ep, m_ptr, m_host, m_capacity, a.tok_desc, s);
   } else {
     PatchRows<float> al{static_cast<const float*>(a.images), a.tok_desc, a.cu_seqlens, a.B,
                         a.level, ilog2(a.patch), a.img_h, a.img_w};
