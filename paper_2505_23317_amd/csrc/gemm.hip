@@ -560,15 +560,28 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   }
 }
 
+// Sum over each group of 16 consecutive lanes, delivered to all 16 (quad swaps, then the
+// mirror of each half-row and of the row: a fixed order, no LDS).
+__device__ __forceinline__ float row16_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));
+  return v;
+}
+
 // ---------------------------------------------------------------------------
 // Residual contraction + LayerNorm of the new residual rows in one kernel.
 // ---------------------------------------------------------------------------
 // x[m, :] += A[m, :] . W^T + bias;  out[m, :] = LayerNorm(x[m, :]) * g + b.
 // A workgroup owns BM complete rows (all D = N output columns), so the row statistics
-// are at hand in the epilogue: in-lane sums over the lane's registers, one exchange
-// between the two half-wavefronts, and one pass through LDS across the four
-// wavefronts (wavefront w owns columns [w*D/4, (w+1)*D/4)).  Mean first, then the
-// variance of the centred values, like the stand-alone kernel.
+// are at hand in the epilogue.  The accumulators (a row per lane) first pass through a
+// per-wavefront LDS area and come back with 16 lanes per row and four consecutive
+// columns per lane: in that form the old residual is read, the new one and the
+// normalised row are written as runs of 128-256 bytes, a row's sum is a 16-lane
+// reduction plus one pass through LDS across the four wavefronts (wavefront w owns
+// columns [w*D/4, (w+1)*D/4)), and bias, gain and offset are one float4 each per lane.
+// Mean first, then the variance of the centred values, like the stand-alone kernel.
 //
 // Few rows per workgroup means one workgroup per CU and one wavefront per SIMD, so
 // latency is hidden by depth instead of occupancy: K-slabs of 64 run through a ring of
@@ -592,12 +605,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_rowln_kernel(
       sA2[BM * 128], sA3[BM * 128];
   __shared__ __attribute__((aligned(1024))) unsigned char sB0[D * 128], sB1[D * 128],
       sB2[D * 128], sB3[D * 128];
-  __shared__ float s_red[2][4][BM];
+  __shared__ __attribute__((aligned(16))) float s_red[2][BM][4];   // [pass][row][wavefront]
 #define CFDETR_RING(arr_, s_) ((s_) == 0 ? arr_##0 : (s_) == 1 ? arr_##1 : (s_) == 2 ? arr_##2 : arr_##3)
 
   const int M = m_ptr ? *m_ptr : m_host;
-  const int m0 = blockIdx.x * BM;
-  if (m0 >= M) return;   // surplus workgroup: the grid covers the capacity
+  const int total = (M + BM - 1) / BM;
+  if ((int)blockIdx.x >= total) return;   // surplus workgroup: the grid covers the capacity
+  // same workgroup -> XCD -> row range map as the contraction that produced A: its rows
+  // are then still in this XCD's L2
+  const int m0 = xcd_tile_order(blockIdx.x, total) * BM;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int lrow = lane >> 3, lpos = lane & 7;
@@ -628,24 +644,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_rowln_kernel(
   for (int s = 0; s < kStages - 1; ++s)
     if (s < nk) CFDETR_ISSUE_RING(s * BK, s);
 
-  // Everything the epilogue reads is requested now and arrives during the main loop.
-  // Lane -> row l32 of each 32-row tile; register r of tile j -> column
-  // wave*WTN + 32*j + 8*(r/4) + 4*g + r%4, i.e. piece q = r/4 starts at column
-  // wave*WTN + 32*j + 8*q + 4*g.
-  float4 bb[NT][4], gg[NT][4], be[NT][4], xx[MT][NT][4];
+  // Everything the epilogue reads is requested now and arrives during the main loop, in
+  // the epilogue's own layout: lane -> row crow (+ RPC per step) of a 32-row tile and
+  // columns cn .. cn+3 of the wavefront's WTN.
+  constexpr int LPR = WTN / 4;          // lanes per row (4 columns each); 16 for D = 256
+  constexpr int RPC = 64 / LPR;         // rows per step
+  constexpr int NSTEP = 32 / RPC;
+  static_assert(LPR == 16, "the row sums assume 16 lanes per row");
+  const int crow = lane / LPR, cn = wave * WTN + (lane % LPR) * 4;
+  const float4 bias4 = *reinterpret_cast<const float4*>(bias + cn);
+  const float4 gain4 = *reinterpret_cast<const float4*>(ln_g + cn);
+  const float4 offs4 = *reinterpret_cast<const float4*>(ln_b + cn);
+  float4 xin[MT][NSTEP];
 #pragma unroll
-  for (int j = 0; j < NT; ++j)
+  for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int n = wave * WTN + j * 32 + 8 * q + 4 * g;
-      bb[j][q] = *reinterpret_cast<const float4*>(bias + n);
-      gg[j][q] = *reinterpret_cast<const float4*>(ln_g + n);
-      be[j][q] = *reinterpret_cast<const float4*>(ln_b + n);
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-        xx[i][j][q] = *reinterpret_cast<const float4*>(
-            resid + (size_t)min(m0 + i * 32 + l32, M - 1) * D + n);
-    }
+    for (int t = 0; t < NSTEP; ++t)
+      xin[i][t] = *reinterpret_cast<const float4*>(
+          resid + (size_t)min(m0 + i * 32 + t * RPC + crow, M - 1) * D + cn);
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -697,80 +713,77 @@ __global__ __launch_bounds__(256) void gemm_bf16_rowln_kernel(
   }
 #undef CFDETR_ISSUE_RING
 #undef CFDETR_RING
-  // Epilogue: new residual rows, then their LayerNorm (mean first, then the variance of
-  // the centred values).
-  float mean[MT], rstd[MT];
+  // Epilogue.  Accumulators -> LDS (lane = row l32, register r of tile j = column
+  // 32*j + 8*(r/4) + 4*g + r%4 of the wavefront's WTN) -> back with 16 lanes per row.
+  // The area is the wavefront's own and LDS serves its instructions in order; the ring it
+  // overlays is free once every wavefront has passed the barrier.
+  constexpr int STRIDE = WTN * 4 + 16;   // bytes; rows 16 bytes apart in bank space
+  static_assert(2 * 32 * STRIDE <= (int)sizeof(sB0), "staging area exceeds a ring buffer");
+  __builtin_amdgcn_s_barrier();
+  unsigned char* stg = (wave < 2 ? sB0 : sB1) + (wave & 1) * (32 * STRIDE);
+  float4 v[MT][NSTEP];
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
-    const int m = m0 + i * 32 + l32;
-    float* xrow = resid + (size_t)m * D;
-    float sum = 0.f;
 #pragma unroll
     for (int j = 0; j < NT; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = wave * WTN + j * 32 + 8 * q + 4 * g;
-        float4 v;
-        v.x = acc[i][j][4 * q] + bb[j][q].x + xx[i][j][q].x;
-        v.y = acc[i][j][4 * q + 1] + bb[j][q].y + xx[i][j][q].y;
-        v.z = acc[i][j][4 * q + 2] + bb[j][q].z + xx[i][j][q].z;
-        v.w = acc[i][j][4 * q + 3] + bb[j][q].w + xx[i][j][q].w;
-        if (m < M) *reinterpret_cast<float4*>(xrow + n) = v;
-        acc[i][j][4 * q] = v.x;
-        acc[i][j][4 * q + 1] = v.y;
-        acc[i][j][4 * q + 2] = v.z;
-        acc[i][j][4 * q + 3] = v.w;
-        sum += (v.x + v.y) + (v.z + v.w);
-      }
-    sum += __shfl_xor(sum, 32, kWave);
-    if (g == 0) s_red[0][wave][i * 32 + l32] = sum;
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(stg + l32 * STRIDE + (j * 32 + 8 * q + 4 * g) * 4) =
+            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                        acc[i][j][4 * q + 3]);
+#pragma unroll
+    for (int t = 0; t < NSTEP; ++t) {
+      const int row = t * RPC + crow;
+      const float4 a4 = *reinterpret_cast<const float4*>(stg + row * STRIDE + (lane % LPR) * 16);
+      float4 r;
+      r.x = a4.x + bias4.x + xin[i][t].x;
+      r.y = a4.y + bias4.y + xin[i][t].y;
+      r.z = a4.z + bias4.z + xin[i][t].z;
+      r.w = a4.w + bias4.w + xin[i][t].w;
+      v[i][t] = r;
+      const int m = m0 + i * 32 + row;
+      if (m < M) *reinterpret_cast<float4*>(resid + (size_t)m * D + cn) = r;
+      const float part = row16_sum((r.x + r.y) + (r.z + r.w));
+      if (lane % LPR == 0) s_red[0][i * 32 + row][wave] = part;
+    }
   }
   __syncthreads();
+  float mean[MT][NSTEP];
 #pragma unroll
-  for (int i = 0; i < MT; ++i) {
-    const int rr = i * 32 + l32;
-    mean[i] = ((s_red[0][0][rr] + s_red[0][1][rr]) + (s_red[0][2][rr] + s_red[0][3][rr])) *
-              (1.0f / (float)D);
-    float sq = 0.f;
+  for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float c = acc[i][j][r] - mean[i];
-        sq = fmaf(c, c, sq);
-      }
-    sq += __shfl_xor(sq, 32, kWave);
-    if (g == 0) s_red[1][wave][rr] = sq;
-  }
+    for (int t = 0; t < NSTEP; ++t) {
+      const int row = i * 32 + t * RPC + crow;
+      const float4 p = *reinterpret_cast<const float4*>(&s_red[0][row][0]);
+      mean[i][t] = ((p.x + p.y) + (p.z + p.w)) * (1.0f / (float)D);
+      const float cx = v[i][t].x - mean[i][t], cy = v[i][t].y - mean[i][t];
+      const float cz = v[i][t].z - mean[i][t], cw = v[i][t].w - mean[i][t];
+      const float part = row16_sum(fmaf(cx, cx, cy * cy) + fmaf(cz, cz, cw * cw));
+      if (lane % LPR == 0) s_red[1][row][wave] = part;
+    }
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < MT; ++i) {
-    const int rr = i * 32 + l32;
-    const float var = ((s_red[1][0][rr] + s_red[1][1][rr]) + (s_red[1][2][rr] + s_red[1][3][rr])) *
-                      (1.0f / (float)D);
-    rstd[i] = rsqrtf(var + eps);
-    const int m = m0 + rr;
-    if (m >= M) continue;
-    const bool second = out2 != nullptr && m >= split_row;
-    const size_t row_off = (size_t)(second ? m - split_row : m) * D;
-    void* obase = second ? out2 : out;
+  for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = wave * WTN + j * 32 + 8 * q + 4 * g;
-        const float r0 = (acc[i][j][4 * q] - mean[i]) * rstd[i] * gg[j][q].x + be[j][q].x;
-        const float r1 = (acc[i][j][4 * q + 1] - mean[i]) * rstd[i] * gg[j][q].y + be[j][q].y;
-        const float r2 = (acc[i][j][4 * q + 2] - mean[i]) * rstd[i] * gg[j][q].z + be[j][q].z;
-        const float r3 = (acc[i][j][4 * q + 3] - mean[i]) * rstd[i] * gg[j][q].w + be[j][q].w;
-        if (kOutBf16)
-          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(obase) + row_off + n) =
-              make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
-        else
-          *reinterpret_cast<float4*>(static_cast<float*>(obase) + row_off + n) =
-              make_float4(r0, r1, r2, r3);
-      }
-  }
+    for (int t = 0; t < NSTEP; ++t) {
+      const int row = i * 32 + t * RPC + crow;
+      const int m = m0 + row;
+      if (m >= M) continue;
+      const float4 p = *reinterpret_cast<const float4*>(&s_red[1][row][0]);
+      const float rstd = rsqrtf(((p.x + p.y) + (p.z + p.w)) * (1.0f / (float)D) + eps);
+      const float r0 = (v[i][t].x - mean[i][t]) * rstd * gain4.x + offs4.x;
+      const float r1 = (v[i][t].y - mean[i][t]) * rstd * gain4.y + offs4.y;
+      const float r2 = (v[i][t].z - mean[i][t]) * rstd * gain4.z + offs4.z;
+      const float r3 = (v[i][t].w - mean[i][t]) * rstd * gain4.w + offs4.w;
+      const bool second = out2 != nullptr && m >= split_row;
+      const size_t at = (size_t)(second ? m - split_row : m) * D + cn;
+      void* obase = second ? out2 : out;
+      if (kOutBf16)
+        *reinterpret_cast<uint2*>(static_cast<bf16_t*>(obase) + at) =
+            make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+      else
+        *reinterpret_cast<float4*>(static_cast<float*>(obase) + at) = make_float4(r0, r1, r2, r3);
+    }
 }
 
 // ---------------------------------------------------------------------------
