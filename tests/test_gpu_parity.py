@@ -226,6 +226,28 @@ REDUCED = {
 }
 
 
+LIMITS = {
+    # the largest batch the library takes: 64 small frames
+    "max_batch": synth.Config("b64", 64, 64, 96, (16, 8), 64, 2, 1, 128, "bf16",
+                              box_rule="poisson", box_lambda=2.0, side_lo=8, side_hi=40),
+    # the widest model: d = 1024 with 32 heads of 32, one 8x8 patch level pair
+    "max_width_32_heads": synth.Config("d1024h32", 2, 64, 64, (16, 8), 1024, 32, 1, 128, "bf16",
+                                       box_rule="poisson", box_lambda=2.0, side_lo=8, side_hi=40),
+    # heads of 64 at the widest model, single level (no refinement possible)
+    "one_level_16_heads": synth.Config("d1024h16", 2, 64, 96, (16,), 1024, 16, 2, 64, "bf16",
+                                       box_rule="poisson", box_lambda=2.0, side_lo=8, side_hi=40),
+}
+
+
+@pytest.mark.parametrize("act", ["fp32", "bf16"])
+@pytest.mark.parametrize("name", sorted(LIMITS))
+def test_limits_of_the_configuration(K, act, name):
+    cfg = LIMITS[name]
+    _say(f"[case] {name} {act}")
+    wl = synth.make_workload(cfg, seed=29)
+    check_all(gpu_multilevel(K, cfg, wl, act), oracle_multilevel(cfg, wl), act, name)
+
+
 @pytest.mark.parametrize("act", ["fp32", "bf16"])
 @pytest.mark.parametrize("name", sorted(REDUCED))
 def test_reduced_large_shapes(K, act, name):
