@@ -272,6 +272,82 @@ CFDETR_API cfdetr_status cfdetr_multilevel_batch(cfdetr_ctx* ctx, const void* im
                                       float* y_mixed, int32_t* tok_desc, int32_t* cu_seqlens,
                                       int32_t* level_counts, void* hip_stream);
 
+/* ------------------------------------------------------------------------
+ * NPFP** scheduling decisions (Sec. IV).  Host memory only; no GPU work, no context,
+ * no allocation.  Tasks are identified by index, index 0 has the highest priority,
+ * deadlines equal periods.  At most 64 tasks.  WCETs come from tables measured
+ * offline, as in the paper: coarse batches by batch size (c[x] for x subtasks, c[0]
+ * unused), fine batches by the workload level of the largest member and the batch size
+ * (row-major c[level * (max_size + 1) + size]).
+ * ------------------------------------------------------------------------ */
+
+typedef enum {
+  CFDETR_POLICY_C = 0,    /* NPFP^C: coarse subtasks one by one, no fine subtasks      */
+  CFDETR_POLICY_C_F = 1,  /* NPFP^CF                                                   */
+  CFDETR_POLICY_BC_F = 2, /* NPFP^[C]F: coarse subtasks batched                        */
+  CFDETR_POLICY_C_BF = 3, /* NPFP^C[F]: fine subtasks batched                          */
+  CFDETR_POLICY_BC_BF = 4 /* NPFP^[C][F]                                               */
+} cfdetr_policy;
+
+typedef enum { CFDETR_SCHED_IDLE = 0, CFDETR_SCHED_COARSE = 1, CFDETR_SCHED_FINE = 2 } cfdetr_sched_action;
+
+/*
+ * Offline schedulability test of individually executed coarse subtasks (Lemma 1,
+ * Eq. 3-4): R_i is the fixed point of R = C_i + B_i + sum_{h<i} ceil(R / T_h) C_h started
+ * at C_i + B_i, B_i the longest coarse subtask of lower priority.
+ *   period, c_coarse [n] in; response [n] out (infinity if the iteration passes T_i
+ *   before it settles); *schedulable = 1 iff every R_i <= T_i.
+ */
+CFDETR_API cfdetr_status cfdetr_sched_response_times(int32_t n, const double* period,
+                                          const double* c_coarse, double* response,
+                                          int32_t* schedulable);
+
+/*
+ * Coarse batch assignment (Algo. 2): of the n_active active coarse subtasks, how many of
+ * the highest-priority ones run now as one batch: the largest x >= 2 with
+ * c_batch_by_size[x] <= next_release - t (Eq. 5), else 1 (0 if none is active).
+ * Returns -1 on a bad argument.
+ */
+CFDETR_API int32_t cfdetr_sched_coarse_batch(int32_t n_active, double t, double next_release,
+                                  const double* c_batch_by_size);
+
+/*
+ * Dynamic batch assignment of the active fine subtasks (Algo. 3, Lemma 3, Eq. 6).
+ *   workload [n]  level of each subtask (0 = smallest), listed by priority
+ *   deadline [n]  absolute deadlines
+ *   t, next_coarse_release: now and the earliest future release of any task
+ * Out: order [n]: the subtasks sorted by workload (stable); batch_end [n]: batch b is
+ * order[batch_end[b-1] .. batch_end[b]) (batch_end[-1] = 0); *n_batches; dba [n+1]
+ * (may be NULL): least total WCET of a schedulable partition of the first k sorted
+ * subtasks, infinity if none.  A batch must end by every deadline in it and by
+ * next_coarse_release.  If not all subtasks can be placed, the batches cover the longest
+ * prefix of `order` that can.  Ties go to the shorter last batch.
+ */
+CFDETR_API cfdetr_status cfdetr_sched_fine_batches(int32_t n, const int32_t* workload,
+                                        const double* deadline, double t,
+                                        double next_coarse_release, const double* c_batch,
+                                        int32_t n_levels, int32_t max_size, int32_t* order,
+                                        int32_t* batch_end, int32_t* n_batches, double* dba);
+
+/*
+ * The decision at a scheduling instant (Algo. 1): coarse subtasks first (one, or a batch
+ * under the [C] policies); else fine subtasks (one, if it ends before the next coarse
+ * release, or the batches of cfdetr_sched_fine_batches under the [F] policies); else idle.
+ *   active_coarse [n_coarse], active_fine [n_fine]: task indices in priority order;
+ *   fine_workload, fine_deadline aligned with active_fine; next_release: earliest future
+ *   release of any task.
+ * Out: *kind; tasks [max(n_coarse, n_fine)]: the tasks to run, batch after batch;
+ * batch_end / *n_batches as above (one batch for a coarse decision).
+ */
+CFDETR_API cfdetr_status cfdetr_sched_decide(cfdetr_policy policy, double t, int32_t n_coarse,
+                                  const int32_t* active_coarse, int32_t n_fine,
+                                  const int32_t* active_fine, const int32_t* fine_workload,
+                                  const double* fine_deadline, double next_release,
+                                  const double* c_coarse_by_size, const double* c_fine,
+                                  int32_t n_levels, int32_t max_size,
+                                  cfdetr_sched_action* kind, int32_t* tasks,
+                                  int32_t* batch_end, int32_t* n_batches);
+
 /*
  * Per-kernel timing with HIP events on the stream the kernels run on.
  * Between begin and end every launch is bracketed by an event pair (this costs

@@ -9,7 +9,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcfdetr.so")
-SOURCES = ["api.hip", "select.hip", "roi.hip", "rowwise.hip", "gemm.hip", "attention.hip"]
+SOURCES = ["api.hip", "select.hip", "roi.hip", "rowwise.hip", "gemm.hip", "attention.hip",
+           "sched.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # Per-source extras.  The attention kernel reads every MFMA result back for the

@@ -33,7 +33,11 @@ EXPORTS = [
     "cfdetr_sync_status", "cfdetr_coarse_encode", "cfdetr_propose_rois", "cfdetr_select_fine",
     "cfdetr_fine_encode", "cfdetr_fine_encode_padded",
     "cfdetr_multilevel_batch", "cfdetr_profile_begin", "cfdetr_profile_end",
+    "cfdetr_sched_response_times", "cfdetr_sched_coarse_batch", "cfdetr_sched_fine_batches",
+    "cfdetr_sched_decide",
 ]
+POLICIES = {"C": 0, "CF": 1, "[C]F": 2, "C[F]": 3, "[C][F]": 4}
+SCHED_ACTIONS = ["idle", "coarse", "fine"]
 
 
 class CfdetrConfig(ctypes.Structure):
@@ -107,6 +111,17 @@ def load_library() -> ctypes.CDLL:
     lib.cfdetr_fine_encode_padded.restype = ctypes.c_int
     lib.cfdetr_multilevel_batch.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.cfdetr_multilevel_batch.restype = ctypes.c_int
+    dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
+    dbl = ctypes.c_double
+    lib.cfdetr_sched_response_times.argtypes = [i32, dp, dp, dp, ip]
+    lib.cfdetr_sched_response_times.restype = ctypes.c_int
+    lib.cfdetr_sched_coarse_batch.argtypes = [i32, dbl, dbl, dp]
+    lib.cfdetr_sched_coarse_batch.restype = i32
+    lib.cfdetr_sched_fine_batches.argtypes = [i32, ip, dp, dbl, dbl, dp, i32, i32, ip, ip, ip, dp]
+    lib.cfdetr_sched_fine_batches.restype = ctypes.c_int
+    lib.cfdetr_sched_decide.argtypes = [ctypes.c_int, dbl, i32, ip, i32, ip, ip, dp, dbl, dp, dp,
+                                        i32, i32, ip, ip, ip, ip]
+    lib.cfdetr_sched_decide.restype = ctypes.c_int
     lib.cfdetr_profile_begin.argtypes = [vp]
     lib.cfdetr_profile_begin.restype = ctypes.c_int
     lib.cfdetr_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float),
@@ -188,6 +203,77 @@ def cfdetr_multilevel_batch(ctx, images, B, boxes, tier, box_offsets, y_coarse, 
     _check(load_library().cfdetr_multilevel_batch(ctx, images, B, boxes, tier, box_offsets,
                                                   y_coarse, y_mixed, tok_desc, cu_seqlens,
                                                   level_counts, stream), ctx)
+
+
+# ---- scheduling decisions (host data; lists in, lists out) ---------------------
+def _darr(v):
+    return (ctypes.c_double * max(len(v), 1))(*[float(x) for x in v])
+
+
+def _iarr(v):
+    return (ctypes.c_int32 * max(len(v), 1))(*[int(x) for x in v])
+
+
+def _fine_table(c_fine):
+    """[[level][size]] -> flat row-major table, n_levels, max_size."""
+    n_levels, max_size = len(c_fine), len(c_fine[0]) - 1
+    flat = [float(x) for row in c_fine for x in row]
+    return _darr(flat), n_levels, max_size
+
+
+def cfdetr_sched_response_times(period, c_coarse):
+    n = len(period)
+    R = (ctypes.c_double * n)()
+    ok = ctypes.c_int32()
+    _check(load_library().cfdetr_sched_response_times(n, _darr(period), _darr(c_coarse), R,
+                                                      ctypes.byref(ok)))
+    return bool(ok.value), list(R)
+
+
+def cfdetr_sched_coarse_batch(n_active, t, next_release, c_batch_by_size) -> int:
+    return int(load_library().cfdetr_sched_coarse_batch(n_active, t, next_release,
+                                                        _darr(c_batch_by_size)))
+
+
+def cfdetr_sched_fine_batches(workload, deadline, t, next_coarse_release, c_fine):
+    """Returns (order, cuts, dba) like the paper's tables: cuts are half-open ranges."""
+    n = len(workload)
+    tab, n_levels, max_size = _fine_table(c_fine)
+    order, ends = (ctypes.c_int32 * max(n, 1))(), (ctypes.c_int32 * max(n, 1))()
+    nb = ctypes.c_int32()
+    dba = (ctypes.c_double * (n + 1))()
+    _check(load_library().cfdetr_sched_fine_batches(n, _iarr(workload), _darr(deadline), t,
+                                                    next_coarse_release, tab, n_levels, max_size,
+                                                    order, ends, ctypes.byref(nb), dba))
+    cuts, a = [], 0
+    for b in range(nb.value):
+        cuts.append((a, ends[b]))
+        a = ends[b]
+    return list(order)[:n], cuts, list(dba)
+
+
+def cfdetr_sched_decide(policy: str, t, active_coarse, active_fine, fine_workload, fine_deadline,
+                        next_release, c_coarse_by_size, c_fine):
+    """Returns (kind, tasks): ("coarse", [tasks]) | ("fine", [[batch], ...]) | ("idle", [])."""
+    tab, n_levels, max_size = _fine_table(c_fine)
+    m = max(len(active_coarse), len(active_fine), 1)
+    kind, nb = ctypes.c_int32(), ctypes.c_int32()
+    tasks, ends = (ctypes.c_int32 * m)(), (ctypes.c_int32 * m)()
+    _check(load_library().cfdetr_sched_decide(
+        POLICIES[policy], t, len(active_coarse), _iarr(active_coarse), len(active_fine),
+        _iarr(active_fine), _iarr(fine_workload), _darr(fine_deadline), next_release,
+        _darr(c_coarse_by_size), tab, n_levels, max_size, ctypes.byref(kind), tasks, ends,
+        ctypes.byref(nb)))
+    name = SCHED_ACTIONS[kind.value]
+    if name == "coarse":
+        return name, list(tasks)[:ends[0]]
+    if name == "fine":
+        out, a = [], 0
+        for b in range(nb.value):
+            out.append(list(tasks)[a:ends[b]])
+            a = ends[b]
+        return name, out
+    return name, []
 
 
 def cfdetr_profile_begin(ctx) -> None:
