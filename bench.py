@@ -225,6 +225,59 @@ def padded_comparison(cfg_id, steps, warmup):
             "ms_varlen": ms_var, "ms_padded": ms_pad, "padded_over_varlen": ms_pad / ms_var}
 
 
+def wcet_table(cfg_id, runs=30):
+    """Execution-time tables in the form the scheduling calls take (Sec. IV: WCETs are
+    measured offline and looked up at run time): coarse subtask batches by batch size, fine
+    subtask batches by (workload level of the largest member, batch size).  The workload
+    levels S, M, L are frames whose refined area covers 1/4, 1/2 and all of the coarse
+    cells; every entry is the largest of `runs` timed executions plus 10 %."""
+    import torch
+    from paper_2505_23317_amd import cfdetr, synth
+
+    cfg = synth.config(cfg_id)
+    wl = synth.make_workload(cfg_id)
+    enc = cfdetr.Encoder(cfg, wl["weights"], act_dtype="bf16")
+    img = enc.upload_images(wl["images"])
+    out = enc.alloc_outputs(cfg.B)
+    top = cfg.n_levels - 1
+
+    def worst(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        best = 0.0
+        for _ in range(runs):
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            best = max(best, time.perf_counter() - t0)
+        return 1.1e3 * best
+
+    coarse = [0.0] + [worst(lambda k=k: enc.coarse_encode(img, k, out["x0_cache"], out["y_coarse"]))
+                      for k in range(1, cfg.B + 1)]
+    fine, tokens = [], []
+    for frac in (0.25, 0.5, 1.0):
+        rows = max(1, int(round(frac * cfg.H / cfg.patch[0]))) * cfg.patch[0]
+        boxes = np.tile(np.array([[0, 0, cfg.W, rows]], dtype=np.int32), (cfg.B, 1))
+        b, t, o = enc.upload_boxes(boxes, np.full(cfg.B, top, np.uint8),
+                                   np.arange(cfg.B + 1, dtype=np.int32))
+        row = [0.0]
+        for k in range(1, cfg.B + 1):
+            def run(k=k):
+                enc.select_fine(b, t, o, k, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
+                enc.fine_encode(img, k, out["tok_desc"], out["cu_seqlens"], out["x0_cache"],
+                                out["y_mixed"])
+            row.append(worst(run))
+        torch.cuda.synchronize()
+        tokens.append(int(out["cu_seqlens"].cpu().numpy()[1]))
+        fine.append(row)
+    enc.sync_status()
+    enc.close()
+    return {"workload": f"configs[{cfg_id - 1}] {cfg.name}", "unit": "ms",
+            "coarse_by_batch_size": coarse, "fine_levels_tokens_per_frame": tokens,
+            "fine_by_level_and_batch_size": fine}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -236,6 +289,9 @@ def main() -> int:
     ap.add_argument("--compare-padded", action="store_true",
                     help="also time the fine pass in the paper's padded form against the "
                          "variable-length form (adds padded_baseline to the line)")
+    ap.add_argument("--wcet-table", action="store_true",
+                    help="also measure the execution-time tables the scheduling calls take "
+                         "(adds wcet_table to the line)")
     ap.add_argument("--no-others", action="store_true",
                     help="skip the short extra measurements of the two largest configs")
     args = ap.parse_args()
@@ -293,6 +349,8 @@ def main() -> int:
     if args.compare_padded:
         result["padded_baseline"] = [padded_comparison(c, 20, 3)
                                      for c in sorted({args.config, 3, 4})]
+    if args.wcet_table:
+        result["wcet_table"] = wcet_table(args.config)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, m["wl"], args.config)
     print(json.dumps(result))
