@@ -19,6 +19,8 @@ What it computes, and where the paper states it:
 * multi-level batching (A3, Sec. III-B) runs several frames' token sets, of
   different lengths, through the encoder together; batching is a latency
   device and must not change any frame's result;
+* learned object queries attend to the encoded tokens in a decoder and come out as
+  candidate boxes with a confidence (Sec. II-A);
 * the coarse stage's object queries decide whether a frame is easy or hard
   (A1: average confidence of the queries that are not already certain) and,
   for hard frames, propose the regions to refine (A2: the boxes of the
@@ -334,6 +336,66 @@ def encode_sequence(x: np.ndarray, weights: Dict[str, np.ndarray], heads: int,
     for l in range(weights["w_qkv"].shape[0]):
         x = encoder_layer(x, weights, l, heads, key_mask)
     return layer_norm(x, weights["lnf_g"], weights["lnf_b"])
+
+
+# --------------------------------------------------------------------------
+# decoder: learned object queries read the encoded tokens of their frame and
+# become candidate boxes with a confidence (Sec. II-A)
+# --------------------------------------------------------------------------
+def cross_attention(a: np.ndarray, mem: np.ndarray, w_q: np.ndarray, b_q: np.ndarray,
+                    w_kv: np.ndarray, b_kv: np.ndarray, w_o: np.ndarray, b_o: np.ndarray,
+                    heads: int) -> np.ndarray:
+    """Multi-head attention of queries a [Q, d] over the tokens mem [T, d] of the same
+    frame (Sec. II-A: object queries attend to the encoded patches).  w_kv [2d, d] stacks
+    the key and value projections."""
+    Q, d = a.shape
+    dh = d // heads
+    q = a @ w_q.astype(np.float64).T + b_q.astype(np.float64)
+    kv = mem @ w_kv.astype(np.float64).T + b_kv.astype(np.float64)
+    k, v = kv[:, :d], kv[:, d:]
+    out = np.empty((Q, d), dtype=np.float64)
+    for h in range(heads):
+        sl = slice(h * dh, (h + 1) * dh)
+        out[:, sl] = softmax_rows(q[:, sl] @ k[:, sl].T / math.sqrt(dh)) @ v[:, sl]
+    return out @ w_o.astype(np.float64).T + b_o.astype(np.float64)
+
+
+def decode_frame(mem: np.ndarray, dw: Dict[str, np.ndarray], heads: int) -> np.ndarray:
+    """Object queries of one frame from its encoded tokens mem [T, d]; returns [Q, 5] =
+    (cx, cy, w, h, c), all in (0, 1).
+
+    Readings (the paper describes the DETR pipeline, Sec. II-A, and fixes no layer
+    details): the queries start as learned vectors; every layer is pre-LN,
+    x += SelfAttn(LN1 x); x += CrossAttn(LN2 x, mem); x += W2 GELU(W1 LN3 x); a final
+    LayerNorm; no positional term beyond what the tokens already carry.  Heads: the
+    confidence is the sigmoid of one linear output, the box the sigmoid of a three-layer
+    perceptron with ReLU (centre and size as fractions of the frame)."""
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    x = f64(dw["query_embed"]).copy()
+    for l in range(dw["w_qkv"].shape[0]):
+        a = layer_norm(x, dw["ln1_g"][l], dw["ln1_b"][l])
+        x = x + self_attention(a, dw["w_qkv"][l], dw["b_qkv"][l], dw["w_o"][l], dw["b_o"][l], heads)
+        a = layer_norm(x, dw["ln2_g"][l], dw["ln2_b"][l])
+        x = x + cross_attention(a, mem, dw["w_q"][l], dw["b_q"][l], dw["w_kv"][l], dw["b_kv"][l],
+                                dw["w_o2"][l], dw["b_o2"][l], heads)
+        m = layer_norm(x, dw["ln3_g"][l], dw["ln3_b"][l])
+        hdn = gelu(m @ f64(dw["w_ff1"][l]).T + f64(dw["b_ff1"][l]))
+        x = x + hdn @ f64(dw["w_ff2"][l]).T + f64(dw["b_ff2"][l])
+    z = layer_norm(x, dw["lnf_g"], dw["lnf_b"])
+    sig = lambda u: 1.0 / (1.0 + np.exp(-u))
+    conf = sig(z @ f64(dw["w_cls"]).T + f64(dw["b_cls"]))                      # [Q, 1]
+    h1 = np.maximum(z @ f64(dw["w_box1"]).T + f64(dw["b_box1"]), 0.0)
+    h2 = np.maximum(h1 @ f64(dw["w_box2"]).T + f64(dw["b_box2"]), 0.0)
+    box = sig(h2 @ f64(dw["w_box3"]).T + f64(dw["b_box3"]))                    # [Q, 4]
+    return np.concatenate([box, conf], axis=1)
+
+
+def decode(memory: np.ndarray, cu_seqlens: np.ndarray, dw: Dict[str, np.ndarray],
+           heads: int) -> np.ndarray:
+    """decode_frame for every frame of a batch: memory [T, d] with frame i at rows
+    cu_seqlens[i]..cu_seqlens[i+1]; returns [B, Q, 5].  Frames do not interact."""
+    return np.stack([decode_frame(memory[cu_seqlens[f]:cu_seqlens[f + 1]], dw, heads)
+                     for f in range(len(cu_seqlens) - 1)])
 
 
 # --------------------------------------------------------------------------

@@ -20,7 +20,7 @@ import numpy as np
 
 __all__ = [
     "Config", "CONFIGS", "config", "bf16_round", "bf16_bits", "make_weights",
-    "make_frames", "make_workload", "make_queries", "replace",
+    "make_frames", "make_workload", "make_queries", "make_decoder_weights", "replace",
 ]
 
 
@@ -270,3 +270,38 @@ def make_queries(cfg: Config, seed: int, n_queries: int = 128, easy_frames=()) -
         c = np.where(kinds == 2, rng.uniform(0.8001, 1.0, n_queries), c)
         q[f, :, 4] = c
     return q
+
+
+def make_decoder_weights(cfg: Config, seed: int, n_queries: int = 128, layers: int = 2,
+                         std: float = 0.02) -> Dict[str, np.ndarray]:
+    """Random-init decoder weights (same law as make_weights): learned queries, per layer
+    self-attention, cross-attention and FFN blocks, final LayerNorm, confidence and box
+    heads.  Matrices are bf16-representable float32.  The query vectors and the head
+    matrices are drawn wider (std 1 and 0.5) so that boxes and confidences spread over
+    (0, 1) instead of sitting at 0.5."""
+    rng = np.random.default_rng(90000 + seed)
+    d, F, L = cfg.d, cfg.ffn, layers
+
+    def mat(*shape, s=std):
+        return bf16_round(rng.normal(0.0, s, shape).astype(np.float32))
+
+    def vec(*shape, s=std):
+        return rng.normal(0.0, s, shape).astype(np.float32)
+
+    def gain(*shape):
+        return (1.0 + rng.normal(0.0, std, shape)).astype(np.float32)
+
+    return {
+        "query_embed": rng.normal(0.0, 1.0, (n_queries, d)).astype(np.float32),
+        "ln1_g": gain(L, d), "ln1_b": vec(L, d),
+        "w_qkv": mat(L, 3 * d, d), "b_qkv": vec(L, 3 * d), "w_o": mat(L, d, d), "b_o": vec(L, d),
+        "ln2_g": gain(L, d), "ln2_b": vec(L, d),
+        "w_q": mat(L, d, d), "b_q": vec(L, d), "w_kv": mat(L, 2 * d, d), "b_kv": vec(L, 2 * d),
+        "w_o2": mat(L, d, d), "b_o2": vec(L, d),
+        "ln3_g": gain(L, d), "ln3_b": vec(L, d),
+        "w_ff1": mat(L, F, d), "b_ff1": vec(L, F), "w_ff2": mat(L, d, F), "b_ff2": vec(L, d),
+        "lnf_g": gain(d), "lnf_b": vec(d),
+        "w_cls": mat(1, d, s=0.5), "b_cls": vec(1, s=0.5),
+        "w_box1": mat(d, d, s=0.1), "b_box1": vec(d), "w_box2": mat(d, d, s=0.1), "b_box2": vec(d),
+        "w_box3": mat(4, d, s=0.5), "b_box3": vec(4, s=0.5),
+    }
