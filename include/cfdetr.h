@@ -135,7 +135,9 @@ typedef enum {
   CFDETR_K_FF1 = 8,    /* first FFN projection + GELU                          */
   CFDETR_K_FF2 = 9,    /* second FFN projection + residual                     */
   CFDETR_K_ROI = 10,   /* difficulty test and region proposal                  */
-  CFDETR_K_COUNT = 11
+  CFDETR_K_DEC = 11,   /* decoder kernels that are not one of the families above
+                          (cast, query broadcast, key/value projection, heads)   */
+  CFDETR_K_COUNT = 12
 } cfdetr_kernel_id;
 
 /* Host-side.  Validates cfg, copies it, keeps the weight POINTERS, allocates
@@ -271,6 +273,79 @@ CFDETR_API cfdetr_status cfdetr_multilevel_batch(cfdetr_ctx* ctx, const void* im
                                       const int32_t* box_offsets, float* y_coarse,
                                       float* y_mixed, int32_t* tok_desc, int32_t* cu_seqlens,
                                       int32_t* level_counts, void* hip_stream);
+
+/* ------------------------------------------------------------------------
+ * Decoder (Sec. II-A: learned object queries attend to the encoded tokens of their frame
+ * and come out as candidate boxes with a confidence).  The paper fixes no layer details;
+ * this library's reading: n_queries learned vectors start every frame's queries; each of
+ * the n_layers layers is pre-LN, x += SelfAttn(LN1 x); x += CrossAttn(LN2 x, tokens);
+ * x += W2 GELU(W1 LN3 x); a final LayerNorm; the confidence is the logistic function of
+ * one linear output, the box (cx, cy, w, h as fractions of the frame) the logistic
+ * function of a three-layer perceptron with ReLU.  Widths, head count and FFN width are
+ * the context's.  bf16 contexts only.
+ * Weights (device pointers, matrices in bf16 bit patterns, vectors fp32, row-major,
+ * stacked over layers like the encoder's):
+ *   query_embed [Q, d] fp32
+ *   ln1_g, ln1_b [L, d]; w_qkv [L, 3d, d]; b_qkv [L, 3d]; w_o [L, d, d]; b_o [L, d]
+ *   ln2_g, ln2_b [L, d]; w_q [L, d, d]; b_q [L, d]; w_kv [L, 2d, d] (key rows, value
+ *   rows); b_kv [L, 2d]; w_o2 [L, d, d]; b_o2 [L, d]
+ *   ln3_g, ln3_b [L, d]; w_ff1 [L, F, d]; b_ff1 [L, F]; w_ff2 [L, d, F]; b_ff2 [L, d]
+ *   lnf_g, lnf_b [d]; w_cls [1, d]; b_cls [1]; w_box1, w_box2 [d, d]; b_box1, b_box2 [d];
+ *   w_box3 [4, d]; b_box3 [4]
+ * ------------------------------------------------------------------------ */
+typedef struct {
+  int32_t n_queries; /* 1..1024 */
+  int32_t n_layers;  /* >= 1   */
+  const float* query_embed;
+  const float *ln1_g, *ln1_b;
+  const void* w_qkv;
+  const float* b_qkv;
+  const void* w_o;
+  const float* b_o;
+  const float *ln2_g, *ln2_b;
+  const void* w_q;
+  const float* b_q;
+  const void* w_kv;
+  const float* b_kv;
+  const void* w_o2;
+  const float* b_o2;
+  const float *ln3_g, *ln3_b;
+  const void* w_ff1;
+  const float* b_ff1;
+  const void* w_ff2;
+  const float* b_ff2;
+  const float *lnf_g, *lnf_b;
+  const void* w_cls;
+  const float* b_cls;
+  const void* w_box1;
+  const float* b_box1;
+  const void* w_box2;
+  const float* b_box2;
+  const void* w_box3;
+  const float* b_box3;
+} cfdetr_decoder_weights;
+
+/*
+ * Gives the context a decoder: checks the weights and allocates the decoder's work space
+ * (freed by cfdetr_destroy).  Once per context; the weights must outlive it.
+ */
+CFDETR_API cfdetr_status cfdetr_decoder_attach(cfdetr_ctx* ctx, const cfdetr_decoder_weights* w);
+
+/*
+ * Object queries of every frame from its encoded tokens.
+ *   memory      [T, d] fp32: encoder output (y_coarse or y_mixed), frame i at rows
+ *               cu_seqlens[i] .. cu_seqlens[i+1]; T <= max_tokens_total
+ *   cu_seqlens  [B+1] int32 (device), cu_seqlens[0] = 0, every frame at least one token.
+ *               Checked on the device: a frame without tokens or a total above
+ *               max_tokens_total makes the attention kernels do nothing, leaves `queries`
+ *               undefined, and cfdetr_sync_status reports CFDETR_ECAPACITY.
+ *   queries     [B, Q, 5] fp32 out: (cx, cy, w, h, c), the form cfdetr_propose_rois takes
+ * Uses the context's encoder work space as scratch: a later encode call overwrites it,
+ * and an encode call in flight on another stream must not overlap.
+ */
+CFDETR_API cfdetr_status cfdetr_decode(cfdetr_ctx* ctx, const float* memory,
+                            const int32_t* cu_seqlens, int32_t B, float* queries,
+                            void* hip_stream);
 
 /* ------------------------------------------------------------------------
  * NPFP** scheduling decisions (Sec. IV).  Host memory only; no GPU work, no context,

@@ -24,7 +24,7 @@ CFDETR_OK, CFDETR_EINVAL, CFDETR_ESHAPE, CFDETR_ECAPACITY, CFDETR_ENOMEM, CFDETR
 CFDETR_BF16, CFDETR_FP32 = 0, 1
 CFDETR_MAX_LEVELS = 3
 KERNEL_NAMES = ["select", "plan", "embed", "gather", "layernorm", "qkv", "attention",
-                "out_proj", "ffn1", "ffn2", "roi"]
+                "out_proj", "ffn1", "ffn2", "roi", "dec"]
 CFDETR_K_COUNT = len(KERNEL_NAMES)
 STATUS_NAMES = ["OK", "EINVAL", "ESHAPE", "ECAPACITY", "ENOMEM", "EDEVICE"]
 
@@ -34,7 +34,7 @@ EXPORTS = [
     "cfdetr_fine_encode", "cfdetr_fine_encode_padded",
     "cfdetr_multilevel_batch", "cfdetr_profile_begin", "cfdetr_profile_end",
     "cfdetr_sched_response_times", "cfdetr_sched_coarse_batch", "cfdetr_sched_fine_batches",
-    "cfdetr_sched_decide",
+    "cfdetr_sched_decide", "cfdetr_decoder_attach", "cfdetr_decode",
 ]
 POLICIES = {"C": 0, "CF": 1, "[C]F": 2, "C[F]": 3, "[C][F]": 4}
 SCHED_ACTIONS = ["idle", "coarse", "fine"]
@@ -71,6 +71,19 @@ class CfdetrWeights(ctypes.Structure):
         ("w_ff2", ctypes.c_void_p), ("b_ff2", ctypes.c_void_p),
         ("lnf_g", ctypes.c_void_p), ("lnf_b", ctypes.c_void_p),
     ]
+
+
+DECODER_MATRICES = ("w_qkv", "w_o", "w_q", "w_kv", "w_o2", "w_ff1", "w_ff2", "w_cls", "w_box1",
+                    "w_box2", "w_box3")
+DECODER_FIELDS = ("query_embed", "ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b",
+                  "w_q", "b_q", "w_kv", "b_kv", "w_o2", "b_o2", "ln3_g", "ln3_b", "w_ff1", "b_ff1",
+                  "w_ff2", "b_ff2", "lnf_g", "lnf_b", "w_cls", "b_cls", "w_box1", "b_box1",
+                  "w_box2", "b_box2", "w_box3", "b_box3")
+
+
+class CfdetrDecoderWeights(ctypes.Structure):
+    _fields_ = ([("n_queries", ctypes.c_int32), ("n_layers", ctypes.c_int32)]
+                + [(name, ctypes.c_void_p) for name in DECODER_FIELDS])
 
 
 _lib = None
@@ -122,6 +135,10 @@ def load_library() -> ctypes.CDLL:
     lib.cfdetr_sched_decide.argtypes = [ctypes.c_int, dbl, i32, ip, i32, ip, ip, dp, dbl, dp, dp,
                                         i32, i32, ip, ip, ip, ip]
     lib.cfdetr_sched_decide.restype = ctypes.c_int
+    lib.cfdetr_decoder_attach.argtypes = [vp, ctypes.POINTER(CfdetrDecoderWeights)]
+    lib.cfdetr_decoder_attach.restype = ctypes.c_int
+    lib.cfdetr_decode.argtypes = [vp, vp, vp, i32, vp, vp]
+    lib.cfdetr_decode.restype = ctypes.c_int
     lib.cfdetr_profile_begin.argtypes = [vp]
     lib.cfdetr_profile_begin.restype = ctypes.c_int
     lib.cfdetr_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float),
@@ -179,6 +196,14 @@ def cfdetr_propose_rois(ctx, queries, B, Q, params: CfdetrRoiParams, max_boxes, 
     _check(load_library().cfdetr_propose_rois(ctx, queries, B, Q, ctypes.byref(params), max_boxes,
                                               boxes, tier, box_offsets, hard, mean_conf, stream),
            ctx)
+
+
+def cfdetr_decoder_attach(ctx, weights: CfdetrDecoderWeights) -> None:
+    _check(load_library().cfdetr_decoder_attach(ctx, ctypes.byref(weights)), ctx)
+
+
+def cfdetr_decode(ctx, memory, cu_seqlens, B, queries, stream=0) -> None:
+    _check(load_library().cfdetr_decode(ctx, memory, cu_seqlens, B, queries, stream), ctx)
 
 
 def cfdetr_select_fine(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts,
@@ -390,6 +415,24 @@ class Encoder:
         cfdetr_propose_rois(self.ctx, queries.data_ptr(), B, Q, params, int(boxes.shape[0]),
                             boxes.data_ptr(), tier.data_ptr(), box_offsets.data_ptr(),
                             hard.data_ptr(), mean_conf.data_ptr(), self._stream())
+
+    def attach_decoder(self, weights: Dict[str, np.ndarray]):
+        """weights: float32 numpy arrays named as include/cfdetr.h lists them; uploaded here
+        (matrices as bf16 bit patterns) and kept alive with the context."""
+        self.dec_dev = {k: _to_device(v, k in DECODER_MATRICES) for k, v in weights.items()}
+        w = CfdetrDecoderWeights()
+        w.n_queries = int(weights["query_embed"].shape[0])
+        w.n_layers = int(weights["w_qkv"].shape[0])
+        for name in DECODER_FIELDS:
+            setattr(w, name, self.dec_dev[name].data_ptr())
+        self.n_queries = w.n_queries
+        self.c_dec = w
+        cfdetr_decoder_attach(self.ctx, w)
+
+    def decode(self, memory, cu_seqlens, B, queries):
+        """memory: float32 device tensor [T, d]; queries: float32 device tensor [B, Q, 5] out."""
+        cfdetr_decode(self.ctx, memory.data_ptr(), cu_seqlens.data_ptr(), B, queries.data_ptr(),
+                      self._stream())
 
     def select_fine(self, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts=None):
         cfdetr_select_fine(self.ctx, boxes.data_ptr(), tier.data_ptr(), box_offsets.data_ptr(), B,

@@ -56,6 +56,27 @@ struct cfdetr_ctx {
   int block_q = 0;
   int32_t* err_flag = nullptr;
 
+  // decoder (cfdetr_decoder_attach): its own allocation
+  bool has_dec = false;
+  cfdetr_decoder_weights dw;
+  void* dec_arena = nullptr;
+  float* dx = nullptr;        // residual stream of the queries [Bmax*Q, d] fp32
+  void* da = nullptr;         // LayerNorm output / head input [Bmax*Q, d] bf16
+  void* dqkv = nullptr;       // [Bmax*Q, 3d] bf16 (self-attention), first third reused for
+                              // the cross-attention queries
+  void* d_o = nullptr;        // attention output [Bmax*Q, d]
+  void* dh = nullptr;         // FFN hidden [Bmax*Q, F]; also the box head's hidden rows
+  void* dvt = nullptr;        // V of the queries, feature-major
+  int dvt_ld = 0;
+  int32_t* dcu = nullptr;     // i * Q
+  int32_t* dcu_all = nullptr; // plan outputs for the query sequences
+  int32_t* dm_all = nullptr;
+  int32_t* dpcu = nullptr;
+  int32_t* ditems = nullptr;
+  int dcap8 = 0;
+  int dgrid = 0;
+  int32_t* dqueue = nullptr;  // 8 counters per attention launch (two per layer)
+
   std::string err;
 
   bool prof = false;
@@ -322,6 +343,92 @@ cfdetr_status padded_impl(cfdetr_ctx* ctx, const void* images, int B, const int3
   return run_encoder(ctx, ctx->cu_pad, B, 0, B * t_pad, y_padded, 0, nullptr, s, ctx->kv_len);
 }
 
+// Decoder over the encoded tokens `memory` of B frames (Sec. II-A).  The token side (bf16
+// copy of the tokens, their keys and feature-major values) lives in the encoder's work
+// space, which is idle here; the query side has the decoder's own buffers.
+cfdetr_status decode_impl(cfdetr_ctx* ctx, const float* memory, const int32_t* cu, int B,
+                          float* queries, hipStream_t s) {
+  const cfdetr_config& c = ctx->cfg;
+  const cfdetr_decoder_weights& w = ctx->dw;
+  const int d = c.d_model, F = c.d_ffn, Q = w.n_queries, L = w.n_layers;
+  const int Mq = B * Q, cap_m = c.max_tokens_total;
+  const float eps = c.ln_eps;
+  const float qs = attention_q_scale(d / c.n_heads);
+  // token sequences: offsets, total and padded offsets (the work list is not used).  The
+  // offsets are the caller's: the plan checks them, and after an error the second plan
+  // hands the attention kernels no work.
+  CF_LAUNCH(CFDETR_K_PLAN,
+            launch_plan(cu, B, 0, 0, ctx->block_q, c.n_heads, ctx->items, ctx->cap8, ctx->cu_all,
+                        ctx->m_all, ctx->pcu, ctx->queue_heads, 8, ctx->attn_grid / 8, s, cap_m,
+                        ctx->err_flag, nullptr));
+  CF_LAUNCH(CFDETR_K_DEC, launch_cast_bf16(memory, ctx->a, d, ctx->m_all, cap_m, s));
+  // query sequences: B times Q rows, work list for both attentions of every layer
+  CF_LAUNCH(CFDETR_K_PLAN,
+            launch_plan(ctx->dcu, B, 0, 0, ctx->block_q, c.n_heads, ctx->ditems, ctx->dcap8,
+                        ctx->dcu_all, ctx->dm_all, ctx->dpcu, ctx->dqueue, 16 * L,
+                        ctx->dgrid / 8, s, 0, nullptr, ctx->err_flag));
+  CF_LAUNCH(CFDETR_K_DEC, launch_broadcast_rows(w.query_embed, ctx->dx, Q, d, B, s));
+  const char* wqkv = static_cast<const char*>(w.w_qkv);
+  const char* wo = static_cast<const char*>(w.w_o);
+  const char* wq = static_cast<const char*>(w.w_q);
+  const char* wkv = static_cast<const char*>(w.w_kv);
+  const char* wo2 = static_cast<const char*>(w.w_o2);
+  const char* w1 = static_cast<const char*>(w.w_ff1);
+  const char* w2 = static_cast<const char*>(w.w_ff2);
+  for (int l = 0; l < L; ++l) {
+    // self-attention among the queries of a frame
+    CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->dx, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d,
+                                            ctx->da, true, d, eps, nullptr, Mq, Mq, 0, nullptr, s));
+    CF_LAUNCH(CFDETR_K_QKV,
+              launch_gemm_qkv(ctx->da, wqkv + (size_t)l * 3 * d * d * 2, w.b_qkv + (size_t)l * 3 * d,
+                              d, qs, ctx->dqkv, ctx->dvt, ctx->dvt_ld, ctx->dcu_all, ctx->dpcu, B,
+                              nullptr, Mq, Mq, s));
+    CF_LAUNCH(CFDETR_K_ATTN,
+              launch_attention(ctx->dqkv, ctx->dvt, ctx->dvt_ld, ctx->d_o, ctx->dcu_all, ctx->dpcu,
+                               d, c.n_heads, ctx->ditems, ctx->dcap8, ctx->dqueue + 16 * l,
+                               ctx->dgrid, ctx->block_q, true, nullptr, s));
+    CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->d_o, wo + (size_t)l * d * d * 2, w.b_o + (size_t)l * d,
+                                        d, d, Epilogue::kBiasResidual, nullptr, ctx->dx, true,
+                                        nullptr, Mq, Mq, s));
+    // cross-attention: the queries read the tokens of their frame
+    CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->dx, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d,
+                                            ctx->da, true, d, eps, nullptr, Mq, Mq, 0, nullptr, s));
+    CF_LAUNCH(CFDETR_K_QKV, launch_gemm(ctx->da, wq + (size_t)l * d * d * 2, w.b_q + (size_t)l * d, d,
+                                        d, Epilogue::kBias, ctx->dqkv, nullptr, true, nullptr, Mq,
+                                        Mq, s, qs));
+    CF_LAUNCH(CFDETR_K_DEC,
+              launch_gemm_kv(ctx->a, wkv + (size_t)l * 2 * d * d * 2, w.b_kv + (size_t)l * 2 * d, d,
+                             ctx->qkv, ctx->vt, ctx->vt_ld, ctx->cu_all, ctx->pcu, B, ctx->m_all, 0,
+                             cap_m, s));
+    CF_LAUNCH(CFDETR_K_ATTN,
+              launch_cross_attention(ctx->dqkv, ctx->qkv, ctx->vt, ctx->vt_ld, ctx->d_o,
+                                     ctx->dcu_all, ctx->cu_all, ctx->pcu, d, c.n_heads, ctx->ditems,
+                                     ctx->dcap8, ctx->dqueue + 16 * l + 8, ctx->dgrid, s));
+    CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->d_o, wo2 + (size_t)l * d * d * 2, w.b_o2 + (size_t)l * d,
+                                        d, d, Epilogue::kBiasResidual, nullptr, ctx->dx, true,
+                                        nullptr, Mq, Mq, s));
+    // feed-forward
+    CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->dx, w.ln3_g + (size_t)l * d, w.ln3_b + (size_t)l * d,
+                                            ctx->da, true, d, eps, nullptr, Mq, Mq, 0, nullptr, s));
+    CF_LAUNCH(CFDETR_K_FF1, launch_gemm(ctx->da, w1 + (size_t)l * F * d * 2, w.b_ff1 + (size_t)l * F,
+                                        F, d, Epilogue::kBiasGelu, ctx->dh, nullptr, true, nullptr,
+                                        Mq, Mq, s));
+    CF_LAUNCH(CFDETR_K_FF2, launch_gemm(ctx->dh, w2 + (size_t)l * d * F * 2, w.b_ff2 + (size_t)l * d,
+                                        d, F, Epilogue::kBiasResidual, nullptr, ctx->dx, true,
+                                        nullptr, Mq, Mq, s));
+  }
+  // heads: z = final LayerNorm (bf16); box perceptron hidden rows in dqkv / d_o
+  CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->dx, w.lnf_g, w.lnf_b, ctx->da, true, d, eps, nullptr,
+                                          Mq, Mq, 0, nullptr, s));
+  CF_LAUNCH(CFDETR_K_DEC, launch_gemm(ctx->da, w.w_box1, w.b_box1, d, d, Epilogue::kBiasRelu,
+                                      ctx->dqkv, nullptr, true, nullptr, Mq, Mq, s));
+  CF_LAUNCH(CFDETR_K_DEC, launch_gemm(ctx->dqkv, w.w_box2, w.b_box2, d, d, Epilogue::kBiasRelu,
+                                      ctx->d_o, nullptr, true, nullptr, Mq, Mq, s));
+  CF_LAUNCH(CFDETR_K_DEC, launch_decoder_heads(ctx->da, ctx->d_o, w.w_cls, w.b_cls, w.w_box3,
+                                               w.b_box3, d, Mq, queries, s));
+  return CFDETR_OK;
+}
+
 // A1 -> A2 -> A3 with ONE encoder run: the B coarse grids and the B mixed token sets
 // are 2B independent sequences of the same variable-length batch (same weights), so
 // every layer kernel is launched once for both.  Only the coarse embedding has to
@@ -492,6 +599,7 @@ CFDETR_API void cfdetr_destroy(cfdetr_ctx* ctx) {
   hipDeviceSynchronize();
   for (hipEvent_t ev : ctx->ev) hipEventDestroy(ev);
   if (ctx->arena) hipFree(ctx->arena);
+  if (ctx->dec_arena) hipFree(ctx->dec_arena);
   delete ctx;
 }
 
@@ -512,7 +620,7 @@ CFDETR_API cfdetr_status cfdetr_sync_status(cfdetr_ctx* ctx, void* hip_stream) {
   if (flag) {
     e = hipMemset(ctx->err_flag, 0, 4);
     if (e != hipSuccess) return fail_hip(ctx, "hipMemset", e);
-    return fail(ctx, CFDETR_ECAPACITY, "selection produced more tokens than max_tokens_total");
+    return fail(ctx, CFDETR_ECAPACITY, "a device-side check failed: more tokens or regions than the context holds, or bad sequence offsets");
   }
   return CFDETR_OK;
 }
@@ -605,6 +713,83 @@ CFDETR_API cfdetr_status cfdetr_multilevel_batch(cfdetr_ctx* ctx, const void* im
     return fail(ctx, CFDETR_EINVAL, "pointers must be 16-byte aligned");
   return merged_impl(ctx, images, B, boxes, tier, box_offsets, y_coarse, y_mixed, tok_desc,
                      cu_seqlens, level_counts, static_cast<hipStream_t>(hip_stream));
+}
+
+CFDETR_API cfdetr_status cfdetr_decoder_attach(cfdetr_ctx* ctx, const cfdetr_decoder_weights* w) {
+  if (!ctx) return CFDETR_EINVAL;
+  if (!w) return fail(ctx, CFDETR_EINVAL, "null argument");
+  if (ctx->has_dec) return fail(ctx, CFDETR_EINVAL, "the context already has a decoder");
+  if (!ctx->bf16) return fail(ctx, CFDETR_ESHAPE, "the decoder needs act_dtype bf16");
+  if (w->n_queries < 1 || w->n_queries > 1024 || w->n_layers < 1)
+    return fail(ctx, CFDETR_ESHAPE, "n_queries must be 1..1024 and n_layers >= 1");
+  const void* ptrs[] = {w->query_embed, w->ln1_g, w->ln1_b, w->w_qkv, w->b_qkv, w->w_o,   w->b_o,
+                        w->ln2_g,       w->ln2_b, w->w_q,  w->b_q,   w->w_kv,  w->b_kv, w->w_o2,
+                        w->b_o2,        w->ln3_g, w->ln3_b, w->w_ff1, w->b_ff1, w->w_ff2, w->b_ff2,
+                        w->lnf_g,       w->lnf_b, w->w_cls, w->b_cls, w->w_box1, w->b_box1,
+                        w->w_box2,      w->b_box2, w->w_box3, w->b_box3};
+  for (const void* p : ptrs)
+    if (!p) return fail(ctx, CFDETR_EINVAL, "null decoder weight");
+  const void* al[] = {w->query_embed, w->ln1_g, w->ln1_b, w->w_qkv, w->b_qkv, w->w_o, w->b_o,
+                      w->ln2_g, w->ln2_b, w->w_q, w->b_q, w->w_kv, w->b_kv, w->w_o2, w->b_o2,
+                      w->ln3_g, w->ln3_b, w->w_ff1, w->b_ff1, w->w_ff2, w->b_ff2, w->lnf_g,
+                      w->lnf_b, w->w_box1, w->b_box1, w->w_box2, w->b_box2};
+  for (const void* p : al)
+    if (!aligned16(p)) return fail(ctx, CFDETR_EINVAL, "misaligned decoder weight");
+  const cfdetr_config& c = ctx->cfg;
+  const uint64_t Bm = c.max_batch, Q = w->n_queries, d = c.d_model, F = c.d_ffn;
+  const uint64_t Mq = Bm * Q;
+  // query tiles of a whole run; per queue at most all/8 + those of one sequence
+  const int tiles_seq = (int)((Q + ctx->block_q - 1) / ctx->block_q);
+  ctx->dcap8 = (int)((Bm * tiles_seq * c.n_heads + 7) / 8) + tiles_seq;
+  ctx->dgrid = attention_grid(c.d_model / c.n_heads, true, ctx->dcap8);
+  if (ctx->dgrid < 8) return fail(ctx, CFDETR_EDEVICE, "cannot size the attention grid");
+  ctx->dvt_ld = (int)(Bm * ((Q + 63) & ~uint64_t(63)) + 64);
+  Carver cv;
+  const uint64_t o_x = cv.take(Mq * d * 4), o_a = cv.take(Mq * d * 2), o_qkv = cv.take(Mq * 3 * d * 2);
+  const uint64_t o_o = cv.take(Mq * d * 2), o_h = cv.take(Mq * std::max(F, d) * 2);
+  const uint64_t o_vt = cv.take(d * (uint64_t)ctx->dvt_ld * 2);
+  const uint64_t o_cu = cv.take((Bm + 1) * 4), o_cua = cv.take((Bm + 1) * 4), o_m = cv.take(4);
+  const uint64_t o_pcu = cv.take((Bm + 1) * 4), o_items = cv.take((uint64_t)ctx->dcap8 * 8 * 4);
+  const uint64_t o_q = cv.take((uint64_t)w->n_layers * 16 * 4);
+  hipError_t e = hipMalloc(&ctx->dec_arena, cv.off);
+  if (e != hipSuccess) return fail(ctx, CFDETR_ENOMEM, "hipMalloc of the decoder work space");
+  char* base = static_cast<char*>(ctx->dec_arena);
+  ctx->dx = reinterpret_cast<float*>(base + o_x);
+  ctx->da = base + o_a;
+  ctx->dqkv = base + o_qkv;
+  ctx->d_o = base + o_o;
+  ctx->dh = base + o_h;
+  ctx->dvt = base + o_vt;
+  ctx->dcu = reinterpret_cast<int32_t*>(base + o_cu);
+  ctx->dcu_all = reinterpret_cast<int32_t*>(base + o_cua);
+  ctx->dm_all = reinterpret_cast<int32_t*>(base + o_m);
+  ctx->dpcu = reinterpret_cast<int32_t*>(base + o_pcu);
+  ctx->ditems = reinterpret_cast<int32_t*>(base + o_items);
+  ctx->dqueue = reinterpret_cast<int32_t*>(base + o_q);
+  std::vector<int32_t> cu(Bm + 1);
+  for (uint64_t b = 0; b <= Bm; ++b) cu[b] = (int32_t)(b * Q);
+  e = hipMemcpy(ctx->dcu, cu.data(), cu.size() * 4, hipMemcpyHostToDevice);
+  // padding positions of the feature-major V are read (with probability 0): keep them finite
+  if (e == hipSuccess) e = hipMemset(ctx->dvt, 0, d * (uint64_t)ctx->dvt_ld * 2);
+  if (e != hipSuccess) {
+    hipFree(ctx->dec_arena);
+    ctx->dec_arena = nullptr;
+    return fail_hip(ctx, "decoder work space set-up", e);
+  }
+  ctx->dw = *w;
+  ctx->has_dec = true;
+  return CFDETR_OK;
+}
+
+CFDETR_API cfdetr_status cfdetr_decode(cfdetr_ctx* ctx, const float* memory,
+                            const int32_t* cu_seqlens, int32_t B, float* queries,
+                            void* hip_stream) {
+  cfdetr_status st = check_call(ctx, B);
+  if (st != CFDETR_OK) return st;
+  if (!ctx->has_dec) return fail(ctx, CFDETR_EINVAL, "no decoder attached");
+  if (!memory || !cu_seqlens || !queries) return fail(ctx, CFDETR_EINVAL, "null pointer");
+  if (!aligned16(memory)) return fail(ctx, CFDETR_EINVAL, "memory must be 16-byte aligned");
+  return decode_impl(ctx, memory, cu_seqlens, B, queries, static_cast<hipStream_t>(hip_stream));
 }
 
 CFDETR_API cfdetr_status cfdetr_profile_begin(cfdetr_ctx* ctx) {

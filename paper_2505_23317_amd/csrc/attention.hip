@@ -89,10 +89,11 @@ __device__ __forceinline__ float exp_tile(const f32x16 (&s)[2], bf16x8 (&pf)[2][
 
 template <int DH>
 __global__ __launch_bounds__(256) void attention_bf16_kernel(
-    const bf16_t* __restrict__ qk, const bf16_t* __restrict__ vt, int vt_ld,
-    bf16_t* __restrict__ out, const int32_t* __restrict__ cu, const int32_t* __restrict__ pcu,
-    int d, const int32_t* __restrict__ items, int cap8, int32_t* __restrict__ queue_heads,
-    const int32_t* __restrict__ kv_len) {
+    const bf16_t* __restrict__ qbuf, int q_ld, const bf16_t* __restrict__ kbuf, int k_ld,
+    const bf16_t* __restrict__ vt, int vt_ld, bf16_t* __restrict__ out,
+    const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_k,
+    const int32_t* __restrict__ pcu, int d, const int32_t* __restrict__ items, int cap8,
+    int32_t* __restrict__ queue_heads, const int32_t* __restrict__ kv_len) {
   constexpr int BQ = 128;
   constexpr int KS = DH / 16;          // k-steps of Q.K^T
   constexpr int MO = DH / 32;          // 32-row blocks of O^T
@@ -112,7 +113,6 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
-  const int ld = 3 * d;
   const int home = blockIdx.x & 7;   // queue of this workgroup; w mod 8 is also its XCD
   bool first = true;
 
@@ -142,10 +142,12 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 
     const int frame = item >> 24, head = (item >> 19) & 31, qt = item & 0x7FFFF;
     const int seq0 = cu[frame], T = cu[frame + 1] - seq0;
-    // keys of the sequence that take part (all of them unless the caller padded it)
-    const int TK = kv_len ? min(kv_len[frame], T) : T;
-    const bf16_t* qbase = qk + (size_t)seq0 * ld + head * DH;
-    const bf16_t* kbase = qbase + d;
+    // the keys come from sequence `frame` of cu_k (the same sequence for self-attention),
+    // all of them unless the caller padded it
+    const int kseq0 = cu_k[frame], TKall = cu_k[frame + 1] - kseq0;
+    const int TK = kv_len ? min(kv_len[frame], TKall) : TKall;
+    const bf16_t* qbase = qbuf + (size_t)seq0 * q_ld + head * DH;
+    const bf16_t* kbase = kbuf + (size_t)kseq0 * k_ld + head * DH;
 
     // Q operands: lane = query, 8 consecutive dh per k-step.
     bf16x8 qf[KS];
@@ -153,7 +155,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
       const int q_load = min(qt * BQ + wave * 32 + l32, T - 1);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        qf[ks] = *reinterpret_cast<const bf16x8*>(qbase + (size_t)q_load * ld + ks * 16 + g * 8);
+        qf[ks] = *reinterpret_cast<const bf16x8*>(qbase + (size_t)q_load * q_ld + ks * 16 + g * 8);
     }
     // V^T: LDS row rho = dh index; 64 keys = 8 chunks of 8.
     const bf16_t* v_src[VI];
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     _Pragma("unroll") for (int j = 0; j < KI; ++j) {                                         \
       const int key = min((kv0_) + k_key[j], TK - 1);                                        \
       __builtin_amdgcn_global_load_lds(                                                      \
-          (global_void_ptr)(kbase + (size_t)key * ld + k_chunk[j] * 8),                      \
+          (global_void_ptr)(kbase + (size_t)key * k_ld + k_chunk[j] * 8),                    \
           (lds_void_ptr)(((buf_) ? sK1 : sK0) + (wave * KI + j) * 1024), 16, 0, 0);          \
     }                                                                                        \
     _Pragma("unroll") for (int j = 0; j < VI; ++j) __builtin_amdgcn_global_load_lds(         \
@@ -410,12 +412,15 @@ hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* ou
     const bf16_t* v = static_cast<const bf16_t*>(vt);
     bf16_t* o = static_cast<bf16_t*>(out);
     dim3 grid(grid_size);
+    // self-attention: queries and keys are thirds of the same rows
     if (dh == 64)
-      hipLaunchKernelGGL(attention_bf16_kernel<64>, grid, dim3(256), 0, s, in, v, vt_ld, o,
-                         cu_seqlens, pcu, d, items, cap8, queue_heads, kv_len);
+      hipLaunchKernelGGL(attention_bf16_kernel<64>, grid, dim3(256), 0, s, in, 3 * d, in + d, 3 * d,
+                         v, vt_ld, o, cu_seqlens, cu_seqlens, pcu, d, items, cap8, queue_heads,
+                         kv_len);
     else if (dh == 32)
-      hipLaunchKernelGGL(attention_bf16_kernel<32>, grid, dim3(256), 0, s, in, v, vt_ld, o,
-                         cu_seqlens, pcu, d, items, cap8, queue_heads, kv_len);
+      hipLaunchKernelGGL(attention_bf16_kernel<32>, grid, dim3(256), 0, s, in, 3 * d, in + d, 3 * d,
+                         v, vt_ld, o, cu_seqlens, cu_seqlens, pcu, d, items, cap8, queue_heads,
+                         kv_len);
     else
       return hipErrorInvalidValue;
   } else {
@@ -432,6 +437,28 @@ hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* ou
     else
       return hipErrorInvalidValue;
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_cross_attention(const void* q, const void* k, const void* vt, int vt_ld,
+                                  void* out, const int32_t* cu_q, const int32_t* cu_k,
+                                  const int32_t* pcu_k, int d, int heads, const int32_t* items,
+                                  int cap8, int32_t* queue_heads, int grid_size, hipStream_t s) {
+  if (grid_size < 8 || grid_size % 8 != 0 || grid_size > 8 * cap8) return hipErrorInvalidValue;
+  const int dh = d / heads;
+  const bf16_t* qb = static_cast<const bf16_t*>(q);
+  const bf16_t* kb = static_cast<const bf16_t*>(k);
+  const bf16_t* v = static_cast<const bf16_t*>(vt);
+  bf16_t* o = static_cast<bf16_t*>(out);
+  dim3 grid(grid_size);
+  if (dh == 64)
+    hipLaunchKernelGGL(attention_bf16_kernel<64>, grid, dim3(256), 0, s, qb, d, kb, d, v, vt_ld, o,
+                       cu_q, cu_k, pcu_k, d, items, cap8, queue_heads, nullptr);
+  else if (dh == 32)
+    hipLaunchKernelGGL(attention_bf16_kernel<32>, grid, dim3(256), 0, s, qb, d, kb, d, v, vt_ld, o,
+                       cu_q, cu_k, pcu_k, d, items, cap8, queue_heads, nullptr);
+  else
+    return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

@@ -63,14 +63,24 @@ __device__ __forceinline__ float gelu_fast(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
-template <typename TAct, bool kGelu>
+constexpr int kActNone = 0, kActGelu = 1, kActRelu = 2;
+
+template <typename TAct, int kAct>
 struct EpiAct;
 
-template <bool kGelu>
-struct EpiAct<bf16_t, kGelu> {
+// out = act((v + bias) * scale) in bf16
+template <int kAct>
+struct EpiAct<bf16_t, kAct> {
   const float* bias;
   bf16_t* out;
   int ldc;
+  float scale;
+  __device__ __forceinline__ float act(float r) const {
+    r *= scale;
+    if (kAct == kActGelu) return gelu_fast(r);
+    if (kAct == kActRelu) return fmaxf(r, 0.f);
+    return r;
+  }
   static constexpr bool kExtra = kNoExtra;
   __device__ __forceinline__ int32_t row_info(int) const { return 0; }
   __device__ __forceinline__ bool row_ok(int32_t) const { return true; }
@@ -82,13 +92,8 @@ struct EpiAct<bf16_t, kGelu> {
   }
   __device__ __forceinline__ void store4(int m, int n, const float* v, const float4& b,
                                          const float4&, int32_t) const {
-    float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
-    if (kGelu) {
-      r0 = gelu_fast(r0);
-      r1 = gelu_fast(r1);
-      r2 = gelu_fast(r2);
-      r3 = gelu_fast(r3);
-    }
+    const float r0 = act(v[0] + b.x), r1 = act(v[1] + b.y), r2 = act(v[2] + b.z),
+                r3 = act(v[3] + b.w);
     uint2 w = make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
     *reinterpret_cast<uint2*>(out + (size_t)m * ldc + n) = w;
   }
@@ -97,13 +102,8 @@ struct EpiAct<bf16_t, kGelu> {
   __device__ __forceinline__ bool staged(int) const { return true; }
   __device__ __forceinline__ void stage4(unsigned char* p, int, const float* v,
                                          const float4& b) const {
-    float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
-    if (kGelu) {
-      r0 = gelu_fast(r0);
-      r1 = gelu_fast(r1);
-      r2 = gelu_fast(r2);
-      r3 = gelu_fast(r3);
-    }
+    const float r0 = act(v[0] + b.x), r1 = act(v[1] + b.y), r2 = act(v[2] + b.z),
+                r3 = act(v[3] + b.w);
     *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
   }
   __device__ __forceinline__ void copy16(int m, int n, const uint4& d, const float4&) const {
@@ -111,8 +111,8 @@ struct EpiAct<bf16_t, kGelu> {
   }
 };
 
-template <bool kGelu>
-struct EpiAct<float, kGelu> {
+template <int kAct>
+struct EpiAct<float, kAct> {
   const float* bias;
   float* out;
   int ldc;
@@ -126,7 +126,7 @@ struct EpiAct<float, kGelu> {
   __device__ __forceinline__ void store4(int m, int n, const float* v, const float4& b,
                                          const float4&, int32_t) const {
     float4 r = make_float4(v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w);
-    if (kGelu) r = make_float4(gelu_erf(r.x), gelu_erf(r.y), gelu_erf(r.z), gelu_erf(r.w));
+    if (kAct == kActGelu) r = make_float4(gelu_erf(r.x), gelu_erf(r.y), gelu_erf(r.z), gelu_erf(r.w));
     *reinterpret_cast<float4*>(out + (size_t)m * ldc + n) = r;
   }
 };
@@ -178,8 +178,9 @@ struct EpiQkv {
   const float* bias;
   bf16_t* qk;
   int ldc;    // 3d
-  int d2;     // 2d: first v column
-  float q_scale;   // queries (columns below d2/2) leave multiplied by this
+  int d2;     // first v column (2d for q|k|v, d for k|v)
+  int q_cols; // columns below this are queries (d, or 0 when there are none)
+  float q_scale;   // queries leave multiplied by this
   bf16_t* vt;
   int vt_ld;
   const int32_t* cu;
@@ -201,7 +202,7 @@ struct EpiQkv {
                                          const float4&, int32_t pos) const {
     float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
     if (n < d2) {
-      if (2 * n < d2) {
+      if (n < q_cols) {
         r0 *= q_scale;
         r1 *= q_scale;
         r2 *= q_scale;
@@ -225,7 +226,7 @@ struct EpiQkv {
   __device__ __forceinline__ void stage4(unsigned char* p, int n, const float* v,
                                          const float4& b) const {
     float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
-    if (2 * n < d2) {
+    if (n < q_cols) {
       r0 *= q_scale;
       r1 *= q_scale;
       r2 *= q_scale;
@@ -1226,26 +1227,42 @@ hipError_t launch_gemm_qkv(const void* A, const void* W, const float* bias, int 
                            float q_scale, void* qk, void* vt, int vt_ld, const int32_t* cu_seqlens, const int32_t* pcu,
                            int B, const int32_t* m_ptr, int m_host, int m_capacity,
                            hipStream_t s) {
-  EpiQkv ep{bias, static_cast<bf16_t*>(qk), 3 * d, 2 * d, q_scale, static_cast<bf16_t*>(vt), vt_ld,
-            cu_seqlens, pcu, B};
+  EpiQkv ep{bias, static_cast<bf16_t*>(qk), 3 * d, 2 * d, d, q_scale, static_cast<bf16_t*>(vt),
+            vt_ld, cu_seqlens, pcu, B};
   hipError_t e = launch_direct(A, W, 3 * d, d, ep, m_ptr, m_host, m_capacity, s);
+  if (e != hipSuccess) return e;
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_kv(const void* A, const void* W, const float* bias, int d, void* k,
+                          void* vt, int vt_ld, const int32_t* cu_seqlens, const int32_t* pcu,
+                          int B, const int32_t* m_ptr, int m_host, int m_capacity,
+                          hipStream_t s) {
+  EpiQkv ep{bias, static_cast<bf16_t*>(k), d, d, 0, 1.0f, static_cast<bf16_t*>(vt), vt_ld,
+            cu_seqlens, pcu, B};
+  hipError_t e = launch_direct(A, W, 2 * d, d, ep, m_ptr, m_host, m_capacity, s);
   if (e != hipSuccess) return e;
   return hipGetLastError();
 }
 
 hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, int K,
                        Epilogue epi, void* out_act, float* resid, bool use_bf16,
-                       const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
+                       const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s,
+                       float scale) {
   hipError_t e = hipSuccess;
   if (use_bf16) {
     bf16_t* o = static_cast<bf16_t*>(out_act);
     switch (epi) {
       case Epilogue::kBias:
-        e = launch_direct(A, W, N, K, EpiAct<bf16_t, false>{bias, o, N}, m_ptr, m_host,
+        e = launch_direct(A, W, N, K, EpiAct<bf16_t, kActNone>{bias, o, N, scale}, m_ptr, m_host,
                           m_capacity, s);
         break;
       case Epilogue::kBiasGelu:
-        e = launch_direct(A, W, N, K, EpiAct<bf16_t, true>{bias, o, N}, m_ptr, m_host,
+        e = launch_direct(A, W, N, K, EpiAct<bf16_t, kActGelu>{bias, o, N, scale}, m_ptr, m_host,
+                          m_capacity, s);
+        break;
+      case Epilogue::kBiasRelu:
+        e = launch_direct(A, W, N, K, EpiAct<bf16_t, kActRelu>{bias, o, N, scale}, m_ptr, m_host,
                           m_capacity, s);
         break;
       case Epilogue::kBiasResidual:
@@ -1257,13 +1274,15 @@ hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, i
     float* o = static_cast<float*>(out_act);
     switch (epi) {
       case Epilogue::kBias:
-        e = launch_f32(al, W, N, K, EpiAct<float, false>{bias, o, N}, m_ptr, m_host, m_capacity,
+        e = launch_f32(al, W, N, K, EpiAct<float, kActNone>{bias, o, N}, m_ptr, m_host, m_capacity,
                        nullptr, s);
         break;
       case Epilogue::kBiasGelu:
-        e = launch_f32(al, W, N, K, EpiAct<float, true>{bias, o, N}, m_ptr, m_host, m_capacity,
+        e = launch_f32(al, W, N, K, EpiAct<float, kActGelu>{bias, o, N}, m_ptr, m_host, m_capacity,
                        nullptr, s);
         break;
+      case Epilogue::kBiasRelu:
+        return hipErrorInvalidValue;   // only the bf16 path has it
       case Epilogue::kBiasResidual:
         e = launch_f32(al, W, N, K, EpiResidual{bias, resid, N}, m_ptr, m_host, m_capacity, nullptr,
                        s);

@@ -49,10 +49,15 @@ hipError_t launch_pad_tokens(const int32_t* tok_desc, const int32_t* cu_seqlens,
 // Also sets queue_heads[0..n_heads_q), the fetch counters of the attention launches
 // that follow (eight per launch), to queue_start = (attention grid) / 8: the entries
 // before that are handed out by workgroup index.
+// max_total > 0 checks offsets that a caller wrote: a length below 1, or a total above
+// max_total, cuts the lengths to what fits and sets *err_flag.  gate (may be null): if
+// *gate is not 0 the work list comes out empty, so that the attention launches that
+// follow do nothing after an earlier kernel has raised the error flag.
 hipError_t launch_plan(const int32_t* cu_seqlens, int B, int n_prefix, int prefix_len,
                        int block_q, int heads, int32_t* items, int cap8, int32_t* cu_all,
                        int32_t* m_all, int32_t* pcu, int32_t* queue_heads, int n_heads_q,
-                       int queue_start, hipStream_t s);
+                       int queue_start, hipStream_t s, int max_total = 0,
+                       int32_t* err_flag = nullptr, const int32_t* gate = nullptr);
 
 // ---- row-wise kernels (rowwise.hip) ----------------------------------------
 // Position tables of one level: pe_row [rows, d/2], pe_col [cols, d/2] (fp32).
@@ -65,6 +70,17 @@ hipError_t launch_layernorm(const float* x, const float* g, const float* b, void
                             bool out_is_bf16, int d, float eps, const int32_t* m_ptr,
                             int m_host, int m_capacity, int split_row, void* out2,
                             hipStream_t s);
+// out (bf16 bit patterns) = in (fp32) for the first M * d elements, M = *m_ptr.
+hipError_t launch_cast_bf16(const float* in, void* out, int d, const int32_t* m_ptr,
+                            int m_capacity, hipStream_t s);
+// dst[f*rows .. (f+1)*rows) = src[0 .. rows) for f < copies (rows of d floats).
+hipError_t launch_broadcast_rows(const float* src, float* dst, int rows, int d, int copies,
+                                 hipStream_t s);
+// Heads of the decoder: out[m] = (sigmoid(hb[m] . w_box[0..3] + b_box), sigmoid(z[m] . w_cls
+// + b_cls)) for m < M; z and hb [M, d] and the weight rows in bf16, out [M, 5] fp32.
+hipError_t launch_decoder_heads(const void* z, const void* hb, const void* w_cls,
+                                const float* b_cls, const void* w_box, const float* b_box, int d,
+                                int M, float* out, hipStream_t s);
 // x[t] = x0[frame(t)*n0 + row*cols0 + col] for every level-0 token t < cu[B].
 hipError_t launch_gather_coarse(const int32_t* tok_desc, const int32_t* cu_seqlens, int B,
                                 const float* x0, int n0, int cols0, int d, float* x,
@@ -91,14 +107,24 @@ hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, in
                         bool use_bf16, const int32_t* m_ptr, int m_host, int m_capacity,
                         hipStream_t s);
 
-enum class Epilogue { kBias, kBiasGelu, kBiasResidual };
-// C = A[M,K] . W[N,K]^T + bias, then per `epi`:
+enum class Epilogue { kBias, kBiasGelu, kBiasRelu, kBiasResidual };
+// C = (A[M,K] . W[N,K]^T + bias) * scale (scale: bf16 path only), then per `epi`:
 //   kBias         -> out_act (activation dtype)
 //   kBiasGelu     -> GELU, out_act
-//   kBiasResidual -> resid[M,N] (fp32) += result, in place
+//   kBiasRelu     -> max(., 0), out_act (bf16 path only)
+//   kBiasResidual -> resid[M,N] (fp32) += result, in place (no scale)
 hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, int K,
                        Epilogue epi, void* out_act, float* resid, bool use_bf16,
-                       const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s);
+                       const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s,
+                       float scale = 1.0f);
+
+// bf16 key/value projection of the decoder's cross-attention: W [2d, d] stacks the key and
+// value rows; keys go token-major to k [M, d], values feature-major to vt like
+// launch_gemm_qkv.
+hipError_t launch_gemm_kv(const void* A, const void* W, const float* bias, int d, void* k,
+                          void* vt, int vt_ld, const int32_t* cu_seqlens, const int32_t* pcu,
+                          int B, const int32_t* m_ptr, int m_host, int m_capacity,
+                          hipStream_t s);
 
 // Residual contraction followed by LayerNorm of the updated rows, in one kernel (bf16
 // operands): resid[M,d] += A[M,K] . W[d,K]^T + bias, then
@@ -137,6 +163,15 @@ hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* ou
                             const int32_t* cu_seqlens, const int32_t* pcu, int d, int heads,
                             const int32_t* items, int cap8, int32_t* queue_heads, int grid_size,
                             int block_q, bool use_bf16, const int32_t* kv_len, hipStream_t s);
+// bf16 attention of query rows over the keys and values of another set of rows (the
+// decoder's cross-attention): q [Mq, d] and k [Mk, d] (head h at columns h*dh, q
+// pre-multiplied by attention_q_scale), v feature-major in vt at the padded offsets pcu_k
+// of the key sequences; sequence i of cu_q attends to sequence i of cu_k.  Work items and
+// counters as for launch_attention, planned over the query sequences.
+hipError_t launch_cross_attention(const void* q, const void* k, const void* vt, int vt_ld,
+                                  void* out, const int32_t* cu_q, const int32_t* cu_k,
+                                  const int32_t* pcu_k, int d, int heads, const int32_t* items,
+                                  int cap8, int32_t* queue_heads, int grid_size, hipStream_t s);
 // Grid of launch_attention on the current device: a multiple of 8, at most 8*cap8;
 // 0 if the device cannot be queried.
 int attention_grid(int d_head, bool use_bf16, int cap8);

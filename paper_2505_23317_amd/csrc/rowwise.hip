@@ -92,7 +92,76 @@ __global__ __launch_bounds__(256) void gather_coarse_kernel(
     *reinterpret_cast<float4*>(dst + e) = *reinterpret_cast<const float4*>(src + e);
 }
 
+__global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict__ in,
+                                                        bf16_t* __restrict__ out, int d,
+                                                        const int32_t* __restrict__ m_ptr) {
+  const size_t n = (size_t)(*m_ptr) * d;
+  const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+  if (i >= n) return;   // d is a multiple of 64, so n is a multiple of 8
+  const float4 a = *reinterpret_cast<const float4*>(in + i);
+  const float4 b = *reinterpret_cast<const float4*>(in + i + 4);
+  *reinterpret_cast<uint4*>(out + i) = make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w),
+                                                  pack_bf16x2(b.x, b.y), pack_bf16x2(b.z, b.w));
+}
+
+__global__ __launch_bounds__(256) void broadcast_rows_kernel(const float* __restrict__ src,
+                                                             float* __restrict__ dst, int n4) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n4)
+    reinterpret_cast<float4*>(dst)[(size_t)blockIdx.y * n4 + i] =
+        reinterpret_cast<const float4*>(src)[i];
+}
+
+// One wavefront per query row: five dot products of length d, then the logistic function.
+__global__ __launch_bounds__(256) void decoder_heads_kernel(
+    const bf16_t* __restrict__ z, const bf16_t* __restrict__ hb, const bf16_t* __restrict__ w_cls,
+    const float* __restrict__ b_cls, const bf16_t* __restrict__ w_box,
+    const float* __restrict__ b_box, int d, int M, float* __restrict__ out) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  const int lane = threadIdx.x & 63;
+  float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int e = lane; e < d; e += 64) {
+    const float hv = bf16_to_f32(hb[(size_t)row * d + e]);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = fmaf(hv, bf16_to_f32(w_box[(size_t)c * d + e]), acc[c]);
+    acc[4] = fmaf(bf16_to_f32(z[(size_t)row * d + e]), bf16_to_f32(w_cls[e]), acc[4]);
+  }
+#pragma unroll
+  for (int c = 0; c < 5; ++c) acc[c] = wave_sum(acc[c]);
+  if (lane < 5) {
+    const float u = acc[lane] + (lane < 4 ? b_box[lane] : b_cls[0]);
+    out[(size_t)row * 5 + lane] = 1.0f / (1.0f + __expf(-u));
+  }
+}
+
 }  // namespace
+
+hipError_t launch_cast_bf16(const float* in, void* out, int d, const int32_t* m_ptr,
+                            int m_capacity, hipStream_t s) {
+  const size_t n8 = ((size_t)m_capacity * d + 7) / 8;
+  hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, in,
+                     static_cast<bf16_t*>(out), d, m_ptr);
+  return hipGetLastError();
+}
+
+hipError_t launch_broadcast_rows(const float* src, float* dst, int rows, int d, int copies,
+                                 hipStream_t s) {
+  const int n4 = rows * d / 4;
+  hipLaunchKernelGGL(broadcast_rows_kernel, dim3((n4 + 255) / 256, copies), dim3(256), 0, s, src,
+                     dst, n4);
+  return hipGetLastError();
+}
+
+hipError_t launch_decoder_heads(const void* z, const void* hb, const void* w_cls,
+                                const float* b_cls, const void* w_box, const float* b_box, int d,
+                                int M, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(decoder_heads_kernel, dim3((M + 3) / 4), dim3(256), 0, s,
+                     static_cast<const bf16_t*>(z), static_cast<const bf16_t*>(hb),
+                     static_cast<const bf16_t*>(w_cls), b_cls, static_cast<const bf16_t*>(w_box),
+                     b_box, d, M, out);
+  return hipGetLastError();
+}
 
 hipError_t launch_pe_tables(int patch, int rows, int cols, int img_h, int img_w, int d,
                             float* pe_row, float* pe_col, hipStream_t s) {

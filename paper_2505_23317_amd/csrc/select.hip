@@ -185,7 +185,9 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
                                                    int32_t* __restrict__ m_all,
                                                    int32_t* __restrict__ pcu,
                                                    int32_t* __restrict__ queue_heads,
-                                                   int n_heads_q, int queue_start) {
+                                                   int n_heads_q, int queue_start, int max_total,
+                                                   int32_t* __restrict__ err_flag,
+                                                   const int32_t* __restrict__ gate) {
   __shared__ int s_len[2 * kMaxBatch];
   __shared__ int s_order[2 * kMaxBatch];
   __shared__ int s_gstart[2 * kMaxBatch * kMaxHeads];
@@ -195,6 +197,26 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
   for (int i = tid; i < n_heads_q; i += blockDim.x) queue_heads[i] = queue_start;
   if (tid < nseq) s_len[tid] = tid < n_prefix ? prefix_len : cu[tid - n_prefix + 1] - cu[tid - n_prefix];
   __syncthreads();
+  if (max_total > 0) {
+    // offsets a caller wrote: every length must be at least 1 and the total must fit;
+    // otherwise the lengths are cut to what fits and the error flag is raised
+    if (tid == 0) {
+      int pos = 0;
+      bool bad = false;
+      for (int i = 0; i < nseq; ++i) {
+        int len = s_len[i];
+        if (len < 1 || len > max_total - pos) {
+          bad = true;
+          len = max(0, min(len, max_total - pos));
+          s_len[i] = len;
+        }
+        pos += len;
+      }
+      if (bad) *err_flag = 1;
+    }
+    __syncthreads();
+  }
+  const bool gated = gate != nullptr && *gate != 0;   // an earlier kernel found an error
   if (tid < nseq) {
     const int len = s_len[tid];
     int rank = 0;
@@ -212,7 +234,7 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
       s_gstart[G] = pos;
       pos += (s_len[s_order[G / heads]] + block_q - 1) / block_q;
     }
-    s_count[tid] = min(pos, cap8);
+    s_count[tid] = gated ? 0 : min(pos, cap8);
   }
   if (tid == 8) {
     int pos = 0, ppos = 0;
@@ -286,9 +308,11 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
 hipError_t launch_plan(const int32_t* cu_seqlens, int B, int n_prefix, int prefix_len,
                        int block_q, int heads, int32_t* items, int cap8, int32_t* cu_all,
                        int32_t* m_all, int32_t* pcu, int32_t* queue_heads, int n_heads_q,
-                       int queue_start, hipStream_t s) {
+                       int queue_start, hipStream_t s, int max_total, int32_t* err_flag,
+                       const int32_t* gate) {
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, cu_seqlens, B, n_prefix, prefix_len,
-                     block_q, heads, items, cap8, cu_all, m_all, pcu, queue_heads, n_heads_q, queue_start);
+                     block_q, heads, items, cap8, cu_all, m_all, pcu, queue_heads, n_heads_q,
+                     queue_start, max_total, err_flag, gate);
   return hipGetLastError();
 }
 

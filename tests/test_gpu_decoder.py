@@ -1,0 +1,278 @@
+"""GPU parity of the decoder (object queries over the encoded tokens, confidence and box
+heads; the DETR pipeline of Sec. II-A as this library reads it) against the CPU oracle.
+
+The outputs are logistic values in (0, 1), so max|gpu - ref| / max|ref| is an absolute
+error on that scale; the bar is the one of the bf16 encoder path, 2e-2.  Every case also
+shows, with the oracle alone, that a wrong operand in cross-attention (the tokens of
+another frame) or in self-attention (no mixing between queries) would move the result by
+more than that bar, so the comparison has the power to see such a mistake."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import cfdetr_oracle as O
+from paper_2505_23317_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def K():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2505_23317_amd import cfdetr
+    cfdetr.load_library()
+    return cfdetr
+
+
+def model(d, heads, ffn, B, H=256, W=256):
+    """An encoder shape that only fixes widths and capacity: 64 coarse cells a frame."""
+    return synth.Config(f"dec_d{d}h{heads}", B, H, W, (32, 16), d, heads, 1, ffn, "bf16",
+                        box_rule="poisson", box_lambda=2.0, side_lo=8, side_hi=40)
+
+
+def decoder_weights(cfg, seed, Q, layers):
+    """make_decoder_weights rescaled so that every width gives logits of a few units:
+    wider attention matrices (std 0.96 / sqrt(d): which tokens a query reads matters) and
+    narrower output heads (outputs spread over (0, 1) instead of saturated ones)."""
+    dw = synth.make_decoder_weights(cfg, seed, n_queries=Q, layers=layers)
+    rng = np.random.default_rng(4242 + seed)
+    for k in ("w_qkv", "w_o", "w_q", "w_kv", "w_o2"):
+        dw[k] = synth.bf16_round(rng.normal(0.0, 0.96 / np.sqrt(cfg.d), dw[k].shape).astype(np.float32))
+    for k in ("w_cls", "w_box3"):
+        dw[k] = synth.bf16_round((dw[k] * (4.0 / np.sqrt(cfg.d))).astype(np.float32))
+    for k in ("w_box1", "w_box2"):
+        dw[k] = synth.bf16_round((dw[k] * np.sqrt(256.0 / cfg.d)).astype(np.float32))
+    return dw
+
+
+def memory_of(lengths, d, seed):
+    """Encoder-like rows (unit variance, as after the final LayerNorm)."""
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    rng = np.random.default_rng(555 + seed)
+    return rng.normal(0.0, 1.0, (int(cu[-1]), d)).astype(np.float32), cu
+
+
+def gpu_decode(K, enc, mem, cu, Q):
+    import torch
+    B = len(cu) - 1
+    dmem = torch.from_numpy(mem).cuda()
+    dcu = torch.from_numpy(cu).cuda()
+    out = torch.full((B, Q, 5), -3.0, dtype=torch.float32, device="cuda")
+    enc.decode(dmem, dcu, B, out)
+    enc.sync_status()
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+CASES = {
+    # name: (d, heads, ffn, Q, layers, memory lengths)
+    "heads_of_32_ragged": (256, 8, 1024, 100, 2, [300, 77, 513]),
+    "heads_of_64": (256, 4, 512, 128, 1, [64, 129, 1, 200]),
+    "one_query_one_token": (128, 4, 256, 1, 2, [1, 5]),
+    "most_queries": (128, 2, 256, 1024, 1, [190, 64]),
+    "wide_model": (768, 12, 3072, 300, 1, [256, 131]),
+}
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_decoder_matches_the_oracle(K, name):
+    d, heads, ffn, Q, layers, lengths = CASES[name]
+    B = len(lengths)
+    cfg = model(d, heads, ffn, B)
+    _say(f"[case] decoder {name}: d={d} heads={heads} Q={Q} layers={layers} tokens={lengths}")
+    dw = decoder_weights(cfg, 3, Q, layers)
+    mem, cu = memory_of(lengths, d, seed=len(name))
+    ref = O.decode(mem, cu, dw, heads)
+    assert ref.shape == (B, Q, 5) and ref.min() >= 0.0 and ref.max() <= 1.0
+    assert ref.std() > 0.1                                     # not saturated, not constant
+
+    # what a mistake would cost, shown on the oracle alone
+    if B > 1 and min(lengths) > 1:
+        rolled = np.concatenate([mem[cu[1]:], mem[:cu[1]]])
+        cu_rolled = np.concatenate([[0], np.cumsum(lengths[1:] + lengths[:1])]).astype(np.int32)
+        wrong = O.decode(rolled, cu_rolled, dw, heads)         # frame i reads the tokens of frame i+1
+        assert np.abs(wrong - ref).max() > 2 * TOL
+    if Q > 1:
+        solo = {k: (v[:1] if k == "query_embed" else v) for k, v in dw.items()}
+        alone = O.decode(mem, cu, solo, heads)                 # query 0 without the others
+        assert np.abs(alone[:, 0] - ref[:, 0]).max() > TOL
+
+    enc = K.Encoder(cfg, synth.make_weights(cfg, 1), max_tokens_total=max(sum(lengths), B * 64))
+    enc.attach_decoder(dw)
+    got = gpu_decode(K, enc, mem, cu, Q)
+    err = float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
+    _say(f"[parity] decoder {name}: err {err:.2e} (bar {TOL:.0e})")
+    assert np.isfinite(got).all()
+    assert err <= TOL, (name, err)
+    # a second call with fewer frames and other lengths reuses the work space
+    if B > 1:
+        sub = lengths[:-1][::-1]
+        mem2, cu2 = memory_of(sub, d, seed=99)
+        ref2 = O.decode(mem2, cu2, dw, heads)
+        got2 = gpu_decode(K, enc, mem2, cu2, Q)
+        err2 = float(np.abs(got2.astype(np.float64) - ref2).max() / np.abs(ref2).max())
+        _say(f"[parity] decoder {name} second call: err {err2:.2e}")
+        assert err2 <= TOL, (name, err2)
+    enc.close()
+
+
+def test_frames_do_not_interact_and_the_batch_does_not_change_a_frame(K):
+    d, heads, ffn, Q = 256, 8, 1024, 100
+    lengths = [300, 77, 513]
+    cfg = model(d, heads, ffn, 3)
+    dw = decoder_weights(cfg, 5, Q, 2)
+    mem, cu = memory_of(lengths, d, seed=7)
+    enc = K.Encoder(cfg, synth.make_weights(cfg, 1), max_tokens_total=sum(lengths))
+    enc.attach_decoder(dw)
+    whole = gpu_decode(K, enc, mem, cu, Q)
+    for f in range(3):
+        one = gpu_decode(K, enc, mem[cu[f]:cu[f + 1]].copy(),
+                         np.array([0, lengths[f]], np.int32), Q)
+        np.testing.assert_array_equal(one[0], whole[f])        # bit for bit
+    enc.close()
+
+
+def test_coarse_stage_in_a_closed_loop(K):
+    """Images -> coarse encode -> decode -> region proposal -> selection -> fine encode, all
+    on the device, against the same chain of the oracle.  The queries are compared to the
+    bar; the regions are compared through what the bar leaves decided: a query whose
+    oracle confidence is clear of both thresholds must be classified as the oracle does."""
+    import torch
+    cfg = synth.replace(synth.config(3), B=2, layers=2)
+    Q, tau_hi, tau_lo = 100, float(np.float32(0.8)), float(np.float32(0.05))
+    wl = synth.make_workload(cfg, seed=31)
+    dw = decoder_weights(cfg, 8, Q, 2)
+    _say("[case] closed loop: oracle chain")
+    _, yc = O.coarse_encode(wl["images"], cfg.patch, wl["weights"], cfg.heads)
+    n0 = cfg.n_cells(0)
+    cu0 = (np.arange(cfg.B + 1) * n0).astype(np.int32)
+    ref_q = O.decode(yc, cu0, dw, cfg.heads)
+    rb, rt, ro, rh, rm = O.propose_rois(ref_q.astype(np.float32), cfg.H, cfg.W, tau_hi, tau_lo, 1)
+
+    _say("[case] closed loop: device chain")
+    enc = K.Encoder(cfg, wl["weights"])
+    enc.attach_decoder(dw)
+    img = enc.upload_images(wl["images"])
+    out = enc.alloc_outputs(cfg.B)
+    enc.coarse_encode(img, cfg.B, out["x0_cache"], out["y_coarse"])
+    dq = torch.empty((cfg.B, Q, 5), dtype=torch.float32, device="cuda")
+    enc.decode(out["y_coarse"], torch.from_numpy(cu0).cuda(), cfg.B, dq)
+    boxes = torch.zeros((cfg.B * Q, 4), dtype=torch.int32, device="cuda")
+    tier = torch.zeros(cfg.B * Q, dtype=torch.uint8, device="cuda")
+    offs = torch.zeros(cfg.B + 1, dtype=torch.int32, device="cuda")
+    hard = torch.zeros(cfg.B, dtype=torch.int32, device="cuda")
+    mean = torch.zeros(cfg.B, dtype=torch.float32, device="cuda")
+    enc.propose_rois(dq, K.CfdetrRoiParams(tau_hi, tau_lo, 1.0, 0.0, 1), boxes, tier, offs, hard, mean)
+    enc.select_fine(boxes, tier, offs, cfg.B, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
+    enc.fine_encode(img, cfg.B, out["tok_desc"], out["cu_seqlens"], out["x0_cache"], out["y_mixed"])
+    enc.sync_status()
+    torch.cuda.synchronize()
+
+    got_q = dq.cpu().numpy()
+    err = float(np.abs(got_q.astype(np.float64) - ref_q).max() / np.abs(ref_q).max())
+    _say(f"[parity] closed loop queries: err {err:.2e} (bar {TOL:.0e})")
+    assert err <= TOL
+    got_offs = offs.cpu().numpy()
+    conf = ref_q[:, :, 4]
+    clear = (np.abs(conf - tau_hi) > TOL) & (np.abs(conf - tau_lo) > TOL)
+    for f in range(cfg.B):
+        n_ref = int(ro[f + 1] - ro[f])
+        n_unclear = int((~clear[f]).sum())
+        n_got = int(got_offs[f + 1] - got_offs[f])
+        if abs(rm[f] - tau_lo) > TOL:
+            assert int(hard.cpu().numpy()[f]) == int(rh[f])
+        if rh[f]:
+            assert abs(n_got - n_ref) <= n_unclear, (f, n_got, n_ref, n_unclear)
+        if n_unclear == 0 and rh[f]:
+            # same queries propose: the boxes differ by the query error in pixels at most
+            gb = boxes.cpu().numpy()[got_offs[f]:got_offs[f + 1]]
+            assert np.abs(gb - rb[ro[f]:ro[f + 1]]).max() <= TOL * max(cfg.H, cfg.W) + 1
+    assert abs(float(mean.cpu().numpy()[0]) - rm[0]) <= TOL
+    cu = out["cu_seqlens"].cpu().numpy()
+    T = int(cu[-1])
+    assert (np.diff(cu) >= n0).all() and T <= enc.max_tokens
+    assert np.isfinite(out["y_mixed"].cpu().numpy()[:T]).all()
+    _say(f"[loop] regions {got_offs.tolist()} (oracle {ro.tolist()}) tokens {np.diff(cu).tolist()}")
+    enc.close()
+
+
+def test_decoder_leaves_the_encoder_as_it_was(K):
+    import torch
+    cfg = synth.replace(synth.config(3), B=3, layers=2)
+    wl = synth.make_workload(cfg, seed=12)
+    enc = K.Encoder(cfg, wl["weights"])
+    enc.attach_decoder(decoder_weights(cfg, 2, 77, 1))
+    img = enc.upload_images(wl["images"])
+    b, t, o = enc.upload_boxes(wl["boxes"], wl["tier"], wl["box_offsets"])
+    first = enc.alloc_outputs(cfg.B)
+    enc.multilevel_batch(img, cfg.B, b, t, o, first)
+    dq = torch.empty((cfg.B, 77, 5), dtype=torch.float32, device="cuda")
+    enc.decode(first["y_mixed"], first["cu_seqlens"], cfg.B, dq)
+    again = enc.alloc_outputs(cfg.B)
+    enc.multilevel_batch(img, cfg.B, b, t, o, again)
+    enc.sync_status()
+    torch.cuda.synchronize()
+    assert torch.isfinite(dq).all()
+    for k in ("y_coarse", "y_mixed", "tok_desc", "cu_seqlens"):
+        assert torch.equal(first[k], again[k]), k
+    enc.close()
+
+
+def test_decoder_argument_and_sequence_errors(K):
+    import torch
+    cfg = model(128, 4, 256, 2)
+    w = synth.make_weights(cfg, 1)
+    dw = decoder_weights(cfg, 1, 16, 1)
+    mem = torch.zeros((128, 128), dtype=torch.float32, device="cuda")
+    out = torch.zeros((2, 16, 5), dtype=torch.float32, device="cuda")
+    cu = torch.tensor([0, 64, 128], dtype=torch.int32, device="cuda")
+
+    enc = K.Encoder(cfg, w, max_tokens_total=128)   # capacity: the 128 rows of `mem`
+    with pytest.raises(K.CfdetrError) as e:       # no decoder yet
+        enc.decode(mem, cu, 2, out)
+    assert e.value.status == K.CFDETR_EINVAL
+    enc.attach_decoder(dw)
+    with pytest.raises(K.CfdetrError) as e:       # only one decoder per context
+        enc.attach_decoder(dw)
+    assert e.value.status == K.CFDETR_EINVAL
+    with pytest.raises(K.CfdetrError) as e:
+        enc.decode(mem, cu, 3, out)               # more frames than max_batch
+    assert e.value.status == K.CFDETR_ECAPACITY
+    with pytest.raises(K.CfdetrError) as e:
+        K.cfdetr_decode(enc.ctx, None, cu.data_ptr(), 2, out.data_ptr(), 0)
+    assert e.value.status == K.CFDETR_EINVAL
+    enc.decode(mem, cu, 2, out)
+    enc.sync_status()
+    # offsets the device check refuses: a frame without tokens, a total beyond the capacity
+    for bad in ([0, 0, 128], [0, 64, 4096], [0, 100, 90]):
+        enc.decode(mem, torch.tensor(bad, dtype=torch.int32, device="cuda"), 2, out)
+        with pytest.raises(K.CfdetrError) as e:
+            enc.sync_status()
+        assert e.value.status == K.CFDETR_ECAPACITY, bad
+    enc.decode(mem, cu, 2, out)                   # and the context still works
+    enc.sync_status()
+    enc.close()
+
+    fp32 = K.Encoder(cfg, w, act_dtype="fp32")
+    with pytest.raises(K.CfdetrError) as e:
+        fp32.attach_decoder(dw)
+    assert e.value.status == K.CFDETR_ESHAPE
+    fp32.close()
+
+    bad_w = dict(dw)
+    bad_w["query_embed"] = np.zeros((2000, 128), np.float32)     # more than 1024 queries
+    enc = K.Encoder(cfg, w)
+    with pytest.raises(K.CfdetrError) as e:
+        enc.attach_decoder(bad_w)
+    assert e.value.status == K.CFDETR_ESHAPE
+    enc.close()
