@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -55,6 +56,8 @@ struct cfdetr_ctx {
   int32_t* kv_len = nullptr;
   int block_q = 0;
   int32_t* err_flag = nullptr;
+  void* tail_packed = nullptr;   // w_o, w_ff1, w_ff2 of every layer in the fused kernel's order
+  uint64_t tail_packed_layer = 0;   // bytes per layer; 0: the shape has no fused kernel
 
   // decoder (cfdetr_decoder_attach): its own allocation
   bool has_dec = false;
@@ -218,6 +221,7 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
   // Where a workgroup can own whole rows, the residual contractions also apply the
   // LayerNorm that follows them, and only the very first one is a launch of its own.
   const bool fused_ln = gemm_residual_ln_supported(d, bf);
+  const bool fused_tail = fused_ln && ctx->tail_packed_layer != 0 && !getenv("CFDETR_DEV_SPLIT_FFN");
   for (int l = 0; l < c.n_layers; ++l) {
     const char* wqkv = static_cast<const char*>(w.w_qkv) + (size_t)l * 3 * d * d * es;
     const char* wo = static_cast<const char*>(w.w_o) + (size_t)l * d * d * es;
@@ -241,6 +245,22 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
               launch_attention(ctx->qkv, ctx->vt, ctx->vt_ld, ctx->o, cu_all, ctx->pcu, d,
                                c.n_heads, ctx->items, ctx->cap8, ctx->queue_heads + 8 * l,
                                ctx->attn_grid, ctx->block_q, bf, kv_len, s));
+    if (fused_tail) {
+      // out-projection, LayerNorm, feed-forward block and the LayerNorm after it (the next
+      // layer's first one, or the final one) in one kernel
+      const float* g = last ? w.lnf_g : w.ln1_g + (size_t)(l + 1) * d;
+      const float* b = last ? w.lnf_b : w.ln1_b + (size_t)(l + 1) * d;
+      CF_LAUNCH(CFDETR_K_FF2,
+                launch_layer_tail(ctx->o,
+                                  static_cast<const char*>(ctx->tail_packed) +
+                                      (size_t)l * ctx->tail_packed_layer,
+                                  w.b_o + (size_t)l * d, w.ln2_g + (size_t)l * d,
+                                  w.ln2_b + (size_t)l * d, w.b_ff1 + (size_t)l * F,
+                                  w.b_ff2 + (size_t)l * d, d, F, ctx->x, g, b, eps,
+                                  last ? (void*)y0 : ctx->a, !last, last ? split_row : 0,
+                                  last ? (void*)y1 : nullptr, m_ptr, 0, m_cap, s));
+      continue;
+    }
     if (fused_ln) {
       CF_LAUNCH(CFDETR_K_OUT,
                 launch_gemm_residual_ln(ctx->o, wo, w.b_o + (size_t)l * d, d, d, ctx->x,
@@ -532,6 +552,9 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   const uint64_t o_nroi = cv.take((uint64_t)kMaxBatch * 4);
   const uint64_t o_tpad = cv.take((uint64_t)cfg->max_tokens_total * 4);
   const uint64_t o_cupad = cv.take((uint64_t)(kMaxBatch + 1) * 4), o_kvlen = cv.take((uint64_t)kMaxBatch * 4);
+  if (layer_tail_supported((int)d, (int)F, c->bf16))
+    c->tail_packed_layer = layer_tail_packed_bytes((int)d, (int)F);
+  const uint64_t o_pack = cv.take(c->tail_packed_layer * cfg->n_layers);
   c->arena_bytes = cv.off;
   e = hipMalloc(&c->arena, c->arena_bytes);
   if (e != hipSuccess) {
@@ -565,6 +588,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->tok_pad = reinterpret_cast<int32_t*>(base + o_tpad);
   c->cu_pad = reinterpret_cast<int32_t*>(base + o_cupad);
   c->kv_len = reinterpret_cast<int32_t*>(base + o_kvlen);
+  c->tail_packed = base + o_pack;
 
   // static tables: coarse grid descriptors, zeroed counters, position tables
   std::vector<int32_t> desc(Bm * c->n0), cu(Bm + 1);
@@ -584,6 +608,14 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   for (int l = 0; l < cfg->n_levels && e == hipSuccess; ++l)
     e = launch_pe_tables(p.patch[l], p.rows[l], p.cols[l], p.img_h, p.img_w, (int)d, c->pe_row[l],
                          c->pe_col[l], nullptr);
+  // the weights after attention in the order the fused kernel streams them
+  for (int l = 0; l < cfg->n_layers && e == hipSuccess && c->tail_packed_layer; ++l)
+    e = launch_layer_tail_pack(static_cast<const char*>(w->w_o) + (size_t)l * d * d * 2,
+                               static_cast<const char*>(w->w_ff1) + (size_t)l * F * d * 2,
+                               static_cast<const char*>(w->w_ff2) + (size_t)l * d * F * 2, (int)d,
+                               (int)F,
+                               static_cast<char*>(c->tail_packed) + (size_t)l * c->tail_packed_layer,
+                               nullptr);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     hipFree(c->arena);

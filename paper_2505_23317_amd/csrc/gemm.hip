@@ -300,6 +300,17 @@ __device__ __forceinline__ void dma16_untracked(const void* gptr, const unsigned
                : "memory");   // M0 is reserved: the compiler keeps nothing in it
 }
 
+// The same with the address split into a wave-uniform base (kept in scalar registers,
+// so that advancing it costs no vector instruction) and a 32-bit per-lane byte offset;
+// lds_addr is the wave-uniform LDS byte address.
+__device__ __forceinline__ void dma16_untracked_s(const void* sbase, uint32_t voff,
+                                                  uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(sbase)
+               : "memory");
+}
+
 // Where the rows of the A operand come from.  row(r, M, ok) is the address of element 0
 // of row r (rows that are not to be computed get ok = false and any valid address);
 // col(k) is the offset of element k, for k a multiple of 8 (8 consecutive elements are
@@ -787,6 +798,322 @@ __global__ __launch_bounds__(256) void gemm_bf16_rowln_kernel(
     }
 }
 
+// Phase time stamps of layer_tail_kernel for a development harness that defines these
+// macros before including this file; compiled out otherwise.
+#ifndef CFDETR_TL
+#define CFDETR_TL(i)
+#define CFDETR_TLX(i)
+#endif
+
+// The weights of the second half of a layer (attention output projection, then the
+// feed-forward block) in the order and layout layer_tail_kernel reads them: 1 KB blocks,
+// each the 64 x 16 bytes that one MFMA of one wavefront takes as its weight operand,
+// lane by lane.  Block ((2 c + part) * 8 + w) * 8 + ks.  c = 0 is the output projection
+// (32x32x16 operand: lane (l32, g) holds Wo[32 w + l32][16 (8 part + ks) + 8 g ..]);
+// c >= 1 is chunk c - 1 of 128 hidden units: part 0 = W1 rows (16x16x32 operand: lane
+// (l16, kg) holds W1[128 (c-1) + 16 w + l16][32 ks + 8 kg ..]), part 1 = W2 columns
+// (32x32x16 operand: lane (l32, g) holds W2[32 w + l32][128 (c-1) + 16 ks + 8 g ..]).
+// One thread per 16 bytes.
+__global__ __launch_bounds__(256) void layer_tail_pack_kernel(const bf16_t* __restrict__ Wo,
+                                                              const bf16_t* __restrict__ W1,
+                                                              const bf16_t* __restrict__ W2,
+                                                              int F, bf16_t* __restrict__ out) {
+  constexpr int D = 256, FC = 128;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;   // 16-byte unit of the output
+  if (i >= (D * D + F * D * 2) / 8) return;
+  const int lane = i & 63, ks = (i >> 6) & 7, w = (i >> 9) & 7, part = (i >> 12) & 1, c = i >> 13;
+  const bf16_t* src;
+  if (c == 0)
+    src = Wo + (size_t)(w * 32 + (lane & 31)) * D + (part * 8 + ks) * 16 + (lane >> 5) * 8;
+  else if (part == 0)
+    src = W1 + (size_t)((c - 1) * FC + w * 16 + (lane & 15)) * D + ks * 32 + (lane >> 4) * 8;
+  else
+    src = W2 + (size_t)(w * 32 + (lane & 31)) * F + (c - 1) * FC + ks * 16 + (lane >> 5) * 8;
+  reinterpret_cast<uint4*>(out)[i] = *reinterpret_cast<const uint4*>(src);
+}
+
+// Sum over each group of 8 consecutive lanes, delivered to all 8.
+__device__ __forceinline__ float row8_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));
+  return v;
+}
+
+// Shared by the two row updates of layer_tail_kernel.  The 32 x 32 accumulator of a
+// wavefront (lane (l32, g), register r = row l32, column 8 (r / 4) + 4 g + r % 4 of the
+// wavefront's 32) passes through the wavefront's own LDS area and comes back with 8 lanes
+// per row and four consecutive columns per lane (row 8 t + lane / 8, t = 0..3).  In that
+// form: v = acc + bias + xin, then mean and 1/sigma of the complete 256-wide rows (a
+// row's sum is an 8-lane reduction plus one pass through LDS across the 8 wavefronts).
+// Mean first, then the variance of the centred values, like the stand-alone kernel.
+// All 512 threads must call it (two barriers).
+__device__ __forceinline__ void tail_rows_stats(const f32x16& acc, const float4& bias4,
+                                                const float4 (&xin)[4], unsigned char* stg,
+                                                float (*s_red)[32][8], int wave, int lane,
+                                                float eps, float4 (&v)[4], float (&mean)[4],
+                                                float (&rstd)[4]) {
+  constexpr int STRIDE = 32 * 4 + 16;
+  const int l32 = lane & 31, g = lane >> 5, crow = lane >> 3, lp = lane & 7;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    *reinterpret_cast<float4*>(stg + l32 * STRIDE + (8 * q + 4 * g) * 4) =
+        make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int row = t * 8 + crow;
+    const float4 a4 = *reinterpret_cast<const float4*>(stg + row * STRIDE + lp * 16);
+    float4 r;
+    r.x = a4.x + bias4.x + xin[t].x;
+    r.y = a4.y + bias4.y + xin[t].y;
+    r.z = a4.z + bias4.z + xin[t].z;
+    r.w = a4.w + bias4.w + xin[t].w;
+    v[t] = r;
+    const float part = row8_sum((r.x + r.y) + (r.z + r.w));
+    if (lp == 0) s_red[0][row][wave] = part;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int row = t * 8 + crow;
+    const float4 p0 = *reinterpret_cast<const float4*>(&s_red[0][row][0]);
+    const float4 p1 = *reinterpret_cast<const float4*>(&s_red[0][row][4]);
+    mean[t] = (((p0.x + p0.y) + (p0.z + p0.w)) + ((p1.x + p1.y) + (p1.z + p1.w))) * (1.0f / 256.0f);
+    const float cx = v[t].x - mean[t], cy = v[t].y - mean[t];
+    const float cz = v[t].z - mean[t], cw = v[t].w - mean[t];
+    const float part = row8_sum(fmaf(cx, cx, cy * cy) + fmaf(cz, cz, cw * cw));
+    if (lp == 0) s_red[1][row][wave] = part;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int row = t * 8 + crow;
+    const float4 p0 = *reinterpret_cast<const float4*>(&s_red[1][row][0]);
+    const float4 p1 = *reinterpret_cast<const float4*>(&s_red[1][row][4]);
+    const float var = (((p0.x + p0.y) + (p0.z + p0.w)) + ((p1.x + p1.y) + (p1.z + p1.w))) * (1.0f / 256.0f);
+    rstd[t] = rsqrtf(var + eps);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Everything of a layer that follows attention, in one kernel (width 256).
+// ---------------------------------------------------------------------------
+//   x[m, :] += O[m, :] . Wo^T + bo;            a = LayerNorm(x) * g2 + b2
+//   x[m, :] += GELU(a . W1^T + b1) . W2^T + bf;  out[m, :] = LayerNorm(x[m, :]) * g + b
+// All of it is local to a row, so a workgroup that owns 32 complete rows can do it
+// without the residual stream, the normalised rows or the hidden activations leaving
+// the CU in between.  Eight wavefronts; wavefront w owns output columns 32 w .. 32 w + 31
+// of both products into x (32x32x16 MFMA, operand O or the hidden chunk).  The hidden
+// width is walked in chunks of 128: for a chunk each wavefront first computes 16 hidden
+// columns (16x16x32 MFMA; one operand is the 32 normalised rows, held in registers, the
+// other its 16 rows of W1), applies bias and GELU and puts them into LDS as bf16; after
+// one barrier every wavefront multiplies the 32 x 128 chunk with its 32 rows of W2.  Two
+// LDS buffers alternate between chunks, so one barrier per chunk is enough: nobody can
+// start writing chunk c+2 before everybody has passed barrier c+1, which every
+// wavefront reaches only after it has read chunk c.
+//
+// 32 rows per workgroup leave one workgroup per CU, and with four wavefronts (one per
+// SIMD) every LDS read, every GELU and every MFMA would wait for the one before; eight
+// wavefronts put two on each SIMD, so that one's MFMAs run under the other's GELU.
+//
+// No wavefront shares a weight with another, so the weights do not pass through LDS at
+// all: they are packed beforehand (layer_tail_pack_kernel) so that a plain 16-byte load
+// per lane delivers an MFMA operand, 1 KB contiguous per instruction, and every operand
+// register is reloaded for the next chunk right after the MFMA that used it: 16 KB of
+// weights per wavefront are in flight at any time.  Per 32 rows a workgroup streams Wo,
+// W1 and W2 once (1.1 MB for F = 1024); with every CU doing so at once, the L2 cache's
+// bandwidth is the bound of this kernel.  LDS carries only the normalised rows and the
+// hidden chunk.
+//
+// The sums run over K in ascending order like the separate kernels', so a row's result
+// does not depend on the batch it is in.
+template <bool kOutBf16>
+__global__ __launch_bounds__(512) void layer_tail_kernel(
+    const bf16_t* __restrict__ O, const bf16_t* __restrict__ Wp, const float* __restrict__ bo,
+    const float* __restrict__ ln2_g, const float* __restrict__ ln2_b,
+    const float* __restrict__ b1, const float* __restrict__ bf, int F,
+    float* __restrict__ resid, const float* __restrict__ ln_g, const float* __restrict__ ln_b,
+    float eps, void* __restrict__ out, int split_row, void* __restrict__ out2,
+    const int32_t* __restrict__ m_ptr, int m_host) {
+  constexpr int D = 256, BM = 32, FC = 128, NW = 8, WTN = 32;
+  constexpr int kMaxF = 2048;
+  constexpr int STRIDE = WTN * 4 + 16;   // bytes of a staging row
+  __shared__ __attribute__((aligned(16))) unsigned char sA[BM * D * 2];
+  __shared__ __attribute__((aligned(16))) unsigned char sH0[BM * FC * 2], sH1[BM * FC * 2];
+  __shared__ __attribute__((aligned(16))) unsigned char s_stage[NW * 32 * STRIDE];
+  __shared__ __attribute__((aligned(16))) float s_b1[kMaxF];
+  __shared__ __attribute__((aligned(16))) float s_red[2][BM][NW];   // [pass][row][wavefront]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
+  const int l32 = lane & 31, g = lane >> 5;     // 32x32x16 operands: row, k half
+  const int l16 = lane & 15, kg = lane >> 4;    // 16x16x32 operands: row, k quarter
+  const int nchunk = F / FC;
+  CFDETR_TLX(0);
+
+  // weight operands of chunk c (0: output projection): 16 blocks of 1 KB per wavefront;
+  // a wave-uniform base and a 32-bit lane offset
+  const unsigned char* const wsrc = reinterpret_cast<const unsigned char*>(Wp) + (size_t)wave * 8192;
+  const uint32_t voff = lane * 16;
+#define CFDETR_TAIL_W(c_, part_, ks_)                                                         \
+  (*reinterpret_cast<const bf16x8*>(wsrc + (size_t)(2 * (c_) + (part_)) * (NW * 8192) +      \
+                                    (ks_) * 1024 + voff))
+  bf16x8 w1[8], w2[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) w1[ks] = CFDETR_TAIL_W(0, 0, ks);
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) w2[ks] = CFDETR_TAIL_W(0, 1, ks);
+
+  const int M = m_ptr ? *m_ptr : m_host;
+  const int total = (M + BM - 1) / BM;
+  if ((int)blockIdx.x >= total) return;   // surplus workgroup: the grid covers the capacity
+  const int m0 = xcd_tile_order(blockIdx.x, total) * BM;
+  // rows and columns of this lane where rows are spread over 8 lanes (4 columns each)
+  const int crow = lane >> 3, lp = lane & 7, cn = wave * WTN + lp * 4;
+  float4 v[4];      // the residual rows in that form
+  float mean[4], rstd[4];
+  unsigned char* const stg = s_stage + wave * (32 * STRIDE);
+  f32x16 acc;
+  bf16x8 areg[2][8];
+  {
+    // ---- attention output times Wo: lane (l32, g) holds elements 16 ks + 8 g .. of row l32
+    bf16x8 oreg[16];
+    const bf16_t* orow = O + (size_t)min(m0 + l32, M - 1) * D + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) oreg[ks] = *reinterpret_cast<const bf16x8*>(orow + ks * 16);
+    const float4 bo4 = *reinterpret_cast<const float4*>(bo + cn);
+    const float4 gain4 = *reinterpret_cast<const float4*>(ln2_g + cn);
+    const float4 offs4 = *reinterpret_cast<const float4*>(ln2_b + cn);
+    float4 xin[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      xin[t] = *reinterpret_cast<const float4*>(resid + (size_t)min(m0 + t * 8 + crow, M - 1) * D + cn);
+    for (int i = tid * 4; i < F; i += 2048)
+      *reinterpret_cast<float4*>(s_b1 + i) = *reinterpret_cast<const float4*>(b1 + i);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1[ks], oreg[ks], acc, 0, 0, 0);
+      w1[ks] = CFDETR_TAIL_W(1, 0, ks);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2[ks], oreg[8 + ks], acc, 0, 0, 0);
+      w2[ks] = CFDETR_TAIL_W(1, 1, ks);
+    }
+    CFDETR_TLX(1);
+    tail_rows_stats(acc, bo4, xin, stg, s_red, wave, lane, eps, v, mean, rstd);
+    // normalised rows, bf16, into LDS: 512 bytes a row, 16-byte chunks swizzled with the row
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int row = t * 8 + crow;
+      const float r0 = (v[t].x - mean[t]) * rstd[t] * gain4.x + offs4.x;
+      const float r1 = (v[t].y - mean[t]) * rstd[t] * gain4.y + offs4.y;
+      const float r2 = (v[t].z - mean[t]) * rstd[t] * gain4.z + offs4.z;
+      const float r3 = (v[t].w - mean[t]) * rstd[t] * gain4.w + offs4.w;
+      const int idx = wave * 4 + (lp >> 1);
+      *reinterpret_cast<uint2*>(sA + row * (D * 2) + (((idx & ~7) | ((idx ^ row) & 7)) << 4) + (lp & 1) * 8) =
+          make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+    }
+    __syncthreads();
+    // as MFMA operand for all 8 k-steps of 32: lane (l16, kg) holds elements
+    // 32 ks + 8 kg .. + 8 of rows l16 and 16 + l16
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      const int row = hf * 16 + l16;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const int idx = 4 * ks + kg;
+        areg[hf][ks] = *reinterpret_cast<const bf16x8*>(sA + row * (D * 2) + (((idx & ~7) | ((idx ^ row) & 7)) << 4));
+      }
+    }
+  }
+  CFDETR_TLX(2);
+
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+
+  for (int c = 0; c < nchunk; ++c) {
+    // the chunk whose weights are fetched while this one is computed (the last chunk
+    // fetches itself once more: in bounds, never used)
+    const int cn1 = min(c + 1, nchunk - 1) + 1;
+    unsigned char* const sH = (c & 1) ? sH1 : sH0;
+    CFDETR_TL(0);
+    // ---- 16 hidden columns of this wavefront for both halves of the rows: bias, then
+    // 8 k-steps over the 256 inputs
+    f32x4 hid[2];
+    {
+      const float4 b = *reinterpret_cast<const float4*>(s_b1 + c * FC + wave * 16 + 4 * kg);
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        hid[hf][0] = b.x;
+        hid[hf][1] = b.y;
+        hid[hf][2] = b.z;
+        hid[hf][3] = b.w;
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+        hid[hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1[ks], areg[hf][ks], hid[hf], 0, 0, 0);
+      w1[ks] = CFDETR_TAIL_W(cn1, 0, ks);
+    }
+    CFDETR_TL(1);
+    // GELU, bf16, into the chunk buffer: lane = row (per half), 4 consecutive columns
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      const int row = hf * 16 + l16;
+      const uint2 pk = make_uint2(pack_bf16x2(gelu_fast(hid[hf][0]), gelu_fast(hid[hf][1])),
+                                  pack_bf16x2(gelu_fast(hid[hf][2]), gelu_fast(hid[hf][3])));
+      *reinterpret_cast<uint2*>(sH + row * (FC * 2) + (((2 * wave + (kg >> 1)) ^ (row & 7)) << 4) +
+                                (kg & 1) * 8) = pk;
+    }
+    CFDETR_TL(2);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    CFDETR_TL(3);
+    // ---- the chunk times this wavefront's 32 rows of W2
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const int hc = 2 * ks + g;     // 16-byte chunk of the hidden row
+      const bf16x8 fa = *reinterpret_cast<const bf16x8*>(sH + l32 * (FC * 2) + ((hc ^ (l32 & 7)) << 4));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2[ks], fa, acc, 0, 0, 0);
+      w2[ks] = CFDETR_TAIL_W(cn1, 1, ks);
+    }
+    CFDETR_TL(4);
+  }
+  CFDETR_TLX(3);
+#undef CFDETR_TAIL_W
+  // ---- x = x + FFN; the new residual rows go out, and their LayerNorm
+  const float4 bf4 = *reinterpret_cast<const float4*>(bf + cn);
+  const float4 gain4 = *reinterpret_cast<const float4*>(ln_g + cn);
+  const float4 offs4 = *reinterpret_cast<const float4*>(ln_b + cn);
+  float4 x2[4];
+  tail_rows_stats(acc, bf4, v, stg, s_red, wave, lane, eps, x2, mean, rstd);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int m = m0 + t * 8 + crow;
+    if (m >= M) continue;
+    *reinterpret_cast<float4*>(resid + (size_t)m * D + cn) = x2[t];
+    const float r0 = (x2[t].x - mean[t]) * rstd[t] * gain4.x + offs4.x;
+    const float r1 = (x2[t].y - mean[t]) * rstd[t] * gain4.y + offs4.y;
+    const float r2 = (x2[t].z - mean[t]) * rstd[t] * gain4.z + offs4.z;
+    const float r3 = (x2[t].w - mean[t]) * rstd[t] * gain4.w + offs4.w;
+    const bool second = out2 != nullptr && m >= split_row;
+    const size_t at = (size_t)(second ? m - split_row : m) * D + cn;
+    void* obase = second ? out2 : out;
+    if (kOutBf16)
+      *reinterpret_cast<uint2*>(static_cast<bf16_t*>(obase) + at) =
+          make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+    else
+      *reinterpret_cast<float4*>(static_cast<float*>(obase) + at) = make_float4(r0, r1, r2, r3);
+  }
+  CFDETR_TLX(4);
+}
+
 // ---------------------------------------------------------------------------
 // Patch embedding: rows of A are gathered pixels.
 // ---------------------------------------------------------------------------
@@ -1188,6 +1515,41 @@ hipError_t launch_gemm_residual_ln(const void* A, const void* W, const float* bi
     return launch_rowln<256, 4>(a, w, bias, K, resid, ln_g, ln_b, eps, out, out_is_bf16, split_row,
                                 out2, m_ptr, m_host, m_capacity, s);
   return hipErrorInvalidValue;
+}
+
+bool layer_tail_supported(int d, int F, bool use_bf16) {
+  return use_bf16 && d == 256 && F % 128 == 0 && F <= 2048;
+}
+
+uint64_t layer_tail_packed_bytes(int d, int F) { return ((uint64_t)d * d + 2 * (uint64_t)F * d) * 2; }
+
+hipError_t launch_layer_tail_pack(const void* Wo, const void* W1, const void* W2, int d, int F,
+                                  void* packed, hipStream_t s) {
+  if (!layer_tail_supported(d, F, true)) return hipErrorInvalidValue;
+  const int units = (int)(layer_tail_packed_bytes(d, F) / 16);
+  hipLaunchKernelGGL(layer_tail_pack_kernel, dim3((units + 255) / 256), dim3(256), 0, s,
+                     static_cast<const bf16_t*>(Wo), static_cast<const bf16_t*>(W1),
+                     static_cast<const bf16_t*>(W2), F, static_cast<bf16_t*>(packed));
+  return hipGetLastError();
+}
+
+hipError_t launch_layer_tail(const void* O, const void* packed, const float* bo,
+                             const float* ln2_g, const float* ln2_b, const float* b1,
+                             const float* b2, int d, int F, float* resid, const float* ln_g,
+                             const float* ln_b, float eps, void* out, bool out_is_bf16,
+                             int split_row, void* out2, const int32_t* m_ptr, int m_host,
+                             int m_capacity, hipStream_t s) {
+  if (!layer_tail_supported(d, F, true)) return hipErrorInvalidValue;
+  dim3 grid((m_capacity + 31) / 32);
+  const bf16_t* o = static_cast<const bf16_t*>(O);
+  const bf16_t* wp = static_cast<const bf16_t*>(packed);
+  if (out_is_bf16)
+    hipLaunchKernelGGL((layer_tail_kernel<true>), grid, dim3(512), 0, s, o, wp, bo, ln2_g, ln2_b, b1,
+                       b2, F, resid, ln_g, ln_b, eps, out, split_row, out2, m_ptr, m_host);
+  else
+    hipLaunchKernelGGL((layer_tail_kernel<false>), grid, dim3(512), 0, s, o, wp, bo, ln2_g, ln2_b, b1,
+                       b2, F, resid, ln_g, ln_b, eps, out, split_row, out2, m_ptr, m_host);
+  return hipGetLastError();
 }
 
 hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, int d,
