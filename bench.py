@@ -146,6 +146,11 @@ def measure(cfg_id, steps, warmup, profile_steps):
         # everything after attention ran as one kernel per layer, counted under ffn2: it
         # does the output projection and both feed-forward products
         work["ffn2"] = ("flop", work["out_proj"][1] + work["ffn1"][1] + work["ffn2"][1])
+        if prof["qkv"]["launches"] // profile_steps < cfg.layers:
+            # ... and the next layer's q/k/v projection; only the first layer's is a launch
+            per_layer = work["qkv"][1] / cfg.layers
+            work["ffn2"] = ("flop", work["ffn2"][1] + per_layer * (cfg.layers - 1))
+            work["qkv"] = ("flop", per_layer)
     kernels = {}
     for name, p in prof.items():
         if p["launches"] == 0:

@@ -232,7 +232,9 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
       CF_LAUNCH(CFDETR_K_LN,
                 launch_layernorm(ctx->x, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d, ctx->a,
                                  bf, d, eps, m_ptr, 0, m_cap, 0, nullptr, s));
-    if (bf)
+    if (fused_tail && l > 0) {
+      // q, k, v of this layer came out of the previous layer's last kernel
+    } else if (bf)
       CF_LAUNCH(CFDETR_K_QKV,
                 launch_gemm_qkv(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, d,
                                 attention_q_scale(d / c.n_heads), ctx->qkv, ctx->vt,
@@ -248,17 +250,31 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
     if (fused_tail) {
       // out-projection, LayerNorm, feed-forward block and the LayerNorm after it (the next
       // layer's first one, or the final one) in one kernel
-      const float* g = last ? w.lnf_g : w.ln1_g + (size_t)(l + 1) * d;
-      const float* b = last ? w.lnf_b : w.ln1_b + (size_t)(l + 1) * d;
-      CF_LAUNCH(CFDETR_K_FF2,
-                launch_layer_tail(ctx->o,
-                                  static_cast<const char*>(ctx->tail_packed) +
-                                      (size_t)l * ctx->tail_packed_layer,
-                                  w.b_o + (size_t)l * d, w.ln2_g + (size_t)l * d,
-                                  w.ln2_b + (size_t)l * d, w.b_ff1 + (size_t)l * F,
-                                  w.b_ff2 + (size_t)l * d, d, F, ctx->x, g, b, eps,
-                                  last ? (void*)y0 : ctx->a, !last, last ? split_row : 0,
-                                  last ? (void*)y1 : nullptr, m_ptr, 0, m_cap, s));
+      LayerTailArgs ta{};
+      ta.O = ctx->o;
+      ta.packed = static_cast<const char*>(ctx->tail_packed) + (size_t)l * ctx->tail_packed_layer;
+      ta.b_o = w.b_o + (size_t)l * d;
+      ta.ln2_g = w.ln2_g + (size_t)l * d;
+      ta.ln2_b = w.ln2_b + (size_t)l * d;
+      ta.b_ff1 = w.b_ff1 + (size_t)l * F;
+      ta.b_ff2 = w.b_ff2 + (size_t)l * d;
+      ta.resid = ctx->x;
+      ta.ln_g = last ? w.lnf_g : w.ln1_g + (size_t)(l + 1) * d;
+      ta.ln_b = last ? w.lnf_b : w.ln1_b + (size_t)(l + 1) * d;
+      ta.eps = eps;
+      ta.last = last;
+      ta.out = y0;
+      ta.split_row = split_row;
+      ta.out2 = y1;
+      ta.b_qkv = last ? nullptr : w.b_qkv + (size_t)(l + 1) * 3 * d;
+      ta.q_scale = attention_q_scale(d / c.n_heads);
+      ta.qk = ctx->qkv;
+      ta.vt = ctx->vt;
+      ta.vt_ld = ctx->vt_ld;
+      ta.cu = cu_all;
+      ta.pcu = ctx->pcu;
+      ta.B = nseq;
+      CF_LAUNCH(CFDETR_K_FF2, launch_layer_tail(ta, d, F, m_ptr, 0, m_cap, s));
       continue;
     }
     if (fused_ln) {
@@ -610,12 +626,14 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
                          c->pe_col[l], nullptr);
   // the weights after attention in the order the fused kernel streams them
   for (int l = 0; l < cfg->n_layers && e == hipSuccess && c->tail_packed_layer; ++l)
-    e = launch_layer_tail_pack(static_cast<const char*>(w->w_o) + (size_t)l * d * d * 2,
-                               static_cast<const char*>(w->w_ff1) + (size_t)l * F * d * 2,
-                               static_cast<const char*>(w->w_ff2) + (size_t)l * d * F * 2, (int)d,
-                               (int)F,
-                               static_cast<char*>(c->tail_packed) + (size_t)l * c->tail_packed_layer,
-                               nullptr);
+    e = launch_layer_tail_pack(
+        static_cast<const char*>(w->w_o) + (size_t)l * d * d * 2,
+        static_cast<const char*>(w->w_ff1) + (size_t)l * F * d * 2,
+        static_cast<const char*>(w->w_ff2) + (size_t)l * d * F * 2,
+        l + 1 < cfg->n_layers ? static_cast<const char*>(w->w_qkv) + (size_t)(l + 1) * 3 * d * d * 2
+                              : nullptr,
+        (int)d, (int)F, static_cast<char*>(c->tail_packed) + (size_t)l * c->tail_packed_layer,
+        nullptr);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     hipFree(c->arena);

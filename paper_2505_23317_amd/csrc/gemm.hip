@@ -805,30 +805,42 @@ __global__ __launch_bounds__(256) void gemm_bf16_rowln_kernel(
 #define CFDETR_TLX(i)
 #endif
 
-// The weights of the second half of a layer (attention output projection, then the
-// feed-forward block) in the order and layout layer_tail_kernel reads them: 1 KB blocks,
-// each the 64 x 16 bytes that one MFMA of one wavefront takes as its weight operand,
-// lane by lane.  Block ((2 c + part) * 8 + w) * 8 + ks.  c = 0 is the output projection
-// (32x32x16 operand: lane (l32, g) holds Wo[32 w + l32][16 (8 part + ks) + 8 g ..]);
-// c >= 1 is chunk c - 1 of 128 hidden units: part 0 = W1 rows (16x16x32 operand: lane
-// (l16, kg) holds W1[128 (c-1) + 16 w + l16][32 ks + 8 kg ..]), part 1 = W2 columns
-// (32x32x16 operand: lane (l32, g) holds W2[32 w + l32][128 (c-1) + 16 ks + 8 g ..]).
+// The weights that layer_tail_kernel streams, in its order and layout: 1 KB blocks, each
+// the 64 x 16 bytes that one MFMA of one wavefront takes as its weight operand, lane by
+// lane.  Block ((2 c + part) * 8 + w) * 8 + ks, for wavefront w:
+//   c = 0: the output projection (32x32x16 operand: lane (l32, g) holds
+//     Wo[32 w + l32][16 (8 part + ks) + 8 g ..]);
+//   c = 1 .. F/128: chunk c - 1 of 128 hidden units: part 0 = W1 rows (16x16x32 operand:
+//     lane (l16, kg) holds W1[128 (c-1) + 16 w + l16][32 ks + 8 kg ..]), part 1 = W2
+//     columns (32x32x16 operand: lane (l32, g) holds W2[32 w + l32][128 (c-1) + 16 ks + 8 g ..]);
+//   c = F/128 + 1 .. + 3: the next layer's query/key/value projection, 48 blocks per
+//     wavefront: block b = 16 (c - F/128 - 1) + 8 part + ks is k-step b / 3 of the
+//     wavefront's column tile b % 3 (32x32x16 operand: lane (l32, g) holds
+//     Wqkv[96 w + 32 (b % 3) + l32][16 (b / 3) + 8 g ..]); skipped when Wqkv is null.
 // One thread per 16 bytes.
 __global__ __launch_bounds__(256) void layer_tail_pack_kernel(const bf16_t* __restrict__ Wo,
                                                               const bf16_t* __restrict__ W1,
                                                               const bf16_t* __restrict__ W2,
+                                                              const bf16_t* __restrict__ Wqkv,
                                                               int F, bf16_t* __restrict__ out) {
   constexpr int D = 256, FC = 128;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;   // 16-byte unit of the output
-  if (i >= (D * D + F * D * 2) / 8) return;
+  if (i >= (4 * D * D + F * D * 2) / 8) return;
   const int lane = i & 63, ks = (i >> 6) & 7, w = (i >> 9) & 7, part = (i >> 12) & 1, c = i >> 13;
+  const int nchunk = F / FC;
   const bf16_t* src;
-  if (c == 0)
+  if (c == 0) {
     src = Wo + (size_t)(w * 32 + (lane & 31)) * D + (part * 8 + ks) * 16 + (lane >> 5) * 8;
-  else if (part == 0)
-    src = W1 + (size_t)((c - 1) * FC + w * 16 + (lane & 15)) * D + ks * 32 + (lane >> 4) * 8;
-  else
-    src = W2 + (size_t)(w * 32 + (lane & 31)) * F + (c - 1) * FC + ks * 16 + (lane >> 5) * 8;
+  } else if (c <= nchunk) {
+    if (part == 0)
+      src = W1 + (size_t)((c - 1) * FC + w * 16 + (lane & 15)) * D + ks * 32 + (lane >> 4) * 8;
+    else
+      src = W2 + (size_t)(w * 32 + (lane & 31)) * F + (c - 1) * FC + ks * 16 + (lane >> 5) * 8;
+  } else {
+    if (Wqkv == nullptr) return;
+    const int b = 16 * (c - nchunk - 1) + 8 * part + ks;
+    src = Wqkv + (size_t)(w * 96 + (b % 3) * 32 + (lane & 31)) * D + (b / 3) * 16 + (lane >> 5) * 8;
+  }
   reinterpret_cast<uint4*>(out)[i] = *reinterpret_cast<const uint4*>(src);
 }
 
@@ -927,13 +939,32 @@ __device__ __forceinline__ void tail_rows_stats(const f32x16& acc, const float4&
 //
 // The sums run over K in ascending order like the separate kernels', so a row's result
 // does not depend on the batch it is in.
-template <bool kOutBf16>
+//
+// Unless the layer is the last one (kLast: out = the final LayerNorm in fp32, rows from
+// split_row on to out2), the kernel goes on with the next layer's query/key/value
+// projection of the normalised rows, which otherwise would be the next kernel: q
+// (multiplied by q_scale) and k go to qk [M, 3 * 256] in bf16, v feature-major to vt
+// (position pcu[f] + m - cu[f] of its frame f), as the stand-alone projection writes
+// them; wavefront w owns columns 96 w .. 96 w + 95.  The normalised rows themselves are
+// then not written at all.
+struct TailQkv {
+  const float* bias;   // [768]
+  float q_scale;
+  bf16_t* qk;
+  bf16_t* vt;
+  int vt_ld;
+  const int32_t* cu;
+  const int32_t* pcu;
+  int B;
+};
+
+template <bool kLast>
 __global__ __launch_bounds__(512) void layer_tail_kernel(
     const bf16_t* __restrict__ O, const bf16_t* __restrict__ Wp, const float* __restrict__ bo,
     const float* __restrict__ ln2_g, const float* __restrict__ ln2_b,
     const float* __restrict__ b1, const float* __restrict__ bf, int F,
     float* __restrict__ resid, const float* __restrict__ ln_g, const float* __restrict__ ln_b,
-    float eps, void* __restrict__ out, int split_row, void* __restrict__ out2,
+    float eps, float* __restrict__ out, int split_row, float* __restrict__ out2, TailQkv qkv,
     const int32_t* __restrict__ m_ptr, int m_host) {
   constexpr int D = 256, BM = 32, FC = 128, NW = 8, WTN = 32;
   constexpr int kMaxF = 2048;
@@ -1035,9 +1066,10 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 
   for (int c = 0; c < nchunk; ++c) {
-    // the chunk whose weights are fetched while this one is computed (the last chunk
-    // fetches itself once more: in bounds, never used)
-    const int cn1 = min(c + 1, nchunk - 1) + 1;
+    // the chunk whose weights are fetched while this one is computed (the last chunk of
+    // the last layer fetches itself once more: in bounds, never used)
+    // (with the projection behind it, the last chunk fetches the projection's first blocks)
+    const int cn1 = (kLast ? min(c + 1, nchunk - 1) : c + 1) + 1;
     unsigned char* const sH = (c & 1) ? sH1 : sH0;
     CFDETR_TL(0);
     // ---- 16 hidden columns of this wavefront for both halves of the rows: bias, then
@@ -1086,7 +1118,6 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
     CFDETR_TL(4);
   }
   CFDETR_TLX(3);
-#undef CFDETR_TAIL_W
   // ---- x = x + FFN; the new residual rows go out, and their LayerNorm
   const float4 bf4 = *reinterpret_cast<const float4*>(bf + cn);
   const float4 gain4 = *reinterpret_cast<const float4*>(ln_g + cn);
@@ -1095,22 +1126,95 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
   tail_rows_stats(acc, bf4, v, stg, s_red, wave, lane, eps, x2, mean, rstd);
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    const int m = m0 + t * 8 + crow;
-    if (m >= M) continue;
-    *reinterpret_cast<float4*>(resid + (size_t)m * D + cn) = x2[t];
+    const int row = t * 8 + crow;
+    const int m = m0 + row;
     const float r0 = (x2[t].x - mean[t]) * rstd[t] * gain4.x + offs4.x;
     const float r1 = (x2[t].y - mean[t]) * rstd[t] * gain4.y + offs4.y;
     const float r2 = (x2[t].z - mean[t]) * rstd[t] * gain4.z + offs4.z;
     const float r3 = (x2[t].w - mean[t]) * rstd[t] * gain4.w + offs4.w;
-    const bool second = out2 != nullptr && m >= split_row;
-    const size_t at = (size_t)(second ? m - split_row : m) * D + cn;
-    void* obase = second ? out2 : out;
-    if (kOutBf16)
-      *reinterpret_cast<uint2*>(static_cast<bf16_t*>(obase) + at) =
+    if (m < M) *reinterpret_cast<float4*>(resid + (size_t)m * D + cn) = x2[t];
+    if (kLast) {
+      if (m < M) {
+        const bool second = out2 != nullptr && m >= split_row;
+        float* obase = second ? out2 : out;
+        *reinterpret_cast<float4*>(obase + (size_t)(second ? m - split_row : m) * D + cn) =
+            make_float4(r0, r1, r2, r3);
+      }
+    } else {
+      // operand rows of the projection, as after the first LayerNorm (sA is free: every
+      // wavefront has taken its copy long ago)
+      const int idx = wave * 4 + (lp >> 1);
+      *reinterpret_cast<uint2*>(sA + row * (D * 2) + (((idx & ~7) | ((idx ^ row) & 7)) << 4) + (lp & 1) * 8) =
           make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
-    else
-      *reinterpret_cast<float4*>(static_cast<float*>(obase) + at) = make_float4(r0, r1, r2, r3);
+    }
   }
+  if (kLast) {
+    CFDETR_TLX(4);
+    return;
+  }
+  // ---- the next layer's q, k, v of these rows
+  __syncthreads();
+  bf16x8 qreg[16];   // lane (l32, g): elements 16 ks + 8 g .. of row l32
+#pragma unroll
+  for (int ks = 0; ks < 16; ++ks) {
+    const int idx = 2 * ks + g;
+    qreg[ks] = *reinterpret_cast<const bf16x8*>(sA + l32 * (D * 2) + (((idx & ~7) | ((idx ^ l32) & 7)) << 4));
+  }
+  f32x16 pacc[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) pacc[j][r] = 0.f;
+  // 48 weight blocks, k-step major; the first 16 are in w1, w2 already, and each register
+  // takes block b + 16 as soon as block b has been used
+#pragma unroll
+  for (int b = 0; b < 48; ++b) {
+    bf16x8& wr = (b & 8) ? w2[b & 7] : w1[b & 7];
+    pacc[b % 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr, qreg[b / 3], pacc[b % 3], 0, 0, 0);
+    if (b + 16 < 48) wr = CFDETR_TAIL_W(nchunk + 1 + (b + 16) / 16, ((b + 16) >> 3) & 1, b & 7);
+  }
+  // position of this lane's row (l32) in the feature-major copy of v
+  const int mrow = m0 + l32;
+  int vpos = 0;
+  if (mrow < M) {
+    const int f = frame_of_token(qkv.cu, qkv.B, mrow);
+    vpos = qkv.pcu[f] + (mrow - qkv.cu[f]);
+  }
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const int n0 = wave * 96 + j * 32;   // 32 columns, all q, all k or all v
+    if (n0 < 2 * D) {
+      // through the wavefront's staging area: 8 lanes per row, 4 columns per lane
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(stg + l32 * STRIDE + (8 * q + 4 * g) * 4) =
+            make_float4(pacc[j][4 * q], pacc[j][4 * q + 1], pacc[j][4 * q + 2], pacc[j][4 * q + 3]);
+      const float4 b4 = *reinterpret_cast<const float4*>(qkv.bias + n0 + lp * 4);
+      const float sc = n0 < D ? qkv.q_scale : 1.0f;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int row = t * 8 + crow;
+        const float4 a4 = *reinterpret_cast<const float4*>(stg + row * STRIDE + lp * 16);
+        if (m0 + row < M)
+          *reinterpret_cast<uint2*>(qkv.qk + (size_t)(m0 + row) * (3 * D) + n0 + lp * 4) =
+              make_uint2(pack_bf16x2((a4.x + b4.x) * sc, (a4.y + b4.y) * sc),
+                         pack_bf16x2((a4.z + b4.z) * sc, (a4.w + b4.w) * sc));
+      }
+    } else if (mrow < M) {
+      // a token per lane: the feature-major stores are runs of 32 consecutive positions
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + 8 * q + 4 * g;
+        const float4 b4 = *reinterpret_cast<const float4*>(qkv.bias + n);
+        bf16_t* p = qkv.vt + (size_t)(n - 2 * D) * qkv.vt_ld + vpos;
+        p[0] = f32_to_bf16(pacc[j][4 * q] + b4.x);
+        p[(size_t)qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 1] + b4.y);
+        p[(size_t)2 * qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 2] + b4.z);
+        p[(size_t)3 * qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 3] + b4.w);
+      }
+    }
+  }
+#undef CFDETR_TAIL_W
   CFDETR_TLX(4);
 }
 
@@ -1521,34 +1625,38 @@ bool layer_tail_supported(int d, int F, bool use_bf16) {
   return use_bf16 && d == 256 && F % 128 == 0 && F <= 2048;
 }
 
-uint64_t layer_tail_packed_bytes(int d, int F) { return ((uint64_t)d * d + 2 * (uint64_t)F * d) * 2; }
+uint64_t layer_tail_packed_bytes(int d, int F) {
+  return (4 * (uint64_t)d * d + 2 * (uint64_t)F * d) * 2;
+}
 
-hipError_t launch_layer_tail_pack(const void* Wo, const void* W1, const void* W2, int d, int F,
-                                  void* packed, hipStream_t s) {
+hipError_t launch_layer_tail_pack(const void* Wo, const void* W1, const void* W2,
+                                  const void* Wqkv_next, int d, int F, void* packed,
+                                  hipStream_t s) {
   if (!layer_tail_supported(d, F, true)) return hipErrorInvalidValue;
   const int units = (int)(layer_tail_packed_bytes(d, F) / 16);
   hipLaunchKernelGGL(layer_tail_pack_kernel, dim3((units + 255) / 256), dim3(256), 0, s,
                      static_cast<const bf16_t*>(Wo), static_cast<const bf16_t*>(W1),
-                     static_cast<const bf16_t*>(W2), F, static_cast<bf16_t*>(packed));
+                     static_cast<const bf16_t*>(W2), static_cast<const bf16_t*>(Wqkv_next), F,
+                     static_cast<bf16_t*>(packed));
   return hipGetLastError();
 }
 
-hipError_t launch_layer_tail(const void* O, const void* packed, const float* bo,
-                             const float* ln2_g, const float* ln2_b, const float* b1,
-                             const float* b2, int d, int F, float* resid, const float* ln_g,
-                             const float* ln_b, float eps, void* out, bool out_is_bf16,
-                             int split_row, void* out2, const int32_t* m_ptr, int m_host,
-                             int m_capacity, hipStream_t s) {
+hipError_t launch_layer_tail(const LayerTailArgs& a, int d, int F, const int32_t* m_ptr,
+                             int m_host, int m_capacity, hipStream_t s) {
   if (!layer_tail_supported(d, F, true)) return hipErrorInvalidValue;
   dim3 grid((m_capacity + 31) / 32);
-  const bf16_t* o = static_cast<const bf16_t*>(O);
-  const bf16_t* wp = static_cast<const bf16_t*>(packed);
-  if (out_is_bf16)
-    hipLaunchKernelGGL((layer_tail_kernel<true>), grid, dim3(512), 0, s, o, wp, bo, ln2_g, ln2_b, b1,
-                       b2, F, resid, ln_g, ln_b, eps, out, split_row, out2, m_ptr, m_host);
+  const bf16_t* o = static_cast<const bf16_t*>(a.O);
+  const bf16_t* wp = static_cast<const bf16_t*>(a.packed);
+  TailQkv q{a.b_qkv, a.q_scale, static_cast<bf16_t*>(a.qk), static_cast<bf16_t*>(a.vt), a.vt_ld,
+            a.cu, a.pcu, a.B};
+  if (a.last)
+    hipLaunchKernelGGL((layer_tail_kernel<true>), grid, dim3(512), 0, s, o, wp, a.b_o, a.ln2_g,
+                       a.ln2_b, a.b_ff1, a.b_ff2, F, a.resid, a.ln_g, a.ln_b, a.eps, a.out,
+                       a.split_row, a.out2, q, m_ptr, m_host);
   else
-    hipLaunchKernelGGL((layer_tail_kernel<false>), grid, dim3(512), 0, s, o, wp, bo, ln2_g, ln2_b, b1,
-                       b2, F, resid, ln_g, ln_b, eps, out, split_row, out2, m_ptr, m_host);
+    hipLaunchKernelGGL((layer_tail_kernel<false>), grid, dim3(512), 0, s, o, wp, a.b_o, a.ln2_g,
+                       a.ln2_b, a.b_ff1, a.b_ff2, F, a.resid, a.ln_g, a.ln_b, a.eps, a.out,
+                       a.split_row, a.out2, q, m_ptr, m_host);
   return hipGetLastError();
 }
 

@@ -139,21 +139,41 @@ hipError_t launch_gemm_residual_ln(const void* A, const void* W, const float* bi
                                    hipStream_t s);
 
 // Everything of a layer after attention, with the LayerNorm that follows it, in one
-// kernel:  resid[M,d] += O[M,d] . Wo[d,d]^T + bo;  a = LayerNorm(resid) * ln2_g + ln2_b;
-// resid += GELU(a . W1[F,d]^T + b1) . W2[d,F]^T + b2;  then out as for
-// launch_gemm_residual_ln.  Nothing but resid and out is written.  The three matrices
-// are read from a packed copy (layer_tail_packed_bytes) that launch_layer_tail_pack
-// writes once.  Only for the shapes layer_tail_supported names.
+// kernel:  resid[M,d] += O[M,d] . Wo[d,d]^T + b_o;  a = LayerNorm(resid) * ln2_g + ln2_b;
+// resid += GELU(a . W1[F,d]^T + b_ff1) . W2[d,F]^T + b_ff2;  n = LayerNorm(resid) * ln_g + ln_b.
+// last: n goes to out in fp32 (rows >= split_row to out2 at row - split_row when out2 is
+// given).  Otherwise the kernel goes on with the next layer's query/key/value projection
+// of n (bias b_qkv [3d]) and writes q, k, v exactly as launch_gemm_qkv does; n itself is
+// not written.  The matrices are read from a packed copy (layer_tail_packed_bytes) that
+// launch_layer_tail_pack writes once (Wqkv_next null for the last layer).  Only for the
+// shapes layer_tail_supported names.
+struct LayerTailArgs {
+  const void* O;
+  const void* packed;
+  const float *b_o, *ln2_g, *ln2_b, *b_ff1, *b_ff2;
+  float* resid;
+  const float *ln_g, *ln_b;
+  float eps;
+  bool last;
+  float* out;      // last only
+  int split_row;
+  float* out2;
+  const float* b_qkv;   // the rest: not last only
+  float q_scale;
+  void* qk;
+  void* vt;
+  int vt_ld;
+  const int32_t* cu;
+  const int32_t* pcu;
+  int B;
+};
 bool layer_tail_supported(int d, int F, bool use_bf16);
 uint64_t layer_tail_packed_bytes(int d, int F);
-hipError_t launch_layer_tail_pack(const void* Wo, const void* W1, const void* W2, int d, int F,
-                                  void* packed, hipStream_t s);
-hipError_t launch_layer_tail(const void* O, const void* packed, const float* bo,
-                             const float* ln2_g, const float* ln2_b, const float* b1,
-                             const float* b2, int d, int F, float* resid, const float* ln_g,
-                             const float* ln_b, float eps, void* out, bool out_is_bf16,
-                             int split_row, void* out2, const int32_t* m_ptr, int m_host,
-                             int m_capacity, hipStream_t s);
+hipError_t launch_layer_tail_pack(const void* Wo, const void* W1, const void* W2,
+                                  const void* Wqkv_next, int d, int F, void* packed,
+                                  hipStream_t s);
+hipError_t launch_layer_tail(const LayerTailArgs& a, int d, int F, const int32_t* m_ptr,
+                             int m_host, int m_capacity, hipStream_t s);
 
 // bf16 query/key/value projection: q and k go to qk [M, 3d] (columns 0..2d, bias added,
 // q multiplied by q_scale = attention_q_scale(d_head) so that the attention kernel gets
