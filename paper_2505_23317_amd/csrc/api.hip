@@ -58,6 +58,7 @@ struct cfdetr_ctx {
   int32_t* err_flag = nullptr;
   void* tail_packed = nullptr;   // w_o, w_ff1, w_ff2 of every layer in the fused kernel's order
   uint64_t tail_packed_layer = 0;   // bytes per layer; 0: the shape has no fused kernel
+  void* head_packed = nullptr;      // w_qkv of the first layer in the same layout
 
   // decoder (cfdetr_decoder_attach): its own allocation
   bool has_dec = false;
@@ -228,12 +229,18 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
     const char* w1 = static_cast<const char*>(w.w_ff1) + (size_t)l * F * d * es;
     const char* w2 = static_cast<const char*>(w.w_ff2) + (size_t)l * d * F * es;
     const bool last = l + 1 == c.n_layers;
-    if (!fused_ln || l == 0)
+    if (fused_tail && l == 0)
+      // first LayerNorm and q/k/v projection in one kernel
+      CF_LAUNCH(CFDETR_K_QKV,
+                launch_layer_head(ctx->x, ctx->head_packed, w.ln1_g, w.ln1_b, eps, w.b_qkv,
+                                  attention_q_scale(d / c.n_heads), ctx->qkv, ctx->vt, ctx->vt_ld,
+                                  cu_all, ctx->pcu, nseq, d, m_ptr, 0, m_cap, s));
+    else if (!fused_ln || l == 0)
       CF_LAUNCH(CFDETR_K_LN,
                 launch_layernorm(ctx->x, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d, ctx->a,
                                  bf, d, eps, m_ptr, 0, m_cap, 0, nullptr, s));
-    if (fused_tail && l > 0) {
-      // q, k, v of this layer came out of the previous layer's last kernel
+    if (fused_tail) {
+      // q, k, v of this layer came out of the kernel before (the previous layer's last)
     } else if (bf)
       CF_LAUNCH(CFDETR_K_QKV,
                 launch_gemm_qkv(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, d,
@@ -571,6 +578,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   if (layer_tail_supported((int)d, (int)F, c->bf16))
     c->tail_packed_layer = layer_tail_packed_bytes((int)d, (int)F);
   const uint64_t o_pack = cv.take(c->tail_packed_layer * cfg->n_layers);
+  const uint64_t o_hpack = cv.take(c->tail_packed_layer ? 3 * d * d * 2 : 0);
   c->arena_bytes = cv.off;
   e = hipMalloc(&c->arena, c->arena_bytes);
   if (e != hipSuccess) {
@@ -605,6 +613,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->cu_pad = reinterpret_cast<int32_t*>(base + o_cupad);
   c->kv_len = reinterpret_cast<int32_t*>(base + o_kvlen);
   c->tail_packed = base + o_pack;
+  c->head_packed = base + o_hpack;
 
   // static tables: coarse grid descriptors, zeroed counters, position tables
   std::vector<int32_t> desc(Bm * c->n0), cu(Bm + 1);
@@ -634,6 +643,8 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
                               : nullptr,
         (int)d, (int)F, static_cast<char*>(c->tail_packed) + (size_t)l * c->tail_packed_layer,
         nullptr);
+  if (e == hipSuccess && c->tail_packed_layer)
+    e = launch_layer_head_pack(w->w_qkv, (int)d, c->head_packed, nullptr);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     hipFree(c->arena);

@@ -844,6 +844,18 @@ __global__ __launch_bounds__(256) void layer_tail_pack_kernel(const bf16_t* __re
   reinterpret_cast<uint4*>(out)[i] = *reinterpret_cast<const uint4*>(src);
 }
 
+// The first layer's q/k/v projection in the same layout (48 blocks per wavefront, three
+// groups of 64 KB), for layer_head_kernel.
+__global__ __launch_bounds__(256) void layer_head_pack_kernel(const bf16_t* __restrict__ Wqkv,
+                                                              bf16_t* __restrict__ out) {
+  constexpr int D = 256;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;   // 16-byte unit of the output
+  if (i >= 3 * D * D / 8) return;
+  const int lane = i & 63, ks = (i >> 6) & 7, w = (i >> 9) & 7, b = (i >> 12) * 8 + ks;
+  reinterpret_cast<uint4*>(out)[i] = *reinterpret_cast<const uint4*>(
+      Wqkv + (size_t)(w * 96 + (b % 3) * 32 + (lane & 31)) * D + (b / 3) * 16 + (lane >> 5) * 8);
+}
+
 // Sum over each group of 8 consecutive lanes, delivered to all 8.
 __device__ __forceinline__ float row8_sum(float v) {
   v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
@@ -852,19 +864,16 @@ __device__ __forceinline__ float row8_sum(float v) {
   return v;
 }
 
-// Shared by the two row updates of layer_tail_kernel.  The 32 x 32 accumulator of a
-// wavefront (lane (l32, g), register r = row l32, column 8 (r / 4) + 4 g + r % 4 of the
-// wavefront's 32) passes through the wavefront's own LDS area and comes back with 8 lanes
-// per row and four consecutive columns per lane (row 8 t + lane / 8, t = 0..3).  In that
-// form: v = acc + bias + xin, then mean and 1/sigma of the complete 256-wide rows (a
-// row's sum is an 8-lane reduction plus one pass through LDS across the 8 wavefronts).
-// Mean first, then the variance of the centred values, like the stand-alone kernel.
-// All 512 threads must call it (two barriers).
-__device__ __forceinline__ void tail_rows_stats(const f32x16& acc, const float4& bias4,
-                                                const float4 (&xin)[4], unsigned char* stg,
-                                                float (*s_red)[32][8], int wave, int lane,
-                                                float eps, float4 (&v)[4], float (&mean)[4],
-                                                float (&rstd)[4]) {
+// Rows of layer_tail_kernel and layer_head_kernel live spread over 8 lanes, four
+// consecutive columns per lane: lane of wavefront w holds columns 32 w + 4 (lane % 8) ..
+// of rows 8 t + lane / 8, t = 0..3.
+//
+// tail_rows_update: the 32 x 32 accumulator of a wavefront (lane (l32, g), register r =
+// row l32, column 8 (r / 4) + 4 g + r % 4 of the wavefront's 32) passes through the
+// wavefront's own LDS area and comes back in that form; v = acc + bias + xin.
+__device__ __forceinline__ void tail_rows_update(const f32x16& acc, const float4& bias4,
+                                                 const float4 (&xin)[4], unsigned char* stg,
+                                                 int lane, float4 (&v)[4]) {
   constexpr int STRIDE = 32 * 4 + 16;
   const int l32 = lane & 31, g = lane >> 5, crow = lane >> 3, lp = lane & 7;
 #pragma unroll
@@ -873,16 +882,26 @@ __device__ __forceinline__ void tail_rows_stats(const f32x16& acc, const float4&
         make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    const int row = t * 8 + crow;
-    const float4 a4 = *reinterpret_cast<const float4*>(stg + row * STRIDE + lp * 16);
-    float4 r;
-    r.x = a4.x + bias4.x + xin[t].x;
-    r.y = a4.y + bias4.y + xin[t].y;
-    r.z = a4.z + bias4.z + xin[t].z;
-    r.w = a4.w + bias4.w + xin[t].w;
-    v[t] = r;
-    const float part = row8_sum((r.x + r.y) + (r.z + r.w));
-    if (lp == 0) s_red[0][row][wave] = part;
+    const float4 a4 = *reinterpret_cast<const float4*>(stg + (t * 8 + crow) * STRIDE + lp * 16);
+    v[t].x = a4.x + bias4.x + xin[t].x;
+    v[t].y = a4.y + bias4.y + xin[t].y;
+    v[t].z = a4.z + bias4.z + xin[t].z;
+    v[t].w = a4.w + bias4.w + xin[t].w;
+  }
+}
+
+// tail_rows_stats: mean and 1/sigma of the complete 256-wide rows (a row's sum is an
+// 8-lane reduction plus one pass through LDS across the 8 wavefronts).  Mean first, then
+// the variance of the centred values, like the stand-alone kernel.  All 512 threads must
+// call it (two barriers).
+__device__ __forceinline__ void tail_rows_stats(const float4 (&v)[4], float (*s_red)[32][8],
+                                                int wave, int lane, float eps, float (&mean)[4],
+                                                float (&rstd)[4]) {
+  const int crow = lane >> 3, lp = lane & 7;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const float part = row8_sum((v[t].x + v[t].y) + (v[t].z + v[t].w));
+    if (lp == 0) s_red[0][t * 8 + crow][wave] = part;
   }
   __syncthreads();
 #pragma unroll
@@ -905,6 +924,152 @@ __device__ __forceinline__ void tail_rows_stats(const f32x16& acc, const float4&
     const float var = (((p0.x + p0.y) + (p0.z + p0.w)) + ((p1.x + p1.y) + (p1.z + p1.w))) * (1.0f / 256.0f);
     rstd[t] = rsqrtf(var + eps);
   }
+}
+
+// Normalised rows (v - mean) * rstd * gain + offs of this lane, as bf16 into the
+// operand buffer sA: 512 bytes a row, 16-byte chunks swizzled with the row.
+__device__ __forceinline__ void tail_rows_to_operand(const float4 (&v)[4], const float (&mean)[4],
+                                                     const float (&rstd)[4], const float4& gain4,
+                                                     const float4& offs4, unsigned char* sA,
+                                                     int wave, int lane) {
+  const int crow = lane >> 3, lp = lane & 7;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int row = t * 8 + crow;
+    const float r0 = (v[t].x - mean[t]) * rstd[t] * gain4.x + offs4.x;
+    const float r1 = (v[t].y - mean[t]) * rstd[t] * gain4.y + offs4.y;
+    const float r2 = (v[t].z - mean[t]) * rstd[t] * gain4.z + offs4.z;
+    const float r3 = (v[t].w - mean[t]) * rstd[t] * gain4.w + offs4.w;
+    const int idx = wave * 4 + (lp >> 1);
+    *reinterpret_cast<uint2*>(sA + row * 512 + (((idx & ~7) | ((idx ^ row) & 7)) << 4) + (lp & 1) * 8) =
+        make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+  }
+}
+
+// Where the q/k/v projection of layer_tail_kernel and layer_head_kernel writes.
+struct TailQkv {
+  const float* bias;   // [768]
+  float q_scale;
+  bf16_t* qk;
+  bf16_t* vt;
+  int vt_ld;
+  const int32_t* cu;
+  const int32_t* pcu;
+  int B;
+};
+
+// The q/k/v projection of the 32 rows in sA (bf16, as tail_rows_to_operand leaves them;
+// the caller has passed a barrier since): q (multiplied by q_scale) and k go to
+// qk [M, 768] in bf16, v feature-major to vt (position pcu[f] + m - cu[f] of its frame
+// f), as the stand-alone projection writes them.  Wavefront w owns columns 96 w ..
+// 96 w + 95 as three 32-column tiles.  Its 48 weight blocks of 1 KB (block b = k-step
+// b / 3 of tile b % 3, see layer_tail_pack_kernel) lie at qsrc + (b / 8) * 64 KB +
+// (b % 8) * 1 KB + voff; the first 16 are in w1, w2 already, and each register takes
+// block b + 16 as soon as block b has been used.
+__device__ __forceinline__ void tail_project_qkv(const unsigned char* sA, bf16x8 (&w1)[8],
+                                                 bf16x8 (&w2)[8], const unsigned char* qsrc,
+                                                 uint32_t voff, const TailQkv& qkv,
+                                                 unsigned char* stg, int m0, int M, int wave,
+                                                 int lane) {
+  constexpr int D = 256, STRIDE = 32 * 4 + 16;
+  const int l32 = lane & 31, g = lane >> 5, crow = lane >> 3, lp = lane & 7;
+  bf16x8 qreg[16];   // lane (l32, g): elements 16 ks + 8 g .. of row l32
+#pragma unroll
+  for (int ks = 0; ks < 16; ++ks) {
+    const int idx = 2 * ks + g;
+    qreg[ks] = *reinterpret_cast<const bf16x8*>(sA + l32 * 512 + (((idx & ~7) | ((idx ^ l32) & 7)) << 4));
+  }
+  f32x16 pacc[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) pacc[j][r] = 0.f;
+#pragma unroll
+  for (int b = 0; b < 48; ++b) {
+    bf16x8& wr = (b & 8) ? w2[b & 7] : w1[b & 7];
+    pacc[b % 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr, qreg[b / 3], pacc[b % 3], 0, 0, 0);
+    if (b + 16 < 48)
+      wr = *reinterpret_cast<const bf16x8*>(qsrc + (size_t)((b + 16) >> 3) * 65536 + (b & 7) * 1024 + voff);
+  }
+  // position of this lane's row (l32) in the feature-major copy of v
+  const int mrow = m0 + l32;
+  int vpos = 0;
+  if (mrow < M) {
+    const int f = frame_of_token(qkv.cu, qkv.B, mrow);
+    vpos = qkv.pcu[f] + (mrow - qkv.cu[f]);
+  }
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const int n0 = wave * 96 + j * 32;   // 32 columns, all q, all k or all v
+    if (n0 < 2 * D) {
+      // through the wavefront's staging area: 8 lanes per row, 4 columns per lane
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(stg + l32 * STRIDE + (8 * q + 4 * g) * 4) =
+            make_float4(pacc[j][4 * q], pacc[j][4 * q + 1], pacc[j][4 * q + 2], pacc[j][4 * q + 3]);
+      const float4 b4 = *reinterpret_cast<const float4*>(qkv.bias + n0 + lp * 4);
+      const float sc = n0 < D ? qkv.q_scale : 1.0f;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int row = t * 8 + crow;
+        const float4 a4 = *reinterpret_cast<const float4*>(stg + row * STRIDE + lp * 16);
+        if (m0 + row < M)
+          *reinterpret_cast<uint2*>(qkv.qk + (size_t)(m0 + row) * (3 * D) + n0 + lp * 4) =
+              make_uint2(pack_bf16x2((a4.x + b4.x) * sc, (a4.y + b4.y) * sc),
+                         pack_bf16x2((a4.z + b4.z) * sc, (a4.w + b4.w) * sc));
+      }
+    } else if (mrow < M) {
+      // a token per lane: the feature-major stores are runs of 32 consecutive positions
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + 8 * q + 4 * g;
+        const float4 b4 = *reinterpret_cast<const float4*>(qkv.bias + n);
+        bf16_t* p = qkv.vt + (size_t)(n - 2 * D) * qkv.vt_ld + vpos;
+        p[0] = f32_to_bf16(pacc[j][4 * q] + b4.x);
+        p[(size_t)qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 1] + b4.y);
+        p[(size_t)2 * qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 2] + b4.z);
+        p[(size_t)3 * qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 3] + b4.w);
+      }
+    }
+  }
+}
+
+// LayerNorm and q/k/v projection of the first layer (width 256): the same rows-per-
+// workgroup scheme as layer_tail_kernel, of which this is the last stage on its own.
+// Wp: the 48 weight blocks per wavefront in the packed layout (three groups of 64 KB).
+__global__ __launch_bounds__(512) void layer_head_kernel(
+    const float* __restrict__ x, const bf16_t* __restrict__ Wp, const float* __restrict__ ln_g,
+    const float* __restrict__ ln_b, float eps, TailQkv qkv, const int32_t* __restrict__ m_ptr,
+    int m_host) {
+  constexpr int D = 256, BM = 32, NW = 8, STRIDE = 32 * 4 + 16;
+  __shared__ __attribute__((aligned(16))) unsigned char sA[BM * D * 2];
+  __shared__ __attribute__((aligned(16))) unsigned char s_stage[NW * 32 * STRIDE];
+  __shared__ __attribute__((aligned(16))) float s_red[2][BM][NW];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const unsigned char* const wsrc = reinterpret_cast<const unsigned char*>(Wp) + (size_t)wave * 8192;
+  const uint32_t voff = lane * 16;
+  bf16x8 w1[8], w2[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) w1[ks] = *reinterpret_cast<const bf16x8*>(wsrc + ks * 1024 + voff);
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) w2[ks] = *reinterpret_cast<const bf16x8*>(wsrc + 65536 + ks * 1024 + voff);
+  const int M = m_ptr ? *m_ptr : m_host;
+  const int total = (M + BM - 1) / BM;
+  if ((int)blockIdx.x >= total) return;   // surplus workgroup: the grid covers the capacity
+  const int m0 = xcd_tile_order(blockIdx.x, total) * BM;
+  const int crow = lane >> 3, lp = lane & 7, cn = wave * 32 + lp * 4;
+  const float4 gain4 = *reinterpret_cast<const float4*>(ln_g + cn);
+  const float4 offs4 = *reinterpret_cast<const float4*>(ln_b + cn);
+  float4 v[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+    v[t] = *reinterpret_cast<const float4*>(x + (size_t)min(m0 + t * 8 + crow, M - 1) * D + cn);
+  float mean[4], rstd[4];
+  tail_rows_stats(v, s_red, wave, lane, eps, mean, rstd);
+  tail_rows_to_operand(v, mean, rstd, gain4, offs4, sA, wave, lane);
+  __syncthreads();
+  tail_project_qkv(sA, w1, w2, wsrc, voff, qkv, s_stage + wave * (32 * STRIDE), m0, M, wave, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -947,17 +1112,6 @@ __device__ __forceinline__ void tail_rows_stats(const f32x16& acc, const float4&
 // (position pcu[f] + m - cu[f] of its frame f), as the stand-alone projection writes
 // them; wavefront w owns columns 96 w .. 96 w + 95.  The normalised rows themselves are
 // then not written at all.
-struct TailQkv {
-  const float* bias;   // [768]
-  float q_scale;
-  bf16_t* qk;
-  bf16_t* vt;
-  int vt_ld;
-  const int32_t* cu;
-  const int32_t* pcu;
-  int B;
-};
-
 template <bool kLast>
 __global__ __launch_bounds__(512) void layer_tail_kernel(
     const bf16_t* __restrict__ O, const bf16_t* __restrict__ Wp, const float* __restrict__ bo,
@@ -1034,19 +1188,9 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
       w2[ks] = CFDETR_TAIL_W(1, 1, ks);
     }
     CFDETR_TLX(1);
-    tail_rows_stats(acc, bo4, xin, stg, s_red, wave, lane, eps, v, mean, rstd);
-    // normalised rows, bf16, into LDS: 512 bytes a row, 16-byte chunks swizzled with the row
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int row = t * 8 + crow;
-      const float r0 = (v[t].x - mean[t]) * rstd[t] * gain4.x + offs4.x;
-      const float r1 = (v[t].y - mean[t]) * rstd[t] * gain4.y + offs4.y;
-      const float r2 = (v[t].z - mean[t]) * rstd[t] * gain4.z + offs4.z;
-      const float r3 = (v[t].w - mean[t]) * rstd[t] * gain4.w + offs4.w;
-      const int idx = wave * 4 + (lp >> 1);
-      *reinterpret_cast<uint2*>(sA + row * (D * 2) + (((idx & ~7) | ((idx ^ row) & 7)) << 4) + (lp & 1) * 8) =
-          make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
-    }
+    tail_rows_update(acc, bo4, xin, stg, lane, v);
+    tail_rows_stats(v, s_red, wave, lane, eps, mean, rstd);
+    tail_rows_to_operand(v, mean, rstd, gain4, offs4, sA, wave, lane);
     __syncthreads();
     // as MFMA operand for all 8 k-steps of 32: lane (l16, kg) holds elements
     // 32 ks + 8 kg .. + 8 of rows l16 and 16 + l16
@@ -1123,97 +1267,35 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
   const float4 gain4 = *reinterpret_cast<const float4*>(ln_g + cn);
   const float4 offs4 = *reinterpret_cast<const float4*>(ln_b + cn);
   float4 x2[4];
-  tail_rows_stats(acc, bf4, v, stg, s_red, wave, lane, eps, x2, mean, rstd);
+  tail_rows_update(acc, bf4, v, stg, lane, x2);
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int row = t * 8 + crow;
-    const int m = m0 + row;
-    const float r0 = (x2[t].x - mean[t]) * rstd[t] * gain4.x + offs4.x;
-    const float r1 = (x2[t].y - mean[t]) * rstd[t] * gain4.y + offs4.y;
-    const float r2 = (x2[t].z - mean[t]) * rstd[t] * gain4.z + offs4.z;
-    const float r3 = (x2[t].w - mean[t]) * rstd[t] * gain4.w + offs4.w;
-    if (m < M) *reinterpret_cast<float4*>(resid + (size_t)m * D + cn) = x2[t];
-    if (kLast) {
-      if (m < M) {
-        const bool second = out2 != nullptr && m >= split_row;
-        float* obase = second ? out2 : out;
-        *reinterpret_cast<float4*>(obase + (size_t)(second ? m - split_row : m) * D + cn) =
-            make_float4(r0, r1, r2, r3);
-      }
-    } else {
-      // operand rows of the projection, as after the first LayerNorm (sA is free: every
-      // wavefront has taken its copy long ago)
-      const int idx = wave * 4 + (lp >> 1);
-      *reinterpret_cast<uint2*>(sA + row * (D * 2) + (((idx & ~7) | ((idx ^ row) & 7)) << 4) + (lp & 1) * 8) =
-          make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
-    }
-  }
+  for (int t = 0; t < 4; ++t)
+    if (m0 + t * 8 + crow < M)
+      *reinterpret_cast<float4*>(resid + (size_t)(m0 + t * 8 + crow) * D + cn) = x2[t];
+  tail_rows_stats(x2, s_red, wave, lane, eps, mean, rstd);
   if (kLast) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int m = m0 + t * 8 + crow;
+      if (m >= M) continue;
+      const float r0 = (x2[t].x - mean[t]) * rstd[t] * gain4.x + offs4.x;
+      const float r1 = (x2[t].y - mean[t]) * rstd[t] * gain4.y + offs4.y;
+      const float r2 = (x2[t].z - mean[t]) * rstd[t] * gain4.z + offs4.z;
+      const float r3 = (x2[t].w - mean[t]) * rstd[t] * gain4.w + offs4.w;
+      const bool second = out2 != nullptr && m >= split_row;
+      float* obase = second ? out2 : out;
+      *reinterpret_cast<float4*>(obase + (size_t)(second ? m - split_row : m) * D + cn) =
+          make_float4(r0, r1, r2, r3);
+    }
     CFDETR_TLX(4);
     return;
   }
-  // ---- the next layer's q, k, v of these rows
+  // ---- the next layer's q, k, v of these rows (sA is free: every wavefront has taken
+  // its copy of the first operand long ago)
+  tail_rows_to_operand(x2, mean, rstd, gain4, offs4, sA, wave, lane);
   __syncthreads();
-  bf16x8 qreg[16];   // lane (l32, g): elements 16 ks + 8 g .. of row l32
-#pragma unroll
-  for (int ks = 0; ks < 16; ++ks) {
-    const int idx = 2 * ks + g;
-    qreg[ks] = *reinterpret_cast<const bf16x8*>(sA + l32 * (D * 2) + (((idx & ~7) | ((idx ^ l32) & 7)) << 4));
-  }
-  f32x16 pacc[3];
-#pragma unroll
-  for (int j = 0; j < 3; ++j)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) pacc[j][r] = 0.f;
-  // 48 weight blocks, k-step major; the first 16 are in w1, w2 already, and each register
-  // takes block b + 16 as soon as block b has been used
-#pragma unroll
-  for (int b = 0; b < 48; ++b) {
-    bf16x8& wr = (b & 8) ? w2[b & 7] : w1[b & 7];
-    pacc[b % 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr, qreg[b / 3], pacc[b % 3], 0, 0, 0);
-    if (b + 16 < 48) wr = CFDETR_TAIL_W(nchunk + 1 + (b + 16) / 16, ((b + 16) >> 3) & 1, b & 7);
-  }
-  // position of this lane's row (l32) in the feature-major copy of v
-  const int mrow = m0 + l32;
-  int vpos = 0;
-  if (mrow < M) {
-    const int f = frame_of_token(qkv.cu, qkv.B, mrow);
-    vpos = qkv.pcu[f] + (mrow - qkv.cu[f]);
-  }
-#pragma unroll
-  for (int j = 0; j < 3; ++j) {
-    const int n0 = wave * 96 + j * 32;   // 32 columns, all q, all k or all v
-    if (n0 < 2 * D) {
-      // through the wavefront's staging area: 8 lanes per row, 4 columns per lane
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<float4*>(stg + l32 * STRIDE + (8 * q + 4 * g) * 4) =
-            make_float4(pacc[j][4 * q], pacc[j][4 * q + 1], pacc[j][4 * q + 2], pacc[j][4 * q + 3]);
-      const float4 b4 = *reinterpret_cast<const float4*>(qkv.bias + n0 + lp * 4);
-      const float sc = n0 < D ? qkv.q_scale : 1.0f;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int row = t * 8 + crow;
-        const float4 a4 = *reinterpret_cast<const float4*>(stg + row * STRIDE + lp * 16);
-        if (m0 + row < M)
-          *reinterpret_cast<uint2*>(qkv.qk + (size_t)(m0 + row) * (3 * D) + n0 + lp * 4) =
-              make_uint2(pack_bf16x2((a4.x + b4.x) * sc, (a4.y + b4.y) * sc),
-                         pack_bf16x2((a4.z + b4.z) * sc, (a4.w + b4.w) * sc));
-      }
-    } else if (mrow < M) {
-      // a token per lane: the feature-major stores are runs of 32 consecutive positions
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n0 + 8 * q + 4 * g;
-        const float4 b4 = *reinterpret_cast<const float4*>(qkv.bias + n);
-        bf16_t* p = qkv.vt + (size_t)(n - 2 * D) * qkv.vt_ld + vpos;
-        p[0] = f32_to_bf16(pacc[j][4 * q] + b4.x);
-        p[(size_t)qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 1] + b4.y);
-        p[(size_t)2 * qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 2] + b4.z);
-        p[(size_t)3 * qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 3] + b4.w);
-      }
-    }
-  }
+  tail_project_qkv(sA, w1, w2, wsrc + (size_t)2 * (nchunk + 1) * (NW * 8192), voff, qkv, stg, m0,
+                   M, wave, lane);
 #undef CFDETR_TAIL_W
   CFDETR_TLX(4);
 }
@@ -1638,6 +1720,25 @@ hipError_t launch_layer_tail_pack(const void* Wo, const void* W1, const void* W2
                      static_cast<const bf16_t*>(Wo), static_cast<const bf16_t*>(W1),
                      static_cast<const bf16_t*>(W2), static_cast<const bf16_t*>(Wqkv_next), F,
                      static_cast<bf16_t*>(packed));
+  return hipGetLastError();
+}
+
+hipError_t launch_layer_head_pack(const void* Wqkv, int d, void* packed, hipStream_t s) {
+  if (d != 256) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(layer_head_pack_kernel, dim3(3 * 256 * 256 / 8 / 256), dim3(256), 0, s,
+                     static_cast<const bf16_t*>(Wqkv), static_cast<bf16_t*>(packed));
+  return hipGetLastError();
+}
+
+hipError_t launch_layer_head(const float* x, const void* packed, const float* ln_g,
+                             const float* ln_b, float eps, const float* b_qkv, float q_scale,
+                             void* qk, void* vt, int vt_ld, const int32_t* cu, const int32_t* pcu,
+                             int B, int d, const int32_t* m_ptr, int m_host, int m_capacity,
+                             hipStream_t s) {
+  if (d != 256) return hipErrorInvalidValue;
+  TailQkv q{b_qkv, q_scale, static_cast<bf16_t*>(qk), static_cast<bf16_t*>(vt), vt_ld, cu, pcu, B};
+  hipLaunchKernelGGL(layer_head_kernel, dim3((m_capacity + 31) / 32), dim3(512), 0, s, x,
+                     static_cast<const bf16_t*>(packed), ln_g, ln_b, eps, q, m_ptr, m_host);
   return hipGetLastError();
 }
 

@@ -175,6 +175,17 @@ hipError_t launch_layer_tail_pack(const void* Wo, const void* W1, const void* W2
 hipError_t launch_layer_tail(const LayerTailArgs& a, int d, int F, const int32_t* m_ptr,
                              int m_host, int m_capacity, hipStream_t s);
 
+// The first layer's LayerNorm and query/key/value projection in the same style (width
+// 256, bf16): q, k, v of LayerNorm(x) * ln_g + ln_b, written as launch_gemm_qkv writes
+// them.  The matrix is read from a packed copy (3 d d elements) that
+// launch_layer_head_pack writes once.
+hipError_t launch_layer_head_pack(const void* Wqkv, int d, void* packed, hipStream_t s);
+hipError_t launch_layer_head(const float* x, const void* packed, const float* ln_g,
+                             const float* ln_b, float eps, const float* b_qkv, float q_scale,
+                             void* qk, void* vt, int vt_ld, const int32_t* cu, const int32_t* pcu,
+                             int B, int d, const int32_t* m_ptr, int m_host, int m_capacity,
+                             hipStream_t s);
+
 // bf16 query/key/value projection: q and k go to qk [M, 3d] (columns 0..2d, bias added,
 // q multiplied by q_scale = attention_q_scale(d_head) so that the attention kernel gets
 // base-2 logits straight from its first MFMA); v goes feature-major to vt [d, vt_ld] at
