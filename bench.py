@@ -81,9 +81,12 @@ def cpu_baseline(cfg, wl, cfg_id):
             "sample": f"{sample}, repeated {passes} times", "seconds": dt, "tokens": int(tokens)}
 
 
-TRAFFIC_FAMILY = {"attention": "attention", "qkv": "gemm_qkv", "ffn1": "gemm_ffn1_gelu",
-                  "out_proj": "gemm_out_proj", "ffn2": "gemm_ffn2",
-                  "layernorm": "layernorm", "embed": "embed", "gather": "gather_coarse"}
+# kernel family of the profile interface -> names it may have in the counter summary (the
+# fused kernels of width 256 first: where they run, the separate ones do not)
+TRAFFIC_FAMILY = {"attention": ["attention"], "qkv": ["layer_head", "gemm_qkv"],
+                  "ffn1": ["gemm_ffn1_gelu"], "out_proj": ["gemm_out_proj"],
+                  "ffn2": ["layer_tail", "gemm_ffn2"], "layernorm": ["layernorm"],
+                  "embed": ["embed"], "gather": ["gather_coarse"]}
 
 
 def hbm_traffic(cfg_id, family):
@@ -93,11 +96,15 @@ def hbm_traffic(cfg_id, family):
     want = TRAFFIC_FAMILY.get(family)
     if want is None or not os.path.exists(path):
         return None
+    found = {}
     with open(path) as f:
         for line in f:
             parts = line.split()
-            if len(parts) == 4 and parts[0] == want:
-                return float(parts[2]) + float(parts[3])
+            if len(parts) == 4 and parts[0] in want:
+                found[parts[0]] = float(parts[2]) + float(parts[3])
+    for name in want:
+        if name in found:
+            return found[name]
     return None
 
 

@@ -4,7 +4,6 @@
 
 #include <algorithm>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -222,7 +221,7 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
   // Where a workgroup can own whole rows, the residual contractions also apply the
   // LayerNorm that follows them, and only the very first one is a launch of its own.
   const bool fused_ln = gemm_residual_ln_supported(d, bf);
-  const bool fused_tail = fused_ln && ctx->tail_packed_layer != 0 && !getenv("CFDETR_DEV_SPLIT_FFN");
+  const bool fused_tail = fused_ln && ctx->tail_packed_layer != 0;
   for (int l = 0; l < c.n_layers; ++l) {
     const char* wqkv = static_cast<const char*>(w.w_qkv) + (size_t)l * 3 * d * d * es;
     const char* wo = static_cast<const char*>(w.w_o) + (size_t)l * d * d * es;

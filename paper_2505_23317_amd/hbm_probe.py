@@ -30,7 +30,9 @@ FAMILIES = [
     ("gemm_qkv", r"gemm_bf16_direct_kernel.*EpiQkv"),
     ("gemm_ffn1_gelu", r"gemm_bf16_direct_kernel.*EpiAct<unsigned short, true>"),
     ("gemm_residual", r"gemm_bf16_direct_kernel.*EpiResidual|gemm_bf16_rowln_kernel"),
-    ("embed", r"gemm_bf16_gather_kernel"),
+    ("layer_tail", r"layer_tail_kernel"),
+    ("layer_head", r"layer_head_kernel"),
+    ("embed", r"gemm_bf16_gather_kernel|gemm_bf16_direct_kernel.*EpiEmbed"),
     ("layernorm", r"layernorm_kernel"),
     ("select_hit", r"select_hit_kernel"),
     ("select_compact", r"select_compact_kernel"),
