@@ -20,7 +20,9 @@
  *   - Every data pointer is a DEVICE pointer (gfx950) owned by the caller,
  *     unless a parameter says "host".  Frames, boxes, weights and the fp32
  *     token/output buffers must be 16-byte aligned (else CFDETR_EINVAL).  The library never frees or keeps
- *     ownership of caller memory.  Weights must outlive the context.
+ *     ownership of caller memory.  Weights must outlive the context and must
+ *     not change while it exists: some kernels read private re-ordered copies
+ *     of the matrices that cfdetr_create makes.
  *   - Work space is allocated once in cfdetr_create from the max_* fields and
  *     released in cfdetr_destroy; the encode calls allocate nothing.
  *   - Calls enqueue work on the given hipStream_t (passed as void*; NULL is
@@ -133,7 +135,8 @@ typedef enum {
   CFDETR_K_ATTN = 6,   /* variable-length self-attention                       */
   CFDETR_K_OUT = 7,    /* output projection + residual                         */
   CFDETR_K_FF1 = 8,    /* first FFN projection + GELU                          */
-  CFDETR_K_FF2 = 9,    /* second FFN projection + residual                     */
+  CFDETR_K_FF2 = 9,    /* second FFN projection + residual; where one kernel does
+                          everything of a layer after attention, that kernel      */
   CFDETR_K_ROI = 10,   /* difficulty test and region proposal                  */
   CFDETR_K_DEC = 11,   /* decoder kernels that are not one of the families above
                           (cast, query broadcast, key/value projection, heads)   */
@@ -142,6 +145,9 @@ typedef enum {
 
 /* Host-side.  Validates cfg, copies it, keeps the weight POINTERS, allocates
  * the work space on the current device and builds the position tables there.
+ * For d_model 256 in bf16 with d_ffn a multiple of 128 up to 2048 it also
+ * copies w_qkv, w_o, w_ff1, w_ff2 into the order its fused layer kernels read
+ * (the weights are read once, here).
  * On failure *out is NULL. */
 CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_weights* w,
                             cfdetr_ctx** out);

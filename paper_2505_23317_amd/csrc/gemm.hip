@@ -806,17 +806,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_rowln_kernel(
 #endif
 
 // The weights that layer_tail_kernel streams, in its order and layout: 1 KB blocks, each
-// the 64 x 16 bytes that one MFMA of one wavefront takes as its weight operand, lane by
-// lane.  Block ((2 c + part) * 8 + w) * 8 + ks, for wavefront w:
-//   c = 0: the output projection (32x32x16 operand: lane (l32, g) holds
-//     Wo[32 w + l32][16 (8 part + ks) + 8 g ..]);
-//   c = 1 .. F/128: chunk c - 1 of 128 hidden units: part 0 = W1 rows (16x16x32 operand:
-//     lane (l16, kg) holds W1[128 (c-1) + 16 w + l16][32 ks + 8 kg ..]), part 1 = W2
-//     columns (32x32x16 operand: lane (l32, g) holds W2[32 w + l32][128 (c-1) + 16 ks + 8 g ..]);
+// the 64 x 16 bytes that one 32x32x16 MFMA of one wavefront takes as its weight operand
+// (lane (l32, g) holds 8 consecutive k of weight row l32), 16 blocks per wavefront and
+// group, 8 wavefronts per group of 128 KB.  Block i of wavefront w in group c:
+//   c = 0: the output projection: Wo[32 w + l32][16 i + 8 g ..];
+//   c = 1 .. F/128: chunk c - 1 of 128 hidden units.  Wavefronts 0-3 produce the hidden
+//     chunk: W1[128 (c-1) + 32 w + l32][16 i + 8 g ..].  Wavefronts 4-7 consume it, each
+//     for 64 output columns as two tiles: W2[64 (w-4) + 32 (i % 2) + l32][128 (c-1) + 16 (i / 2) + 8 g ..];
 //   c = F/128 + 1 .. + 3: the next layer's query/key/value projection, 48 blocks per
-//     wavefront: block b = 16 (c - F/128 - 1) + 8 part + ks is k-step b / 3 of the
-//     wavefront's column tile b % 3 (32x32x16 operand: lane (l32, g) holds
-//     Wqkv[96 w + 32 (b % 3) + l32][16 (b / 3) + 8 g ..]); skipped when Wqkv is null.
+//     wavefront: block b = 16 (c - F/128 - 1) + i is k-step b / 3 of the wavefront's column
+//     tile b % 3: Wqkv[96 w + 32 (b % 3) + l32][16 (b / 3) + 8 g ..]; skipped when Wqkv is
+//     null.
 // One thread per 16 bytes.
 __global__ __launch_bounds__(256) void layer_tail_pack_kernel(const bf16_t* __restrict__ Wo,
                                                               const bf16_t* __restrict__ W1,
@@ -824,35 +824,36 @@ __global__ __launch_bounds__(256) void layer_tail_pack_kernel(const bf16_t* __re
                                                               const bf16_t* __restrict__ Wqkv,
                                                               int F, bf16_t* __restrict__ out) {
   constexpr int D = 256, FC = 128;
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;   // 16-byte unit of the output
-  if (i >= (4 * D * D + F * D * 2) / 8) return;
-  const int lane = i & 63, ks = (i >> 6) & 7, w = (i >> 9) & 7, part = (i >> 12) & 1, c = i >> 13;
+  const int u = blockIdx.x * blockDim.x + threadIdx.x;   // 16-byte unit of the output
+  if (u >= (4 * D * D + F * D * 2) / 8) return;
+  const int lane = u & 63, i = (u >> 6) & 15, w = (u >> 10) & 7, c = u >> 13;
+  const int l32 = lane & 31, g = lane >> 5;
   const int nchunk = F / FC;
   const bf16_t* src;
   if (c == 0) {
-    src = Wo + (size_t)(w * 32 + (lane & 31)) * D + (part * 8 + ks) * 16 + (lane >> 5) * 8;
+    src = Wo + (size_t)(w * 32 + l32) * D + i * 16 + g * 8;
   } else if (c <= nchunk) {
-    if (part == 0)
-      src = W1 + (size_t)((c - 1) * FC + w * 16 + (lane & 15)) * D + ks * 32 + (lane >> 4) * 8;
+    if (w < 4)
+      src = W1 + (size_t)((c - 1) * FC + w * 32 + l32) * D + i * 16 + g * 8;
     else
-      src = W2 + (size_t)(w * 32 + (lane & 31)) * F + (c - 1) * FC + ks * 16 + (lane >> 5) * 8;
+      src = W2 + (size_t)((w - 4) * 64 + (i & 1) * 32 + l32) * F + (c - 1) * FC + (i >> 1) * 16 + g * 8;
   } else {
     if (Wqkv == nullptr) return;
-    const int b = 16 * (c - nchunk - 1) + 8 * part + ks;
-    src = Wqkv + (size_t)(w * 96 + (b % 3) * 32 + (lane & 31)) * D + (b / 3) * 16 + (lane >> 5) * 8;
+    const int b = 16 * (c - nchunk - 1) + i;
+    src = Wqkv + (size_t)(w * 96 + (b % 3) * 32 + l32) * D + (b / 3) * 16 + g * 8;
   }
-  reinterpret_cast<uint4*>(out)[i] = *reinterpret_cast<const uint4*>(src);
+  reinterpret_cast<uint4*>(out)[u] = *reinterpret_cast<const uint4*>(src);
 }
 
-// The first layer's q/k/v projection in the same layout (48 blocks per wavefront, three
-// groups of 64 KB), for layer_head_kernel.
+// The first layer's q/k/v projection in the same layout (three groups of 128 KB), for
+// layer_head_kernel.
 __global__ __launch_bounds__(256) void layer_head_pack_kernel(const bf16_t* __restrict__ Wqkv,
                                                               bf16_t* __restrict__ out) {
   constexpr int D = 256;
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;   // 16-byte unit of the output
-  if (i >= 3 * D * D / 8) return;
-  const int lane = i & 63, ks = (i >> 6) & 7, w = (i >> 9) & 7, b = (i >> 12) * 8 + ks;
-  reinterpret_cast<uint4*>(out)[i] = *reinterpret_cast<const uint4*>(
+  const int u = blockIdx.x * blockDim.x + threadIdx.x;   // 16-byte unit of the output
+  if (u >= 3 * D * D / 8) return;
+  const int lane = u & 63, i = (u >> 6) & 15, w = (u >> 10) & 7, b = (u >> 13) * 16 + i;
+  reinterpret_cast<uint4*>(out)[u] = *reinterpret_cast<const uint4*>(
       Wqkv + (size_t)(w * 96 + (b % 3) * 32 + (lane & 31)) * D + (b / 3) * 16 + (lane >> 5) * 8);
 }
 
@@ -865,24 +866,26 @@ __device__ __forceinline__ float row8_sum(float v) {
 }
 
 // Rows of layer_tail_kernel and layer_head_kernel live spread over 8 lanes, four
-// consecutive columns per lane: lane of wavefront w holds columns 32 w + 4 (lane % 8) ..
-// of rows 8 t + lane / 8, t = 0..3.
-//
-// tail_rows_update: the 32 x 32 accumulator of a wavefront (lane (l32, g), register r =
-// row l32, column 8 (r / 4) + 4 g + r % 4 of the wavefront's 32) passes through the
-// wavefront's own LDS area and comes back in that form; v = acc + bias + xin.
-__device__ __forceinline__ void tail_rows_update(const f32x16& acc, const float4& bias4,
-                                                 const float4 (&xin)[4], unsigned char* stg,
-                                                 int lane, float4 (&v)[4]) {
-  constexpr int STRIDE = 32 * 4 + 16;
-  const int l32 = lane & 31, g = lane >> 5, crow = lane >> 3, lp = lane & 7;
+// consecutive columns per lane: a lane of wavefront w holds columns 32 w + 4 (lane % 8) ..
+// of rows 8 t + lane / 8, t = 0..3.  A 32 x 32 accumulator tile (lane (l32, g), register
+// r = row l32, column 8 (r / 4) + 4 g + r % 4) gets into that form through a 4.5 KB LDS
+// area: tail_tile_put writes the tile, tail_rows_take reads it back as v = tile + bias + xin.
+constexpr int kTailStride = 32 * 4 + 16;   // bytes of a staging row
+
+__device__ __forceinline__ void tail_tile_put(const f32x16& acc, unsigned char* stg, int lane) {
+  const int l32 = lane & 31, g = lane >> 5;
 #pragma unroll
   for (int q = 0; q < 4; ++q)
-    *reinterpret_cast<float4*>(stg + l32 * STRIDE + (8 * q + 4 * g) * 4) =
+    *reinterpret_cast<float4*>(stg + l32 * kTailStride + (8 * q + 4 * g) * 4) =
         make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+}
+
+__device__ __forceinline__ void tail_rows_take(const unsigned char* stg, const float4& bias4,
+                                               const float4 (&xin)[4], int lane, float4 (&v)[4]) {
+  const int crow = lane >> 3, lp = lane & 7;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    const float4 a4 = *reinterpret_cast<const float4*>(stg + (t * 8 + crow) * STRIDE + lp * 16);
+    const float4 a4 = *reinterpret_cast<const float4*>(stg + (t * 8 + crow) * kTailStride + lp * 16);
     v[t].x = a4.x + bias4.x + xin[t].x;
     v[t].y = a4.y + bias4.y + xin[t].y;
     v[t].z = a4.z + bias4.z + xin[t].z;
@@ -946,6 +949,18 @@ __device__ __forceinline__ void tail_rows_to_operand(const float4 (&v)[4], const
   }
 }
 
+// The 32 rows in sA as operand of sixteen 32x32x16 MFMAs: lane (l32, g) gets elements
+// 16 ks + 8 g .. of row l32.
+__device__ __forceinline__ void tail_operand_load(const unsigned char* sA, int lane,
+                                                  bf16x8 (&a)[16]) {
+  const int l32 = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int ks = 0; ks < 16; ++ks) {
+    const int idx = 2 * ks + g;
+    a[ks] = *reinterpret_cast<const bf16x8*>(sA + l32 * 512 + (((idx & ~7) | ((idx ^ l32) & 7)) << 4));
+  }
+}
+
 // Where the q/k/v projection of layer_tail_kernel and layer_head_kernel writes.
 struct TailQkv {
   const float* bias;   // [768]
@@ -963,22 +978,17 @@ struct TailQkv {
 // qk [M, 768] in bf16, v feature-major to vt (position pcu[f] + m - cu[f] of its frame
 // f), as the stand-alone projection writes them.  Wavefront w owns columns 96 w ..
 // 96 w + 95 as three 32-column tiles.  Its 48 weight blocks of 1 KB (block b = k-step
-// b / 3 of tile b % 3, see layer_tail_pack_kernel) lie at qsrc + (b / 8) * 64 KB +
-// (b % 8) * 1 KB + voff; the first 16 are in w1, w2 already, and each register takes
+// b / 3 of tile b % 3, see layer_tail_pack_kernel) lie at qsrc + (b / 16) * 128 KB +
+// (b % 16) * 1 KB + voff; the first 16 are in wreg already, and each register takes
 // block b + 16 as soon as block b has been used.
-__device__ __forceinline__ void tail_project_qkv(const unsigned char* sA, bf16x8 (&w1)[8],
-                                                 bf16x8 (&w2)[8], const unsigned char* qsrc,
-                                                 uint32_t voff, const TailQkv& qkv,
-                                                 unsigned char* stg, int m0, int M, int wave,
-                                                 int lane) {
-  constexpr int D = 256, STRIDE = 32 * 4 + 16;
+__device__ __forceinline__ void tail_project_qkv(const unsigned char* sA, bf16x8 (&wreg)[16],
+                                                 const unsigned char* qsrc, uint32_t voff,
+                                                 const TailQkv& qkv, unsigned char* stg, int m0,
+                                                 int M, int wave, int lane) {
+  constexpr int D = 256;
   const int l32 = lane & 31, g = lane >> 5, crow = lane >> 3, lp = lane & 7;
-  bf16x8 qreg[16];   // lane (l32, g): elements 16 ks + 8 g .. of row l32
-#pragma unroll
-  for (int ks = 0; ks < 16; ++ks) {
-    const int idx = 2 * ks + g;
-    qreg[ks] = *reinterpret_cast<const bf16x8*>(sA + l32 * 512 + (((idx & ~7) | ((idx ^ l32) & 7)) << 4));
-  }
+  bf16x8 qreg[16];
+  tail_operand_load(sA, lane, qreg);
   f32x16 pacc[3];
 #pragma unroll
   for (int j = 0; j < 3; ++j)
@@ -986,10 +996,10 @@ __device__ __forceinline__ void tail_project_qkv(const unsigned char* sA, bf16x8
     for (int r = 0; r < 16; ++r) pacc[j][r] = 0.f;
 #pragma unroll
   for (int b = 0; b < 48; ++b) {
-    bf16x8& wr = (b & 8) ? w2[b & 7] : w1[b & 7];
-    pacc[b % 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr, qreg[b / 3], pacc[b % 3], 0, 0, 0);
+    pacc[b % 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[b & 15], qreg[b / 3], pacc[b % 3], 0, 0, 0);
     if (b + 16 < 48)
-      wr = *reinterpret_cast<const bf16x8*>(qsrc + (size_t)((b + 16) >> 3) * 65536 + (b & 7) * 1024 + voff);
+      wreg[b & 15] = *reinterpret_cast<const bf16x8*>(qsrc + (size_t)((b + 16) >> 4) * 131072 +
+                                                      (b & 15) * 1024 + voff);
   }
   // position of this lane's row (l32) in the feature-major copy of v
   const int mrow = m0 + l32;
@@ -1003,16 +1013,13 @@ __device__ __forceinline__ void tail_project_qkv(const unsigned char* sA, bf16x8
     const int n0 = wave * 96 + j * 32;   // 32 columns, all q, all k or all v
     if (n0 < 2 * D) {
       // through the wavefront's staging area: 8 lanes per row, 4 columns per lane
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<float4*>(stg + l32 * STRIDE + (8 * q + 4 * g) * 4) =
-            make_float4(pacc[j][4 * q], pacc[j][4 * q + 1], pacc[j][4 * q + 2], pacc[j][4 * q + 3]);
+      tail_tile_put(pacc[j], stg, lane);
       const float4 b4 = *reinterpret_cast<const float4*>(qkv.bias + n0 + lp * 4);
       const float sc = n0 < D ? qkv.q_scale : 1.0f;
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         const int row = t * 8 + crow;
-        const float4 a4 = *reinterpret_cast<const float4*>(stg + row * STRIDE + lp * 16);
+        const float4 a4 = *reinterpret_cast<const float4*>(stg + row * kTailStride + lp * 16);
         if (m0 + row < M)
           *reinterpret_cast<uint2*>(qkv.qk + (size_t)(m0 + row) * (3 * D) + n0 + lp * 4) =
               make_uint2(pack_bf16x2((a4.x + b4.x) * sc, (a4.y + b4.y) * sc),
@@ -1036,24 +1043,22 @@ __device__ __forceinline__ void tail_project_qkv(const unsigned char* sA, bf16x8
 
 // LayerNorm and q/k/v projection of the first layer (width 256): the same rows-per-
 // workgroup scheme as layer_tail_kernel, of which this is the last stage on its own.
-// Wp: the 48 weight blocks per wavefront in the packed layout (three groups of 64 KB).
+// Wp: the 48 weight blocks per wavefront in the packed layout (three groups of 128 KB).
 __global__ __launch_bounds__(512) void layer_head_kernel(
     const float* __restrict__ x, const bf16_t* __restrict__ Wp, const float* __restrict__ ln_g,
     const float* __restrict__ ln_b, float eps, TailQkv qkv, const int32_t* __restrict__ m_ptr,
     int m_host) {
-  constexpr int D = 256, BM = 32, NW = 8, STRIDE = 32 * 4 + 16;
+  constexpr int D = 256, BM = 32, NW = 8;
   __shared__ __attribute__((aligned(16))) unsigned char sA[BM * D * 2];
-  __shared__ __attribute__((aligned(16))) unsigned char s_stage[NW * 32 * STRIDE];
+  __shared__ __attribute__((aligned(16))) unsigned char s_stage[NW * 32 * kTailStride];
   __shared__ __attribute__((aligned(16))) float s_red[2][BM][NW];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const unsigned char* const wsrc = reinterpret_cast<const unsigned char*>(Wp) + (size_t)wave * 8192;
+  const unsigned char* const wsrc = reinterpret_cast<const unsigned char*>(Wp) + (size_t)wave * 16384;
   const uint32_t voff = lane * 16;
-  bf16x8 w1[8], w2[8];
+  bf16x8 wreg[16];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) w1[ks] = *reinterpret_cast<const bf16x8*>(wsrc + ks * 1024 + voff);
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) w2[ks] = *reinterpret_cast<const bf16x8*>(wsrc + 65536 + ks * 1024 + voff);
+  for (int i = 0; i < 16; ++i) wreg[i] = *reinterpret_cast<const bf16x8*>(wsrc + i * 1024 + voff);
   const int M = m_ptr ? *m_ptr : m_host;
   const int total = (M + BM - 1) / BM;
   if ((int)blockIdx.x >= total) return;   // surplus workgroup: the grid covers the capacity
@@ -1069,49 +1074,42 @@ __global__ __launch_bounds__(512) void layer_head_kernel(
   tail_rows_stats(v, s_red, wave, lane, eps, mean, rstd);
   tail_rows_to_operand(v, mean, rstd, gain4, offs4, sA, wave, lane);
   __syncthreads();
-  tail_project_qkv(sA, w1, w2, wsrc, voff, qkv, s_stage + wave * (32 * STRIDE), m0, M, wave, lane);
+  tail_project_qkv(sA, wreg, wsrc, voff, qkv, s_stage + wave * (32 * kTailStride), m0, M, wave, lane);
 }
 
 // ---------------------------------------------------------------------------
 // Everything of a layer that follows attention, in one kernel (width 256).
 // ---------------------------------------------------------------------------
 //   x[m, :] += O[m, :] . Wo^T + bo;            a = LayerNorm(x) * g2 + b2
-//   x[m, :] += GELU(a . W1^T + b1) . W2^T + bf;  out[m, :] = LayerNorm(x[m, :]) * g + b
+//   x[m, :] += GELU(a . W1^T + b1) . W2^T + bf;  n = LayerNorm(x[m, :]) * g + b
+//   kLast: out = n (fp32; rows from split_row on to out2); otherwise q, k, v of the next
+//   layer from n (tail_project_qkv), n itself is not written.
 // All of it is local to a row, so a workgroup that owns 32 complete rows can do it
 // without the residual stream, the normalised rows or the hidden activations leaving
-// the CU in between.  Eight wavefronts; wavefront w owns output columns 32 w .. 32 w + 31
-// of both products into x (32x32x16 MFMA, operand O or the hidden chunk).  The hidden
-// width is walked in chunks of 128: for a chunk each wavefront first computes 16 hidden
-// columns (16x16x32 MFMA; one operand is the 32 normalised rows, held in registers, the
-// other its 16 rows of W1), applies bias and GELU and puts them into LDS as bf16; after
-// one barrier every wavefront multiplies the 32 x 128 chunk with its 32 rows of W2.  Two
-// LDS buffers alternate between chunks, so one barrier per chunk is enough: nobody can
-// start writing chunk c+2 before everybody has passed barrier c+1, which every
-// wavefront reaches only after it has read chunk c.
+// the CU in between.  Eight wavefronts; in the output projection and in q/k/v wavefront
+// w owns a 32 (96) column slice of the output.
 //
-// 32 rows per workgroup leave one workgroup per CU, and with four wavefronts (one per
-// SIMD) every LDS read, every GELU and every MFMA would wait for the one before; eight
-// wavefronts put two on each SIMD, so that one's MFMAs run under the other's GELU.
+// The feed-forward block walks the hidden width in chunks of 128 with a split of
+// roles: wavefronts 0-3 produce the hidden chunk (each 32 hidden columns: 16 MFMAs
+// against the normalised rows it holds in registers, then bias, GELU, bf16, into LDS),
+// wavefronts 4-7 consume it (each 64 output columns: 16 MFMAs with the chunk from LDS as
+// operand).  Every SIMD holds one wavefront of each kind, and while the consumers work
+// on chunk c the producers are already at chunk c + 1, so that one kind's MFMAs run
+// under the other's GELU arithmetic instead of all eight wavefronts doing the same thing
+// at the same time.  Two LDS buffers alternate between chunks and one barrier per chunk
+// orders them: the producers pass barrier c after writing chunk c, the consumers before
+// reading it; chunk c + 2 lands in the buffer of chunk c only after barrier c + 1, which
+// a consumer reaches when it is done with chunk c.
 //
 // No wavefront shares a weight with another, so the weights do not pass through LDS at
 // all: they are packed beforehand (layer_tail_pack_kernel) so that a plain 16-byte load
 // per lane delivers an MFMA operand, 1 KB contiguous per instruction, and every operand
 // register is reloaded for the next chunk right after the MFMA that used it: 16 KB of
-// weights per wavefront are in flight at any time.  Per 32 rows a workgroup streams Wo,
-// W1 and W2 once (1.1 MB for F = 1024); with every CU doing so at once, the L2 cache's
-// bandwidth is the bound of this kernel.  LDS carries only the normalised rows and the
-// hidden chunk.
+// weights per wavefront are in flight at any time.  LDS carries only the normalised rows
+// and the hidden chunk.
 //
 // The sums run over K in ascending order like the separate kernels', so a row's result
 // does not depend on the batch it is in.
-//
-// Unless the layer is the last one (kLast: out = the final LayerNorm in fp32, rows from
-// split_row on to out2), the kernel goes on with the next layer's query/key/value
-// projection of the normalised rows, which otherwise would be the next kernel: q
-// (multiplied by q_scale) and k go to qk [M, 3 * 256] in bf16, v feature-major to vt
-// (position pcu[f] + m - cu[f] of its frame f), as the stand-alone projection writes
-// them; wavefront w owns columns 96 w .. 96 w + 95.  The normalised rows themselves are
-// then not written at all.
 template <bool kLast>
 __global__ __launch_bounds__(512) void layer_tail_kernel(
     const bf16_t* __restrict__ O, const bf16_t* __restrict__ Wp, const float* __restrict__ bo,
@@ -1122,32 +1120,27 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
     const int32_t* __restrict__ m_ptr, int m_host) {
   constexpr int D = 256, BM = 32, FC = 128, NW = 8, WTN = 32;
   constexpr int kMaxF = 2048;
-  constexpr int STRIDE = WTN * 4 + 16;   // bytes of a staging row
   __shared__ __attribute__((aligned(16))) unsigned char sA[BM * D * 2];
   __shared__ __attribute__((aligned(16))) unsigned char sH0[BM * FC * 2], sH1[BM * FC * 2];
-  __shared__ __attribute__((aligned(16))) unsigned char s_stage[NW * 32 * STRIDE];
+  __shared__ __attribute__((aligned(16))) unsigned char s_stage[NW * 32 * kTailStride];
   __shared__ __attribute__((aligned(16))) float s_b1[kMaxF];
   __shared__ __attribute__((aligned(16))) float s_red[2][BM][NW];   // [pass][row][wavefront]
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
-  const int l32 = lane & 31, g = lane >> 5;     // 32x32x16 operands: row, k half
-  const int l16 = lane & 15, kg = lane >> 4;    // 16x16x32 operands: row, k quarter
+  const int l32 = lane & 31, g = lane >> 5;     // MFMA operands: row, k half
   const int nchunk = F / FC;
   CFDETR_TLX(0);
 
-  // weight operands of chunk c (0: output projection): 16 blocks of 1 KB per wavefront;
-  // a wave-uniform base and a 32-bit lane offset
-  const unsigned char* const wsrc = reinterpret_cast<const unsigned char*>(Wp) + (size_t)wave * 8192;
+  // weight operands: group c (0: output projection, 1..: hidden chunks, then q/k/v), 16
+  // blocks of 1 KB per wavefront; a wave-uniform base and a 32-bit lane offset
+  const unsigned char* const wsrc = reinterpret_cast<const unsigned char*>(Wp) + (size_t)wave * 16384;
   const uint32_t voff = lane * 16;
-#define CFDETR_TAIL_W(c_, part_, ks_)                                                         \
-  (*reinterpret_cast<const bf16x8*>(wsrc + (size_t)(2 * (c_) + (part_)) * (NW * 8192) +      \
-                                    (ks_) * 1024 + voff))
-  bf16x8 w1[8], w2[8];
+#define CFDETR_TAIL_W(c_, i_) \
+  (*reinterpret_cast<const bf16x8*>(wsrc + (size_t)(c_) * 131072 + (i_) * 1024 + voff))
+  bf16x8 wreg[16];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) w1[ks] = CFDETR_TAIL_W(0, 0, ks);
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) w2[ks] = CFDETR_TAIL_W(0, 1, ks);
+  for (int i = 0; i < 16; ++i) wreg[i] = CFDETR_TAIL_W(0, i);
 
   const int M = m_ptr ? *m_ptr : m_host;
   const int total = (M + BM - 1) / BM;
@@ -1157,9 +1150,7 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
   const int crow = lane >> 3, lp = lane & 7, cn = wave * WTN + lp * 4;
   float4 v[4];      // the residual rows in that form
   float mean[4], rstd[4];
-  unsigned char* const stg = s_stage + wave * (32 * STRIDE);
-  f32x16 acc;
-  bf16x8 areg[2][8];
+  unsigned char* const stg = s_stage + wave * (32 * kTailStride);
   {
     // ---- attention output times Wo: lane (l32, g) holds elements 16 ks + 8 g .. of row l32
     bf16x8 oreg[16];
@@ -1175,99 +1166,127 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
       xin[t] = *reinterpret_cast<const float4*>(resid + (size_t)min(m0 + t * 8 + crow, M - 1) * D + cn);
     for (int i = tid * 4; i < F; i += 2048)
       *reinterpret_cast<float4*>(s_b1 + i) = *reinterpret_cast<const float4*>(b1 + i);
+    f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1[ks], oreg[ks], acc, 0, 0, 0);
-      w1[ks] = CFDETR_TAIL_W(1, 0, ks);
-    }
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2[ks], oreg[8 + ks], acc, 0, 0, 0);
-      w2[ks] = CFDETR_TAIL_W(1, 1, ks);
+    for (int ks = 0; ks < 16; ++ks) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[ks], oreg[ks], acc, 0, 0, 0);
+      wreg[ks] = CFDETR_TAIL_W(1, ks);
     }
     CFDETR_TLX(1);
-    tail_rows_update(acc, bo4, xin, stg, lane, v);
+    tail_tile_put(acc, stg, lane);
+    tail_rows_take(stg, bo4, xin, lane, v);
     tail_rows_stats(v, s_red, wave, lane, eps, mean, rstd);
     tail_rows_to_operand(v, mean, rstd, gain4, offs4, sA, wave, lane);
     __syncthreads();
-    // as MFMA operand for all 8 k-steps of 32: lane (l16, kg) holds elements
-    // 32 ks + 8 kg .. + 8 of rows l16 and 16 + l16
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
-      const int row = hf * 16 + l16;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const int idx = 4 * ks + kg;
-        areg[hf][ks] = *reinterpret_cast<const bf16x8*>(sA + row * (D * 2) + (((idx & ~7) | ((idx ^ row) & 7)) << 4));
-      }
-    }
   }
   CFDETR_TLX(2);
 
-#pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-
-  for (int c = 0; c < nchunk; ++c) {
-    // the chunk whose weights are fetched while this one is computed (the last chunk of
-    // the last layer fetches itself once more: in bounds, never used)
-    // (with the projection behind it, the last chunk fetches the projection's first blocks)
-    const int cn1 = (kLast ? min(c + 1, nchunk - 1) : c + 1) + 1;
-    unsigned char* const sH = (c & 1) ? sH1 : sH0;
-    CFDETR_TL(0);
-    // ---- 16 hidden columns of this wavefront for both halves of the rows: bias, then
-    // 8 k-steps over the 256 inputs
-    f32x4 hid[2];
-    {
-      const float4 b = *reinterpret_cast<const float4*>(s_b1 + c * FC + wave * 16 + 4 * kg);
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {
-        hid[hf][0] = b.x;
-        hid[hf][1] = b.y;
-        hid[hf][2] = b.z;
-        hid[hf][3] = b.w;
-      }
-    }
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf)
-        hid[hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1[ks], areg[hf][ks], hid[hf], 0, 0, 0);
-      w1[ks] = CFDETR_TAIL_W(cn1, 0, ks);
-    }
-    CFDETR_TL(1);
-    // GELU, bf16, into the chunk buffer: lane = row (per half), 4 consecutive columns
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
-      const int row = hf * 16 + l16;
-      const uint2 pk = make_uint2(pack_bf16x2(gelu_fast(hid[hf][0]), gelu_fast(hid[hf][1])),
-                                  pack_bf16x2(gelu_fast(hid[hf][2]), gelu_fast(hid[hf][3])));
-      *reinterpret_cast<uint2*>(sH + row * (FC * 2) + (((2 * wave + (kg >> 1)) ^ (row & 7)) << 4) +
-                                (kg & 1) * 8) = pk;
-    }
-    CFDETR_TL(2);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    CFDETR_TL(3);
-    // ---- the chunk times this wavefront's 32 rows of W2
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const int hc = 2 * ks + g;     // 16-byte chunk of the hidden row
-      const bf16x8 fa = *reinterpret_cast<const bf16x8*>(sH + l32 * (FC * 2) + ((hc ^ (l32 & 7)) << 4));
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2[ks], fa, acc, 0, 0, 0);
-      w2[ks] = CFDETR_TAIL_W(cn1, 1, ks);
-    }
-    CFDETR_TL(4);
+  if (wave < 4) {
+    // ---- producers: hidden columns 32 wave .. of every chunk.  The MFMAs of chunk c + 1
+    // are issued between the GELU evaluations of chunk c (one MFMA, then one element's
+    // arithmetic): a wavefront issues in order, and sixteen dependent MFMAs in a row would
+    // hold back everything behind them for their whole run time.
+    bf16x8 areg[16];
+    tail_operand_load(sA, lane, areg);
+    f32x16 hid;
+#define CFDETR_TAIL_BIAS(c_)                                                                  \
+  _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                             \
+    const float4 b = *reinterpret_cast<const float4*>(s_b1 + (c_) * FC + wave * 32 + 8 * q + 4 * g); \
+    hid[4 * q] = b.x;                                                                         \
+    hid[4 * q + 1] = b.y;                                                                     \
+    hid[4 * q + 2] = b.z;                                                                     \
+    hid[4 * q + 3] = b.w;                                                                     \
   }
+    CFDETR_TAIL_BIAS(0)
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+      hid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[ks], areg[ks], hid, 0, 0, 0);
+      wreg[ks] = CFDETR_TAIL_W(nchunk > 1 || !kLast ? 2 : 1, ks);
+    }
+    for (int c = 0; c < nchunk; ++c) {
+      // the group whose weights are fetched while chunk c + 1 is computed: chunk c + 2,
+      // behind the last chunk the projection (the last layer fetches a chunk once more:
+      // in bounds, never used)
+      const int cnext = (kLast ? min(c + 2, nchunk - 1) : min(c + 2, nchunk)) + 1;
+      unsigned char* const sH = (c & 1) ? sH1 : sH0;
+      CFDETR_TL(0);
+      const f32x16 cur = hid;
+      float gel[16];
+      if (c + 1 < nchunk) {
+        CFDETR_TAIL_BIAS(c + 1)
+#pragma unroll
+        for (int ks = 0; ks < 16; ++ks) {
+          hid = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[ks], areg[ks], hid, 0, 0, 0);
+          wreg[ks] = CFDETR_TAIL_W(cnext, ks);
+          gel[ks] = gelu_fast(cur[ks]);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+          __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);   // one element's arithmetic
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // the weight load
+        }
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < 16; ++ks) gel[ks] = gelu_fast(cur[ks]);
+      }
+      CFDETR_TL(1);
+      // bf16, into the chunk buffer: lane = row, 4 consecutive columns per store
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint2 pk = make_uint2(pack_bf16x2(gel[4 * q], gel[4 * q + 1]),
+                                    pack_bf16x2(gel[4 * q + 2], gel[4 * q + 3]));
+        *reinterpret_cast<uint2*>(sH + l32 * (FC * 2) + (((wave * 4 + q) ^ (l32 & 7)) << 4) + g * 8) = pk;
+      }
+      CFDETR_TL(2);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __builtin_amdgcn_s_barrier();
+      CFDETR_TL(3);
+    }
+#undef CFDETR_TAIL_BIAS
+  } else {
+    // ---- consumers: output columns 64 (wave - 4) .. as two tiles
+    f32x16 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    for (int c = 0; c < nchunk; ++c) {
+      const int cnext = (kLast ? min(c + 1, nchunk - 1) : c + 1) + 1;
+      const unsigned char* const sH = (c & 1) ? sH1 : sH0;
+      CFDETR_TL(0);
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      CFDETR_TL(1);
+      // the whole chunk as operand first (eight reads in flight), then the MFMAs
+      bf16x8 fa[8];
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const int hc = 2 * ks + g;     // 16-byte chunk of the hidden row
+        fa[ks] = *reinterpret_cast<const bf16x8*>(sH + l32 * (FC * 2) + ((hc ^ (l32 & 7)) << 4));
+      }
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[2 * ks + j], fa[ks], acc[j], 0, 0, 0);
+          wreg[2 * ks + j] = CFDETR_TAIL_W(cnext, 2 * ks + j);
+        }
+      }
+      CFDETR_TL(2);
+    }
+    // the two tiles go to the staging areas of the wavefronts that own their columns in
+    // what follows (32 per wavefront)
+    tail_tile_put(acc[0], s_stage + (2 * (wave - 4)) * (32 * kTailStride), lane);
+    tail_tile_put(acc[1], s_stage + (2 * (wave - 4) + 1) * (32 * kTailStride), lane);
+  }
+  __syncthreads();
   CFDETR_TLX(3);
   // ---- x = x + FFN; the new residual rows go out, and their LayerNorm
   const float4 bf4 = *reinterpret_cast<const float4*>(bf + cn);
   const float4 gain4 = *reinterpret_cast<const float4*>(ln_g + cn);
   const float4 offs4 = *reinterpret_cast<const float4*>(ln_b + cn);
   float4 x2[4];
-  tail_rows_update(acc, bf4, v, stg, lane, x2);
+  tail_rows_take(stg, bf4, v, lane, x2);
 #pragma unroll
   for (int t = 0; t < 4; ++t)
     if (m0 + t * 8 + crow < M)
@@ -1290,12 +1309,11 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
     CFDETR_TLX(4);
     return;
   }
-  // ---- the next layer's q, k, v of these rows (sA is free: every wavefront has taken
-  // its copy of the first operand long ago)
+  // ---- the next layer's q, k, v of these rows (sA is free: the producers have taken
+  // their copy long ago)
   tail_rows_to_operand(x2, mean, rstd, gain4, offs4, sA, wave, lane);
   __syncthreads();
-  tail_project_qkv(sA, w1, w2, wsrc + (size_t)2 * (nchunk + 1) * (NW * 8192), voff, qkv, stg, m0,
-                   M, wave, lane);
+  tail_project_qkv(sA, wreg, wsrc + (size_t)(nchunk + 1) * 131072, voff, qkv, stg, m0, M, wave, lane);
 #undef CFDETR_TAIL_W
   CFDETR_TLX(4);
 }
