@@ -294,6 +294,92 @@ def wcet_table(cfg_id, runs=30):
             "fine_by_level_and_batch_size": fine}
 
 
+def coarse_stage_table(cfg_id, n_queries=300, dec_layers=6, runs=30):
+    """The closed loop of the coarse stage on the device (Sec. III-B, A1 -> A2): coarse
+    encode -> decode -> difficulty test and region proposal -> selection -> fine encode,
+    each call timed alone (mean of `runs`, device time from events on the caller's stream)
+    and the whole loop without the host in between.  The decoder has random weights of the
+    encoder's shape (no trained detector exists here), so which frames come out hard is
+    arbitrary; the region proposal is therefore also timed on the synthetic queries of the
+    input recipe.  The oracle's decode of one frame is timed beside it."""
+    import torch
+    from oracle import cfdetr_oracle as O
+    from paper_2505_23317_amd import cfdetr, synth
+
+    cfg = synth.config(cfg_id)
+    wl = synth.make_workload(cfg_id)
+    dw = synth.make_decoder_weights(cfg, cfg_id, n_queries=n_queries, layers=dec_layers)
+    enc = cfdetr.Encoder(cfg, wl["weights"], act_dtype="bf16")
+    enc.attach_decoder(dw)
+    img = enc.upload_images(wl["images"])
+    out = enc.alloc_outputs(cfg.B)
+    B, Q, n0 = cfg.B, n_queries, cfg.n_cells(0)
+    cu0 = torch.arange(B + 1, dtype=torch.int32, device="cuda") * n0
+    dq = torch.empty((B, Q, 5), dtype=torch.float32, device="cuda")
+    sq = torch.from_numpy(synth.make_queries(cfg, cfg_id, n_queries=Q)).cuda()
+    boxes = torch.zeros((B * Q, 4), dtype=torch.int32, device="cuda")
+    tier = torch.zeros(B * Q, dtype=torch.uint8, device="cuda")
+    offs = torch.zeros(B + 1, dtype=torch.int32, device="cuda")
+    hard = torch.zeros(B, dtype=torch.int32, device="cuda")
+    mean = torch.zeros(B, dtype=torch.float32, device="cuda")
+    params = cfdetr.CfdetrRoiParams(0.8, 0.05, 1.0, 0.0, cfg.n_levels - 1)
+
+    def coarse():
+        enc.coarse_encode(img, B, out["x0_cache"], out["y_coarse"])
+
+    def decode():
+        enc.decode(out["y_coarse"], cu0, B, dq)
+
+    def propose(q=None):
+        enc.propose_rois(dq if q is None else q, params, boxes, tier, offs, hard, mean)
+
+    def fine():
+        enc.select_fine(boxes, tier, offs, B, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
+        enc.fine_encode(img, B, out["tok_desc"], out["cu_seqlens"], out["x0_cache"], out["y_mixed"])
+
+    def loop():
+        coarse()
+        decode()
+        propose()
+        fine()
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(runs):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / runs
+
+    coarse()
+    res = {"workload": f"configs[{cfg_id - 1}] {cfg.name}", "unit": "ms", "queries_per_frame": Q,
+           "decoder_layers": dec_layers,
+           "coarse_encode": timed(coarse), "decode": timed(decode)}
+    res["propose_rois_synthetic_queries"] = timed(lambda: propose(sq))
+    fine()                                   # regions of the synthetic queries
+    enc.sync_status()
+    res["tokens_per_frame_mixed"] = np.diff(out["cu_seqlens"].cpu().numpy()).tolist()
+    res["select_and_fine_encode"] = timed(fine)
+    res["whole_loop_decoded_queries"] = timed(loop)
+    enc.sync_status()
+    res["hard_frames_decoded_queries"] = int(hard.cpu().numpy().sum())
+    res["decode_queries_per_s"] = B * Q / (res["decode"] * 1e-3)
+    # the oracle on one frame
+    yc = out["y_coarse"].cpu().numpy()[:n0]
+    t0 = time.perf_counter()
+    reps = 0
+    while time.perf_counter() - t0 < 5.0:
+        O.decode(yc, np.array([0, n0]), dw, cfg.heads)
+        reps += 1
+    res["cpu_oracle_decode_one_frame_ms"] = 1e3 * (time.perf_counter() - t0) / reps
+    enc.close()
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -308,6 +394,9 @@ def main() -> int:
     ap.add_argument("--wcet-table", action="store_true",
                     help="also measure the execution-time tables the scheduling calls take "
                          "(adds wcet_table to the line)")
+    ap.add_argument("--coarse-stage", action="store_true",
+                    help="also time the closed loop coarse encode -> decode -> region proposal "
+                         "-> selection -> fine encode, call by call")
     ap.add_argument("--no-others", action="store_true",
                     help="skip the short extra measurements of the two largest configs")
     args = ap.parse_args()
@@ -367,6 +456,8 @@ def main() -> int:
                                      for c in sorted({args.config, 3, 4})]
     if args.wcet_table:
         result["wcet_table"] = wcet_table(args.config)
+    if args.coarse_stage:
+        result["coarse_stage"] = coarse_stage_table(args.config)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, m["wl"], args.config)
     print(json.dumps(result))

@@ -333,7 +333,8 @@ typedef struct {
 
 /*
  * Gives the context a decoder: checks the weights and allocates the decoder's work space
- * (freed by cfdetr_destroy).  Once per context; the weights must outlive it.
+ * (freed by cfdetr_destroy).  Once per context; the weights must outlive it and must not
+ * change (re-ordered copies of some matrices are made here, as in cfdetr_create).
  */
 CFDETR_API cfdetr_status cfdetr_decoder_attach(cfdetr_ctx* ctx, const cfdetr_decoder_weights* w);
 

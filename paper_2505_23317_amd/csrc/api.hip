@@ -79,6 +79,10 @@ struct cfdetr_ctx {
   int dcap8 = 0;
   int dgrid = 0;
   int32_t* dqueue = nullptr;  // 8 counters per attention launch (two per layer)
+  void* dtail_packed = nullptr;   // per layer: w_o2, w_ff1, w_ff2, next w_qkv in the fused
+  uint64_t dtail_packed_layer = 0;   // kernel's order (0: no fused kernel for this shape)
+  void* dhead_packed = nullptr;   // w_qkv of the first layer
+  float* dz = nullptr;            // final LayerNorm of the queries in fp32 (fused path)
 
   std::string err;
 
@@ -417,35 +421,83 @@ cfdetr_status decode_impl(cfdetr_ctx* ctx, const float* memory, const int32_t* c
   const char* wo2 = static_cast<const char*>(w.w_o2);
   const char* w1 = static_cast<const char*>(w.w_ff1);
   const char* w2 = static_cast<const char*>(w.w_ff2);
+  // With the fused layer kernels (width 256) a layer is six launches: self-attention,
+  // out-projection + LayerNorm, query projection, key/value projection of the tokens,
+  // cross-attention, and one kernel for the second out-projection, the feed-forward
+  // block, the LayerNorm after it and the next layer's q/k/v projection.
+  const bool fused = ctx->dtail_packed_layer != 0;
   for (int l = 0; l < L; ++l) {
+    const bool last = l + 1 == L;
     // self-attention among the queries of a frame
-    CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->dx, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d,
-                                            ctx->da, true, d, eps, nullptr, Mq, Mq, 0, nullptr, s));
-    CF_LAUNCH(CFDETR_K_QKV,
-              launch_gemm_qkv(ctx->da, wqkv + (size_t)l * 3 * d * d * 2, w.b_qkv + (size_t)l * 3 * d,
-                              d, qs, ctx->dqkv, ctx->dvt, ctx->dvt_ld, ctx->dcu_all, ctx->dpcu, B,
-                              nullptr, Mq, Mq, s));
+    if (fused && l == 0) {
+      CF_LAUNCH(CFDETR_K_QKV,
+                launch_layer_head(ctx->dx, ctx->dhead_packed, w.ln1_g, w.ln1_b, eps, w.b_qkv, qs,
+                                  ctx->dqkv, ctx->dvt, ctx->dvt_ld, ctx->dcu_all, ctx->dpcu, B, d,
+                                  nullptr, Mq, Mq, s));
+    } else if (!fused) {
+      CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->dx, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d,
+                                              ctx->da, true, d, eps, nullptr, Mq, Mq, 0, nullptr, s));
+      CF_LAUNCH(CFDETR_K_QKV,
+                launch_gemm_qkv(ctx->da, wqkv + (size_t)l * 3 * d * d * 2, w.b_qkv + (size_t)l * 3 * d,
+                                d, qs, ctx->dqkv, ctx->dvt, ctx->dvt_ld, ctx->dcu_all, ctx->dpcu, B,
+                                nullptr, Mq, Mq, s));
+    }
     CF_LAUNCH(CFDETR_K_ATTN,
               launch_attention(ctx->dqkv, ctx->dvt, ctx->dvt_ld, ctx->d_o, ctx->dcu_all, ctx->dpcu,
                                d, c.n_heads, ctx->ditems, ctx->dcap8, ctx->dqueue + 16 * l,
                                ctx->dgrid, ctx->block_q, true, nullptr, s));
-    CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->d_o, wo + (size_t)l * d * d * 2, w.b_o + (size_t)l * d,
-                                        d, d, Epilogue::kBiasResidual, nullptr, ctx->dx, true,
-                                        nullptr, Mq, Mq, s));
     // cross-attention: the queries read the tokens of their frame
-    CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->dx, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d,
-                                            ctx->da, true, d, eps, nullptr, Mq, Mq, 0, nullptr, s));
+    if (fused) {
+      CF_LAUNCH(CFDETR_K_OUT,
+                launch_gemm_residual_ln(ctx->d_o, wo + (size_t)l * d * d * 2, w.b_o + (size_t)l * d, d,
+                                        d, ctx->dx, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d,
+                                        eps, ctx->da, true, 0, nullptr, nullptr, Mq, Mq, s));
+    } else {
+      CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->d_o, wo + (size_t)l * d * d * 2, w.b_o + (size_t)l * d,
+                                          d, d, Epilogue::kBiasResidual, nullptr, ctx->dx, true,
+                                          nullptr, Mq, Mq, s));
+      CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->dx, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d,
+                                              ctx->da, true, d, eps, nullptr, Mq, Mq, 0, nullptr, s));
+    }
     CF_LAUNCH(CFDETR_K_QKV, launch_gemm(ctx->da, wq + (size_t)l * d * d * 2, w.b_q + (size_t)l * d, d,
-                                        d, Epilogue::kBias, ctx->dqkv, nullptr, true, nullptr, Mq,
+                                        d, Epilogue::kBias, ctx->dh, nullptr, true, nullptr, Mq,
                                         Mq, s, qs));
     CF_LAUNCH(CFDETR_K_DEC,
               launch_gemm_kv(ctx->a, wkv + (size_t)l * 2 * d * d * 2, w.b_kv + (size_t)l * 2 * d, d,
                              ctx->qkv, ctx->vt, ctx->vt_ld, ctx->cu_all, ctx->pcu, B, ctx->m_all, 0,
                              cap_m, s));
     CF_LAUNCH(CFDETR_K_ATTN,
-              launch_cross_attention(ctx->dqkv, ctx->qkv, ctx->vt, ctx->vt_ld, ctx->d_o,
+              launch_cross_attention(ctx->dh, ctx->qkv, ctx->vt, ctx->vt_ld, ctx->d_o,
                                      ctx->dcu_all, ctx->cu_all, ctx->pcu, d, c.n_heads, ctx->ditems,
                                      ctx->dcap8, ctx->dqueue + 16 * l + 8, ctx->dgrid, s));
+    if (fused) {
+      LayerTailArgs ta{};
+      ta.O = ctx->d_o;
+      ta.packed = static_cast<const char*>(ctx->dtail_packed) + (size_t)l * ctx->dtail_packed_layer;
+      ta.b_o = w.b_o2 + (size_t)l * d;
+      ta.ln2_g = w.ln3_g + (size_t)l * d;
+      ta.ln2_b = w.ln3_b + (size_t)l * d;
+      ta.b_ff1 = w.b_ff1 + (size_t)l * F;
+      ta.b_ff2 = w.b_ff2 + (size_t)l * d;
+      ta.resid = ctx->dx;
+      ta.ln_g = last ? w.lnf_g : w.ln1_g + (size_t)(l + 1) * d;
+      ta.ln_b = last ? w.lnf_b : w.ln1_b + (size_t)(l + 1) * d;
+      ta.eps = eps;
+      ta.last = last;
+      ta.out = ctx->dz;
+      ta.split_row = 0;
+      ta.out2 = nullptr;
+      ta.b_qkv = last ? nullptr : w.b_qkv + (size_t)(l + 1) * 3 * d;
+      ta.q_scale = qs;
+      ta.qk = ctx->dqkv;
+      ta.vt = ctx->dvt;
+      ta.vt_ld = ctx->dvt_ld;
+      ta.cu = ctx->dcu_all;
+      ta.pcu = ctx->dpcu;
+      ta.B = B;
+      CF_LAUNCH(CFDETR_K_FF2, launch_layer_tail(ta, d, F, nullptr, Mq, Mq, s));
+      continue;
+    }
     CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->d_o, wo2 + (size_t)l * d * d * 2, w.b_o2 + (size_t)l * d,
                                         d, d, Epilogue::kBiasResidual, nullptr, ctx->dx, true,
                                         nullptr, Mq, Mq, s));
@@ -460,8 +512,11 @@ cfdetr_status decode_impl(cfdetr_ctx* ctx, const float* memory, const int32_t* c
                                         nullptr, Mq, Mq, s));
   }
   // heads: z = final LayerNorm (bf16); box perceptron hidden rows in dqkv / d_o
-  CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->dx, w.lnf_g, w.lnf_b, ctx->da, true, d, eps, nullptr,
-                                          Mq, Mq, 0, nullptr, s));
+  if (fused)
+    CF_LAUNCH(CFDETR_K_DEC, launch_cast_bf16(ctx->dz, ctx->da, d, ctx->dm_all, Mq, s));
+  else
+    CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->dx, w.lnf_g, w.lnf_b, ctx->da, true, d, eps, nullptr,
+                                            Mq, Mq, 0, nullptr, s));
   CF_LAUNCH(CFDETR_K_DEC, launch_gemm(ctx->da, w.w_box1, w.b_box1, d, d, Epilogue::kBiasRelu,
                                       ctx->dqkv, nullptr, true, nullptr, Mq, Mq, s));
   CF_LAUNCH(CFDETR_K_DEC, launch_gemm(ctx->dqkv, w.w_box2, w.b_box2, d, d, Epilogue::kBiasRelu,
@@ -811,6 +866,10 @@ CFDETR_API cfdetr_status cfdetr_decoder_attach(cfdetr_ctx* ctx, const cfdetr_dec
   const uint64_t o_cu = cv.take((Bm + 1) * 4), o_cua = cv.take((Bm + 1) * 4), o_m = cv.take(4);
   const uint64_t o_pcu = cv.take((Bm + 1) * 4), o_items = cv.take((uint64_t)ctx->dcap8 * 8 * 4);
   const uint64_t o_q = cv.take((uint64_t)w->n_layers * 16 * 4);
+  const bool fused = layer_tail_supported((int)d, (int)F, true) && gemm_residual_ln_supported((int)d, true);
+  const uint64_t tail_bytes = fused ? layer_tail_packed_bytes((int)d, (int)F) : 0;
+  const uint64_t o_tail = cv.take(tail_bytes * w->n_layers);
+  const uint64_t o_head = cv.take(fused ? 3 * d * d * 2 : 0), o_z = cv.take(fused ? Mq * d * 4 : 0);
   hipError_t e = hipMalloc(&ctx->dec_arena, cv.off);
   if (e != hipSuccess) return fail(ctx, CFDETR_ENOMEM, "hipMalloc of the decoder work space");
   char* base = static_cast<char*>(ctx->dec_arena);
@@ -826,17 +885,32 @@ CFDETR_API cfdetr_status cfdetr_decoder_attach(cfdetr_ctx* ctx, const cfdetr_dec
   ctx->dpcu = reinterpret_cast<int32_t*>(base + o_pcu);
   ctx->ditems = reinterpret_cast<int32_t*>(base + o_items);
   ctx->dqueue = reinterpret_cast<int32_t*>(base + o_q);
+  ctx->dtail_packed = base + o_tail;
+  ctx->dhead_packed = base + o_head;
+  ctx->dz = reinterpret_cast<float*>(base + o_z);
   std::vector<int32_t> cu(Bm + 1);
   for (uint64_t b = 0; b <= Bm; ++b) cu[b] = (int32_t)(b * Q);
   e = hipMemcpy(ctx->dcu, cu.data(), cu.size() * 4, hipMemcpyHostToDevice);
   // padding positions of the feature-major V are read (with probability 0): keep them finite
   if (e == hipSuccess) e = hipMemset(ctx->dvt, 0, d * (uint64_t)ctx->dvt_ld * 2);
+  // the weights the fused layer kernels stream, in their order
+  for (int l = 0; l < w->n_layers && e == hipSuccess && fused; ++l)
+    e = launch_layer_tail_pack(
+        static_cast<const char*>(w->w_o2) + (size_t)l * d * d * 2,
+        static_cast<const char*>(w->w_ff1) + (size_t)l * F * d * 2,
+        static_cast<const char*>(w->w_ff2) + (size_t)l * d * F * 2,
+        l + 1 < w->n_layers ? static_cast<const char*>(w->w_qkv) + (size_t)(l + 1) * 3 * d * d * 2
+                            : nullptr,
+        (int)d, (int)F, static_cast<char*>(ctx->dtail_packed) + (size_t)l * tail_bytes, nullptr);
+  if (e == hipSuccess && fused) e = launch_layer_head_pack(w->w_qkv, (int)d, ctx->dhead_packed, nullptr);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     hipFree(ctx->dec_arena);
     ctx->dec_arena = nullptr;
     return fail_hip(ctx, "decoder work space set-up", e);
   }
   ctx->dw = *w;
+  ctx->dtail_packed_layer = tail_bytes;
   ctx->has_dec = true;
   return CFDETR_OK;
 }
