@@ -193,6 +193,40 @@ def propose_rois(queries: np.ndarray, H: int, W: int, tau_hi: float, tau_lo: flo
     return (b, np.full(len(b), tier, dtype=np.uint8), np.asarray(offs, dtype=np.int32), hard, mean)
 
 
+def merge_detections(coarse: np.ndarray, fine: np.ndarray, hard: np.ndarray, tau_hi: float,
+                     tau_fine: float):
+    """Final detections of a batch (Sec. III-B, last step of A2: confident coarse
+    detections are kept, the fine stage's detections replace the uncertain ones).
+
+    coarse, fine [B, Q, 5] = (cx, cy, w, h, c) from the coarse and the fine stage; hard [B]
+    from the difficulty test.  Frame f keeps its coarse queries with c > tau_hi, in query
+    order; a hard frame then adds its fine-stage queries with c > tau_fine, in query
+    order (an easy frame has no fine stage: its ``fine`` rows are ignored).
+    Returns det float32 [B, 2Q, 5] (rows past the count are zero), src uint8 [B, 2Q]
+    (0 = coarse stage, 1 = fine stage, 255 past the count), count int32 [B]."""
+    c32 = np.asarray(coarse, dtype=np.float32)
+    f32 = np.asarray(fine, dtype=np.float32)
+    B, Q = c32.shape[:2]
+    det = np.zeros((B, 2 * Q, 5), dtype=np.float32)
+    src = np.full((B, 2 * Q), 255, dtype=np.uint8)
+    count = np.zeros(B, dtype=np.int32)
+    for f in range(B):
+        n = 0
+        for k in range(Q):
+            if float(c32[f, k, 4]) > tau_hi:
+                det[f, n] = c32[f, k]
+                src[f, n] = 0
+                n += 1
+        if hard[f]:
+            for k in range(Q):
+                if float(f32[f, k, 4]) > tau_fine:
+                    det[f, n] = f32[f, k]
+                    src[f, n] = 1
+                    n += 1
+        count[f] = n
+    return det, src, count
+
+
 def pack_tok_desc(tok: np.ndarray) -> np.ndarray:
     """(level,row,col) -> one int32 per token: level<<28 | row<<14 | col."""
     t = np.asarray(tok, dtype=np.int64)

@@ -113,3 +113,61 @@ def test_batch_is_the_concatenation_of_its_frames():
     # the proposals drive the selection: an easy frame keeps its coarse grid
     tok, cu, counts = O.select_fine(boxes, tier, offs, 5, 96, 128, (32, 16, 8))
     assert counts[3].tolist() == [12, 0, 0]
+
+
+# ------------------------------------------------------------------ merge of the two stages
+def _merge_fixture():
+    path = os.path.join(os.path.dirname(__file__), "golden", "merge_worked_example.txt")
+    coarse, fine, out = [], [], {}
+    for line in open(path):
+        p = line.split()
+        if not p or p[0] == "#":
+            continue
+        if p[0] == "in":
+            (coarse if p[1] == "coarse" else fine).append([float(v) for v in p[2:]])
+        elif p[2] == "count":
+            out.setdefault(int(p[1]), {"count": int(p[3]), "det": []})
+        else:
+            out[int(p[1])]["det"].append((int(p[3]), [float(v) for v in p[4:]]))
+    return np.array(coarse, np.float32), np.array(fine, np.float32), out
+
+
+def test_merge_matches_the_hand_worked_example():
+    coarse, fine, want = _merge_fixture()
+    c = np.stack([coarse, coarse])
+    f = np.stack([fine, fine])
+    det, src, count = O.merge_detections(c, f, np.array([1, 0]), 0.75, 0.25)
+    for frame, w in want.items():
+        assert count[frame] == w["count"]
+        for i, (s, row) in enumerate(w["det"]):
+            assert src[frame, i] == s
+            np.testing.assert_array_equal(det[frame, i], np.array(row, np.float32))
+        assert (src[frame, w["count"]:] == 255).all() and not det[frame, w["count"]:].any()
+
+
+def test_merge_counts_order_and_limits():
+    rng = np.random.default_rng(5)
+    B, Q = 5, 37
+    c = rng.uniform(0, 1, (B, Q, 5)).astype(np.float32)
+    f = rng.uniform(0, 1, (B, Q, 5)).astype(np.float32)
+    hard = np.array([1, 0, 1, 1, 0])
+    det, src, count = O.merge_detections(c, f, hard, 0.8, 0.3)
+    for b in range(B):
+        n_c = int((c[b, :, 4] > np.float32(0.8)).sum())
+        n_f = int((f[b, :, 4] > np.float32(0.3)).sum()) if hard[b] else 0
+        assert count[b] == n_c + n_f                                   # closed form of the count
+        assert (src[b, :n_c] == 0).all() and (src[b, n_c:n_c + n_f] == 1).all()
+        # the kept rows are the stage's rows in query order: confidences form the same sequence
+        np.testing.assert_array_equal(det[b, :n_c, 4], c[b, c[b, :, 4] > np.float32(0.8), 4])
+        if hard[b]:
+            np.testing.assert_array_equal(det[b, n_c:n_c + n_f], f[b, f[b, :, 4] > np.float32(0.3)])
+    # limits: nothing is certain and nothing refined -> empty; everything passes -> both stages whole
+    det, src, count = O.merge_detections(c, f, hard, 1.0, 1.0)
+    assert not count.any() and not det.any() and (src == 255).all()
+    det, src, count = O.merge_detections(c, f, np.ones(B, int), -1.0, -1.0)
+    assert (count == 2 * Q).all()
+    np.testing.assert_array_equal(det[:, :Q], c)
+    np.testing.assert_array_equal(det[:, Q:], f)
+    # an easy frame never shows a fine-stage row, whatever the fine stage holds
+    det, src, count = O.merge_detections(c, np.full_like(f, 0.99), np.zeros(B, int), 0.8, 0.0)
+    assert not (src == 1).any()
