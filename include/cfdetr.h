@@ -216,6 +216,27 @@ CFDETR_API cfdetr_status cfdetr_propose_rois(cfdetr_ctx* ctx, const float* queri
                                   void* hip_stream);
 
 /*
+ * End of A2 (Sec. III-B): the final detections of every frame.  Confident coarse
+ * detections are kept, and in a hard frame the fine stage's detections take the place of
+ * the uncertain ones.  The paper fixes no more than that; this library's reading: frame f
+ * keeps its coarse-stage queries with c > tau_hi, in query order, and, if hard[f] != 0,
+ * then adds its fine-stage queries with c > tau_fine, in query order.  An easy frame has
+ * no fine stage: its rows of `fine` are not read for a decision.
+ *   coarse, fine [B, Q, 5] fp32 (cx, cy, w, h, c), e.g. from cfdetr_decode of y_coarse / y_mixed
+ *   hard   [B] int32, as cfdetr_propose_rois writes it
+ *   det    [B, 2Q, 5] fp32 out: the detections of frame f in rows 0 .. count[f]; the other
+ *          rows are cleared to 0
+ *   src    [B, 2Q] uint8 out: 0 = from the coarse stage, 1 = from the fine stage, 255 past
+ *          the count
+ *   count  [B] int32 out
+ * Values are copied unchanged.  1 <= Q <= 65536; tau_hi and tau_fine must not be NaN.
+ */
+CFDETR_API cfdetr_status cfdetr_merge_detections(cfdetr_ctx* ctx, const float* coarse,
+                                     const float* fine, const int32_t* hard, int32_t B,
+                                     int32_t Q, float tau_hi, float tau_fine, float* det,
+                                     uint8_t* src, int32_t* count, void* hip_stream);
+
+/*
  * A2, selective patch split as integer work only (Sec. III-B, A2).
  *   boxes       [n_boxes, 4] int32 (x0, y0, x1, y1), half-open pixel rectangles;
  *               clipped to the frame; empty ones select nothing

@@ -34,7 +34,7 @@ EXPORTS = [
     "cfdetr_fine_encode", "cfdetr_fine_encode_padded",
     "cfdetr_multilevel_batch", "cfdetr_profile_begin", "cfdetr_profile_end",
     "cfdetr_sched_response_times", "cfdetr_sched_coarse_batch", "cfdetr_sched_fine_batches",
-    "cfdetr_sched_decide", "cfdetr_decoder_attach", "cfdetr_decode",
+    "cfdetr_sched_decide", "cfdetr_decoder_attach", "cfdetr_decode", "cfdetr_merge_detections",
 ]
 POLICIES = {"C": 0, "CF": 1, "[C]F": 2, "C[F]": 3, "[C][F]": 4}
 SCHED_ACTIONS = ["idle", "coarse", "fine"]
@@ -135,6 +135,9 @@ def load_library() -> ctypes.CDLL:
     lib.cfdetr_sched_decide.argtypes = [ctypes.c_int, dbl, i32, ip, i32, ip, ip, dp, dbl, dp, dp,
                                         i32, i32, ip, ip, ip, ip]
     lib.cfdetr_sched_decide.restype = ctypes.c_int
+    lib.cfdetr_merge_detections.argtypes = [vp, vp, vp, vp, i32, i32, ctypes.c_float, ctypes.c_float,
+                                            vp, vp, vp, vp]
+    lib.cfdetr_merge_detections.restype = ctypes.c_int
     lib.cfdetr_decoder_attach.argtypes = [vp, ctypes.POINTER(CfdetrDecoderWeights)]
     lib.cfdetr_decoder_attach.restype = ctypes.c_int
     lib.cfdetr_decode.argtypes = [vp, vp, vp, i32, vp, vp]
@@ -196,6 +199,12 @@ def cfdetr_propose_rois(ctx, queries, B, Q, params: CfdetrRoiParams, max_boxes, 
     _check(load_library().cfdetr_propose_rois(ctx, queries, B, Q, ctypes.byref(params), max_boxes,
                                               boxes, tier, box_offsets, hard, mean_conf, stream),
            ctx)
+
+
+def cfdetr_merge_detections(ctx, coarse, fine, hard, B, Q, tau_hi, tau_fine, det, src, count,
+                            stream=0) -> None:
+    _check(load_library().cfdetr_merge_detections(ctx, coarse, fine, hard, B, Q, tau_hi, tau_fine,
+                                                  det, src, count, stream), ctx)
 
 
 def cfdetr_decoder_attach(ctx, weights: CfdetrDecoderWeights) -> None:
@@ -415,6 +424,14 @@ class Encoder:
         cfdetr_propose_rois(self.ctx, queries.data_ptr(), B, Q, params, int(boxes.shape[0]),
                             boxes.data_ptr(), tier.data_ptr(), box_offsets.data_ptr(),
                             hard.data_ptr(), mean_conf.data_ptr(), self._stream())
+
+    def merge_detections(self, coarse, fine, hard, tau_hi, tau_fine, det, src, count):
+        """coarse, fine: float32 device tensors [B, Q, 5]; det [B, 2Q, 5], src [B, 2Q] uint8 and
+        count [B] int32 are outputs."""
+        B, Q = int(coarse.shape[0]), int(coarse.shape[1])
+        cfdetr_merge_detections(self.ctx, coarse.data_ptr(), fine.data_ptr(), hard.data_ptr(), B, Q,
+                                tau_hi, tau_fine, det.data_ptr(), src.data_ptr(), count.data_ptr(),
+                                self._stream())
 
     def attach_decoder(self, weights: Dict[str, np.ndarray]):
         """weights: float32 numpy arrays named as include/cfdetr.h lists them; uploaded here

@@ -774,6 +774,22 @@ CFDETR_API cfdetr_status cfdetr_propose_rois(cfdetr_ctx* ctx, const float* queri
   return CFDETR_OK;
 }
 
+CFDETR_API cfdetr_status cfdetr_merge_detections(cfdetr_ctx* ctx, const float* coarse,
+                                     const float* fine, const int32_t* hard, int32_t B,
+                                     int32_t Q, float tau_hi, float tau_fine, float* det,
+                                     uint8_t* src, int32_t* count, void* hip_stream) {
+  cfdetr_status st = check_call(ctx, B);
+  if (st != CFDETR_OK) return st;
+  if (!coarse || !fine || !hard || !det || !src || !count)
+    return fail(ctx, CFDETR_EINVAL, "null pointer");
+  if (Q < 1 || Q > 65536) return fail(ctx, CFDETR_EINVAL, "bad query count");
+  if (tau_hi != tau_hi || tau_fine != tau_fine) return fail(ctx, CFDETR_EINVAL, "threshold is not a number");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  CF_LAUNCH(CFDETR_K_ROI, launch_merge_detections(coarse, fine, hard, B, Q, tau_hi, tau_fine, det,
+                                                  src, count, s));
+  return CFDETR_OK;
+}
+
 CFDETR_API cfdetr_status cfdetr_select_fine(cfdetr_ctx* ctx, const int32_t* boxes, const uint8_t* tier,
                                  const int32_t* box_offsets, int32_t B, int32_t* tok_desc,
                                  int32_t* cu_seqlens, int32_t* level_counts, void* hip_stream) {

@@ -31,6 +31,13 @@ hipError_t launch_propose_rois(const float* queries, int B, int Q, int H, int W,
                                int32_t* box_offsets, int32_t* hard, float* mean_conf,
                                int32_t* err_flag, hipStream_t s);
 
+// Final detections per frame: coarse queries with c > tau_hi, then (hard frames) fine-stage
+// queries with c > tau_fine, both in query order, into det [B, 2Q, 5] / src [B, 2Q] (0
+// coarse, 1 fine); rows past count[f] are cleared (0 / 255).
+hipError_t launch_merge_detections(const float* coarse, const float* fine, const int32_t* hard,
+                                   int B, int Q, float tau_hi, float tau_fine, float* det,
+                                   uint8_t* src, int32_t* count, hipStream_t s);
+
 // Padded copy of a token table (the paper's own form of A3: every frame's token set is
 // brought to one length).  Frame f gets rows f*t_pad .. (f+1)*t_pad of tok_pad: its own
 // tokens, then repeats of its last one.  cu_pad[f] = f*t_pad, kv_len[f] = its true

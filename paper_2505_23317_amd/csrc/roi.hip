@@ -138,7 +138,62 @@ __global__ __launch_bounds__(kRoiThreads) void roi_emit_kernel(
   }
 }
 
+// Final detections of frame f (end of A2): its coarse queries with c > tau_hi in query
+// order, then, if the frame is hard, its fine-stage queries with c > tau_fine in query
+// order.  Rows past the count are cleared (det 0, src 255).  Candidate j of 2Q is coarse
+// query j or fine query j - Q; one ordered compaction over all of them.
+__global__ __launch_bounds__(kRoiThreads) void merge_detections_kernel(
+    const float* __restrict__ coarse, const float* __restrict__ fine,
+    const int32_t* __restrict__ hard, int Q, float tau_hi, float tau_fine,
+    float* __restrict__ det, uint8_t* __restrict__ src, int32_t* __restrict__ count) {
+  __shared__ int s_wave[kRoiThreads / 64];
+  const int f = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool is_hard = hard[f] != 0;
+  const float* qc = coarse + (size_t)f * Q * 5;
+  const float* qf = fine + (size_t)f * Q * 5;
+  float* out = det + (size_t)f * 2 * Q * 5;
+  uint8_t* osrc = src + (size_t)f * 2 * Q;
+  int base = 0;
+  for (int j0 = 0; j0 < 2 * Q; j0 += kRoiThreads) {
+    const int j = j0 + tid;
+    const bool from_fine = j >= Q;
+    const float* row = from_fine ? qf + 5 * (size_t)(j - Q) : qc + 5 * (size_t)j;
+    bool take = false;
+    if (j < 2 * Q && (!from_fine || is_hard)) take = row[4] > (from_fine ? tau_fine : tau_hi);
+    const unsigned long long ballot = __ballot(take);
+    if (lane == 0) s_wave[wave] = __popcll(ballot);
+    __syncthreads();
+    int pos = base + __popcll(ballot & ((1ull << lane) - 1ull));
+    int chunk = 0;
+    for (int w = 0; w < kRoiThreads / 64; ++w) {
+      pos += w < wave ? s_wave[w] : 0;
+      chunk += s_wave[w];
+    }
+    if (take) {
+#pragma unroll
+      for (int e = 0; e < 5; ++e) out[5 * (size_t)pos + e] = row[e];
+      osrc[pos] = from_fine ? 1 : 0;
+    }
+    base += chunk;
+    __syncthreads();
+  }
+  if (tid == 0) count[f] = base;
+  for (int j = base + tid; j < 2 * Q; j += kRoiThreads) {
+#pragma unroll
+    for (int e = 0; e < 5; ++e) out[5 * (size_t)j + e] = 0.f;
+    osrc[j] = 255;
+  }
+}
+
 }  // namespace
+
+hipError_t launch_merge_detections(const float* coarse, const float* fine, const int32_t* hard,
+                                   int B, int Q, float tau_hi, float tau_fine, float* det,
+                                   uint8_t* src, int32_t* count, hipStream_t s) {
+  hipLaunchKernelGGL(merge_detections_kernel, dim3(B), dim3(kRoiThreads), 0, s, coarse, fine, hard,
+                     Q, tau_hi, tau_fine, det, src, count);
+  return hipGetLastError();
+}
 
 hipError_t launch_propose_rois(const float* queries, int B, int Q, int H, int W, float tau_hi,
                                float tau_lo, float scale, float min_side, int tier_value,

@@ -203,6 +203,25 @@ def test_coarse_stage_in_a_closed_loop(K):
     assert (np.diff(cu) >= n0).all() and T <= enc.max_tokens
     assert np.isfinite(out["y_mixed"].cpu().numpy()[:T]).all()
     _say(f"[loop] regions {got_offs.tolist()} (oracle {ro.tolist()}) tokens {np.diff(cu).tolist()}")
+    # the fine stage's queries and the merge of the two stages, still on the device
+    fq = torch.empty((cfg.B, Q, 5), dtype=torch.float32, device="cuda")
+    enc.decode(out["y_mixed"], out["cu_seqlens"], cfg.B, fq)
+    det = torch.zeros((cfg.B, 2 * Q, 5), dtype=torch.float32, device="cuda")
+    src = torch.zeros((cfg.B, 2 * Q), dtype=torch.uint8, device="cuda")
+    cnt = torch.zeros(cfg.B, dtype=torch.int32, device="cuda")
+    enc.merge_detections(dq, fq, hard, tau_hi, 0.3, det, src, cnt)
+    enc.sync_status()
+    torch.cuda.synchronize()
+    cnt_h, src_h, det_h = cnt.cpu().numpy(), src.cpu().numpy(), det.cpu().numpy()
+    hard_h, fq_h = hard.cpu().numpy(), fq.cpu().numpy()
+    assert np.isfinite(fq_h).all()
+    for f in range(cfg.B):
+        n = int(cnt_h[f])
+        n_c = int((src_h[f, :n] == 0).sum())
+        # what the merge holds is what the two stages delivered: compare the sets it claims
+        np.testing.assert_array_equal(det_h[f, :n_c], got_q[f][got_q[f][:, 4] > np.float32(tau_hi)])
+        want_f = fq_h[f][fq_h[f][:, 4] > np.float32(0.3)] if hard_h[f] else fq_h[f][:0]
+        np.testing.assert_array_equal(det_h[f, n_c:n], want_f)
     enc.close()
 
 

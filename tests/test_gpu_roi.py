@@ -169,3 +169,80 @@ def test_proposal_feeds_the_selection_on_the_device(K):
     n0 = cfg.n_cells(0)
     assert counts[0].tolist() == [n0, 0, 0] and counts[7].tolist() == [n0, 0, 0]
     enc.close()
+
+
+# ------------------------------------------------------------------ merge of the two stages
+def gpu_merge(K, enc, coarse, fine, hard, tau_hi, tau_fine):
+    import torch
+    B, Q = coarse.shape[:2]
+    dc = torch.from_numpy(np.ascontiguousarray(coarse, dtype=np.float32)).cuda()
+    df = torch.from_numpy(np.ascontiguousarray(fine, dtype=np.float32)).cuda()
+    dh = torch.from_numpy(np.ascontiguousarray(hard, dtype=np.int32)).cuda()
+    det = torch.full((B, 2 * Q, 5), -7.0, dtype=torch.float32, device="cuda")
+    src = torch.full((B, 2 * Q), 9, dtype=torch.uint8, device="cuda")
+    count = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    enc.merge_detections(dc, df, dh, tau_hi, tau_fine, det, src, count)
+    enc.sync_status()
+    torch.cuda.synchronize()
+    return det.cpu().numpy(), src.cpu().numpy(), count.cpu().numpy()
+
+
+@pytest.mark.parametrize("Q", [8, 63, 128, 300, 1000])
+def test_merge_of_the_two_stages_is_bit_exact(K, Q):
+    cfg = synth.replace(synth.config(3), B=6)
+    enc = _ctx(K, cfg)
+    _say(f"[case] merge Q={Q}")
+    coarse = synth.make_queries(cfg, seed=11, n_queries=Q, easy_frames=(2,))
+    fine = synth.make_queries(cfg, seed=12, n_queries=Q)
+    hard = O.propose_rois(coarse, cfg.H, cfg.W, TAU_HI, TAU_LO, 1)[3]
+    for tau_hi, tau_fine in ((TAU_HI, 0.3), (TAU_HI, TAU_LO), (0.0, 0.0), (1.0, 1.0), (-1.0, -1.0)):
+        got = gpu_merge(K, enc, coarse, fine, hard, tau_hi, tau_fine)
+        ref = O.merge_detections(coarse, fine, hard, float(np.float32(tau_hi)),
+                                 float(np.float32(tau_fine)))
+        np.testing.assert_array_equal(got[2], ref[2])
+        np.testing.assert_array_equal(got[1], ref[1])
+        np.testing.assert_array_equal(got[0], ref[0])
+    # thresholds that are exact binary fractions: equality keeps nothing
+    c2 = coarse.copy()
+    c2[:, ::2, 4] = 0.75
+    f2 = fine.copy()
+    f2[:, ::3, 4] = 0.25
+    got = gpu_merge(K, enc, c2, f2, np.ones(cfg.B, np.int32), 0.75, 0.25)
+    ref = O.merge_detections(c2, f2, np.ones(cfg.B, np.int32), 0.75, 0.25)
+    for g, r in zip(got, ref):
+        np.testing.assert_array_equal(g, r)
+    # a single query per frame
+    c1, f1 = coarse[:, :1].copy(), fine[:, :1].copy()
+    c1[:, 0, 4] = [0.9, 0.1, 0.9, 0.1, 0.9, 0.1]
+    f1[:, 0, 4] = [0.9, 0.9, 0.1, 0.1, 0.9, 0.9]
+    h1 = np.array([1, 1, 1, 1, 0, 0], np.int32)
+    got = gpu_merge(K, enc, c1, f1, h1, TAU_HI, 0.3)
+    ref = O.merge_detections(c1, f1, h1, TAU_HI, float(np.float32(0.3)))
+    assert ref[2].tolist() == [2, 1, 1, 0, 1, 0]
+    for g, r in zip(got, ref):
+        np.testing.assert_array_equal(g, r)
+    enc.close()
+
+
+def test_merge_argument_errors(K):
+    import torch
+    cfg = synth.config(2)
+    enc = _ctx(K, cfg)
+    q = torch.zeros((1, 8, 5), dtype=torch.float32, device="cuda")
+    hard = torch.zeros(1, dtype=torch.int32, device="cuda")
+    det = torch.zeros((1, 16, 5), dtype=torch.float32, device="cuda")
+    src = torch.zeros((1, 16), dtype=torch.uint8, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def call(B=1, Q=8, tau=0.8, coarse=q.data_ptr()):
+        K.cfdetr_merge_detections(enc.ctx, coarse, q.data_ptr(), hard.data_ptr(), B, Q, tau, 0.3,
+                                  det.data_ptr(), src.data_ptr(), cnt.data_ptr(), 0)
+
+    call()
+    for kw, status in ((dict(B=0), K.CFDETR_EINVAL), (dict(B=2), K.CFDETR_ECAPACITY),
+                       (dict(Q=0), K.CFDETR_EINVAL), (dict(tau=float("nan")), K.CFDETR_EINVAL),
+                       (dict(coarse=None), K.CFDETR_EINVAL)):
+        with pytest.raises(K.CfdetrError) as e:
+            call(**kw)
+        assert e.value.status == status, kw
+    enc.close()
