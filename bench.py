@@ -295,9 +295,9 @@ def wcet_table(cfg_id, runs=30):
 
 
 def coarse_stage_table(cfg_id, n_queries=300, dec_layers=6, runs=30):
-    """The closed loop of the coarse stage on the device (Sec. III-B, A1 -> A2): coarse
-    encode -> decode -> difficulty test and region proposal -> selection -> fine encode,
-    each call timed alone (mean of `runs`, device time from events on the caller's stream)
+    """The closed loop of the two stages on the device (Sec. III-B, A1 -> A2): coarse
+    encode -> decode -> difficulty test and region proposal -> selection -> fine encode ->
+    decode -> merge, each call timed alone (mean of `runs`, device time from events on the caller's stream)
     and the whole loop without the host in between.  The decoder has random weights of the
     encoder's shape (no trained detector exists here), so which frames come out hard is
     arbitrary; the region proposal is therefore also timed on the synthetic queries of the
@@ -323,6 +323,10 @@ def coarse_stage_table(cfg_id, n_queries=300, dec_layers=6, runs=30):
     hard = torch.zeros(B, dtype=torch.int32, device="cuda")
     mean = torch.zeros(B, dtype=torch.float32, device="cuda")
     params = cfdetr.CfdetrRoiParams(0.8, 0.05, 1.0, 0.0, cfg.n_levels - 1)
+    fq = torch.empty((B, Q, 5), dtype=torch.float32, device="cuda")
+    det = torch.empty((B, 2 * Q, 5), dtype=torch.float32, device="cuda")
+    src = torch.empty((B, 2 * Q), dtype=torch.uint8, device="cuda")
+    cnt = torch.empty(B, dtype=torch.int32, device="cuda")
 
     def coarse():
         enc.coarse_encode(img, B, out["x0_cache"], out["y_coarse"])
@@ -337,11 +341,19 @@ def coarse_stage_table(cfg_id, n_queries=300, dec_layers=6, runs=30):
         enc.select_fine(boxes, tier, offs, B, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
         enc.fine_encode(img, B, out["tok_desc"], out["cu_seqlens"], out["x0_cache"], out["y_mixed"])
 
+    def decode_fine():
+        enc.decode(out["y_mixed"], out["cu_seqlens"], B, fq)
+
+    def merge():
+        enc.merge_detections(dq, fq, hard, 0.8, 0.3, det, src, cnt)
+
     def loop():
         coarse()
         decode()
         propose()
         fine()
+        decode_fine()
+        merge()
 
     def timed(fn):
         for _ in range(3):
@@ -364,6 +376,8 @@ def coarse_stage_table(cfg_id, n_queries=300, dec_layers=6, runs=30):
     enc.sync_status()
     res["tokens_per_frame_mixed"] = np.diff(out["cu_seqlens"].cpu().numpy()).tolist()
     res["select_and_fine_encode"] = timed(fine)
+    res["decode_fine_stage"] = timed(decode_fine)
+    res["merge_detections"] = timed(merge)
     res["whole_loop_decoded_queries"] = timed(loop)
     enc.sync_status()
     res["hard_frames_decoded_queries"] = int(hard.cpu().numpy().sum())
