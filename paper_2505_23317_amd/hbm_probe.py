@@ -129,6 +129,48 @@ def report(fetch_csv: str, write_csv: str, cfg_id: int) -> None:
         print(f"{fam} {len(f)} {kf * sum(f) / len(f):.0f} {kw * sum(w) / len(w):.0f}")
 
 
+def counters(csvs, cfg_id: int, names) -> None:
+    """Per-launch averages of every counter in rocprofv3 counter files of `run`, by kernel
+    family (same families as `report`), plus each counter as a fraction of GRBM_GUI_ACTIVE
+    times the number of SIMDs where that is a meaningful ratio."""
+    print(f"# Shader counters per launch, cfdetr_multilevel_batch, config {cfg_id}")
+    print("# command, from the repository root on the MI355X box (OUT = any scratch folder):")
+    print(f"#   rocprofv3 --pmc {' '.join(names)} --kernel-trace --output-format csv -d OUT -o t "
+          f"-- python3 -m paper_2505_23317_amd.hbm_probe run --config {cfg_id}")
+    print(f"#   python3 -m paper_2505_23317_amd.hbm_probe counters OUT/t_counter_collection.csv "
+          f"--config {cfg_id}")
+    print("# values are sums over the chip (SQ counters: over its 1024 SIMDs = 256 CUs x 4;")
+    print("# GRBM_GUI_ACTIVE: over its 8 XCDs), averaged over the launches of a family.")
+    print("# 'per SIMD-cycle' divides by the SIMD-cycles the kernel had: GRBM_GUI_ACTIVE / 8 x 1024.")
+    print("# For SQ_VALU_MFMA_BUSY_CYCLES that is the share of time the matrix unit was busy (it")
+    print("# equals SQ_INSTS_MFMA x 32 cycles for 32x32x16 bf16); for SQ_ACTIVE_INST_* the share of")
+    print("# time an instruction of that kind was executing; SQ_ACTIVE_INST_* and SQ_WAIT_* count in")
+    print("# units of 4 cycles (SQ_ACTIVE_INST_VALU / SQ_INSTS_VALU = 1.2-1.3 is the mix of 4- and")
+    print("# 16-cycle instructions), so their shares are printed times 4.")
+    tot = collections.defaultdict(lambda: collections.defaultdict(float))
+    cnt = collections.defaultdict(lambda: collections.defaultdict(int))
+    for path in csvs:
+        with open(path) as f:
+            for r in csv.DictReader(f):
+                for fam, pat in FAMILIES:
+                    if re.search(pat, r["Kernel_Name"]):
+                        tot[fam][r["Counter_Name"]] += float(r["Counter_Value"])
+                        cnt[fam][r["Counter_Name"]] += 1
+                        break
+    for fam, _ in FAMILIES:
+        if fam not in tot:
+            continue
+        avg = {c: tot[fam][c] / cnt[fam][c] for c in tot[fam]}
+        active = avg.get("GRBM_GUI_ACTIVE", 0.0)
+        print(f"{fam} ({max(cnt[fam].values())} launches)")
+        for c in sorted(avg):
+            line = f"   {c:30s} {avg[c]:16.0f}"
+            if active > 0 and c != "GRBM_GUI_ACTIVE":
+                quad = 4.0 if c.startswith("SQ_ACTIVE_INST") or c.startswith("SQ_WAIT") else 1.0
+                line += f"   {quad * avg[c] / (active * 128):8.3f} per SIMD-cycle"
+            print(line)
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -138,7 +180,17 @@ def main() -> None:
     p.add_argument("fetch_csv")
     p.add_argument("write_csv")
     p.add_argument("--config", type=int, default=3)
+    c = sub.add_parser("counters")
+    c.add_argument("csv", nargs="+")
+    c.add_argument("--config", type=int, default=3)
+    c.add_argument("--names", nargs="*", default=["GRBM_GUI_ACTIVE", "SQ_VALU_MFMA_BUSY_CYCLES",
+                                                  "SQ_ACTIVE_INST_VALU", "SQ_ACTIVE_INST_LDS",
+                                                  "SQ_ACTIVE_INST_VMEM", "SQ_INSTS_MFMA",
+                                                  "SQ_INSTS_VALU", "SQ_WAIT_INST_ANY"])
     a = ap.parse_args()
+    if a.cmd == "counters":
+        counters(a.csv, a.config, a.names)
+        return
     if a.cmd == "run":
         run(a.config)
     else:
