@@ -45,7 +45,7 @@ struct cfdetr_ctx {
   uint8_t* hit[2] = {};   // selection flags; the two arrays alternate between calls
   int hit_bytes = 0;
   int parity = 0;
-  int32_t* items = nullptr;   // attention work items, 8 * cap8 entries
+  int32_t* items = nullptr;   // attention work items, 8 * cap8 entries of four words
   int cap8 = 0;               // entries per queue (one queue per XCD)
   int32_t* queue_heads = nullptr;   // 8 fetch counters per layer, set by the plan kernel
   int attn_grid = 0;                // workgroups of an attention launch
@@ -254,8 +254,7 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
                                           Epilogue::kBias, ctx->qkv, nullptr, bf, m_ptr, 0, m_cap,
                                           s));
     CF_LAUNCH(CFDETR_K_ATTN,
-              launch_attention(ctx->qkv, ctx->vt, ctx->vt_ld, ctx->o, cu_all, ctx->pcu, d,
-                               c.n_heads, ctx->items, ctx->cap8, ctx->queue_heads + 8 * l,
+              launch_attention(ctx->qkv, ctx->vt, ctx->vt_ld, ctx->o, d, c.n_heads, ctx->items, ctx->cap8, ctx->queue_heads + 8 * l,
                                ctx->attn_grid, ctx->block_q, bf, kv_len, s));
     if (fused_tail) {
       // out-projection, LayerNorm, feed-forward block and the LayerNorm after it (the next
@@ -443,8 +442,7 @@ cfdetr_status decode_impl(cfdetr_ctx* ctx, const float* memory, const int32_t* c
                                 nullptr, Mq, Mq, s));
     }
     CF_LAUNCH(CFDETR_K_ATTN,
-              launch_attention(ctx->dqkv, ctx->dvt, ctx->dvt_ld, ctx->d_o, ctx->dcu_all, ctx->dpcu,
-                               d, c.n_heads, ctx->ditems, ctx->dcap8, ctx->dqueue + 16 * l,
+              launch_attention(ctx->dqkv, ctx->dvt, ctx->dvt_ld, ctx->d_o, d, c.n_heads, ctx->ditems, ctx->dcap8, ctx->dqueue + 16 * l,
                                ctx->dgrid, ctx->block_q, true, nullptr, s));
     // cross-attention: the queries read the tokens of their frame
     if (fused) {
@@ -468,7 +466,7 @@ cfdetr_status decode_impl(cfdetr_ctx* ctx, const float* memory, const int32_t* c
                              cap_m, s));
     CF_LAUNCH(CFDETR_K_ATTN,
               launch_cross_attention(ctx->dh, ctx->qkv, ctx->vt, ctx->vt_ld, ctx->d_o,
-                                     ctx->dcu_all, ctx->cu_all, ctx->pcu, d, c.n_heads, ctx->ditems,
+                                     ctx->cu_all, ctx->pcu, d, c.n_heads, ctx->ditems,
                                      ctx->dcap8, ctx->dqueue + 16 * l + 8, ctx->dgrid, s));
     if (fused) {
       LayerTailArgs ta{};
@@ -624,7 +622,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   const uint64_t hit_bytes = Bm * (uint64_t)(c->nonfinest > 0 ? c->nonfinest : 1);
   const uint64_t o_hit0 = cv.take(hit_bytes), o_hit1 = cv.take(hit_bytes);
   c->hit_bytes = (int)hit_bytes;
-  const uint64_t o_items = cv.take((uint64_t)c->cap8 * 8 * 4), o_err = cv.take(4);
+  const uint64_t o_items = cv.take((uint64_t)c->cap8 * 8 * 16), o_err = cv.take(4);
   const uint64_t o_qh = cv.take((uint64_t)cfg->n_layers * 8 * 4);
   const uint64_t o_nroi = cv.take((uint64_t)kMaxBatch * 4);
   const uint64_t o_tpad = cv.take((uint64_t)cfg->max_tokens_total * 4);
@@ -880,7 +878,7 @@ CFDETR_API cfdetr_status cfdetr_decoder_attach(cfdetr_ctx* ctx, const cfdetr_dec
   const uint64_t o_o = cv.take(Mq * d * 2), o_h = cv.take(Mq * std::max(F, d) * 2);
   const uint64_t o_vt = cv.take(d * (uint64_t)ctx->dvt_ld * 2);
   const uint64_t o_cu = cv.take((Bm + 1) * 4), o_cua = cv.take((Bm + 1) * 4), o_m = cv.take(4);
-  const uint64_t o_pcu = cv.take((Bm + 1) * 4), o_items = cv.take((uint64_t)ctx->dcap8 * 8 * 4);
+  const uint64_t o_pcu = cv.take((Bm + 1) * 4), o_items = cv.take((uint64_t)ctx->dcap8 * 8 * 16);
   const uint64_t o_q = cv.take((uint64_t)w->n_layers * 16 * 4);
   const bool fused = layer_tail_supported((int)d, (int)F, true) && gemm_residual_ln_supported((int)d, true);
   const uint64_t tail_bytes = fused ? layer_tail_packed_bytes((int)d, (int)F) : 0;

@@ -44,6 +44,12 @@
 // The fp32 kernel (check mode) is the same online softmax with one query per thread.
 #include "kernels.h"
 
+// Phase time stamps of attention_bf16_kernel for a development harness that defines
+// this macro before including the file; nothing otherwise.
+#ifndef CFDETR_ATL
+#define CFDETR_ATL(i_)
+#endif
+
 namespace cfdetr {
 
 namespace {
@@ -91,9 +97,9 @@ template <int DH>
 __global__ __launch_bounds__(256) void attention_bf16_kernel(
     const bf16_t* __restrict__ qbuf, int q_ld, const bf16_t* __restrict__ kbuf, int k_ld,
     const bf16_t* __restrict__ vt, int vt_ld, bf16_t* __restrict__ out,
-    const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_k,
-    const int32_t* __restrict__ pcu, int d, const int32_t* __restrict__ items, int cap8,
-    int32_t* __restrict__ queue_heads, const int32_t* __restrict__ kv_len) {
+    const int32_t* __restrict__ cu_k, const int32_t* __restrict__ pcu_k, int d,
+    const int4* __restrict__ items, int cap8, int32_t* __restrict__ queue_heads,
+    const int32_t* __restrict__ kv_len) {
   constexpr int BQ = 128;
   constexpr int KS = DH / 16;          // k-steps of Q.K^T
   constexpr int MO = DH / 32;          // 32-row blocks of O^T
@@ -114,7 +120,12 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int home = blockIdx.x & 7;   // queue of this workgroup; w mod 8 is also its XCD
-  bool first = true;
+  // first item: entry blockIdx/8 of the home queue; later ones through the counter, which
+  // starts behind the entries handed out this way
+  int entry = blockIdx.x >> 3;
+  CFDETR_ATL(0);
+  // -1: the queue holds no more entries than were handed out by index (launch_plan)
+  const bool drained = queue_heads[home] < 0;
 
   // Loader roles.  K: LDS row rho <- key (rho & 32) | swap23(rho & 31), chunk swizzled.
   int k_key[KI];
@@ -127,24 +138,22 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
   }
 
   for (;;) {
-    // every wavefront is done with the previous item's tiles and with s_item
-    __syncthreads();
-    if (tid == 0) {
-      // first item: entry blockIdx/8 of the home queue; later ones through the counter,
-      // which starts behind the entries handed out this way
-      const int j = first ? (int)(blockIdx.x >> 3) : atomicAdd(&queue_heads[home], 1);
-      s_item = j < cap8 ? items[home + 8 * j] : -1;
-    }
-    first = false;
-    __syncthreads();
-    const int32_t item = s_item;
+    // An entry is four words: the item, then offset, length and padded offset of its
+    // sequence; the index is uniform, so this is one scalar load and a workgroup needs
+    // nothing else before it can ask for its queries and first keys.
+    if (entry >= cap8) break;
+    const int4 rec = items[home + 8 * entry];
+    const int32_t item = rec.x;
     if (item < 0) break;   // entries are in use from the front: the queue is empty
+    CFDETR_ATL(1);
 
     const int frame = item >> 24, head = (item >> 19) & 31, qt = item & 0x7FFFF;
-    const int seq0 = cu[frame], T = cu[frame + 1] - seq0;
-    // the keys come from sequence `frame` of cu_k (the same sequence for self-attention),
-    // all of them unless the caller padded it
-    const int kseq0 = cu_k[frame], TKall = cu_k[frame + 1] - kseq0;
+    const int seq0 = rec.y, T = rec.z;
+    // the keys come from sequence `frame` of cu_k (cross-attention) or are the queries' own
+    // sequence, all of them unless the caller padded it
+    const int kseq0 = cu_k ? cu_k[frame] : seq0;
+    const int TKall = cu_k ? cu_k[frame + 1] - kseq0 : T;
+    const int kpad0 = cu_k ? pcu_k[frame] : rec.w;
     const int TK = kv_len ? min(kv_len[frame], TKall) : TKall;
     const bf16_t* qbase = qbuf + (size_t)seq0 * q_ld + head * DH;
     const bf16_t* kbase = kbuf + (size_t)kseq0 * k_ld + head * DH;
@@ -163,7 +172,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     for (int j = 0; j < VI; ++j) {
       const int rho = (wave * VI + j) * 8 + (lane >> 3);
       const int chunk = (lane & 7) ^ swz<128>(rho);
-      v_src[j] = vt + (size_t)(head * DH + rho) * vt_ld + pcu[frame] + chunk * 8;
+      v_src[j] = vt + (size_t)(head * DH + rho) * vt_ld + kpad0 + chunk * 8;
     }
 
 #define CFDETR_ATTN_ISSUE(kv0_, buf_)                                                        \
@@ -202,6 +211,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
       // every wavefront's part and retires all reads of the other buffer.
       __builtin_amdgcn_s_waitcnt(0x0F70);
       __syncthreads();
+      if (it == 0) CFDETR_ATL(2);
       if (it + 1 < n_kv) CFDETR_ATTN_ISSUE(kv0 + kBlockKV, b ^ 1);
       const unsigned char* cK = b ? sK1 : sK0;
       const unsigned char* cV = b ? sV1 : sV0;
@@ -278,6 +288,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 #undef CFDETR_ATTN_ISSUE
 #undef CFDETR_ATTN_LOGITS
 
+    CFDETR_ATL(3);
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     const float inv = 1.0f / l_tot;
     const int q_local = qt * BQ + wave * 32 + l32;
@@ -294,21 +305,30 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
           *reinterpret_cast<uint2*>(orow + i * 32 + rq * 8 + g * 4) = w;
         }
     }
+    // the next entry; the barriers also keep the next item's first fill behind every
+    // wavefront's last reads of this one's tiles
+    CFDETR_ATL(4);
+    if (drained) break;
+    __syncthreads();
+    if (tid == 0) s_item = atomicAdd(&queue_heads[home], 1);
+    __syncthreads();
+    entry = __builtin_amdgcn_readfirstlane(s_item);
   }
 }
 
 // fp32 check mode: one query per thread, keys in tiles of 32 through LDS.
 template <int DH>
 __global__ __launch_bounds__(256) void attention_f32_kernel(
-    const float* __restrict__ qkv, float* __restrict__ out, const int32_t* __restrict__ cu, int d,
-    const int32_t* __restrict__ items, float scale, const int32_t* __restrict__ kv_len) {
+    const float* __restrict__ qkv, float* __restrict__ out, int d,
+    const int4* __restrict__ items, float scale, const int32_t* __restrict__ kv_len) {
   constexpr int TILE = 32;
   __shared__ float sK[TILE][DH];
   __shared__ float sV[TILE][DH];
-  const int32_t item = items[blockIdx.x];
+  const int4 rec = items[blockIdx.x];
+  const int32_t item = rec.x;
   if (item < 0) return;
   const int frame = item >> 24, head = (item >> 19) & 31, qt = item & 0x7FFFF;
-  const int seq0 = cu[frame], T = cu[frame + 1] - seq0;
+  const int seq0 = rec.y, T = rec.z;
   const int TK = kv_len ? min(kv_len[frame], T) : T;
   const int ld = 3 * d;
   const float* qbase = qkv + (size_t)seq0 * ld + head * DH;
@@ -400,13 +420,13 @@ int attention_grid(int d_head, bool use_bf16, int cap8) {
   return (int)(all < resident ? all : resident);
 }
 
-hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* out,
-                            const int32_t* cu_seqlens, const int32_t* pcu, int d, int heads,
+hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* out, int d, int heads,
                             const int32_t* items, int cap8, int32_t* queue_heads, int grid_size,
                             int block_q, bool use_bf16, const int32_t* kv_len, hipStream_t s) {
   if (block_q != 128 || grid_size < 8 || grid_size % 8 != 0 || grid_size > 8 * cap8)
     return hipErrorInvalidValue;
   const int dh = d / heads;
+  const int4* recs = reinterpret_cast<const int4*>(items);
   if (use_bf16) {
     const bf16_t* in = static_cast<const bf16_t*>(qkv);
     const bf16_t* v = static_cast<const bf16_t*>(vt);
@@ -415,12 +435,10 @@ hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* ou
     // self-attention: queries and keys are thirds of the same rows
     if (dh == 64)
       hipLaunchKernelGGL(attention_bf16_kernel<64>, grid, dim3(256), 0, s, in, 3 * d, in + d, 3 * d,
-                         v, vt_ld, o, cu_seqlens, cu_seqlens, pcu, d, items, cap8, queue_heads,
-                         kv_len);
+                         v, vt_ld, o, nullptr, nullptr, d, recs, cap8, queue_heads, kv_len);
     else if (dh == 32)
       hipLaunchKernelGGL(attention_bf16_kernel<32>, grid, dim3(256), 0, s, in, 3 * d, in + d, 3 * d,
-                         v, vt_ld, o, cu_seqlens, cu_seqlens, pcu, d, items, cap8, queue_heads,
-                         kv_len);
+                         v, vt_ld, o, nullptr, nullptr, d, recs, cap8, queue_heads, kv_len);
     else
       return hipErrorInvalidValue;
   } else {
@@ -429,11 +447,11 @@ hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* ou
     const float* in = static_cast<const float*>(qkv);
     float* o = static_cast<float*>(out);
     if (dh == 64)
-      hipLaunchKernelGGL(attention_f32_kernel<64>, grid, dim3(block_q), 0, s, in, o, cu_seqlens, d,
-                         items, scale, kv_len);
+      hipLaunchKernelGGL(attention_f32_kernel<64>, grid, dim3(block_q), 0, s, in, o, d, recs, scale,
+                         kv_len);
     else if (dh == 32)
-      hipLaunchKernelGGL(attention_f32_kernel<32>, grid, dim3(block_q), 0, s, in, o, cu_seqlens, d,
-                         items, scale, kv_len);
+      hipLaunchKernelGGL(attention_f32_kernel<32>, grid, dim3(block_q), 0, s, in, o, d, recs, scale,
+                         kv_len);
     else
       return hipErrorInvalidValue;
   }
@@ -441,11 +459,12 @@ hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* ou
 }
 
 hipError_t launch_cross_attention(const void* q, const void* k, const void* vt, int vt_ld,
-                                  void* out, const int32_t* cu_q, const int32_t* cu_k,
+                                  void* out, const int32_t* cu_k,
                                   const int32_t* pcu_k, int d, int heads, const int32_t* items,
                                   int cap8, int32_t* queue_heads, int grid_size, hipStream_t s) {
   if (grid_size < 8 || grid_size % 8 != 0 || grid_size > 8 * cap8) return hipErrorInvalidValue;
   const int dh = d / heads;
+  const int4* recs = reinterpret_cast<const int4*>(items);
   const bf16_t* qb = static_cast<const bf16_t*>(q);
   const bf16_t* kb = static_cast<const bf16_t*>(k);
   const bf16_t* v = static_cast<const bf16_t*>(vt);
@@ -453,10 +472,10 @@ hipError_t launch_cross_attention(const void* q, const void* k, const void* vt, 
   dim3 grid(grid_size);
   if (dh == 64)
     hipLaunchKernelGGL(attention_bf16_kernel<64>, grid, dim3(256), 0, s, qb, d, kb, d, v, vt_ld, o,
-                       cu_q, cu_k, pcu_k, d, items, cap8, queue_heads, nullptr);
+                       cu_k, pcu_k, d, recs, cap8, queue_heads, nullptr);
   else if (dh == 32)
     hipLaunchKernelGGL(attention_bf16_kernel<32>, grid, dim3(256), 0, s, qb, d, kb, d, v, vt_ld, o,
-                       cu_q, cu_k, pcu_k, d, items, cap8, queue_heads, nullptr);
+                       cu_k, pcu_k, d, recs, cap8, queue_heads, nullptr);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

@@ -50,12 +50,15 @@ hipError_t launch_pad_tokens(const int32_t* tok_desc, const int32_t* cu_seqlens,
 // n_prefix sequences of prefix_len tokens (coarse grids of a merged run; may be 0)
 // followed by the B sequences delimited by cu_seqlens.  Writes cu_all[0..nseq] and
 // m_all (offsets and total), pcu[0..nseq] (offsets with every sequence padded to a
-// multiple of 64: the layout of the feature-major copy of V), and items[0..8*cap8):
-// the attention work item of workgroup w (sequence<<24 | head<<19 | query tile, or
-// -1), arranged so that all tiles of one (sequence, head) run on the same XCD.
+// multiple of 64: the layout of the feature-major copy of V), and items[0..8*cap8)
+// entries of four words (so items holds 32*cap8 words): the attention work item of
+// workgroup w (sequence<<24 | head<<19 | query tile, or -1) followed by the offset,
+// length and padded offset of its sequence, arranged so that all tiles of one
+// (sequence, head) run on the same XCD.
 // Also sets queue_heads[0..n_heads_q), the fetch counters of the attention launches
 // that follow (eight per launch), to queue_start = (attention grid) / 8: the entries
-// before that are handed out by workgroup index.
+// before that are handed out by workgroup index; or to -1 for a queue with no entries
+// beyond those.
 // max_total > 0 checks offsets that a caller wrote: a length below 1, or a total above
 // max_total, cuts the lengths to what fits and sets *err_flag.  gate (may be null): if
 // *gate is not 0 the work list comes out empty, so that the attention launches that
@@ -210,21 +213,22 @@ float attention_q_scale(int d_head);
 // third of qkv and expects q pre-multiplied by attention_q_scale; its grid_size
 // (= attention_grid) workgroups serve eight queues (items[x + 8j], j = 0, 1, ... for
 // queue x): workgroup w takes entry w/8 of queue w%8 and then fetches through the
-// counter queue_heads[w%8], which must be grid_size/8 at launch and is used up by it.
+// counter queue_heads[w%8], which must be grid_size/8 at launch and is used up by it
+// (-1: the queue has no further entries and is not asked).
 // The fp32 kernel maps workgroup w to entry w (grid_size = 8*cap8).
 // Softmax over the keys of the same frame only; with kv_len (may be null) only over the
 // first kv_len[i] keys of sequence i, the rest being padding.
-hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* out,
-                            const int32_t* cu_seqlens, const int32_t* pcu, int d, int heads,
+// The sequences' offsets come with the work items (launch_plan).
+hipError_t launch_attention(const void* qkv, const void* vt, int vt_ld, void* out, int d, int heads,
                             const int32_t* items, int cap8, int32_t* queue_heads, int grid_size,
                             int block_q, bool use_bf16, const int32_t* kv_len, hipStream_t s);
 // bf16 attention of query rows over the keys and values of another set of rows (the
 // decoder's cross-attention): q [Mq, d] and k [Mk, d] (head h at columns h*dh, q
 // pre-multiplied by attention_q_scale), v feature-major in vt at the padded offsets pcu_k
-// of the key sequences; sequence i of cu_q attends to sequence i of cu_k.  Work items and
+// of the key sequences; query sequence i attends to sequence i of cu_k.  Work items and
 // counters as for launch_attention, planned over the query sequences.
 hipError_t launch_cross_attention(const void* q, const void* k, const void* vt, int vt_ld,
-                                  void* out, const int32_t* cu_q, const int32_t* cu_k,
+                                  void* out, const int32_t* cu_k,
                                   const int32_t* pcu_k, int d, int heads, const int32_t* items,
                                   int cap8, int32_t* queue_heads, int grid_size, hipStream_t s);
 // Grid of launch_attention on the current device: a multiple of 8, at most 8*cap8;

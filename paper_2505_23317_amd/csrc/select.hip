@@ -168,7 +168,9 @@ __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
 // cu[0..B] delimits.  Outputs:
 //   cu_all[0..nseq]  offsets of all sequences, m_all = their total
 //   pcu[0..nseq]     offsets when every sequence is padded to a multiple of 64
-//   items[0..8*cap8) attention work items, sequence<<24 | head<<19 | query tile, or -1.
+//   items[0..8*cap8) attention work items of four words: sequence<<24 | head<<19 | query
+//                    tile (or -1: no item), then the sequence's offset, length and padded
+//                    offset, so that a workgroup gets all it needs to start in one load.
 // Workgroups are dealt to the 8 XCDs round-robin (workgroup w runs on XCD w % 8), and
 // every XCD has its own L2.  All query tiles of one (sequence, head) read the same
 // keys and values, so a whole group goes to one XCD: groups are ordered longest
@@ -192,9 +194,10 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
   __shared__ int s_order[2 * kMaxBatch];
   __shared__ int s_gstart[2 * kMaxBatch * kMaxHeads];
   __shared__ int s_count[8];
+  __shared__ int s_cu[2 * kMaxBatch], s_pcu[2 * kMaxBatch];
   const int tid = threadIdx.x;
   const int nseq = n_prefix + B;
-  for (int i = tid; i < n_heads_q; i += blockDim.x) queue_heads[i] = queue_start;
+  int4* const items4 = reinterpret_cast<int4*>(items);
   if (tid < nseq) s_len[tid] = tid < n_prefix ? prefix_len : cu[tid - n_prefix + 1] - cu[tid - n_prefix];
   __syncthreads();
   if (max_total > 0) {
@@ -241,6 +244,8 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
     for (int i = 0; i < nseq; ++i) {
       cu_all[i] = pos;
       pcu[i] = ppos;
+      s_cu[i] = pos;
+      s_pcu[i] = ppos;
       pos += s_len[i];
       ppos += (s_len[i] + 63) & ~63;
     }
@@ -254,10 +259,14 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
     const int nt = (s_len[f] + block_q - 1) / block_q;
     const int j0 = s_gstart[G];
     for (int q = 0; q < nt && j0 + q < cap8; ++q)
-      items[8 * (j0 + q) + x] = (f << 24) | (h << 19) | q;
+      items4[8 * (j0 + q) + x] = make_int4((f << 24) | (h << 19) | q, s_cu[f], s_len[f], s_pcu[f]);
   }
   for (int i = tid; i < 8 * cap8; i += blockDim.x)
-    if ((i >> 3) >= s_count[i & 7]) items[i] = -1;
+    if ((i >> 3) >= s_count[i & 7]) items4[i] = make_int4(-1, 0, 0, 0);
+  // fetch counters: behind the entries handed out by workgroup index, or -1 where those
+  // are the whole queue (nothing to fetch: a workgroup need not ask)
+  for (int i = tid; i < n_heads_q; i += blockDim.x)
+    queue_heads[i] = s_count[i & 7] <= queue_start ? -1 : queue_start;
 }
 
 __global__ __launch_bounds__(256) void pad_tokens_kernel(const int32_t* __restrict__ tok_desc,
