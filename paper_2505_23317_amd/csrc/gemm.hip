@@ -365,6 +365,12 @@ __device__ __forceinline__ int lds_row_key(int r) {
   return ROWB == 128 ? ((r >> 1) & 7) : ((r >> 2) & 3);
 }
 
+// Phase time stamps of gemm_bf16_direct_kernel for a development harness that defines this
+// macro before including the file; nothing otherwise.
+#ifndef CFDETR_GTL
+#define CFDETR_GTL(i_)
+#endif
+
 template <int BM, int BN, int NWM, int NWN, int kStages, int BKT, typename AROWS, typename EP>
 __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     AROWS arows, const bf16_t* __restrict__ W, int N, int K, EP ep,
@@ -382,6 +388,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile / wavefront mismatch");
   static_assert(kStages >= 2 && kStages <= 4 && (kStages - 2) * LPW < 64, "ring depth");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_direct[];
+  CFDETR_GTL(0);
 
   const int M = m_ptr ? *m_ptr : m_host;
   const int n_blocks = N / BN;
@@ -461,6 +468,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   for (int s = 0; s < kStages - 1; ++s)
     if (s < nk) CFDETR_ISSUE_SLAB(s * BKT, s);
   int buf = 0;   // ring position of slab `it`
+  CFDETR_GTL(1);
   for (int it = 0; it < nk; ++it) {
     const int ahead = min(kStages - 2, nk - 1 - it);   // later slabs that may stay in flight
     if (kStages == 4 && ahead >= 2)
@@ -470,6 +478,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     else
       __builtin_amdgcn_s_waitcnt(0x0F70);
     __builtin_amdgcn_s_barrier();
+    if (it == 0) CFDETR_GTL(2);
     if (it + kStages - 1 < nk) {
       const int nb = buf == 0 ? kStages - 1 : buf - 1;   // (buf + kStages - 1) % kStages
       CFDETR_ISSUE_SLAB((it + kStages - 1) * BKT, nb);
@@ -499,6 +508,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     }
   }
 #undef CFDETR_ISSUE_SLAB
+  CFDETR_GTL(3);
 
   // Epilogue, one 32-row tile of the wavefront at a time.  With a row per lane a store
   // instruction would touch 32 rows with 16 bytes each; instead the finished values
@@ -545,6 +555,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
           if (mb + row < M) ep.copy16(mb + row, nw0 + cchunk * (16 / ES), d, xin[t]);
         }
       }
+      CFDETR_GTL(4);
       return;
     }
   }
@@ -570,6 +581,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
       }
     }
   }
+  CFDETR_GTL(4);
 }
 
 // Sum over each group of 16 consecutive lanes, delivered to all 16 (quad swaps, then the
@@ -893,10 +905,12 @@ __device__ __forceinline__ void tail_rows_take(const unsigned char* stg, const f
   }
 }
 
-// tail_rows_stats: mean and 1/sigma of the complete 256-wide rows (a row's sum is an
-// 8-lane reduction plus one pass through LDS across the 8 wavefronts).  Mean first, then
-// the variance of the centred values, like the stand-alone kernel.  All 512 threads must
-// call it (two barriers).
+// tail_rows_stats: mean and 1/sigma of the complete 256-wide rows.  Every wavefront has
+// 32 columns of a row (8 lanes x 4): it takes their sum and the sum of squares around
+// their own mean (two 8-lane reductions), the eight pairs meet in LDS, and the row's mean
+// and variance follow from them (the sum of squares around the common mean is the sum of
+// the partial ones plus 32 (mean_w - mean)^2 for each part): as exact as centring on the
+// row's mean first, with one barrier instead of two.  All 512 threads must call it.
 __device__ __forceinline__ void tail_rows_stats(const float4 (&v)[4], float (*s_red)[32][8],
                                                 int wave, int lane, float eps, float (&mean)[4],
                                                 float (&rstd)[4]) {
@@ -904,7 +918,13 @@ __device__ __forceinline__ void tail_rows_stats(const float4 (&v)[4], float (*s_
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const float part = row8_sum((v[t].x + v[t].y) + (v[t].z + v[t].w));
-    if (lp == 0) s_red[0][t * 8 + crow][wave] = part;
+    const float mw = part * (1.0f / 32.0f);
+    const float cx = v[t].x - mw, cy = v[t].y - mw, cz = v[t].z - mw, cw = v[t].w - mw;
+    const float sq = row8_sum(fmaf(cx, cx, cy * cy) + fmaf(cz, cz, cw * cw));
+    if (lp == 0) {
+      s_red[0][t * 8 + crow][wave] = part;
+      s_red[1][t * 8 + crow][wave] = sq;
+    }
   }
   __syncthreads();
 #pragma unroll
@@ -912,19 +932,16 @@ __device__ __forceinline__ void tail_rows_stats(const float4 (&v)[4], float (*s_
     const int row = t * 8 + crow;
     const float4 p0 = *reinterpret_cast<const float4*>(&s_red[0][row][0]);
     const float4 p1 = *reinterpret_cast<const float4*>(&s_red[0][row][4]);
+    const float4 q0 = *reinterpret_cast<const float4*>(&s_red[1][row][0]);
+    const float4 q1 = *reinterpret_cast<const float4*>(&s_red[1][row][4]);
     mean[t] = (((p0.x + p0.y) + (p0.z + p0.w)) + ((p1.x + p1.y) + (p1.z + p1.w))) * (1.0f / 256.0f);
-    const float cx = v[t].x - mean[t], cy = v[t].y - mean[t];
-    const float cz = v[t].z - mean[t], cw = v[t].w - mean[t];
-    const float part = row8_sum(fmaf(cx, cx, cy * cy) + fmaf(cz, cz, cw * cw));
-    if (lp == 0) s_red[1][row][wave] = part;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int row = t * 8 + crow;
-    const float4 p0 = *reinterpret_cast<const float4*>(&s_red[1][row][0]);
-    const float4 p1 = *reinterpret_cast<const float4*>(&s_red[1][row][4]);
-    const float var = (((p0.x + p0.y) + (p0.z + p0.w)) + ((p1.x + p1.y) + (p1.z + p1.w))) * (1.0f / 256.0f);
+    const float m32 = mean[t] * 32.0f;   // a part's sum if it had the row's mean
+    const float d0 = p0.x - m32, d1 = p0.y - m32, d2 = p0.z - m32, d3 = p0.w - m32;
+    const float d4 = p1.x - m32, d5 = p1.y - m32, d6 = p1.z - m32, d7 = p1.w - m32;
+    const float within = ((q0.x + q0.y) + (q0.z + q0.w)) + ((q1.x + q1.y) + (q1.z + q1.w));
+    const float between = (fmaf(d0, d0, d1 * d1) + fmaf(d2, d2, d3 * d3)) +
+                          (fmaf(d4, d4, d5 * d5) + fmaf(d6, d6, d7 * d7));
+    const float var = fmaf(between, 1.0f / 32.0f, within) * (1.0f / 256.0f);
     rstd[t] = rsqrtf(var + eps);
   }
 }
