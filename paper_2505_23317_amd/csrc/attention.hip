@@ -45,9 +45,10 @@
 #include "kernels.h"
 
 // Phase time stamps of attention_bf16_kernel for a development harness that defines
-// this macro before including the file; nothing otherwise.
+// these macros before including the file; nothing otherwise.
 #ifndef CFDETR_ATL
 #define CFDETR_ATL(i_)
+#define CFDETR_ATL_TILES(n_)
 #endif
 
 namespace cfdetr {
@@ -289,6 +290,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 #undef CFDETR_ATTN_LOGITS
 
     CFDETR_ATL(3);
+    CFDETR_ATL_TILES(n_kv);
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     const float inv = 1.0f / l_tot;
     const int q_local = qt * BQ + wave * 32 + l32;
