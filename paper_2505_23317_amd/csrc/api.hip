@@ -78,6 +78,9 @@ struct cfdetr_ctx {
   int32_t* ditems = nullptr;
   int dcap8 = 0;
   int dgrid = 0;
+  void* dmid_packed = nullptr;   // per layer: first out-projection and cross-attention query projection, packed
+  void* dk_all = nullptr;     // keys of the tokens for every decoder layer, [L][max_tokens_total, d]
+  void* dvt_all = nullptr;    // their values, feature-major, [L][d, vt_ld]
   int32_t* dqueue = nullptr;  // 8 counters per attention launch (two per layer)
   void* dtail_packed = nullptr;   // per layer: w_o2, w_ff1, w_ff2, next w_qkv in the fused
   uint64_t dtail_packed_layer = 0;   // kernel's order (0: no fused kernel for this shape)
@@ -413,17 +416,23 @@ cfdetr_status decode_impl(cfdetr_ctx* ctx, const float* memory, const int32_t* c
                         ctx->dcu_all, ctx->dm_all, ctx->dpcu, ctx->dqueue, 16 * L,
                         ctx->dgrid / 8, s, 0, nullptr, ctx->err_flag));
   CF_LAUNCH(CFDETR_K_DEC, launch_broadcast_rows(w.query_embed, ctx->dx, Q, d, B, s));
+  // The tokens' keys and values for the cross-attention of every layer depend on the tokens
+  // and the weights only: one contraction for all layers, ahead of the loop.
+  const size_t k_stride = (size_t)cap_m * d, v_stride = (size_t)d * ctx->vt_ld;
+  CF_LAUNCH(CFDETR_K_DEC,
+            launch_gemm_kv_layers(ctx->a, w.w_kv, w.b_kv, d, L, ctx->dk_all, k_stride, ctx->dvt_all,
+                                  v_stride, ctx->vt_ld, ctx->cu_all, ctx->pcu, B, ctx->m_all, 0,
+                                  cap_m, s));
   const char* wqkv = static_cast<const char*>(w.w_qkv);
   const char* wo = static_cast<const char*>(w.w_o);
   const char* wq = static_cast<const char*>(w.w_q);
-  const char* wkv = static_cast<const char*>(w.w_kv);
   const char* wo2 = static_cast<const char*>(w.w_o2);
   const char* w1 = static_cast<const char*>(w.w_ff1);
   const char* w2 = static_cast<const char*>(w.w_ff2);
-  // With the fused layer kernels (width 256) a layer is six launches: self-attention,
-  // out-projection + LayerNorm, query projection, key/value projection of the tokens,
-  // cross-attention, and one kernel for the second out-projection, the feed-forward
-  // block, the LayerNorm after it and the next layer's q/k/v projection.
+  // With the fused layer kernels (width 256) a layer is four launches: self-attention, one
+  // kernel for its out-projection, the LayerNorm behind it and the query projection,
+  // cross-attention, and one kernel for the second out-projection, the feed-forward block,
+  // the LayerNorm after it and the next layer's q/k/v projection.
   const bool fused = ctx->dtail_packed_layer != 0;
   for (int l = 0; l < L; ++l) {
     const bool last = l + 1 == L;
@@ -446,10 +455,11 @@ cfdetr_status decode_impl(cfdetr_ctx* ctx, const float* memory, const int32_t* c
                                ctx->dgrid, ctx->block_q, true, nullptr, s));
     // cross-attention: the queries read the tokens of their frame
     if (fused) {
+      // first out-projection, LayerNorm and the query projection in one kernel
       CF_LAUNCH(CFDETR_K_OUT,
-                launch_gemm_residual_ln(ctx->d_o, wo + (size_t)l * d * d * 2, w.b_o + (size_t)l * d, d,
-                                        d, ctx->dx, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d,
-                                        eps, ctx->da, true, 0, nullptr, nullptr, Mq, Mq, s));
+                launch_layer_mid(ctx->d_o, static_cast<const char*>(ctx->dmid_packed) + (size_t)l * 2 * d * d * 2,
+                                 w.b_o + (size_t)l * d, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d,
+                                 eps, ctx->dx, w.b_q + (size_t)l * d, qs, ctx->dh, d, nullptr, Mq, Mq, s));
     } else {
       CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->d_o, wo + (size_t)l * d * d * 2, w.b_o + (size_t)l * d,
                                           d, d, Epilogue::kBiasResidual, nullptr, ctx->dx, true,
@@ -457,15 +467,14 @@ cfdetr_status decode_impl(cfdetr_ctx* ctx, const float* memory, const int32_t* c
       CF_LAUNCH(CFDETR_K_LN, launch_layernorm(ctx->dx, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d,
                                               ctx->da, true, d, eps, nullptr, Mq, Mq, 0, nullptr, s));
     }
-    CF_LAUNCH(CFDETR_K_QKV, launch_gemm(ctx->da, wq + (size_t)l * d * d * 2, w.b_q + (size_t)l * d, d,
-                                        d, Epilogue::kBias, ctx->dh, nullptr, true, nullptr, Mq,
-                                        Mq, s, qs));
-    CF_LAUNCH(CFDETR_K_DEC,
-              launch_gemm_kv(ctx->a, wkv + (size_t)l * 2 * d * d * 2, w.b_kv + (size_t)l * 2 * d, d,
-                             ctx->qkv, ctx->vt, ctx->vt_ld, ctx->cu_all, ctx->pcu, B, ctx->m_all, 0,
-                             cap_m, s));
+    if (!fused)
+      CF_LAUNCH(CFDETR_K_QKV, launch_gemm(ctx->da, wq + (size_t)l * d * d * 2, w.b_q + (size_t)l * d, d,
+                                          d, Epilogue::kBias, ctx->dh, nullptr, true, nullptr, Mq,
+                                          Mq, s, qs));
     CF_LAUNCH(CFDETR_K_ATTN,
-              launch_cross_attention(ctx->dh, ctx->qkv, ctx->vt, ctx->vt_ld, ctx->d_o,
+              launch_cross_attention(ctx->dh, static_cast<const bf16_t*>(ctx->dk_all) + l * k_stride,
+                                     static_cast<const bf16_t*>(ctx->dvt_all) + l * v_stride,
+                                     ctx->vt_ld, ctx->d_o,
                                      ctx->cu_all, ctx->pcu, d, c.n_heads, ctx->ditems,
                                      ctx->dcap8, ctx->dqueue + 16 * l + 8, ctx->dgrid, s));
     if (fused) {
@@ -884,6 +893,9 @@ CFDETR_API cfdetr_status cfdetr_decoder_attach(cfdetr_ctx* ctx, const cfdetr_dec
   const uint64_t tail_bytes = fused ? layer_tail_packed_bytes((int)d, (int)F) : 0;
   const uint64_t o_tail = cv.take(tail_bytes * w->n_layers);
   const uint64_t o_head = cv.take(fused ? 3 * d * d * 2 : 0), o_z = cv.take(fused ? Mq * d * 4 : 0);
+  const uint64_t o_mid = cv.take(fused ? 2 * d * d * 2 * w->n_layers : 0);
+  const uint64_t k_bytes = (uint64_t)c.max_tokens_total * d * 2, v_bytes = d * (uint64_t)ctx->vt_ld * 2;
+  const uint64_t o_kall = cv.take(k_bytes * w->n_layers), o_vall = cv.take(v_bytes * w->n_layers);
   hipError_t e = hipMalloc(&ctx->dec_arena, cv.off);
   if (e != hipSuccess) return fail(ctx, CFDETR_ENOMEM, "hipMalloc of the decoder work space");
   char* base = static_cast<char*>(ctx->dec_arena);
@@ -902,11 +914,15 @@ CFDETR_API cfdetr_status cfdetr_decoder_attach(cfdetr_ctx* ctx, const cfdetr_dec
   ctx->dtail_packed = base + o_tail;
   ctx->dhead_packed = base + o_head;
   ctx->dz = reinterpret_cast<float*>(base + o_z);
+  ctx->dmid_packed = base + o_mid;
+  ctx->dk_all = base + o_kall;
+  ctx->dvt_all = base + o_vall;
   std::vector<int32_t> cu(Bm + 1);
   for (uint64_t b = 0; b <= Bm; ++b) cu[b] = (int32_t)(b * Q);
   e = hipMemcpy(ctx->dcu, cu.data(), cu.size() * 4, hipMemcpyHostToDevice);
   // padding positions of the feature-major V are read (with probability 0): keep them finite
   if (e == hipSuccess) e = hipMemset(ctx->dvt, 0, d * (uint64_t)ctx->dvt_ld * 2);
+  if (e == hipSuccess) e = hipMemset(ctx->dvt_all, 0, v_bytes * w->n_layers);
   // the weights the fused layer kernels stream, in their order
   for (int l = 0; l < w->n_layers && e == hipSuccess && fused; ++l)
     e = launch_layer_tail_pack(
@@ -917,6 +933,10 @@ CFDETR_API cfdetr_status cfdetr_decoder_attach(cfdetr_ctx* ctx, const cfdetr_dec
                             : nullptr,
         (int)d, (int)F, static_cast<char*>(ctx->dtail_packed) + (size_t)l * tail_bytes, nullptr);
   if (e == hipSuccess && fused) e = launch_layer_head_pack(w->w_qkv, (int)d, ctx->dhead_packed, nullptr);
+  for (int l = 0; l < w->n_layers && e == hipSuccess && fused; ++l)
+    e = launch_layer_mid_pack(static_cast<const char*>(w->w_o) + (size_t)l * d * d * 2,
+                              static_cast<const char*>(w->w_q) + (size_t)l * d * d * 2, (int)d,
+                              static_cast<char*>(ctx->dmid_packed) + (size_t)l * 2 * d * d * 2, nullptr);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     hipFree(ctx->dec_arena);

@@ -239,6 +239,63 @@ struct EpiQkv {
   }
 };
 
+// Key and value projections of several layers in one contraction (the decoder's cross-
+// attention: the tokens are the same for every layer).  Column n belongs to layer
+// n / (2d); inside a layer the first d columns are keys (token-major, k + layer *
+// k_stride), the others values (feature-major, vt + layer * vt_stride, like EpiQkv).
+struct EpiKvLayers {
+  const float* bias;
+  bf16_t* k;
+  size_t k_stride;
+  int d;
+  bf16_t* vt;
+  size_t vt_stride;
+  int vt_ld;
+  const int32_t* cu;
+  const int32_t* pcu;
+  int B;
+  __device__ __forceinline__ int32_t row_info(int m) const {
+    const int f = frame_of_token(cu, B, m);
+    return pcu[f] + (m - cu[f]);
+  }
+  __device__ __forceinline__ bool row_ok(int32_t) const { return true; }
+  static constexpr bool kExtra = kNoExtra;
+  __device__ __forceinline__ float4 bias4(int n) const {
+    return *reinterpret_cast<const float4*>(bias + n);
+  }
+  __device__ __forceinline__ float4 extra4(int, int, int32_t) const {
+    return make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  __device__ __forceinline__ void store4(int m, int n, const float* v, const float4& b,
+                                         const float4&, int32_t pos) const {
+    const float r0 = v[0] + b.x, r1 = v[1] + b.y, r2 = v[2] + b.z, r3 = v[3] + b.w;
+    const int layer = n / (2 * d), nn = n - layer * 2 * d;
+    if (nn < d) {
+      *reinterpret_cast<uint2*>(k + layer * k_stride + (size_t)m * d + nn) =
+          make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
+    } else {
+      bf16_t* p = vt + layer * vt_stride + (size_t)(nn - d) * vt_ld + pos;
+      p[0] = f32_to_bf16(r0);
+      p[(size_t)vt_ld] = f32_to_bf16(r1);
+      p[(size_t)2 * vt_ld] = f32_to_bf16(r2);
+      p[(size_t)3 * vt_ld] = f32_to_bf16(r3);
+    }
+  }
+  // staged form for the key columns (a wavefront's columns are all keys or all values of
+  // one layer: d is a multiple of its 64 columns)
+  static constexpr int kStageElem = 2;
+  __device__ __forceinline__ bool staged(int n_first) const { return n_first % (2 * d) < d; }
+  __device__ __forceinline__ void stage4(unsigned char* p, int, const float* v,
+                                         const float4& b) const {
+    *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(v[0] + b.x, v[1] + b.y),
+                                              pack_bf16x2(v[2] + b.z, v[3] + b.w));
+  }
+  __device__ __forceinline__ void copy16(int m, int n, const uint4& data, const float4&) const {
+    const int layer = n / (2 * d), nn = n - layer * 2 * d;
+    *reinterpret_cast<uint4*>(k + layer * k_stride + (size_t)m * d + nn) = data;
+  }
+};
+
 struct EpiEmbed {
   const float* bias;
   const float* pe_row;
@@ -869,6 +926,20 @@ __global__ __launch_bounds__(256) void layer_head_pack_kernel(const bf16_t* __re
       Wqkv + (size_t)(w * 96 + (b % 3) * 32 + (lane & 31)) * D + (b / 3) * 16 + (lane >> 5) * 8);
 }
 
+// Two 256 x 256 matrices (an output projection and the projection behind the LayerNorm
+// that follows it) in the layout of group 0 above, 128 KB each, for layer_mid_kernel.
+__global__ __launch_bounds__(256) void layer_mid_pack_kernel(const bf16_t* __restrict__ Wo,
+                                                             const bf16_t* __restrict__ Wq,
+                                                             bf16_t* __restrict__ out) {
+  constexpr int D = 256;
+  const int u = blockIdx.x * blockDim.x + threadIdx.x;   // 16-byte unit of the output
+  if (u >= 2 * D * D / 8) return;
+  const int lane = u & 63, i = (u >> 6) & 15, w = (u >> 10) & 7, c = u >> 13;
+  const bf16_t* src = c == 0 ? Wo : Wq;
+  reinterpret_cast<uint4*>(out)[u] = *reinterpret_cast<const uint4*>(
+      src + (size_t)(32 * w + (lane & 31)) * D + 16 * i + 8 * (lane >> 5));
+}
+
 // Sum over each group of 8 consecutive lanes, delivered to all 8.
 __device__ __forceinline__ float row8_sum(float v) {
   v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
@@ -1092,6 +1163,86 @@ __global__ __launch_bounds__(512) void layer_head_kernel(
   tail_rows_to_operand(v, mean, rstd, gain4, offs4, sA, wave, lane);
   __syncthreads();
   tail_project_qkv(sA, wreg, wsrc, voff, qkv, s_stage + wave * (32 * kTailStride), m0, M, wave, lane);
+}
+
+// Output projection of an attention block, the LayerNorm behind it and a projection of the
+// normalised rows, in one kernel (width 256; the decoder between its two attentions):
+//   x[m, :] += O[m, :] . Wo^T + bo;   q[m, :] = ((LayerNorm(x[m, :]) * g + b) . Wq^T + bq) * q_scale
+// Same scheme as layer_tail_kernel: 32 rows per workgroup, wavefront w owns 32 output
+// columns of either product, weights packed by layer_mid_pack_kernel.
+__global__ __launch_bounds__(512) void layer_mid_kernel(
+    const bf16_t* __restrict__ O, const bf16_t* __restrict__ Wp, const float* __restrict__ bo,
+    const float* __restrict__ ln_g, const float* __restrict__ ln_b, float eps,
+    float* __restrict__ resid, const float* __restrict__ bq, float q_scale,
+    bf16_t* __restrict__ q_out, const int32_t* __restrict__ m_ptr, int m_host) {
+  constexpr int D = 256, BM = 32, NW = 8;
+  __shared__ __attribute__((aligned(16))) unsigned char sA[BM * D * 2];
+  __shared__ __attribute__((aligned(16))) unsigned char s_stage[NW * 32 * kTailStride];
+  __shared__ __attribute__((aligned(16))) float s_red[2][BM][NW];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, g = lane >> 5;
+  const unsigned char* const wsrc = reinterpret_cast<const unsigned char*>(Wp) + (size_t)wave * 16384;
+  const uint32_t voff = lane * 16;
+  bf16x8 wreg[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) wreg[i] = *reinterpret_cast<const bf16x8*>(wsrc + i * 1024 + voff);
+  const int M = m_ptr ? *m_ptr : m_host;
+  const int total = (M + BM - 1) / BM;
+  if ((int)blockIdx.x >= total) return;   // surplus workgroup: the grid covers the capacity
+  const int m0 = xcd_tile_order(blockIdx.x, total) * BM;
+  const int crow = lane >> 3, lp = lane & 7, cn = wave * 32 + lp * 4;
+  unsigned char* const stg = s_stage + wave * (32 * kTailStride);
+  bf16x8 oreg[16];
+  const bf16_t* orow = O + (size_t)min(m0 + l32, M - 1) * D + g * 8;
+#pragma unroll
+  for (int ks = 0; ks < 16; ++ks) oreg[ks] = *reinterpret_cast<const bf16x8*>(orow + ks * 16);
+  const float4 bo4 = *reinterpret_cast<const float4*>(bo + cn);
+  const float4 gain4 = *reinterpret_cast<const float4*>(ln_g + cn);
+  const float4 offs4 = *reinterpret_cast<const float4*>(ln_b + cn);
+  const float4 bq4 = *reinterpret_cast<const float4*>(bq + cn);
+  float4 xin[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+    xin[t] = *reinterpret_cast<const float4*>(resid + (size_t)min(m0 + t * 8 + crow, M - 1) * D + cn);
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 16; ++ks) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[ks], oreg[ks], acc, 0, 0, 0);
+    wreg[ks] = *reinterpret_cast<const bf16x8*>(wsrc + 131072 + ks * 1024 + voff);   // Wq
+  }
+  float4 v[4];
+  float mean[4], rstd[4];
+  tail_tile_put(acc, stg, lane);
+  tail_rows_take(stg, bo4, xin, lane, v);
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+    if (m0 + t * 8 + crow < M)
+      *reinterpret_cast<float4*>(resid + (size_t)(m0 + t * 8 + crow) * D + cn) = v[t];
+  tail_rows_stats(v, s_red, wave, lane, eps, mean, rstd);
+  tail_rows_to_operand(v, mean, rstd, gain4, offs4, sA, wave, lane);
+  __syncthreads();
+  bf16x8 areg[16];
+  tail_operand_load(sA, lane, areg);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 16; ++ks)
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[ks], areg[ks], acc, 0, 0, 0);
+  // through the wavefront's staging area (its own reads of the first tile are done: LDS
+  // serves a wavefront's instructions in order): 8 lanes per row, 4 columns per lane
+  tail_tile_put(acc, stg, lane);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int row = t * 8 + crow;
+    const float4 a4 = *reinterpret_cast<const float4*>(stg + row * kTailStride + lp * 16);
+    if (m0 + row < M)
+      *reinterpret_cast<uint2*>(q_out + (size_t)(m0 + row) * D + cn) =
+          make_uint2(pack_bf16x2((a4.x + bq4.x) * q_scale, (a4.y + bq4.y) * q_scale),
+                     pack_bf16x2((a4.z + bq4.z) * q_scale, (a4.w + bq4.w) * q_scale));
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -1777,6 +1928,25 @@ hipError_t launch_layer_head(const float* x, const void* packed, const float* ln
   return hipGetLastError();
 }
 
+hipError_t launch_layer_mid_pack(const void* Wo, const void* Wq, int d, void* packed, hipStream_t s) {
+  if (d != 256) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(layer_mid_pack_kernel, dim3(2 * 256 * 256 / 8 / 256), dim3(256), 0, s,
+                     static_cast<const bf16_t*>(Wo), static_cast<const bf16_t*>(Wq),
+                     static_cast<bf16_t*>(packed));
+  return hipGetLastError();
+}
+
+hipError_t launch_layer_mid(const void* O, const void* packed, const float* b_o, const float* ln_g,
+                            const float* ln_b, float eps, float* resid, const float* b_q,
+                            float q_scale, void* q_out, int d, const int32_t* m_ptr, int m_host,
+                            int m_capacity, hipStream_t s) {
+  if (d != 256) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(layer_mid_kernel, dim3((m_capacity + 31) / 32), dim3(512), 0, s,
+                     static_cast<const bf16_t*>(O), static_cast<const bf16_t*>(packed), b_o, ln_g,
+                     ln_b, eps, resid, b_q, q_scale, static_cast<bf16_t*>(q_out), m_ptr, m_host);
+  return hipGetLastError();
+}
+
 hipError_t launch_layer_tail(const LayerTailArgs& a, int d, int F, const int32_t* m_ptr,
                              int m_host, int m_capacity, hipStream_t s) {
   if (!layer_tail_supported(d, F, true)) return hipErrorInvalidValue;
@@ -1840,13 +2010,14 @@ hipError_t launch_gemm_qkv(const void* A, const void* W, const float* bias, int 
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_kv(const void* A, const void* W, const float* bias, int d, void* k,
-                          void* vt, int vt_ld, const int32_t* cu_seqlens, const int32_t* pcu,
-                          int B, const int32_t* m_ptr, int m_host, int m_capacity,
-                          hipStream_t s) {
-  EpiQkv ep{bias, static_cast<bf16_t*>(k), d, d, 0, 1.0f, static_cast<bf16_t*>(vt), vt_ld,
-            cu_seqlens, pcu, B};
-  hipError_t e = launch_direct(A, W, 2 * d, d, ep, m_ptr, m_host, m_capacity, s);
+hipError_t launch_gemm_kv_layers(const void* A, const void* W, const float* bias, int d, int layers,
+                                 void* k, size_t k_stride, void* vt, size_t vt_stride, int vt_ld,
+                                 const int32_t* cu_seqlens, const int32_t* pcu, int B,
+                                 const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
+  if (d % 64 != 0) return hipErrorInvalidValue;   // a wavefront's columns must not straddle k | v
+  EpiKvLayers ep{bias, static_cast<bf16_t*>(k), k_stride, d, static_cast<bf16_t*>(vt), vt_stride,
+                 vt_ld, cu_seqlens, pcu, B};
+  hipError_t e = launch_direct(A, W, layers * 2 * d, d, ep, m_ptr, m_host, m_capacity, s);
   if (e != hipSuccess) return e;
   return hipGetLastError();
 }

@@ -128,13 +128,15 @@ hipError_t launch_gemm(const void* A, const void* W, const float* bias, int N, i
                        const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s,
                        float scale = 1.0f);
 
-// bf16 key/value projection of the decoder's cross-attention: W [2d, d] stacks the key and
-// value rows; keys go token-major to k [M, d], values feature-major to vt like
-// launch_gemm_qkv.
-hipError_t launch_gemm_kv(const void* A, const void* W, const float* bias, int d, void* k,
-                          void* vt, int vt_ld, const int32_t* cu_seqlens, const int32_t* pcu,
-                          int B, const int32_t* m_ptr, int m_host, int m_capacity,
-                          hipStream_t s);
+// bf16 key/value projections of the decoder's cross-attention for `layers` layers at once
+// (the tokens are the same for all of them): W [layers * 2d, d] and bias [layers * 2d] stack
+// the layers' key and value rows; layer l's keys go token-major to k + l * k_stride
+// (elements, [M, d] each), its values feature-major to vt + l * vt_stride like
+// launch_gemm_qkv.  d must be a multiple of 64.
+hipError_t launch_gemm_kv_layers(const void* A, const void* W, const float* bias, int d, int layers,
+                                 void* k, size_t k_stride, void* vt, size_t vt_stride, int vt_ld,
+                                 const int32_t* cu_seqlens, const int32_t* pcu, int B,
+                                 const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s);
 
 // Residual contraction followed by LayerNorm of the updated rows, in one kernel (bf16
 // operands): resid[M,d] += A[M,K] . W[d,K]^T + bias, then
@@ -195,6 +197,17 @@ hipError_t launch_layer_head(const float* x, const void* packed, const float* ln
                              void* qk, void* vt, int vt_ld, const int32_t* cu, const int32_t* pcu,
                              int B, int d, const int32_t* m_ptr, int m_host, int m_capacity,
                              hipStream_t s);
+
+// Between the decoder's two attentions, in the same style (width 256, bf16): the output
+// projection of the first with its residual, the LayerNorm behind it and the query
+// projection of the second:  resid[M,d] += O . Wo^T + b_o;  q_out[M,d] (bf16) =
+// ((LayerNorm(resid) * ln_g + ln_b) . Wq^T + b_q) * q_scale.  Both matrices are read from a
+// packed copy (2 d d elements) that launch_layer_mid_pack writes once.
+hipError_t launch_layer_mid_pack(const void* Wo, const void* Wq, int d, void* packed, hipStream_t s);
+hipError_t launch_layer_mid(const void* O, const void* packed, const float* b_o, const float* ln_g,
+                            const float* ln_b, float eps, float* resid, const float* b_q,
+                            float q_scale, void* q_out, int d, const int32_t* m_ptr, int m_host,
+                            int m_capacity, hipStream_t s);
 
 // bf16 query/key/value projection: q and k go to qk [M, 3d] (columns 0..2d, bias added,
 // q multiplied by q_scale = attention_q_scale(d_head) so that the attention kernel gets
