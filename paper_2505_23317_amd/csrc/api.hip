@@ -49,6 +49,7 @@ struct cfdetr_ctx {
   int cap8 = 0;               // entries per queue (one queue per XCD)
   int32_t* queue_heads = nullptr;   // 8 fetch counters per layer, set by the plan kernel
   int attn_grid = 0;                // workgroups of an attention launch
+  int32_t* m_seen = nullptr;        // pinned host: row totals of earlier runs (merged, fine only), copied back without a wait
   int32_t* n_roi = nullptr;         // regions per frame (scratch of the region proposal)
   int32_t* tok_pad = nullptr;       // padded token table, offsets and true lengths of the
   int32_t* cu_pad = nullptr;        // padded form of the fine pass
@@ -221,10 +222,26 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
   const int nseq = n_prefix + B;
   const int32_t* cu_all = ctx->cu_all;
   const int32_t* m_ptr = ctx->m_all;
+  // The contraction launchers choose their tiles by the rows they expect.  The count of this
+  // run is on the device; the count of the previous run of the same kind (copied back
+  // without waiting for it) is a good guess in a stream of frames.  A coarse-only run has
+  // exactly its capacity.
+  int m_hint = 0;
+  int32_t* m_seen = nullptr;
+  if (cu == ctx->coarse_cu && n_prefix == 0) {
+    m_hint = m_cap;
+  } else if (ctx->m_seen && bf && !(gemm_residual_ln_supported(d, bf) && ctx->tail_packed_layer != 0)) {
+    m_seen = ctx->m_seen + (n_prefix > 0 ? 0 : kv_len ? 2 : 1);
+    m_hint = *static_cast<volatile int32_t*>(m_seen);
+  }
   CF_LAUNCH(CFDETR_K_PLAN,
             launch_plan(cu, B, n_prefix, ctx->n0, ctx->block_q, c.n_heads, ctx->items,
                         ctx->cap8, ctx->cu_all, ctx->m_all, ctx->pcu, ctx->queue_heads,
                         8 * c.n_layers, ctx->attn_grid / 8, s));
+  if (m_seen) {
+    hipError_t e = hipMemcpyAsync(m_seen, ctx->m_all, 4, hipMemcpyDeviceToHost, s);
+    if (e != hipSuccess) return fail_hip(ctx, "copy of the row count", e);
+  }
   // Where a workgroup can own whole rows, the residual contractions also apply the
   // LayerNorm that follows them, and only the very first one is a launch of its own.
   const bool fused_ln = gemm_residual_ln_supported(d, bf);
@@ -251,10 +268,10 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
       CF_LAUNCH(CFDETR_K_QKV,
                 launch_gemm_qkv(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, d,
                                 attention_q_scale(d / c.n_heads), ctx->qkv, ctx->vt,
-                                ctx->vt_ld, cu_all, ctx->pcu, nseq, m_ptr, 0, m_cap, s));
+                                ctx->vt_ld, cu_all, ctx->pcu, nseq, m_ptr, m_hint, m_cap, s));
     else
       CF_LAUNCH(CFDETR_K_QKV, launch_gemm(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, 3 * d, d,
-                                          Epilogue::kBias, ctx->qkv, nullptr, bf, m_ptr, 0, m_cap,
+                                          Epilogue::kBias, ctx->qkv, nullptr, bf, m_ptr, m_hint, m_cap,
                                           s));
     CF_LAUNCH(CFDETR_K_ATTN,
               launch_attention(ctx->qkv, ctx->vt, ctx->vt_ld, ctx->o, d, c.n_heads, ctx->items, ctx->cap8, ctx->queue_heads + 8 * l,
@@ -296,14 +313,14 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
                                         ctx->a, true, 0, nullptr, m_ptr, 0, m_cap, s));
     } else {
       CF_LAUNCH(CFDETR_K_OUT, launch_gemm(ctx->o, wo, w.b_o + (size_t)l * d, d, d,
-                                          Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, 0,
+                                          Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, m_hint,
                                           m_cap, s));
       CF_LAUNCH(CFDETR_K_LN,
                 launch_layernorm(ctx->x, w.ln2_g + (size_t)l * d, w.ln2_b + (size_t)l * d, ctx->a,
                                  bf, d, eps, m_ptr, 0, m_cap, 0, nullptr, s));
     }
     CF_LAUNCH(CFDETR_K_FF1, launch_gemm(ctx->a, w1, w.b_ff1 + (size_t)l * F, F, d,
-                                        Epilogue::kBiasGelu, ctx->h, nullptr, bf, m_ptr, 0, m_cap,
+                                        Epilogue::kBiasGelu, ctx->h, nullptr, bf, m_ptr, m_hint, m_cap,
                                         s));
     if (fused_ln && !last)
       CF_LAUNCH(CFDETR_K_FF2,
@@ -318,7 +335,7 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
                                         s));
     else
       CF_LAUNCH(CFDETR_K_FF2, launch_gemm(ctx->h, w2, w.b_ff2 + (size_t)l * d, d, F,
-                                          Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, 0,
+                                          Epilogue::kBiasResidual, nullptr, ctx->x, bf, m_ptr, m_hint,
                                           m_cap, s));
   }
   if (!fused_ln)
@@ -647,6 +664,12 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
     return fail_create(CFDETR_ENOMEM, std::string("hipMalloc of the work space: ") +
                                           hipGetErrorString(e));
   }
+  // three pinned words for row counts that come back from the device without a wait; the
+  // library works without them (tiles are then chosen for the capacity)
+  if (hipHostMalloc(reinterpret_cast<void**>(&c->m_seen), 3 * sizeof(int32_t), hipHostMallocDefault) == hipSuccess)
+    c->m_seen[0] = c->m_seen[1] = c->m_seen[2] = 0;
+  else
+    c->m_seen = nullptr;
   char* base = static_cast<char*>(c->arena);
   c->x = reinterpret_cast<float*>(base + o_x);
   c->a = base + o_a;
@@ -708,6 +731,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
     e = launch_layer_head_pack(w->w_qkv, (int)d, c->head_packed, nullptr);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
+    if (c->m_seen) hipHostFree(c->m_seen);
     hipFree(c->arena);
     delete c;
     return fail_create(CFDETR_EDEVICE, std::string("context set-up: ") + hipGetErrorString(e));
@@ -720,6 +744,7 @@ CFDETR_API void cfdetr_destroy(cfdetr_ctx* ctx) {
   if (!ctx) return;
   hipDeviceSynchronize();
   for (hipEvent_t ev : ctx->ev) hipEventDestroy(ev);
+  if (ctx->m_seen) hipHostFree(ctx->m_seen);
   if (ctx->arena) hipFree(ctx->arena);
   if (ctx->dec_arena) hipFree(ctx->dec_arena);
   delete ctx;

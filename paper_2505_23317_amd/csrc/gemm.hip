@@ -1795,20 +1795,41 @@ hipError_t launch_direct_tile(const AROWS& a, const bf16_t* w, int N, int K, con
   return hipSuccess;
 }
 
+int cu_count() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
 // Tile choice by problem size: 256x256 (8 wavefronts, 128x64 each) for wide outputs
 // over many rows, 128x128 (4 wavefronts, 64x64 each) while that still yields a
-// workgroup per CU, else 64x64.
+// workgroup per CU, else 64x64.  The rows that count are the likely ones: with the row
+// count on the device (m_ptr), m_host > 0 is the caller's estimate of it (the kernels do
+// not read it) and the capacity stands in otherwise.  A CU holds one 256-tile or two
+// 128-tiles; a 256-tile is four times the work and takes about 1.8 times as long as a
+// pair of 128-tiles, so what decides at a few rounds is how full the last round is.
 template <typename EP>
 hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& ep,
                          const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
   const DenseRows a{static_cast<const bf16_t*>(A), K};
   const bf16_t* w = static_cast<const bf16_t*>(W);
-  const long tiles128 = (long)((m_capacity + 127) / 128) * (N / 128);
+  const int m = m_ptr ? (m_host > 0 && m_host < m_capacity ? m_host : m_capacity) : m_host;
+  const long cus = cu_count();
+  const long tiles128 = (long)((m + 127) / 128) * (N / 128);
+  const long tiles256 = (long)((m + 255) / 256) * (N / 256);
+  const long rounds128 = (tiles128 + 2 * cus - 1) / (2 * cus), rounds256 = (tiles256 + cus - 1) / cus;
   // A deeper ring (3 or 4 buffers, also with slabs of 32) measured no faster for these
   // tiles: their main loops are bound by LDS traffic, not by the latency of the loads.
-  if (N % 256 == 0 && N >= 2048 && m_capacity >= 16384)
+  if (N % 256 == 0 && N >= 2048 && m >= 8192 && 9 * rounds256 <= 5 * rounds128)
     return launch_direct_tile<256, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
-  if (N % 128 == 0 && tiles128 >= 256)
+  if (N % 128 == 0 && tiles128 >= cus)
     return launch_direct_tile<128, 128, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
   return launch_direct_tile<64, 64, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
 }
