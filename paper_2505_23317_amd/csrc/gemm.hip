@@ -1827,7 +1827,7 @@ hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& e
   const long rounds128 = (tiles128 + 2 * cus - 1) / (2 * cus), rounds256 = (tiles256 + cus - 1) / cus;
   // A deeper ring (3 or 4 buffers, also with slabs of 32) measured no faster for these
   // tiles: their main loops are bound by LDS traffic, not by the latency of the loads.
-  if (N % 256 == 0 && N >= 2048 && m >= 8192 && 9 * rounds256 <= 5 * rounds128)
+  if (N % 256 == 0 && m >= 8192 && 9 * rounds256 <= 5 * rounds128)
     return launch_direct_tile<256, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
   if (N % 128 == 0 && tiles128 >= cus)
     return launch_direct_tile<128, 128, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
