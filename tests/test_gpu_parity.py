@@ -389,6 +389,33 @@ def test_two_runs_are_bit_identical(K):
         np.testing.assert_array_equal(a[k], b[k])
 
 
+def test_a_second_run_on_one_context_is_bit_identical(K):
+    """The contraction kernels choose their tiles from the row count of the context's previous
+    run of the same kind (the first run only has the capacity): the choice must not show in the
+    results.  cfg5's shape (width 768) with enough rows for the large tile to be in play."""
+    import torch
+    cfg = synth.replace(synth.config(5), B=8, layers=1)
+    wl = synth.make_workload(cfg, seed=44)
+    enc = K.Encoder(cfg, wl["weights"], act_dtype="bf16")
+    img = enc.upload_images(wl["images"])
+    b, t, o = enc.upload_boxes(wl["boxes"], wl["tier"], wl["box_offsets"])
+    runs = []
+    for _ in range(3):
+        out = enc.alloc_outputs(cfg.B)
+        enc.multilevel_batch(img, cfg.B, b, t, o, out)
+        enc.sync_status()
+        torch.cuda.synchronize()
+        runs.append({k: v.cpu().numpy() for k, v in out.items()})
+    enc.close()
+    T = int(runs[0]["cu_seqlens"][-1])
+    _say(f"[case] three runs on one context, {T} mixed tokens + {cfg.B} coarse grids")
+    assert T + cfg.B * (cfg.H // cfg.patch[0]) * (cfg.W // cfg.patch[0]) >= 8192
+    for r in runs[1:]:
+        np.testing.assert_array_equal(r["cu_seqlens"], runs[0]["cu_seqlens"])
+        np.testing.assert_array_equal(r["y_coarse"], runs[0]["y_coarse"])
+        np.testing.assert_array_equal(r["y_mixed"][:T], runs[0]["y_mixed"][:T])
+
+
 def test_profile_interface_counts_launches(K):
     cfg = synth.replace(synth.config(2), layers=2)
     wl = synth.make_workload(cfg, seed=47)
