@@ -76,6 +76,63 @@ __global__ __launch_bounds__(256) void layernorm_kernel(
   }
 }
 
+// The same with four elements per lane and step (16-byte loads, 8- or 16-byte stores), for
+// widths that are a multiple of four.  (Two rows per wavefront, both requested before either
+// is reduced, measured no faster.)
+constexpr int kLnMaxQuads = kLnMaxPairs / 2;
+
+__device__ __forceinline__ void store_quad(float* p, float a, float b, float c, float d) {
+  *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+}
+__device__ __forceinline__ void store_quad(bf16_t* p, float a, float b, float c, float d) {
+  *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
+}
+
+template <typename TOut>
+__global__ __launch_bounds__(256) void layernorm4_kernel(
+    const float* __restrict__ x, const float* __restrict__ g, const float* __restrict__ b,
+    TOut* __restrict__ out, int d, float eps, const int32_t* __restrict__ m_ptr, int m_host,
+    int split_row, TOut* __restrict__ out2) {
+  const int M = m_ptr ? *m_ptr : m_host;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  const int lane = threadIdx.x & 63;
+  const int quads = d >> 2;
+  const float4* xr = reinterpret_cast<const float4*>(x + (size_t)row * d);
+  float4 v[kLnMaxQuads];
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < kLnMaxQuads; ++j) {
+    const int i = lane + 64 * j;
+    v[j] = (i < quads) ? xr[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    sum += (v[j].x + v[j].y) + (v[j].z + v[j].w);
+  }
+  const float mean = wave_sum(sum) / (float)d;
+  float sq = 0.f;
+#pragma unroll
+  for (int j = 0; j < kLnMaxQuads; ++j) {
+    if (lane + 64 * j < quads) {
+      const float cx = v[j].x - mean, cy = v[j].y - mean, cz = v[j].z - mean, cw = v[j].w - mean;
+      sq += (cx * cx + cy * cy) + (cz * cz + cw * cw);
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)d + eps);
+  TOut* orow = (out2 != nullptr && row >= split_row) ? out2 + (size_t)(row - split_row) * d
+                                                     : out + (size_t)row * d;
+  const float4* g4 = reinterpret_cast<const float4*>(g);
+  const float4* b4 = reinterpret_cast<const float4*>(b);
+#pragma unroll
+  for (int j = 0; j < kLnMaxQuads; ++j) {
+    const int i = lane + 64 * j;
+    if (i < quads) {
+      const float4 gg = g4[i], bb = b4[i];
+      store_quad(orow + 4 * i, (v[j].x - mean) * rstd * gg.x + bb.x,
+                 (v[j].y - mean) * rstd * gg.y + bb.y, (v[j].z - mean) * rstd * gg.z + bb.z,
+                 (v[j].w - mean) * rstd * gg.w + bb.w);
+    }
+  }
+}
+
 // One wavefront per token: level-0 tokens take their row of the coarse cache.
 __global__ __launch_bounds__(256) void gather_coarse_kernel(
     const int32_t* __restrict__ tok_desc, const int32_t* __restrict__ cu, int B,
@@ -178,6 +235,17 @@ hipError_t launch_layernorm(const float* x, const float* g, const float* b, void
                             int m_host, int m_capacity, int split_row, void* out2,
                             hipStream_t s) {
   dim3 grid((m_capacity + 3) / 4);
+  if (d % 4 == 0) {
+    if (out_is_bf16)
+      hipLaunchKernelGGL(layernorm4_kernel<bf16_t>, grid, dim3(256), 0, s, x, g, b,
+                         static_cast<bf16_t*>(out), d, eps, m_ptr, m_host, split_row,
+                         static_cast<bf16_t*>(out2));
+    else
+      hipLaunchKernelGGL(layernorm4_kernel<float>, grid, dim3(256), 0, s, x, g, b,
+                         static_cast<float*>(out), d, eps, m_ptr, m_host, split_row,
+                         static_cast<float*>(out2));
+    return hipGetLastError();
+  }
   if (out_is_bf16)
     hipLaunchKernelGGL(layernorm_kernel<bf16_t>, grid, dim3(256), 0, s, x, g, b,
                        static_cast<bf16_t*>(out), d, eps, m_ptr, m_host, split_row,

@@ -33,7 +33,7 @@ FAMILIES = [
     ("layer_tail", r"layer_tail_kernel"),
     ("layer_head", r"layer_head_kernel"),
     ("embed", r"gemm_bf16_gather_kernel|gemm_bf16_direct_kernel.*EpiEmbed"),
-    ("layernorm", r"layernorm_kernel"),
+    ("layernorm", r"layernorm4?_kernel"),
     ("select_hit", r"select_hit_kernel"),
     ("select_compact", r"select_compact_kernel"),
     ("gather_coarse", r"gather_coarse_kernel"),
