@@ -456,11 +456,11 @@ def main() -> int:
         for cid in (4, 5):
             if cid == args.config:
                 continue
-            mo = measure(cid, 10, 3, 3)
+            mo = measure(cid, 40, 8, 3)
             oc = mo["cfg"]
             others.append({"workload": f"configs[{cid - 1}] {oc.name}",
-                           "tokens_per_s": mo["tokens_per_step"] * 10 / mo["elapsed"],
-                           "frames_per_s": oc.B * 10 / mo["elapsed"],
+                           "tokens_per_s": mo["tokens_per_step"] * 40 / mo["elapsed"],
+                           "frames_per_s": oc.B * 40 / mo["elapsed"],
                            "ms_per_step": mo["ms_per_step"],
                            "whole_step_mfma_frac": mo["whole_step_mfma_frac"],
                            "roofline": mo["roofline"]})
