@@ -210,9 +210,27 @@ cfdetr_status embed_level(cfdetr_ctx* ctx, const void* images, int level,
 // n_prefix coarse grids (n0 tokens each) followed by the B sequences of cu; the
 // plan kernel turns that into ctx->cu_all / ctx->m_all, which every kernel reads
 // on the device.  Output rows below split_row go to y0, the others to y1.
+// The plan of an encoder run over n_prefix coarse grids followed by the caller's sequences.
+PlanArgs encoder_plan(const cfdetr_ctx* ctx, int n_prefix) {
+  PlanArgs p{};
+  p.n_prefix = n_prefix;
+  p.prefix_len = ctx->n0;
+  p.block_q = ctx->block_q;
+  p.heads = ctx->cfg.n_heads;
+  p.items = ctx->items;
+  p.cap8 = ctx->cap8;
+  p.cu_all = ctx->cu_all;
+  p.m_all = ctx->m_all;
+  p.pcu = ctx->pcu;
+  p.queue_heads = ctx->queue_heads;
+  p.n_heads_q = 8 * ctx->cfg.n_layers;
+  p.queue_start = ctx->attn_grid / 8;
+  return p;
+}
+
 cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefix, int m_cap,
                           float* y0, int split_row, float* y1, hipStream_t s,
-                          const int32_t* kv_len = nullptr) {
+                          const int32_t* kv_len = nullptr, bool plan_done = false) {
   const cfdetr_config& c = ctx->cfg;
   const cfdetr_weights& w = ctx->w;
   const int d = c.d_model, F = c.d_ffn;
@@ -234,10 +252,8 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
     m_seen = ctx->m_seen + (n_prefix > 0 ? 0 : kv_len ? 2 : 1);
     m_hint = *static_cast<volatile int32_t*>(m_seen);
   }
-  CF_LAUNCH(CFDETR_K_PLAN,
-            launch_plan(cu, B, n_prefix, ctx->n0, ctx->block_q, c.n_heads, ctx->items,
-                        ctx->cap8, ctx->cu_all, ctx->m_all, ctx->pcu, ctx->queue_heads,
-                        8 * c.n_layers, ctx->attn_grid / 8, s));
+  if (!plan_done)   // (the selection kernel of a merged run has made the plan already)
+    CF_LAUNCH(CFDETR_K_PLAN, launch_plan(cu, B, encoder_plan(ctx, n_prefix), s));
   if (m_seen) {
     hipError_t e = hipMemcpyAsync(m_seen, ctx->m_all, 4, hipMemcpyDeviceToHost, s);
     if (e != hipSuccess) return fail_hip(ctx, "copy of the row count", e);
@@ -355,14 +371,15 @@ cfdetr_status coarse_impl(cfdetr_ctx* ctx, const void* images, int B, float* x0_
 
 cfdetr_status select_impl(cfdetr_ctx* ctx, const int32_t* boxes, const uint8_t* tier,
                           const int32_t* box_offsets, int B, int32_t* tok_desc,
-                          int32_t* cu_seqlens, int32_t* level_counts, hipStream_t s) {
+                          int32_t* cu_seqlens, int32_t* level_counts, hipStream_t s,
+                          const PlanArgs* plan = nullptr) {
   uint8_t* cur = ctx->hit[ctx->parity];
   uint8_t* next = ctx->hit[ctx->parity ^ 1];
   ctx->parity ^= 1;
   CF_LAUNCH(CFDETR_K_SELECT,
             launch_select(ctx->pyr, boxes, tier, box_offsets, B, ctx->nonfinest, cur, next,
                           ctx->hit_bytes, ctx->cfg.max_tokens_total, tok_desc, cu_seqlens, level_counts,
-                          ctx->err_flag, s));
+                          ctx->err_flag, s, plan));
   return CFDETR_OK;
 }
 
@@ -422,16 +439,27 @@ cfdetr_status decode_impl(cfdetr_ctx* ctx, const float* memory, const int32_t* c
   // token sequences: offsets, total and padded offsets (the work list is not used).  The
   // offsets are the caller's: the plan checks them, and after an error the second plan
   // hands the attention kernels no work.
-  CF_LAUNCH(CFDETR_K_PLAN,
-            launch_plan(cu, B, 0, 0, ctx->block_q, c.n_heads, ctx->items, ctx->cap8, ctx->cu_all,
-                        ctx->m_all, ctx->pcu, ctx->queue_heads, 8, ctx->attn_grid / 8, s, cap_m,
-                        ctx->err_flag, nullptr));
+  {
+    PlanArgs p = encoder_plan(ctx, 0);
+    p.n_heads_q = 8;
+    CF_LAUNCH(CFDETR_K_PLAN, launch_plan(cu, B, p, s, cap_m, ctx->err_flag, nullptr));
+  }
   CF_LAUNCH(CFDETR_K_DEC, launch_cast_bf16(memory, ctx->a, d, ctx->m_all, cap_m, s));
   // query sequences: B times Q rows, work list for both attentions of every layer
-  CF_LAUNCH(CFDETR_K_PLAN,
-            launch_plan(ctx->dcu, B, 0, 0, ctx->block_q, c.n_heads, ctx->ditems, ctx->dcap8,
-                        ctx->dcu_all, ctx->dm_all, ctx->dpcu, ctx->dqueue, 16 * L,
-                        ctx->dgrid / 8, s, 0, nullptr, ctx->err_flag));
+  {
+    PlanArgs p{};
+    p.block_q = ctx->block_q;
+    p.heads = c.n_heads;
+    p.items = ctx->ditems;
+    p.cap8 = ctx->dcap8;
+    p.cu_all = ctx->dcu_all;
+    p.m_all = ctx->dm_all;
+    p.pcu = ctx->dpcu;
+    p.queue_heads = ctx->dqueue;
+    p.n_heads_q = 16 * L;
+    p.queue_start = ctx->dgrid / 8;
+    CF_LAUNCH(CFDETR_K_PLAN, launch_plan(ctx->dcu, B, p, s, 0, nullptr, ctx->err_flag));
+  }
   CF_LAUNCH(CFDETR_K_DEC, launch_broadcast_rows(w.query_embed, ctx->dx, Q, d, B, s));
   // The tokens' keys and values for the cross-attention of every layer depend on the tokens
   // and the weights only: one contraction for all layers, ahead of the loop.
@@ -562,12 +590,14 @@ cfdetr_status merged_impl(cfdetr_ctx* ctx, const void* images, int B, const int3
   cfdetr_status st = embed_level(ctx, images, 0, ctx->coarse_desc, ctx->coarse_cu, B, ctx->x,
                                  ctx->x0, nullptr, Mc, Mc, s);
   if (st != CFDETR_OK) return st;
-  st = select_impl(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts, s);
+  // the selection also plans the run over the B coarse grids and the B mixed sets
+  const PlanArgs plan = encoder_plan(ctx, B);
+  st = select_impl(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts, s, &plan);
   if (st != CFDETR_OK) return st;
   st = fine_embed(ctx, images, B, tok_desc, cu_seqlens, ctx->x0, Mc, s);
   if (st != CFDETR_OK) return st;
   return run_encoder(ctx, cu_seqlens, B, B, Mc + ctx->cfg.max_tokens_total, y_coarse, Mc,
-                     y_mixed, s);
+                     y_mixed, s, nullptr, true);
 }
 
 }  // namespace

@@ -6,6 +6,20 @@
 
 namespace cfdetr {
 
+// What launch_plan writes and how (see there); also accepted by launch_select, whose last
+// workgroup then makes the plan for the run that follows (the n_prefix prefix sequences plus
+// the B token sets it has just counted).
+struct PlanArgs {
+  int n_prefix, prefix_len, block_q, heads;
+  int32_t* items;
+  int cap8;
+  int32_t* cu_all;
+  int32_t* m_all;
+  int32_t* pcu;
+  int32_t* queue_heads;
+  int n_heads_q, queue_start;
+};
+
 // ---- A2 selection (select.hip) -------------------------------------------
 // hit        [B, nonfinest] bytes, all zero on entry: flag of every cell of the levels
 //            below the finest (level-major) that a box asking for a finer level
@@ -15,7 +29,7 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
                          const int32_t* box_offsets, int B, int nonfinest, uint8_t* hit,
                          uint8_t* hit_next, int hit_bytes, int max_tokens, int32_t* tok_desc,
                          int32_t* cu_seqlens, int32_t* level_counts, int32_t* err_flag,
-                         hipStream_t s);
+                         hipStream_t s, const PlanArgs* plan = nullptr);
 
 // ---- A1 difficulty test + A2 region proposal (roi.hip) ----------------------
 // queries [B, Q, 5] = (cx, cy, w, h, c), centre and size as fractions of the frame.
@@ -63,11 +77,9 @@ hipError_t launch_pad_tokens(const int32_t* tok_desc, const int32_t* cu_seqlens,
 // max_total, cuts the lengths to what fits and sets *err_flag.  gate (may be null): if
 // *gate is not 0 the work list comes out empty, so that the attention launches that
 // follow do nothing after an earlier kernel has raised the error flag.
-hipError_t launch_plan(const int32_t* cu_seqlens, int B, int n_prefix, int prefix_len,
-                       int block_q, int heads, int32_t* items, int cap8, int32_t* cu_all,
-                       int32_t* m_all, int32_t* pcu, int32_t* queue_heads, int n_heads_q,
-                       int queue_start, hipStream_t s, int max_total = 0,
-                       int32_t* err_flag = nullptr, const int32_t* gate = nullptr);
+hipError_t launch_plan(const int32_t* cu_seqlens, int B, const PlanArgs& plan, hipStream_t s,
+                       int max_total = 0, int32_t* err_flag = nullptr,
+                       const int32_t* gate = nullptr);
 
 // ---- row-wise kernels (rowwise.hip) ----------------------------------------
 // Position tables of one level: pe_row [rows, d/2], pe_col [cols, d/2] (fp32).

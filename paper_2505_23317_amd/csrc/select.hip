@@ -53,14 +53,125 @@ __global__ __launch_bounds__(kHitThreads) void select_hit_kernel(
   if (flag) hit[(size_t)frame * nonfinest + cell] = 1;   // several lanes may write the same 1
 }
 
+// Sequence list of one encoder run, and the attention work list over it.
+// The sequences are `n_prefix` sequences of `prefix_len` tokens each (the coarse grids
+// of a merged coarse+mixed run; n_prefix may be 0) followed by the B sequences that
+// cu[0..B] delimits.  Outputs:
+//   cu_all[0..nseq]  offsets of all sequences, m_all = their total
+//   pcu[0..nseq]     offsets when every sequence is padded to a multiple of 64
+//   items[0..8*cap8) attention work items of four words: sequence<<24 | head<<19 | query
+//                    tile (or -1: no item), then the sequence's offset, length and padded
+//                    offset, so that a workgroup gets all it needs to start in one load.
+// Workgroups are dealt to the 8 XCDs round-robin (workgroup w runs on XCD w % 8), and
+// every XCD has its own L2.  All query tiles of one (sequence, head) read the same
+// keys and values, so a whole group goes to one XCD: groups are ordered longest
+// sequence first and dealt round-robin, group G to XCD G % 8, whose workgroups
+// 8*j + G%8 take its tiles in order.  Costs fall with G, so the XCD loads differ by at
+// most one group, and no XCD gets more than total/8 + (tiles of the longest sequence)
+// items, which is what cap8 provides.
+constexpr int kMaxHeads = 32;
+
+// The plan proper: the lengths of the nseq sequences are in s_len (shared, published by a
+// barrier); all threads of a workgroup of at least 2 * kMaxBatch threads call it.
+__device__ __forceinline__ void plan_body(const PlanArgs& p, int nseq, const int* s_len, bool gated) {
+  __shared__ int s_order[2 * kMaxBatch];
+  __shared__ int s_gstart[2 * kMaxBatch * kMaxHeads];
+  __shared__ int s_count[8];
+  __shared__ int s_cu[2 * kMaxBatch], s_pcu[2 * kMaxBatch];
+  const int tid = threadIdx.x;
+  const int heads = p.heads, block_q = p.block_q, cap8 = p.cap8;
+  int4* const items4 = reinterpret_cast<int4*>(p.items);
+  if (tid < nseq) {
+    const int len = s_len[tid];
+    int rank = 0;
+    for (int j = 0; j < nseq; ++j) {
+      const int lj = s_len[j];
+      rank += (lj > len) || (lj == len && j < tid);
+    }
+    s_order[rank] = tid;
+  }
+  __syncthreads();
+  const int ngroups = nseq * heads;
+  if (tid < 8) {   // XCD tid: slots of its groups
+    int pos = 0;
+    for (int G = tid; G < ngroups; G += 8) {
+      s_gstart[G] = pos;
+      pos += (s_len[s_order[G / heads]] + block_q - 1) / block_q;
+    }
+    s_count[tid] = gated ? 0 : min(pos, cap8);
+  }
+  if (tid == 8) {
+    int pos = 0, ppos = 0;
+    for (int i = 0; i < nseq; ++i) {
+      p.cu_all[i] = pos;
+      p.pcu[i] = ppos;
+      s_cu[i] = pos;
+      s_pcu[i] = ppos;
+      pos += s_len[i];
+      ppos += (s_len[i] + 63) & ~63;
+    }
+    p.cu_all[nseq] = pos;
+    p.pcu[nseq] = ppos;
+    *p.m_all = pos;
+  }
+  __syncthreads();
+  for (int G = tid; G < ngroups; G += blockDim.x) {   // one thread per group
+    const int f = s_order[G / heads], h = G % heads, x = G & 7;
+    const int nt = (s_len[f] + block_q - 1) / block_q;
+    const int j0 = s_gstart[G];
+    for (int q = 0; q < nt && j0 + q < cap8; ++q)
+      items4[8 * (j0 + q) + x] = make_int4((f << 24) | (h << 19) | q, s_cu[f], s_len[f], s_pcu[f]);
+  }
+  for (int i = tid; i < 8 * cap8; i += blockDim.x)
+    if ((i >> 3) >= s_count[i & 7]) items4[i] = make_int4(-1, 0, 0, 0);
+  // fetch counters: behind the entries handed out by workgroup index, or -1 where those
+  // are the whole queue (nothing to fetch: a workgroup need not ask)
+  for (int i = tid; i < p.n_heads_q; i += blockDim.x)
+    p.queue_heads[i] = s_count[i & 7] <= p.queue_start ? -1 : p.queue_start;
+}
+
+__global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ cu, int B, PlanArgs p,
+                                                   int max_total, int32_t* __restrict__ err_flag,
+                                                   const int32_t* __restrict__ gate) {
+  __shared__ int s_len[2 * kMaxBatch];
+  const int tid = threadIdx.x;
+  const int nseq = p.n_prefix + B;
+  if (tid < nseq) s_len[tid] = tid < p.n_prefix ? p.prefix_len : cu[tid - p.n_prefix + 1] - cu[tid - p.n_prefix];
+  __syncthreads();
+  if (max_total > 0) {
+    // offsets a caller wrote: every length must be at least 1 and the total must fit;
+    // otherwise the lengths are cut to what fits and the error flag is raised
+    if (tid == 0) {
+      int pos = 0;
+      bool bad = false;
+      for (int i = 0; i < nseq; ++i) {
+        int len = s_len[i];
+        if (len < 1 || len > max_total - pos) {
+          bad = true;
+          len = max(0, min(len, max_total - pos));
+          s_len[i] = len;
+        }
+        pos += len;
+      }
+      if (bad) *err_flag = 1;
+    }
+    __syncthreads();
+  }
+  const bool gated = gate != nullptr && *gate != 0;   // an earlier kernel found an error
+  plan_body(p, nseq, s_len, gated);
+}
+
 __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
     Pyramid pyr, int B, int nonfinest, const uint8_t* __restrict__ hit,
     uint8_t* __restrict__ hit_next, int hit_bytes, int max_tokens,
     int32_t* __restrict__ tok_desc,
     int32_t* __restrict__ cu_seqlens, int32_t* __restrict__ level_counts,
-    int32_t* __restrict__ err_flag) {
+    int32_t* __restrict__ err_flag, PlanArgs plan) {
   __shared__ int s_split[kMaxBatch][kMaxLevels];   // hit cells per (frame, level)
   __shared__ int s_wave[kCompactThreads / kWave];
+  // Workgroup B, if there is one (plan.items set), compacts nothing: the lengths that every
+  // workgroup works out for its offset are all the attention plan needs, so it makes that
+  // plan while the others compact, and the encoder that follows has no launch for it.
   const int frame = blockIdx.x;
   const int tid = threadIdx.x;
   const int n = pyr.n_levels;
@@ -105,6 +216,22 @@ __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
     const int tj = pyr.rows[0] * pyr.cols[0] + 3 * sj;
     if (j < frame) base += tj;
     total_tokens += tj;
+  }
+  if (frame >= B) {
+    __shared__ int s_len[2 * kMaxBatch];
+    const bool too_many = total_tokens > (long long)max_tokens;   // then every length is 0
+    if (tid < plan.n_prefix + B) {
+      int len = plan.prefix_len;
+      if (tid >= plan.n_prefix) {
+        int sj = 0;
+        for (int l = 0; l + 1 < n; ++l) sj += s_split[tid - plan.n_prefix][l];
+        len = too_many ? 0 : pyr.rows[0] * pyr.cols[0] + 3 * sj;
+      }
+      s_len[tid] = len;
+    }
+    __syncthreads();
+    plan_body(plan, plan.n_prefix + B, s_len, false);
+    return;
   }
   // The flag array of the call after this one starts from zero: all of it (that call
   // may have more frames than this one), shared out among the workgroups.
@@ -162,113 +289,6 @@ __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
   }
 }
 
-// Sequence list of one encoder run, and the attention work list over it.
-// The sequences are `n_prefix` sequences of `prefix_len` tokens each (the coarse grids
-// of a merged coarse+mixed run; n_prefix may be 0) followed by the B sequences that
-// cu[0..B] delimits.  Outputs:
-//   cu_all[0..nseq]  offsets of all sequences, m_all = their total
-//   pcu[0..nseq]     offsets when every sequence is padded to a multiple of 64
-//   items[0..8*cap8) attention work items of four words: sequence<<24 | head<<19 | query
-//                    tile (or -1: no item), then the sequence's offset, length and padded
-//                    offset, so that a workgroup gets all it needs to start in one load.
-// Workgroups are dealt to the 8 XCDs round-robin (workgroup w runs on XCD w % 8), and
-// every XCD has its own L2.  All query tiles of one (sequence, head) read the same
-// keys and values, so a whole group goes to one XCD: groups are ordered longest
-// sequence first and dealt round-robin, group G to XCD G % 8, whose workgroups
-// 8*j + G%8 take its tiles in order.  Costs fall with G, so the XCD loads differ by at
-// most one group, and no XCD gets more than total/8 + (tiles of the longest sequence)
-// items, which is what cap8 provides.
-constexpr int kMaxHeads = 32;
-
-__global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ cu, int B,
-                                                   int n_prefix, int prefix_len, int block_q,
-                                                   int heads, int32_t* __restrict__ items,
-                                                   int cap8, int32_t* __restrict__ cu_all,
-                                                   int32_t* __restrict__ m_all,
-                                                   int32_t* __restrict__ pcu,
-                                                   int32_t* __restrict__ queue_heads,
-                                                   int n_heads_q, int queue_start, int max_total,
-                                                   int32_t* __restrict__ err_flag,
-                                                   const int32_t* __restrict__ gate) {
-  __shared__ int s_len[2 * kMaxBatch];
-  __shared__ int s_order[2 * kMaxBatch];
-  __shared__ int s_gstart[2 * kMaxBatch * kMaxHeads];
-  __shared__ int s_count[8];
-  __shared__ int s_cu[2 * kMaxBatch], s_pcu[2 * kMaxBatch];
-  const int tid = threadIdx.x;
-  const int nseq = n_prefix + B;
-  int4* const items4 = reinterpret_cast<int4*>(items);
-  if (tid < nseq) s_len[tid] = tid < n_prefix ? prefix_len : cu[tid - n_prefix + 1] - cu[tid - n_prefix];
-  __syncthreads();
-  if (max_total > 0) {
-    // offsets a caller wrote: every length must be at least 1 and the total must fit;
-    // otherwise the lengths are cut to what fits and the error flag is raised
-    if (tid == 0) {
-      int pos = 0;
-      bool bad = false;
-      for (int i = 0; i < nseq; ++i) {
-        int len = s_len[i];
-        if (len < 1 || len > max_total - pos) {
-          bad = true;
-          len = max(0, min(len, max_total - pos));
-          s_len[i] = len;
-        }
-        pos += len;
-      }
-      if (bad) *err_flag = 1;
-    }
-    __syncthreads();
-  }
-  const bool gated = gate != nullptr && *gate != 0;   // an earlier kernel found an error
-  if (tid < nseq) {
-    const int len = s_len[tid];
-    int rank = 0;
-    for (int j = 0; j < nseq; ++j) {
-      const int lj = s_len[j];
-      rank += (lj > len) || (lj == len && j < tid);
-    }
-    s_order[rank] = tid;
-  }
-  __syncthreads();
-  const int ngroups = nseq * heads;
-  if (tid < 8) {   // XCD tid: slots of its groups
-    int pos = 0;
-    for (int G = tid; G < ngroups; G += 8) {
-      s_gstart[G] = pos;
-      pos += (s_len[s_order[G / heads]] + block_q - 1) / block_q;
-    }
-    s_count[tid] = gated ? 0 : min(pos, cap8);
-  }
-  if (tid == 8) {
-    int pos = 0, ppos = 0;
-    for (int i = 0; i < nseq; ++i) {
-      cu_all[i] = pos;
-      pcu[i] = ppos;
-      s_cu[i] = pos;
-      s_pcu[i] = ppos;
-      pos += s_len[i];
-      ppos += (s_len[i] + 63) & ~63;
-    }
-    cu_all[nseq] = pos;
-    pcu[nseq] = ppos;
-    *m_all = pos;
-  }
-  __syncthreads();
-  for (int G = tid; G < ngroups; G += blockDim.x) {   // one thread per group
-    const int f = s_order[G / heads], h = G % heads, x = G & 7;
-    const int nt = (s_len[f] + block_q - 1) / block_q;
-    const int j0 = s_gstart[G];
-    for (int q = 0; q < nt && j0 + q < cap8; ++q)
-      items4[8 * (j0 + q) + x] = make_int4((f << 24) | (h << 19) | q, s_cu[f], s_len[f], s_pcu[f]);
-  }
-  for (int i = tid; i < 8 * cap8; i += blockDim.x)
-    if ((i >> 3) >= s_count[i & 7]) items4[i] = make_int4(-1, 0, 0, 0);
-  // fetch counters: behind the entries handed out by workgroup index, or -1 where those
-  // are the whole queue (nothing to fetch: a workgroup need not ask)
-  for (int i = tid; i < n_heads_q; i += blockDim.x)
-    queue_heads[i] = s_count[i & 7] <= queue_start ? -1 : queue_start;
-}
-
 __global__ __launch_bounds__(256) void pad_tokens_kernel(const int32_t* __restrict__ tok_desc,
                                                          const int32_t* __restrict__ cu, int B,
                                                          int t_pad, int32_t* __restrict__ tok_pad,
@@ -301,27 +321,24 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
                          const int32_t* box_offsets, int B, int nonfinest, uint8_t* hit,
                          uint8_t* hit_next, int hit_bytes, int max_tokens, int32_t* tok_desc,
                          int32_t* cu_seqlens, int32_t* level_counts, int32_t* err_flag,
-                         hipStream_t s) {
+                         hipStream_t s, const PlanArgs* plan) {
   if (nonfinest > 0) {
     const int cells_per_block = kHitThreads / kBoxLanes;
     dim3 grid((nonfinest + cells_per_block - 1) / cells_per_block, B);
     hipLaunchKernelGGL(select_hit_kernel, grid, dim3(kHitThreads), 0, s, pyr, boxes, tier,
                        box_offsets, nonfinest, hit);
   }
-  hipLaunchKernelGGL(select_compact_kernel, dim3(B), dim3(kCompactThreads), 0, s, pyr, B,
-                     nonfinest, hit, hit_next, hit_bytes, max_tokens, tok_desc, cu_seqlens,
-                     level_counts, err_flag);
+  PlanArgs none{};
+  hipLaunchKernelGGL(select_compact_kernel, dim3(B + (plan ? 1 : 0)), dim3(kCompactThreads), 0, s,
+                     pyr, B, nonfinest, hit, hit_next, hit_bytes, max_tokens, tok_desc, cu_seqlens,
+                     level_counts, err_flag, plan ? *plan : none);
   return hipGetLastError();
 }
 
-hipError_t launch_plan(const int32_t* cu_seqlens, int B, int n_prefix, int prefix_len,
-                       int block_q, int heads, int32_t* items, int cap8, int32_t* cu_all,
-                       int32_t* m_all, int32_t* pcu, int32_t* queue_heads, int n_heads_q,
-                       int queue_start, hipStream_t s, int max_total, int32_t* err_flag,
-                       const int32_t* gate) {
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, cu_seqlens, B, n_prefix, prefix_len,
-                     block_q, heads, items, cap8, cu_all, m_all, pcu, queue_heads, n_heads_q,
-                     queue_start, max_total, err_flag, gate);
+hipError_t launch_plan(const int32_t* cu_seqlens, int B, const PlanArgs& plan, hipStream_t s,
+                       int max_total, int32_t* err_flag, const int32_t* gate) {
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, cu_seqlens, B, plan, max_total, err_flag,
+                     gate);
   return hipGetLastError();
 }
 

@@ -435,7 +435,8 @@ def test_profile_interface_counts_launches(K):
     assert prof["ffn2"]["launches"] == cfg.layers
     assert prof["out_proj"]["launches"] == 0 and prof["ffn1"]["launches"] == 0
     assert prof["qkv"]["launches"] == 1
-    assert prof["plan"]["launches"] == 1
+    # the selection kernel of a merged run also makes the attention plan
+    assert prof["plan"]["launches"] == 0
     assert prof["select"]["launches"] == 1 and prof["gather"]["launches"] == 1
     assert prof["embed"]["launches"] == 2
     assert all(v["ms"] >= 0 for v in prof.values())
