@@ -1193,10 +1193,13 @@ __global__ __launch_bounds__(512) void layer_mid_kernel(
   const int m0 = xcd_tile_order(blockIdx.x, total) * BM;
   const int crow = lane >> 3, lp = lane & 7, cn = wave * 32 + lp * 4;
   unsigned char* const stg = s_stage + wave * (32 * kTailStride);
-  bf16x8 oreg[16];
-  const bf16_t* orow = O + (size_t)min(m0 + l32, M - 1) * D + g * 8;
+  // the 32 rows of O once per workgroup, through the operand buffer (as in layer_tail_kernel)
 #pragma unroll
-  for (int ks = 0; ks < 16; ++ks) oreg[ks] = *reinterpret_cast<const bf16x8*>(orow + ks * 16);
+  for (int j = 0; j < 2; ++j) {
+    const int row = wave * 4 + 2 * j + (lane >> 5), p = lane & 31;
+    const int c = (p & ~7) | ((p ^ row) & 7);
+    dma16_untracked(O + (size_t)min(m0 + row, M - 1) * D + c * 8, sA + (wave * 4 + 2 * j) * 512);
+  }
   const float4 bo4 = *reinterpret_cast<const float4*>(bo + cn);
   const float4 gain4 = *reinterpret_cast<const float4*>(ln_g + cn);
   const float4 offs4 = *reinterpret_cast<const float4*>(ln_b + cn);
@@ -1205,6 +1208,10 @@ __global__ __launch_bounds__(512) void layer_mid_kernel(
 #pragma unroll
   for (int t = 0; t < 4; ++t)
     xin[t] = *reinterpret_cast<const float4*>(resid + (size_t)min(m0 + t * 8 + crow, M - 1) * D + cn);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // this wavefront's rows of O are in LDS
+  __syncthreads();
+  bf16x8 oreg[16];
+  tail_operand_load(sA, lane, oreg);
   f32x16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -1320,11 +1327,16 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
   float mean[4], rstd[4];
   unsigned char* const stg = s_stage + wave * (32 * kTailStride);
   {
-    // ---- attention output times Wo: lane (l32, g) holds elements 16 ks + 8 g .. of row l32
-    bf16x8 oreg[16];
-    const bf16_t* orow = O + (size_t)min(m0 + l32, M - 1) * D + g * 8;
+    // ---- attention output times Wo.  The 32 rows of O come in once per workgroup (four
+    // rows per wavefront, straight into the operand buffer: lane -> LDS chunk position,
+    // fetching the chunk that the row's swizzle puts there); every wavefront then takes
+    // them as operands (lane (l32, g): elements 16 ks + 8 g .. of row l32) from LDS.
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) oreg[ks] = *reinterpret_cast<const bf16x8*>(orow + ks * 16);
+    for (int j = 0; j < 2; ++j) {
+      const int row = wave * 4 + 2 * j + (lane >> 5), p = lane & 31;
+      const int c = (p & ~7) | ((p ^ row) & 7);
+      dma16_untracked(O + (size_t)min(m0 + row, M - 1) * D + c * 8, sA + (wave * 4 + 2 * j) * 512);
+    }
     const float4 bo4 = *reinterpret_cast<const float4*>(bo + cn);
     const float4 gain4 = *reinterpret_cast<const float4*>(ln2_g + cn);
     const float4 offs4 = *reinterpret_cast<const float4*>(ln2_b + cn);
@@ -1334,6 +1346,10 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
       xin[t] = *reinterpret_cast<const float4*>(resid + (size_t)min(m0 + t * 8 + crow, M - 1) * D + cn);
     for (int i = tid * 4; i < F; i += 2048)
       *reinterpret_cast<float4*>(s_b1 + i) = *reinterpret_cast<const float4*>(b1 + i);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // this wavefront's rows of O are in LDS
+    __syncthreads();
+    bf16x8 oreg[16];
+    tail_operand_load(sA, lane, oreg);
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
