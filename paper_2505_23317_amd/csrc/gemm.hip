@@ -1069,19 +1069,40 @@ struct TailQkv {
 // b / 3 of tile b % 3, see layer_tail_pack_kernel) lie at qsrc + (b / 16) * 128 KB +
 // (b % 16) * 1 KB + voff; the first 16 are in wreg already, and each register takes
 // block b + 16 as soon as block b has been used.
+// Start values of the three accumulator tiles of tail_project_qkv: the bias of the columns
+// a lane holds (register r of lane group g: column 8 (r / 4) + 4 g + r % 4 of the tile), and
+// the position of the lane's row in the feature-major copy of v.  Both are loads from global
+// memory: a caller asks for them well before the projection, so that they have arrived.
+__device__ __forceinline__ void tail_qkv_prepare(const TailQkv& qkv, int m0, int M, int wave,
+                                                 int lane, f32x16 (&pacc)[3], int& vpos) {
+  const int l32 = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < 3; ++j)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 b4 = *reinterpret_cast<const float4*>(qkv.bias + wave * 96 + j * 32 + 8 * q + 4 * g);
+      pacc[j][4 * q] = b4.x;
+      pacc[j][4 * q + 1] = b4.y;
+      pacc[j][4 * q + 2] = b4.z;
+      pacc[j][4 * q + 3] = b4.w;
+    }
+  const int mrow = m0 + l32;
+  vpos = 0;
+  if (mrow < M && wave * 96 + 95 >= 512) {   // only wavefronts with v columns need it
+    const int f = frame_of_token(qkv.cu, qkv.B, mrow);
+    vpos = qkv.pcu[f] + (mrow - qkv.cu[f]);
+  }
+}
+
 __device__ __forceinline__ void tail_project_qkv(const unsigned char* sA, bf16x8 (&wreg)[16],
                                                  const unsigned char* qsrc, uint32_t voff,
                                                  const TailQkv& qkv, unsigned char* stg, int m0,
-                                                 int M, int wave, int lane) {
+                                                 int M, int wave, int lane, f32x16 (&pacc)[3],
+                                                 int vpos) {
   constexpr int D = 256;
   const int l32 = lane & 31, g = lane >> 5, crow = lane >> 3, lp = lane & 7;
   bf16x8 qreg[16];
   tail_operand_load(sA, lane, qreg);
-  f32x16 pacc[3];
-#pragma unroll
-  for (int j = 0; j < 3; ++j)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) pacc[j][r] = 0.f;
 #pragma unroll
   for (int b = 0; b < 48; ++b) {
     pacc[b % 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[b & 15], qreg[b / 3], pacc[b % 3], 0, 0, 0);
@@ -1089,20 +1110,13 @@ __device__ __forceinline__ void tail_project_qkv(const unsigned char* sA, bf16x8
       wreg[b & 15] = *reinterpret_cast<const bf16x8*>(qsrc + (size_t)((b + 16) >> 4) * 131072 +
                                                       (b & 15) * 1024 + voff);
   }
-  // position of this lane's row (l32) in the feature-major copy of v
   const int mrow = m0 + l32;
-  int vpos = 0;
-  if (mrow < M) {
-    const int f = frame_of_token(qkv.cu, qkv.B, mrow);
-    vpos = qkv.pcu[f] + (mrow - qkv.cu[f]);
-  }
 #pragma unroll
   for (int j = 0; j < 3; ++j) {
     const int n0 = wave * 96 + j * 32;   // 32 columns, all q, all k or all v
     if (n0 < 2 * D) {
       // through the wavefront's staging area: 8 lanes per row, 4 columns per lane
       tail_tile_put(pacc[j], stg, lane);
-      const float4 b4 = *reinterpret_cast<const float4*>(qkv.bias + n0 + lp * 4);
       const float sc = n0 < D ? qkv.q_scale : 1.0f;
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -1110,20 +1124,18 @@ __device__ __forceinline__ void tail_project_qkv(const unsigned char* sA, bf16x8
         const float4 a4 = *reinterpret_cast<const float4*>(stg + row * kTailStride + lp * 16);
         if (m0 + row < M)
           *reinterpret_cast<uint2*>(qkv.qk + (size_t)(m0 + row) * (3 * D) + n0 + lp * 4) =
-              make_uint2(pack_bf16x2((a4.x + b4.x) * sc, (a4.y + b4.y) * sc),
-                         pack_bf16x2((a4.z + b4.z) * sc, (a4.w + b4.w) * sc));
+              make_uint2(pack_bf16x2(a4.x * sc, a4.y * sc), pack_bf16x2(a4.z * sc, a4.w * sc));
       }
     } else if (mrow < M) {
       // a token per lane: the feature-major stores are runs of 32 consecutive positions
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int n = n0 + 8 * q + 4 * g;
-        const float4 b4 = *reinterpret_cast<const float4*>(qkv.bias + n);
         bf16_t* p = qkv.vt + (size_t)(n - 2 * D) * qkv.vt_ld + vpos;
-        p[0] = f32_to_bf16(pacc[j][4 * q] + b4.x);
-        p[(size_t)qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 1] + b4.y);
-        p[(size_t)2 * qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 2] + b4.z);
-        p[(size_t)3 * qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 3] + b4.w);
+        p[0] = f32_to_bf16(pacc[j][4 * q]);
+        p[(size_t)qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 1]);
+        p[(size_t)2 * qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 2]);
+        p[(size_t)3 * qkv.vt_ld] = f32_to_bf16(pacc[j][4 * q + 3]);
       }
     }
   }
@@ -1158,11 +1170,15 @@ __global__ __launch_bounds__(512) void layer_head_kernel(
 #pragma unroll
   for (int t = 0; t < 4; ++t)
     v[t] = *reinterpret_cast<const float4*>(x + (size_t)min(m0 + t * 8 + crow, M - 1) * D + cn);
+  f32x16 pacc[3];
+  int vpos;
+  tail_qkv_prepare(qkv, m0, M, wave, lane, pacc, vpos);
   float mean[4], rstd[4];
   tail_rows_stats(v, s_red, wave, lane, eps, mean, rstd);
   tail_rows_to_operand(v, mean, rstd, gain4, offs4, sA, wave, lane);
   __syncthreads();
-  tail_project_qkv(sA, wreg, wsrc, voff, qkv, s_stage + wave * (32 * kTailStride), m0, M, wave, lane);
+  tail_project_qkv(sA, wreg, wsrc, voff, qkv, s_stage + wave * (32 * kTailStride), m0, M, wave, lane,
+                   pacc, vpos);
 }
 
 // Output projection of an attention block, the LayerNorm behind it and a projection of the
@@ -1471,6 +1487,10 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
   const float4 offs4 = *reinterpret_cast<const float4*>(ln_b + cn);
   float4 x2[4];
   tail_rows_take(stg, bf4, v, lane, x2);
+  // asked for behind the loads the rows above wait for, used after the LayerNorm
+  f32x16 pacc[3];
+  int vpos = 0;
+  if (!kLast) tail_qkv_prepare(qkv, m0, M, wave, lane, pacc, vpos);
 #pragma unroll
   for (int t = 0; t < 4; ++t)
     if (m0 + t * 8 + crow < M)
@@ -1497,7 +1517,8 @@ __global__ __launch_bounds__(512) void layer_tail_kernel(
   // their copy long ago)
   tail_rows_to_operand(x2, mean, rstd, gain4, offs4, sA, wave, lane);
   __syncthreads();
-  tail_project_qkv(sA, wreg, wsrc + (size_t)(nchunk + 1) * 131072, voff, qkv, stg, m0, M, wave, lane);
+  tail_project_qkv(sA, wreg, wsrc + (size_t)(nchunk + 1) * 131072, voff, qkv, stg, m0, M, wave, lane,
+                   pacc, vpos);
 #undef CFDETR_TAIL_W
   CFDETR_TLX(4);
 }
