@@ -368,49 +368,65 @@ __device__ __forceinline__ void dma16_untracked_s(const void* sbase, uint32_t vo
                : "memory");
 }
 
-// Where the rows of the A operand come from.  row(r, M, ok) is the address of element 0
-// of row r (rows that are not to be computed get ok = false and any valid address);
-// col(k) is the offset of element k, for k a multiple of 8 (8 consecutive elements are
-// contiguous in memory).
+// Where the rows of the A operand come from, as the three parts of a byte address that a
+// load of 8 consecutive elements needs: base() + slab_off(k0) is the same for a whole
+// wavefront (k0: first element of a K-slab of 64) and stays in scalar registers;
+// row_off(r, M, ok) + lane_off(a) is the lane's own 32-bit part (row r; a: first of the
+// lane's 8 elements inside the slab, a multiple of 8).  Rows that are not to be computed
+// get ok = false and the offset of some valid row.  The callers see to it that the
+// matrix (the batch of frames) is smaller than 4 GB.
 struct DenseRows {   // an activation matrix [M, K], K innermost
   const bf16_t* A;
   int K;
   static constexpr bool kSparse = false;
-  __device__ __forceinline__ const bf16_t* row(int r, int M, bool& ok) const {
-    ok = r < M;
-    return A + (size_t)min(r, M - 1) * K;
+  __device__ __forceinline__ const unsigned char* base() const {
+    return reinterpret_cast<const unsigned char*>(A);
   }
-  __device__ __forceinline__ size_t col(int k) const { return (size_t)k; }
+  __device__ __forceinline__ uint32_t row_off(int r, int M, bool& ok) const {
+    ok = r < M;
+    return (uint32_t)min(r, M - 1) * (uint32_t)K * 2u;
+  }
+  __device__ __forceinline__ size_t slab_off(int k0) const { return (size_t)k0 * 2; }
+  __device__ __forceinline__ uint32_t lane_off(int a) const { return (uint32_t)a * 2u; }
 };
 
 // Patch pixels of bf16 frames as rows (implicit im2col): row m is the patch of token m
 // flattened (channel, row, column), for the tokens of one level only.  8 consecutive
-// elements are 8 consecutive pixels of one patch row (patches are at least 8 wide).
+// elements are 8 consecutive pixels of one patch row (patches are at least 8 wide).  A
+// slab of 64 elements starts at a multiple of 64 and the patch side P is a power of two,
+// so a slab lies in one channel and covers whole patch rows (P < 64) or a piece of one:
+// element k0 + a is (a / P) image rows and a % P pixels behind element k0.
 struct PatchPixelRows {
   const bf16_t* images;
   const int32_t* tok_desc;
   const int32_t* cu;
   int B, level, log2p, img_h, img_w;
   static constexpr bool kSparse = true;
-  __device__ __forceinline__ const bf16_t* row(int r, int M, bool& ok) const {
-    size_t off = 0;
+  __device__ __forceinline__ const unsigned char* base() const {
+    return reinterpret_cast<const unsigned char*>(images);
+  }
+  __device__ __forceinline__ uint32_t row_off(int r, int M, bool& ok) const {
+    uint32_t off = 0;   // not ok: frame 0's first patch, in bounds, result discarded
     ok = r < M;
     if (ok) {
       const int32_t desc = tok_desc[r];
       ok = tok_level(desc) == level;
       if (ok) {
         const int frame = frame_of_token(cu, B, r);
-        off = ((size_t)frame * 3 * img_h + ((size_t)tok_row(desc) << log2p)) * img_w +
-              ((size_t)tok_col(desc) << log2p);
+        off = ((uint32_t)(frame * 3 * img_h + (tok_row(desc) << log2p)) * (uint32_t)img_w +
+               (uint32_t)(tok_col(desc) << log2p)) * 2u;
       }
     }
-    return images + off;   // not ok: frame 0's first patch, in bounds, result discarded
+    return off;
   }
-  __device__ __forceinline__ size_t col(int k) const {
-    const int c = k >> (2 * log2p);
-    const int r = (k >> log2p) & ((1 << log2p) - 1);
-    const int x = k & ((1 << log2p) - 1);
-    return ((size_t)c * img_h + r) * img_w + x;
+  __device__ __forceinline__ size_t slab_off(int k0) const {
+    const int c = k0 >> (2 * log2p);
+    const int r = (k0 >> log2p) & ((1 << log2p) - 1);
+    const int x = k0 & ((1 << log2p) - 1);
+    return (((size_t)c * img_h + r) * img_w + x) * 2;
+  }
+  __device__ __forceinline__ uint32_t lane_off(int a) const {
+    return ((uint32_t)(a >> log2p) * (uint32_t)img_w + (uint32_t)(a & ((1 << log2p) - 1))) * 2u;
   }
 };
 
@@ -455,22 +471,22 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   const int m0 = (pid / n_blocks) * BM;
   const int n0 = (pid % n_blocks) * BN;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
   const int wm = wave / NWN, wn = wave % NWN;
   // Loader role: a wave instruction fills RPI consecutive LDS rows (1 KB).  Lane ->
   // (row lane/CPR of the group, LDS chunk position lane%CPR) and fetches the logical
-  // chunk position ^ swizzle key of that row.
+  // chunk position ^ swizzle key of that row.  Of an address only the lane's 32-bit
+  // offset lives in a vector register; what changes from slab to slab is wave-uniform
+  // and is kept (and advanced) in scalar registers.
   const int lrow = lane / CPR, lpos = lane % CPR;
-  const bf16_t* ag[A_INST];   // element 0 of the lane's row
-  int ac[A_INST];             // first of the lane's 8 elements inside a slab
-  const bf16_t* wg[B_INST];
+  uint32_t avo[A_INST], wvo[B_INST];
   bool any_row = false;
 #pragma unroll
   for (int j = 0; j < A_INST; ++j) {
     const int rt = (wave * A_INST + j) * RPI + lrow;      // row inside the tile
     bool ok;
-    ag[j] = arows.row(m0 + rt, M, ok);                    // not ok: any valid row
-    ac[j] = (lpos ^ lds_row_key<ROWB>(rt)) * 8;
+    avo[j] = arows.row_off(m0 + rt, M, ok) + arows.lane_off((lpos ^ lds_row_key<ROWB>(rt)) * 8);
     any_row |= ok;
   }
   if (AROWS::kSparse) {
@@ -480,8 +496,10 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
 #pragma unroll
   for (int j = 0; j < B_INST; ++j) {
     const int rt = (wave * B_INST + j) * RPI + lrow;
-    wg[j] = W + (size_t)(n0 + rt) * K + (lpos ^ lds_row_key<ROWB>(rt)) * 8;
+    wvo[j] = ((uint32_t)(n0 + rt) * (uint32_t)K + (uint32_t)((lpos ^ lds_row_key<ROWB>(rt)) * 8)) * 2u;
   }
+  // the low half of a flat pointer into LDS is the LDS address
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem_direct;
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -514,11 +532,13 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   // wavefront's reads of the buffer the next issue overwrites.
 #define CFDETR_ISSUE_SLAB(k0_, buf_)                                                          \
   do {                                                                                        \
-    unsigned char* st_ = smem_direct + (buf_) * STAGE;                                        \
+    const unsigned char* ab_ = arows.base() + arows.slab_off(k0_);                            \
+    const unsigned char* wb_ = reinterpret_cast<const unsigned char*>(W) + (size_t)(k0_) * 2; \
+    const uint32_t st_ = lds0 + (buf_) * STAGE;                                               \
     _Pragma("unroll") for (int j = 0; j < A_INST; ++j)                                        \
-        dma16_untracked(ag[j] + arows.col((k0_) + ac[j]), st_ + (wave * A_INST + j) * 1024);  \
+        dma16_untracked_s(ab_, avo[j], st_ + (wave * A_INST + j) * 1024);                     \
     _Pragma("unroll") for (int j = 0; j < B_INST; ++j)                                        \
-        dma16_untracked(wg[j] + (k0_), st_ + BM * ROWB + (wave * B_INST + j) * 1024);         \
+        dma16_untracked_s(wb_, wvo[j], st_ + BM * ROWB + (wave * B_INST + j) * 1024);         \
   } while (0)
 
 #pragma unroll
@@ -543,6 +563,24 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     const unsigned char* pa = smem_direct + buf * STAGE;
     const unsigned char* pb = pa + BM * ROWB;
     buf = buf + 1 == kStages ? 0 : buf + 1;
+    if constexpr (MT * NT == 1) {
+      // One MFMA per 16 k and one chain of them: all operand reads of the slab first,
+      // so that their latency is paid once per slab, not once per MFMA.
+      bf16x8 fa[BKT / 16], fb[BKT / 16];
+      const int ra = wm * WTM + l32, rb = wn * WTN + l32;
+#pragma unroll
+      for (int ks = 0; ks < BKT / 16; ++ks) {
+        const int c = 2 * ks + g;
+        fa[ks] = *reinterpret_cast<const bf16x8*>(pa + ra * ROWB + ((c ^ lds_row_key<ROWB>(ra)) << 4));
+        fb[ks] = *reinterpret_cast<const bf16x8*>(pb + rb * ROWB + ((c ^ lds_row_key<ROWB>(rb)) << 4));
+      }
+#pragma unroll
+      for (int ks = 0; ks < BKT / 16; ++ks)
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks], fa[ks], acc[0][0], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * (BKT / 16), 0);   // the LDS reads
+      __builtin_amdgcn_sched_group_barrier(0x008, BKT / 16, 0);         // then the MFMAs
+      continue;
+    }
 #pragma unroll
     for (int ks = 0; ks < BKT / 16; ++ks) {
       const int c = 2 * ks + g;  // logical 16-byte chunk of this lane's 8 k
@@ -1822,6 +1860,8 @@ template <int BM, int BN, int NWM, int NWN, int S, int BKT, typename AROWS, type
 hipError_t launch_direct_tile(const AROWS& a, const bf16_t* w, int N, int K, const EP& ep,
                               const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
   auto kern = gemm_bf16_direct_kernel<BM, BN, NWM, NWN, S, BKT, AROWS, EP>;
+  // the kernel addresses the weights with 32-bit byte offsets (the rows: see the callers)
+  if ((size_t)N * K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
   constexpr size_t lds = (size_t)S * (BM + BN) * BKT * 2;
   static_assert(lds <= 160 * 1024, "ring exceeds the LDS");
   static bool configured = false;
@@ -1857,6 +1897,7 @@ hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& e
                          const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
   const DenseRows a{static_cast<const bf16_t*>(A), K};
   const bf16_t* w = static_cast<const bf16_t*>(W);
+  if ((size_t)m_capacity * K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
   const int m = m_ptr ? (m_host > 0 && m_host < m_capacity ? m_host : m_capacity) : m_host;
   const long cus = cu_count();
   const long tiles128 = (long)((m + 127) / 128) * (N / 128);
@@ -2030,7 +2071,13 @@ hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, in
   const int K = 3 * a.patch * a.patch;
   EpiEmbed ep{bias, a.pe_row, a.pe_col, a.out, a.out2, d, a.tok_desc, a.level};
   hipError_t e = hipSuccess;
-  if (a.image_is_bf16 && use_bf16) {
+  // the direct kernel addresses pixels with 32-bit byte offsets from the first frame
+  const bool frames_fit = (size_t)a.B * 3 * a.img_h * a.img_w * 2 < ((size_t)1 << 32);
+  if (a.image_is_bf16 && use_bf16 && !frames_fit) {
+    PatchRows<bf16_t> al{static_cast<const bf16_t*>(a.images), a.tok_desc, a.cu_seqlens, a.B,
+                         a.level, ilog2(a.patch), a.img_h, a.img_w};
+    e = launch_gather(al, w, d, K, ep, m_ptr, m_host, m_capacity, s);
+  } else if (a.image_is_bf16 && use_bf16) {
     // bf16 pixels need no conversion: patch rows go straight from the frames into LDS,
     // through a deep ring when the problem is too small to hide latency by occupancy
     const PatchPixelRows rows{static_cast<const bf16_t*>(a.images), a.tok_desc, a.cu_seqlens, a.B,
