@@ -546,7 +546,75 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     if (s < nk) CFDETR_ISSUE_SLAB(s * BKT, s);
   int buf = 0;   // ring position of slab `it`
   CFDETR_GTL(1);
-  for (int it = 0; it < nk; ++it) {
+  constexpr bool kChain = MT * NT == 1 && kStages == 4 && BKT == 64;
+  if constexpr (kChain) {
+    // A wavefront with a single 32x32 tile (small problems: a workgroup per CU, one
+    // wavefront per SIMD) has four dependent MFMAs per slab and nothing to run beside
+    // them, so the slab's operand reads, its MFMAs and the barrier would simply add up.
+    // Here the operands of slab it + 1 are read while the MFMAs of slab it run (two sets
+    // of operand registers, the loop unrolled twice so that they never move): slab it + 1
+    // has landed and is published by the barrier of step it, slab it + 2 is in flight,
+    // and the load issued in step it overwrites slab it - 1, which every wavefront has
+    // consumed before it reaches that barrier.
+    const int ra = wm * WTM + l32, rb = wn * WTN + l32;
+    uint32_t oa[4], ob[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int c = 2 * ks + g;
+      oa[ks] = ra * ROWB + ((c ^ lds_row_key<ROWB>(ra)) << 4);
+      ob[ks] = BM * ROWB + rb * ROWB + ((c ^ lds_row_key<ROWB>(rb)) << 4);
+    }
+    bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
+    auto read_slab = [&](int b, bf16x8(&fa)[4], bf16x8(&fb)[4]) {
+      const unsigned char* p = smem_direct + b * STAGE;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        fa[ks] = *reinterpret_cast<const bf16x8*>(p + oa[ks]);
+        fb[ks] = *reinterpret_cast<const bf16x8*>(p + ob[ks]);
+      }
+    };
+    auto step = [&](int it, bf16x8(&ca)[4], bf16x8(&cb)[4], bf16x8(&na)[4], bf16x8(&nb)[4]) {
+      if (it + 2 < nk)
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (LPW & 15) | ((LPW >> 4) << 14));
+      else
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+      __builtin_amdgcn_s_barrier();
+      if (it + 3 < nk) CFDETR_ISSUE_SLAB((it + 3) * BKT, (it + 3) & 3);
+      // each MFMA is followed by two of the next slab's reads: the reads are issued while
+      // the MFMA before them runs, and the one wait for operands (ahead of the first MFMA)
+      // finds only reads that are a whole step old
+      // (behind the last slab they read a buffer that holds nothing new: never used)
+      const unsigned char* p = smem_direct + ((it + 1) & 3) * STAGE;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cb[ks], ca[ks], acc[0][0], 0, 0, 0);
+        na[ks] = *reinterpret_cast<const bf16x8*>(p + oa[ks]);
+        nb[ks] = *reinterpret_cast<const bf16x8*>(p + ob[ks]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    };
+    if (nk >= 3)
+      __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LPW) & 15) | (((2 * LPW) >> 4) << 14));
+    else if (nk == 2)
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (LPW & 15) | ((LPW >> 4) << 14));
+    else
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+    CFDETR_GTL(2);
+    read_slab(0, fa0, fb0);
+    for (int it = 0; it < nk; it += 2) {
+      step(it, fa0, fb0, fa1, fb1);
+      if (it + 1 < nk) step(it + 1, fa1, fb1, fa0, fb0);
+    }
+  }
+  for (int it = 0; !kChain && it < nk; ++it) {
     const int ahead = min(kStages - 2, nk - 1 - it);   // later slabs that may stay in flight
     if (kStages == 4 && ahead >= 2)
       __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LPW) & 15) | (((2 * LPW) >> 4) << 14));
@@ -563,24 +631,6 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     const unsigned char* pa = smem_direct + buf * STAGE;
     const unsigned char* pb = pa + BM * ROWB;
     buf = buf + 1 == kStages ? 0 : buf + 1;
-    if constexpr (MT * NT == 1) {
-      // One MFMA per 16 k and one chain of them: all operand reads of the slab first,
-      // so that their latency is paid once per slab, not once per MFMA.
-      bf16x8 fa[BKT / 16], fb[BKT / 16];
-      const int ra = wm * WTM + l32, rb = wn * WTN + l32;
-#pragma unroll
-      for (int ks = 0; ks < BKT / 16; ++ks) {
-        const int c = 2 * ks + g;
-        fa[ks] = *reinterpret_cast<const bf16x8*>(pa + ra * ROWB + ((c ^ lds_row_key<ROWB>(ra)) << 4));
-        fb[ks] = *reinterpret_cast<const bf16x8*>(pb + rb * ROWB + ((c ^ lds_row_key<ROWB>(rb)) << 4));
-      }
-#pragma unroll
-      for (int ks = 0; ks < BKT / 16; ++ks)
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks], fa[ks], acc[0][0], 0, 0, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 * (BKT / 16), 0);   // the LDS reads
-      __builtin_amdgcn_sched_group_barrier(0x008, BKT / 16, 0);         // then the MFMAs
-      continue;
-    }
 #pragma unroll
     for (int ks = 0; ks < BKT / 16; ++ks) {
       const int c = 2 * ks + g;  // logical 16-byte chunk of this lane's 8 k
@@ -1909,7 +1959,7 @@ hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& e
     return launch_direct_tile<256, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
   if (N % 128 == 0 && tiles128 >= cus)
     return launch_direct_tile<128, 128, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
-  return launch_direct_tile<64, 64, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+  return launch_direct_tile<64, 64, 2, 2, 4, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
 }
 
 template <int BM, int BN, typename TPix>
