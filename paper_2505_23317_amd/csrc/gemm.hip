@@ -631,25 +631,43 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     const unsigned char* pa = smem_direct + buf * STAGE;
     const unsigned char* pb = pa + BM * ROWB;
     buf = buf + 1 == kStages ? 0 : buf + 1;
-#pragma unroll
-    for (int ks = 0; ks < BKT / 16; ++ks) {
+    // Operands of 16 k at a time, two sets of registers: the reads of the next 16 k are
+    // issued between the MFMAs of the current ones, one read behind each MFMA, so that the
+    // wavefront's MFMAs do not stop for the LDS latency inside a slab.
+    bf16x8 fa[2][MT], fb[2][NT];
+    auto read_ops = [&](int ks, bf16x8(&oa)[MT], bf16x8(&ob)[NT]) {
       const int c = 2 * ks + g;  // logical 16-byte chunk of this lane's 8 k
-      bf16x8 fa[MT], fb[NT];
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
         const int r = wm * WTM + i * 32 + l32;
-        fa[i] = *reinterpret_cast<const bf16x8*>(pa + r * ROWB + ((c ^ lds_row_key<ROWB>(r)) << 4));
+        oa[i] = *reinterpret_cast<const bf16x8*>(pa + r * ROWB + ((c ^ lds_row_key<ROWB>(r)) << 4));
       }
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const int r = wn * WTN + j * 32 + l32;
-        fb[j] = *reinterpret_cast<const bf16x8*>(pb + r * ROWB + ((c ^ lds_row_key<ROWB>(r)) << 4));
+        ob[j] = *reinterpret_cast<const bf16x8*>(pb + r * ROWB + ((c ^ lds_row_key<ROWB>(r)) << 4));
       }
+    };
+    read_ops(0, fa[0], fb[0]);
+    __builtin_amdgcn_sched_group_barrier(0x100, MT + NT, 0);
+#pragma unroll
+    for (int ks = 0; ks < BKT / 16; ++ks) {
+      if (ks + 1 < BKT / 16) read_ops(ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[ks & 1][i], acc[i][j], 0, 0, 0);
+      if (ks + 1 < BKT / 16) {
+#pragma unroll
+        for (int t = 0; t < MT + NT; ++t) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, MT * NT - (MT + NT), 0);
+      } else {
+        __builtin_amdgcn_sched_group_barrier(0x008, MT * NT, 0);
+      }
     }
   }
 #undef CFDETR_ISSUE_SLAB
