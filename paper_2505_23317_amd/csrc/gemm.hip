@@ -1953,13 +1953,14 @@ int cu_count() {
   return cus;
 }
 
-// Tile choice by problem size: 256x256 (8 wavefronts, 128x64 each) for wide outputs
-// over many rows, 128x128 (4 wavefronts, 64x64 each) while that still yields a
-// workgroup per CU, else 64x64.  The rows that count are the likely ones: with the row
-// count on the device (m_ptr), m_host > 0 is the caller's estimate of it (the kernels do
-// not read it) and the capacity stands in otherwise.  A CU holds one 256-tile or two
-// 128-tiles; a 256-tile is four times the work and takes about 1.8 times as long as a
-// pair of 128-tiles, so what decides at a few rounds is how full the last round is.
+// Tile choice by problem size: 256x256 (8 wavefronts, 128x64 each) or 192x256 (96x64
+// each) for wide outputs over many rows, 128x128 (4 wavefronts, 64x64 each) while that
+// still yields a workgroup per CU, else 64x64.  The rows that count are the likely ones:
+// with the row count on the device (m_ptr), m_host > 0 is the caller's estimate of it (the
+// kernels do not read it) and the capacity stands in otherwise.  A CU holds one large tile
+// or two 128-tiles; a 256-tile is four times the work of a 128-tile and takes about 1.8
+// times as long as a pair of them, a 192x256 tile 1.45 times, so what decides at a few
+// rounds is how full the last round is: the estimate is rounds x time per round.
 template <typename EP>
 hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& ep,
                          const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
@@ -1970,11 +1971,27 @@ hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& e
   const long cus = cu_count();
   const long tiles128 = (long)((m + 127) / 128) * (N / 128);
   const long tiles256 = (long)((m + 255) / 256) * (N / 256);
+  const long tiles192 = (long)((m + 191) / 192) * (N / 256);
   const long rounds128 = (tiles128 + 2 * cus - 1) / (2 * cus), rounds256 = (tiles256 + cus - 1) / cus;
+  const long rounds192 = (tiles192 + cus - 1) / cus;
   // A deeper ring (3 or 4 buffers, also with slabs of 32) measured no faster for these
   // tiles: their main loops are bound by LDS traffic, not by the latency of the loads.
-  if (N % 256 == 0 && m >= 8192 && 9 * rounds256 <= 5 * rounds128)
+#ifdef CFDETR_TILE_OVERRIDE
+  // a development harness sets the tile: 256, 192, 128 (0: the rule below)
+  if (CFDETR_TILE_OVERRIDE == 256 && N % 256 == 0)
     return launch_direct_tile<256, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+  if (CFDETR_TILE_OVERRIDE == 192 && N % 256 == 0)
+    return launch_direct_tile<192, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+  if (CFDETR_TILE_OVERRIDE == 128)
+    return launch_direct_tile<128, 128, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+#endif
+  if (N % 256 == 0 && m >= 8192) {
+    const long t256 = 180 * rounds256, t192 = 145 * rounds192, t128 = 100 * rounds128;
+    if (t192 < t256 && t192 <= t128)
+      return launch_direct_tile<192, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+    if (t256 <= t128)
+      return launch_direct_tile<256, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+  }
   if (N % 128 == 0 && tiles128 >= cus)
     return launch_direct_tile<128, 128, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
   return launch_direct_tile<64, 64, 2, 2, 4, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
