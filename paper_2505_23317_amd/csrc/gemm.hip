@@ -330,6 +330,15 @@ struct EpiEmbed {
   }
 };
 
+// The patch embedding contracts K in two halves and adds them (first + second) whenever K
+// is a multiple of 128, in every form of the kernel: small problems give the halves to two
+// groups of wavefronts, and a token must come out the same, bit for bit, whichever form
+// embedded it (the coarse-stage result is reused for the coarse tokens of the mixed batch).
+template <typename EP>
+struct SumHalves { static constexpr bool value = false; };
+template <>
+struct SumHalves<EpiEmbed> { static constexpr bool value = true; };
+
 // Maps a workgroup id to a tile id such that each of the 8 XCDs (workgroups are dealt
 // to them round-robin) works on a contiguous run of tiles and its L2 sees the same
 // activation rows again and again.
@@ -444,8 +453,8 @@ __device__ __forceinline__ int lds_row_key(int r) {
 #define CFDETR_GTL(i_)
 #endif
 
-template <int BM, int BN, int NWM, int NWN, int kStages, int BKT, typename AROWS, typename EP>
-__global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
+template <int BM, int BN, int NWM, int NWN, int kStages, int BKT, typename AROWS, typename EP, int KS = 1>
+__global__ __launch_bounds__(64 * NWM * NWN * KS) void gemm_bf16_direct_kernel(
     AROWS arows, const bf16_t* __restrict__ W, int N, int K, EP ep,
     const int32_t* __restrict__ m_ptr, int m_host) {
   constexpr int NW = NWM * NWN;
@@ -460,6 +469,12 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   static_assert(BKT == 32 || BKT == 64, "slab width");
   static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile / wavefront mismatch");
   static_assert(kStages >= 2 && kStages <= 4 && (kStages - 2) * LPW < 64, "ring depth");
+  // KS = 2: a second group of wavefronts with a ring of its own contracts the second half
+  // of K for the same tile, and the halves are added (first + second) at the end.  For
+  // problems of fewer tiles than CUs, where a wavefront per SIMD leaves every unit idle
+  // most of the time.  K must be a multiple of 2 BKT.
+  static_assert(KS == 1 || (KS == 2 && MT * NT == 1 && kStages == 4 && BKT == 64 && EP::kStageElem == 0),
+                "K split: single-tile wavefronts, direct epilogue");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_direct[];
   CFDETR_GTL(0);
 
@@ -472,7 +487,9 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   const int n0 = (pid % n_blocks) * BN;
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
+  const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
+  const int grp = KS == 1 ? 0 : wave_all / NW;   // which part of K
+  const int wave = KS == 1 ? wave_all : wave_all % NW;
   const int wm = wave / NWN, wn = wave % NWN;
   // Loader role: a wave instruction fills RPI consecutive LDS rows (1 KB).  Lane ->
   // (row lane/CPR of the group, LDS chunk position lane%CPR) and fetches the logical
@@ -499,7 +516,8 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     wvo[j] = ((uint32_t)(n0 + rt) * (uint32_t)K + (uint32_t)((lpos ^ lds_row_key<ROWB>(rt)) * 8)) * 2u;
   }
   // the low half of a flat pointer into LDS is the LDS address
-  const uint32_t lds0 = (uint32_t)(uintptr_t)smem_direct;
+  unsigned char* const ring = smem_direct + grp * (kStages * STAGE);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)ring;
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -510,7 +528,21 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int l32 = lane & 31, g = lane >> 5;
-  const int nk = K / BKT;
+  const int nk = K / (BKT * KS);
+  const int kbase = grp * nk * BKT;   // first k of this group's part
+  // one group and two halves: the sums so far are set aside in front of slab it_half
+  constexpr bool kHalves = SumHalves<EP>::value && KS == 1;
+  const int it_half = (kHalves && K % (2 * BKT) == 0) ? nk / 2 : -1;
+  f32x16 lo[kHalves ? MT : 1][kHalves ? NT : 1];
+#define CFDETR_SET_ASIDE(it_)                                                  \
+  if (kHalves && (it_) == it_half) {                                           \
+    _Pragma("unroll") for (int i = 0; i < MT; ++i)                             \
+    _Pragma("unroll") for (int j = 0; j < NT; ++j)                             \
+    _Pragma("unroll") for (int r = 0; r < 16; ++r) {                           \
+      lo[kHalves ? i : 0][kHalves ? j : 0][r] = acc[i][j][r];                  \
+      acc[i][j][r] = 0.f;                                                      \
+    }                                                                          \
+  }
 
   // What the epilogue needs per row and per column is requested now and arrives while
   // the main loop runs.  Result layout (transposed product): lane -> row l32 of each
@@ -532,8 +564,9 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
   // wavefront's reads of the buffer the next issue overwrites.
 #define CFDETR_ISSUE_SLAB(k0_, buf_)                                                          \
   do {                                                                                        \
-    const unsigned char* ab_ = arows.base() + arows.slab_off(k0_);                            \
-    const unsigned char* wb_ = reinterpret_cast<const unsigned char*>(W) + (size_t)(k0_) * 2; \
+    const unsigned char* ab_ = arows.base() + arows.slab_off(kbase + (k0_));                  \
+    const unsigned char* wb_ =                                                                \
+        reinterpret_cast<const unsigned char*>(W) + (size_t)(kbase + (k0_)) * 2;              \
     const uint32_t st_ = lds0 + (buf_) * STAGE;                                               \
     _Pragma("unroll") for (int j = 0; j < A_INST; ++j)                                        \
         dma16_untracked_s(ab_, avo[j], st_ + (wave * A_INST + j) * 1024);                     \
@@ -566,7 +599,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     }
     bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
     auto read_slab = [&](int b, bf16x8(&fa)[4], bf16x8(&fb)[4]) {
-      const unsigned char* p = smem_direct + b * STAGE;
+      const unsigned char* p = ring + b * STAGE;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         fa[ks] = *reinterpret_cast<const bf16x8*>(p + oa[ks]);
@@ -574,6 +607,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
       }
     };
     auto step = [&](int it, bf16x8(&ca)[4], bf16x8(&cb)[4], bf16x8(&na)[4], bf16x8(&nb)[4]) {
+      CFDETR_SET_ASIDE(it)
       if (it + 2 < nk)
         __builtin_amdgcn_s_waitcnt(0x0F70 | (LPW & 15) | ((LPW >> 4) << 14));
       else
@@ -584,7 +618,7 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
       // the MFMA before them runs, and the one wait for operands (ahead of the first MFMA)
       // finds only reads that are a whole step old
       // (behind the last slab they read a buffer that holds nothing new: never used)
-      const unsigned char* p = smem_direct + ((it + 1) & 3) * STAGE;
+      const unsigned char* p = ring + ((it + 1) & 3) * STAGE;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cb[ks], ca[ks], acc[0][0], 0, 0, 0);
@@ -614,7 +648,21 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
       if (it + 1 < nk) step(it + 1, fa1, fb1, fa0, fb0);
     }
   }
+  if constexpr (KS == 2) {
+    // the second group's sums cross through its ring (free now), register by register
+    __syncthreads();
+    float* const xs = reinterpret_cast<float*>(smem_direct + kStages * STAGE) + wave * (16 * 64) + lane;
+    if (grp == 1) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) xs[r * 64] = acc[0][0][r];
+    }
+    __syncthreads();
+    if (grp == 1) return;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[0][0][r] += xs[r * 64];
+  }
   for (int it = 0; !kChain && it < nk; ++it) {
+    CFDETR_SET_ASIDE(it)
     const int ahead = min(kStages - 2, nk - 1 - it);   // later slabs that may stay in flight
     if (kStages == 4 && ahead >= 2)
       __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * LPW) & 15) | (((2 * LPW) >> 4) << 14));
@@ -671,6 +719,16 @@ __global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_direct_kernel(
     }
   }
 #undef CFDETR_ISSUE_SLAB
+#undef CFDETR_SET_ASIDE
+  if (kHalves && it_half >= 0) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          acc[i][j][r] = lo[kHalves ? i : 0][kHalves ? j : 0][r] + acc[i][j][r];
+  }
   CFDETR_GTL(3);
 
   // Epilogue, one 32-row tile of the wavefront at a time.  With a row per lane a store
@@ -1924,19 +1982,20 @@ hipError_t allow_lds(Kern kern, size_t bytes, bool* configured) {
   return e;
 }
 
-template <int BM, int BN, int NWM, int NWN, int S, int BKT, typename AROWS, typename EP>
+template <int BM, int BN, int NWM, int NWN, int S, int BKT, int KS = 1, typename AROWS, typename EP>
 hipError_t launch_direct_tile(const AROWS& a, const bf16_t* w, int N, int K, const EP& ep,
                               const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
-  auto kern = gemm_bf16_direct_kernel<BM, BN, NWM, NWN, S, BKT, AROWS, EP>;
+  auto kern = gemm_bf16_direct_kernel<BM, BN, NWM, NWN, S, BKT, AROWS, EP, KS>;
+  if (K % (BKT * KS) != 0) return hipErrorInvalidValue;
   // the kernel addresses the weights with 32-bit byte offsets (the rows: see the callers)
   if ((size_t)N * K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
-  constexpr size_t lds = (size_t)S * (BM + BN) * BKT * 2;
+  constexpr size_t lds = (size_t)KS * S * (BM + BN) * BKT * 2;
   static_assert(lds <= 160 * 1024, "ring exceeds the LDS");
   static bool configured = false;
   hipError_t e = allow_lds(kern, lds, &configured);
   if (e != hipSuccess) return e;
   dim3 grid(((m_capacity + BM - 1) / BM) * (N / BN));
-  hipLaunchKernelGGL(kern, grid, dim3(64 * NWM * NWN), lds, s, a, w, N, K, ep, m_ptr, m_host);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * NWM * NWN * KS), lds, s, a, w, N, K, ep, m_ptr, m_host);
   return hipSuccess;
 }
 
@@ -2171,8 +2230,12 @@ hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, in
     // the coarse grid has a row count the host knows; the finer levels only a capacity
     const int m_likely = m_ptr ? m_capacity : m_host;
     const long tiles128 = (long)((m_likely + 127) / 128) * (d / 128);
+    const long tiles64 = (long)((m_likely + 63) / 64) * (d / 64);
     if (d % 128 == 0 && tiles128 >= 256)
       e = launch_direct_tile<128, 128, 2, 2, 2, 64>(rows, wb, d, K, ep, m_ptr, m_host, m_capacity, s);
+    else if (tiles64 <= cu_count() && K % 128 == 0)
+      // a workgroup per CU at most: two groups of wavefronts share the contraction of a tile
+      e = launch_direct_tile<64, 64, 2, 2, 4, 64, 2>(rows, wb, d, K, ep, m_ptr, m_host, m_capacity, s);
     else
       e = launch_direct_tile<64, 64, 2, 2, 4, 64>(rows, wb, d, K, ep, m_ptr, m_host, m_capacity, s);
   } else if (a.image_is_bf16) {
