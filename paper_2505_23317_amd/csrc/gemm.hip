@@ -2233,8 +2233,9 @@ hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, in
     const long tiles64 = (long)((m_likely + 63) / 64) * (d / 64);
     if (d % 128 == 0 && tiles128 >= 256)
       e = launch_direct_tile<128, 128, 2, 2, 2, 64>(rows, wb, d, K, ep, m_ptr, m_host, m_capacity, s);
-    else if (tiles64 <= cu_count() && K % 128 == 0)
-      // a workgroup per CU at most: two groups of wavefronts share the contraction of a tile
+    else if ((tiles64 <= cu_count() || K >= 6144) && K % 128 == 0)
+      // a workgroup per CU at most, or a very long contraction (patches of 64 x 64): two
+      // groups of wavefronts share the contraction of a tile
       e = launch_direct_tile<64, 64, 2, 2, 4, 64, 2>(rows, wb, d, K, ep, m_ptr, m_host, m_capacity, s);
     else
       e = launch_direct_tile<64, 64, 2, 2, 4, 64>(rows, wb, d, K, ep, m_ptr, m_host, m_capacity, s);
