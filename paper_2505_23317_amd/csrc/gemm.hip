@@ -9,16 +9,18 @@
 // 4 packed values) and row validity is a per-lane question.
 //
 // Two bf16 kernels share that orientation:
-//  * gemm_bf16_direct_kernel: activations x weights.  K-slabs of 64 go from global
-//    memory straight into LDS (global_load_lds, 16 bytes per lane, no VGPR round
-//    trip), double-buffered, one barrier per slab.  LDS rows are 128 bytes,
-//    unpadded; the 16-byte chunks of row r are stored at position chunk ^ ((r/2) & 7),
-//    which keeps the operand reads of 16 consecutive rows (what one LDS cycle serves)
-//    on disjoint banks.  The swizzle costs nothing: the lane that fills LDS position
-//    p of row r simply fetches logical chunk p ^ ((r/2) & 7) from global memory.
-//  * gemm_bf16_gather_kernel: the patch embedding as an implicit-im2col GEMM.  The
-//    A rows are pixels gathered patch by patch (bf16 or fp32 frames), staged through
-//    registers into padded LDS rows.
+//  * gemm_bf16_direct_kernel: activations x weights, and the patch embedding of bf16
+//    frames (the A rows are then patch pixels: an implicit im2col).  K-slabs of 64 go
+//    from global memory straight into LDS (global_load_lds, 16 bytes per lane, no VGPR
+//    round trip) through a ring of two or four buffers, one barrier per slab.  LDS rows
+//    are 128 bytes, unpadded; the 16-byte chunks of row r are stored at position
+//    chunk ^ ((r/2) & 7), which keeps the operand reads of 16 consecutive rows (what
+//    one LDS cycle serves) on disjoint banks.  The swizzle costs nothing: the lane that
+//    fills LDS position p of row r simply fetches logical chunk p ^ ((r/2) & 7) from
+//    global memory.
+//  * gemm_bf16_gather_kernel: the patch embedding of fp32 frames.  The A rows are
+//    pixels gathered patch by patch, converted and staged through registers into
+//    padded LDS rows.
 // A workgroup -> tile mapping that gives each XCD (own L2) a contiguous run of tiles,
 // M read from device memory (grids are sized for the capacity; surplus workgroups
 // leave at once), and an all-fp32 kernel for the check mode complete the file.
