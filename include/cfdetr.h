@@ -256,6 +256,21 @@ CFDETR_API cfdetr_status cfdetr_select_fine(cfdetr_ctx* ctx, const int32_t* boxe
                                  void* hip_stream);
 
 /*
+ * cfdetr_select_fine with the outcome of the difficulty test (Sec. III-B, A1: an easy
+ * frame is done after the coarse stage and its fine-grained processing is skipped).
+ *   hard  [B] int32 (device), as cfdetr_propose_rois writes it: a frame with hard[f] == 0
+ *         gets no token at all: cu_seqlens[f+1] == cu_seqlens[f], its level_counts are 0,
+ *         and cfdetr_fine_encode computes and writes nothing for it.
+ * Everything else as in cfdetr_select_fine (which keeps such a frame in the batch as a
+ * coarse-only token set, whose result equals its coarse result).
+ */
+CFDETR_API cfdetr_status cfdetr_select_fine_hard(cfdetr_ctx* ctx, const int32_t* boxes,
+                                      const uint8_t* tier, const int32_t* box_offsets,
+                                      const int32_t* hard, int32_t B, int32_t* tok_desc,
+                                      int32_t* cu_seqlens, int32_t* level_counts,
+                                      void* hip_stream);
+
+/*
  * A2 + A3, encoder over the mixed-granularity token sets as one variable-length
  * batch (Sec. III-B, A2 "reuse the coarse-stage tokens", A3 patch-level batch).
  *   images, B    as in cfdetr_coarse_encode
@@ -263,7 +278,11 @@ CFDETR_API cfdetr_status cfdetr_select_fine(cfdetr_ctx* ctx, const int32_t* boxe
  *   x0_cache     [B*N0, d] fp32 from cfdetr_coarse_encode on the same frames:
  *                level-0 tokens are copied from it; NULL embeds them again
  *   y_mixed      [max_tokens_total, d] fp32 out; rows past cu_seqlens[B] untouched
- * Attention stays inside [cu_seqlens[i], cu_seqlens[i+1]) for every frame i.
+ * Attention stays inside [cu_seqlens[i], cu_seqlens[i+1]) for every frame i.  A frame may
+ * have no token (cu_seqlens[i+1] == cu_seqlens[i]): nothing is computed for it.
+ * The offsets are checked on the device before anything reads them: a negative length
+ * or a total above max_tokens_total makes the call compute and write nothing, and
+ * cfdetr_sync_status reports CFDETR_ECAPACITY.
  */
 CFDETR_API cfdetr_status cfdetr_fine_encode(cfdetr_ctx* ctx, const void* images, int32_t B,
                                  const int32_t* tok_desc, const int32_t* cu_seqlens,
@@ -280,7 +299,9 @@ CFDETR_API cfdetr_status cfdetr_fine_encode(cfdetr_ctx* ctx, const void* images,
  *   y_padded  [B * t_pad, d] fp32 out: row f*t_pad + j is token j of frame f; rows of
  *             padding hold finite values without meaning
  * A frame longer than t_pad raises the sticky capacity flag (cfdetr_sync_status) and its
- * surplus tokens are ignored.  Other arguments as in cfdetr_fine_encode.
+ * surplus tokens are ignored; a frame without tokens raises it too (the padded form has
+ * no place for one) and its rows hold values without meaning.  Other arguments as in
+ * cfdetr_fine_encode.
  */
 CFDETR_API cfdetr_status cfdetr_fine_encode_padded(cfdetr_ctx* ctx, const void* images, int32_t B,
                                         const int32_t* tok_desc, const int32_t* cu_seqlens,
@@ -365,8 +386,9 @@ CFDETR_API cfdetr_status cfdetr_decoder_attach(cfdetr_ctx* ctx, const cfdetr_dec
  *               cu_seqlens[i] .. cu_seqlens[i+1]; T <= max_tokens_total
  *   cu_seqlens  [B+1] int32 (device), cu_seqlens[0] = 0, every frame at least one token.
  *               Checked on the device: a frame without tokens or a total above
- *               max_tokens_total makes the attention kernels do nothing, leaves `queries`
- *               undefined, and cfdetr_sync_status reports CFDETR_ECAPACITY.
+ *               max_tokens_total makes the call read no token and the attention kernels do
+ *               nothing, leaves `queries` undefined, and cfdetr_sync_status reports
+ *               CFDETR_ECAPACITY.
  *   queries     [B, Q, 5] fp32 out: (cx, cy, w, h, c), the form cfdetr_propose_rois takes
  * Uses the context's encoder work space as scratch: a later encode call overwrites it,
  * and an encode call in flight on another stream must not overlap.

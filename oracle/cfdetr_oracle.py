@@ -104,17 +104,25 @@ def select_frame(boxes: np.ndarray, tier: np.ndarray, H: int, W: int,
 
 
 def select_fine(boxes: np.ndarray, tier: np.ndarray, box_offsets: np.ndarray,
-                B: int, H: int, W: int, patch: Sequence[int]):
+                B: int, H: int, W: int, patch: Sequence[int],
+                hard: Optional[np.ndarray] = None):
     """A2 over a batch: token table, per-frame offsets, per-level counts.
 
     Returns (tok int64 [T,3] rows (level,row,col), cu_seqlens int64 [B+1],
     level_counts int64 [B, n_levels]).  Frames are concatenated in batch order.
+
+    ``hard`` (optional, one flag per frame) is the outcome of the difficulty test of
+    A1 (Sec. III-B): an easy frame is finished after the coarse stage, its fine-grained
+    processing is skipped, so it contributes no token at all.
     """
     n = len(patch)
     toks: List[Tuple[int, int, int]] = []
     cu = [0]
     counts = np.zeros((B, n), dtype=np.int64)
     for i in range(B):
+        if hard is not None and not hard[i]:
+            cu.append(len(toks))
+            continue
         lo, hi = int(box_offsets[i]), int(box_offsets[i + 1])
         leaves = select_frame(boxes[lo:hi], tier[lo:hi], H, W, patch)
         for (lvl, _, _) in leaves:

@@ -31,6 +31,7 @@ STATUS_NAMES = ["OK", "EINVAL", "ESHAPE", "ECAPACITY", "ENOMEM", "EDEVICE"]
 EXPORTS = [
     "cfdetr_create", "cfdetr_destroy", "cfdetr_last_error", "cfdetr_workspace_bytes",
     "cfdetr_sync_status", "cfdetr_coarse_encode", "cfdetr_propose_rois", "cfdetr_select_fine",
+    "cfdetr_select_fine_hard",
     "cfdetr_fine_encode", "cfdetr_fine_encode_padded",
     "cfdetr_multilevel_batch", "cfdetr_profile_begin", "cfdetr_profile_end",
     "cfdetr_sched_response_times", "cfdetr_sched_coarse_batch", "cfdetr_sched_fine_batches",
@@ -118,6 +119,8 @@ def load_library() -> ctypes.CDLL:
     lib.cfdetr_propose_rois.restype = ctypes.c_int
     lib.cfdetr_select_fine.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.cfdetr_select_fine.restype = ctypes.c_int
+    lib.cfdetr_select_fine_hard.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.cfdetr_select_fine_hard.restype = ctypes.c_int
     lib.cfdetr_fine_encode.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
     lib.cfdetr_fine_encode.restype = ctypes.c_int
     lib.cfdetr_fine_encode_padded.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp, vp]
@@ -219,6 +222,12 @@ def cfdetr_select_fine(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, l
                        stream=0) -> None:
     _check(load_library().cfdetr_select_fine(ctx, boxes, tier, box_offsets, B, tok_desc,
                                              cu_seqlens, level_counts, stream), ctx)
+
+
+def cfdetr_select_fine_hard(ctx, boxes, tier, box_offsets, hard, B, tok_desc, cu_seqlens,
+                            level_counts, stream=0) -> None:
+    _check(load_library().cfdetr_select_fine_hard(ctx, boxes, tier, box_offsets, hard, B, tok_desc,
+                                                  cu_seqlens, level_counts, stream), ctx)
 
 
 def cfdetr_fine_encode(ctx, images, B, tok_desc, cu_seqlens, x0_cache, y_mixed, stream=0) -> None:
@@ -456,6 +465,13 @@ class Encoder:
                            tok_desc.data_ptr(), cu_seqlens.data_ptr(),
                            level_counts.data_ptr() if level_counts is not None else None,
                            self._stream())
+
+    def select_fine_hard(self, boxes, tier, box_offsets, hard, B, tok_desc, cu_seqlens,
+                         level_counts=None):
+        cfdetr_select_fine_hard(self.ctx, boxes.data_ptr(), tier.data_ptr(), box_offsets.data_ptr(),
+                                hard.data_ptr(), B, tok_desc.data_ptr(), cu_seqlens.data_ptr(),
+                                level_counts.data_ptr() if level_counts is not None else None,
+                                self._stream())
 
     def fine_encode(self, images, B, tok_desc, cu_seqlens, x0_cache, y_mixed):
         cfdetr_fine_encode(self.ctx, images.data_ptr(), B, tok_desc.data_ptr(),

@@ -253,7 +253,8 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
     m_hint = *static_cast<volatile int32_t*>(m_seen);
   }
   if (!plan_done)   // (the selection kernel of a merged run has made the plan already)
-    CF_LAUNCH(CFDETR_K_PLAN, launch_plan(cu, B, encoder_plan(ctx, n_prefix), s));
+    CF_LAUNCH(CFDETR_K_PLAN, launch_plan(cu, B, encoder_plan(ctx, n_prefix), s,
+                                         m_cap - n_prefix * ctx->n0, 0, ctx->err_flag));
   if (m_seen) {
     hipError_t e = hipMemcpyAsync(m_seen, ctx->m_all, 4, hipMemcpyDeviceToHost, s);
     if (e != hipSuccess) return fail_hip(ctx, "copy of the row count", e);
@@ -372,14 +373,14 @@ cfdetr_status coarse_impl(cfdetr_ctx* ctx, const void* images, int B, float* x0_
 cfdetr_status select_impl(cfdetr_ctx* ctx, const int32_t* boxes, const uint8_t* tier,
                           const int32_t* box_offsets, int B, int32_t* tok_desc,
                           int32_t* cu_seqlens, int32_t* level_counts, hipStream_t s,
-                          const PlanArgs* plan = nullptr) {
+                          const PlanArgs* plan = nullptr, const int32_t* hard = nullptr) {
   uint8_t* cur = ctx->hit[ctx->parity];
   uint8_t* next = ctx->hit[ctx->parity ^ 1];
   ctx->parity ^= 1;
   CF_LAUNCH(CFDETR_K_SELECT,
             launch_select(ctx->pyr, boxes, tier, box_offsets, B, ctx->nonfinest, cur, next,
                           ctx->hit_bytes, ctx->cfg.max_tokens_total, tok_desc, cu_seqlens, level_counts,
-                          ctx->err_flag, s, plan));
+                          ctx->err_flag, s, plan, hard));
   return CFDETR_OK;
 }
 
@@ -407,9 +408,14 @@ cfdetr_status fine_embed(cfdetr_ctx* ctx, const void* images, int B, const int32
 cfdetr_status fine_impl(cfdetr_ctx* ctx, const void* images, int B, const int32_t* tok_desc,
                         const int32_t* cu, const float* x0_cache, float* y_mixed,
                         hipStream_t s) {
-  cfdetr_status st = fine_embed(ctx, images, B, tok_desc, cu, x0_cache, 0, s);
+  // The offsets are the caller's: the plan checks them first (a bad length or a total beyond
+  // the capacity empties the run and raises the error flag), and every kernel after it,
+  // the embedding included, reads the checked copy.
+  const int cap = ctx->cfg.max_tokens_total;
+  CF_LAUNCH(CFDETR_K_PLAN, launch_plan(cu, B, encoder_plan(ctx, 0), s, cap, 0, ctx->err_flag));
+  cfdetr_status st = fine_embed(ctx, images, B, tok_desc, ctx->cu_all, x0_cache, 0, s);
   if (st != CFDETR_OK) return st;
-  return run_encoder(ctx, cu, B, 0, ctx->cfg.max_tokens_total, y_mixed, 0, nullptr, s);
+  return run_encoder(ctx, ctx->cu_all, B, 0, cap, y_mixed, 0, nullptr, s, nullptr, true);
 }
 
 // A3 as the paper states it: every frame's token set brought to t_pad tokens (repeats of
@@ -418,8 +424,11 @@ cfdetr_status fine_impl(cfdetr_ctx* ctx, const void* images, int B, const int32_
 cfdetr_status padded_impl(cfdetr_ctx* ctx, const void* images, int B, const int32_t* tok_desc,
                           const int32_t* cu, const float* x0_cache, int t_pad, float* y_padded,
                           hipStream_t s) {
-  CF_LAUNCH(CFDETR_K_SELECT, launch_pad_tokens(tok_desc, cu, B, t_pad, ctx->tok_pad, ctx->cu_pad,
-                                               ctx->kv_len, ctx->err_flag, s));
+  // the caller's offsets are checked first (as in fine_impl); the padding reads the checked copy
+  CF_LAUNCH(CFDETR_K_PLAN, launch_plan(cu, B, encoder_plan(ctx, 0), s, ctx->cfg.max_tokens_total, 0,
+                                       ctx->err_flag));
+  CF_LAUNCH(CFDETR_K_SELECT, launch_pad_tokens(tok_desc, ctx->cu_all, B, t_pad, ctx->tok_pad,
+                                               ctx->cu_pad, ctx->kv_len, ctx->err_flag, s));
   cfdetr_status st = fine_embed(ctx, images, B, ctx->tok_pad, ctx->cu_pad, x0_cache, 0, s);
   if (st != CFDETR_OK) return st;
   return run_encoder(ctx, ctx->cu_pad, B, 0, B * t_pad, y_padded, 0, nullptr, s, ctx->kv_len);
@@ -442,7 +451,7 @@ cfdetr_status decode_impl(cfdetr_ctx* ctx, const float* memory, const int32_t* c
   {
     PlanArgs p = encoder_plan(ctx, 0);
     p.n_heads_q = 8;
-    CF_LAUNCH(CFDETR_K_PLAN, launch_plan(cu, B, p, s, cap_m, ctx->err_flag, nullptr));
+    CF_LAUNCH(CFDETR_K_PLAN, launch_plan(cu, B, p, s, cap_m, 1, ctx->err_flag, nullptr));
   }
   CF_LAUNCH(CFDETR_K_DEC, launch_cast_bf16(memory, ctx->a, d, ctx->m_all, cap_m, s));
   // query sequences: B times Q rows, work list for both attentions of every layer
@@ -458,7 +467,7 @@ cfdetr_status decode_impl(cfdetr_ctx* ctx, const float* memory, const int32_t* c
     p.queue_heads = ctx->dqueue;
     p.n_heads_q = 16 * L;
     p.queue_start = ctx->dgrid / 8;
-    CF_LAUNCH(CFDETR_K_PLAN, launch_plan(ctx->dcu, B, p, s, 0, nullptr, ctx->err_flag));
+    CF_LAUNCH(CFDETR_K_PLAN, launch_plan(ctx->dcu, B, p, s, 0, 0, nullptr, ctx->err_flag));
   }
   CF_LAUNCH(CFDETR_K_DEC, launch_broadcast_rows(w.query_embed, ctx->dx, Q, d, B, s));
   // The tokens' keys and values for the cross-attention of every layer depend on the tokens
@@ -862,6 +871,20 @@ CFDETR_API cfdetr_status cfdetr_select_fine(cfdetr_ctx* ctx, const int32_t* boxe
   if (!aligned16(boxes)) return fail(ctx, CFDETR_EINVAL, "boxes must be 16-byte aligned");
   return select_impl(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts,
                      static_cast<hipStream_t>(hip_stream));
+}
+
+CFDETR_API cfdetr_status cfdetr_select_fine_hard(cfdetr_ctx* ctx, const int32_t* boxes,
+                                      const uint8_t* tier, const int32_t* box_offsets,
+                                      const int32_t* hard, int32_t B, int32_t* tok_desc,
+                                      int32_t* cu_seqlens, int32_t* level_counts,
+                                      void* hip_stream) {
+  cfdetr_status st = check_call(ctx, B);
+  if (st != CFDETR_OK) return st;
+  if (!boxes || !tier || !box_offsets || !hard || !tok_desc || !cu_seqlens)
+    return fail(ctx, CFDETR_EINVAL, "null pointer");
+  if (!aligned16(boxes)) return fail(ctx, CFDETR_EINVAL, "boxes must be 16-byte aligned");
+  return select_impl(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts,
+                     static_cast<hipStream_t>(hip_stream), nullptr, hard);
 }
 
 CFDETR_API cfdetr_status cfdetr_fine_encode(cfdetr_ctx* ctx, const void* images, int32_t B,

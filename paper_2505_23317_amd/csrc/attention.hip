@@ -216,6 +216,28 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
       if (it + 1 < n_kv) CFDETR_ATTN_ISSUE(kv0 + kBlockKV, b ^ 1);
       const unsigned char* cK = b ? sK1 : sK0;
       const unsigned char* cV = b ? sV1 : sV0;
+      if (kv0 + kBlockKV > TK) {
+        // Last, ragged tile (no fill is in flight any more): the V^T positions past the end
+        // of the sequence are padding that nothing in this run wrote.  They only meet
+        // probabilities that are exactly 0, but 0 * NaN is NaN, so they are cleared here:
+        // whatever an earlier run left there cannot reach a result.
+        unsigned char* wV = b ? sV1 : sV0;
+        const int nvalid = TK - kv0;
+        for (int u = tid; u < DH * 8; u += 256) {
+          const int rho = u >> 3, c = u & 7;   // row (feature), logical chunk of 8 keys
+          const int n = nvalid - 8 * c;        // keys of this chunk inside the sequence
+          if (n < 8) {
+            uint4* q = reinterpret_cast<uint4*>(wV + rho * 128 + ((c ^ swz<128>(rho)) << 4));
+            uint4 w = *q;
+            uint32_t* e = reinterpret_cast<uint32_t*>(&w);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              e[j] &= (2 * j < n ? 0x0000FFFFu : 0u) | (2 * j + 1 < n ? 0xFFFF0000u : 0u);
+            *q = w;
+          }
+        }
+        __syncthreads();
+      }
 
       // S^T - m for the two 32-key sub-tiles; keys past the end of the frame (last tile
       // only) get -inf.

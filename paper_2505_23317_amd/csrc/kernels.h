@@ -21,6 +21,8 @@ struct PlanArgs {
 };
 
 // ---- A2 selection (select.hip) -------------------------------------------
+// hard       (may be null) [B]: a frame with hard[f] == 0 skips the fine stage and gets no
+//            token at all (length 0, counts 0).
 // hit        [B, nonfinest] bytes, all zero on entry: flag of every cell of the levels
 //            below the finest (level-major) that a box asking for a finer level
 //            overlaps; hit_next (hit_bytes long) is the array of the following call
@@ -29,7 +31,8 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
                          const int32_t* box_offsets, int B, int nonfinest, uint8_t* hit,
                          uint8_t* hit_next, int hit_bytes, int max_tokens, int32_t* tok_desc,
                          int32_t* cu_seqlens, int32_t* level_counts, int32_t* err_flag,
-                         hipStream_t s, const PlanArgs* plan = nullptr);
+                         hipStream_t s, const PlanArgs* plan = nullptr,
+                         const int32_t* hard = nullptr);
 
 // ---- A1 difficulty test + A2 region proposal (roi.hip) ----------------------
 // queries [B, Q, 5] = (cx, cy, w, h, c), centre and size as fractions of the frame.
@@ -73,12 +76,13 @@ hipError_t launch_pad_tokens(const int32_t* tok_desc, const int32_t* cu_seqlens,
 // that follow (eight per launch), to queue_start = (attention grid) / 8: the entries
 // before that are handed out by workgroup index; or to -1 for a queue with no entries
 // beyond those.
-// max_total > 0 checks offsets that a caller wrote: a length below 1, or a total above
-// max_total, cuts the lengths to what fits and sets *err_flag.  gate (may be null): if
+// max_total > 0 checks offsets that a caller wrote: a length below min_len, or a total above
+// max_total, gives every one of the B sequences length 0 (the run then computes and writes
+// nothing for them) and sets *err_flag.  gate (may be null): if
 // *gate is not 0 the work list comes out empty, so that the attention launches that
 // follow do nothing after an earlier kernel has raised the error flag.
 hipError_t launch_plan(const int32_t* cu_seqlens, int B, const PlanArgs& plan, hipStream_t s,
-                       int max_total = 0, int32_t* err_flag = nullptr,
+                       int max_total = 0, int min_len = 0, int32_t* err_flag = nullptr,
                        const int32_t* gate = nullptr);
 
 // ---- row-wise kernels (rowwise.hip) ----------------------------------------

@@ -131,7 +131,8 @@ __device__ __forceinline__ void plan_body(const PlanArgs& p, int nseq, const int
 }
 
 __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ cu, int B, PlanArgs p,
-                                                   int max_total, int32_t* __restrict__ err_flag,
+                                                   int max_total, int min_len,
+                                                   int32_t* __restrict__ err_flag,
                                                    const int32_t* __restrict__ gate) {
   __shared__ int s_len[2 * kMaxBatch];
   const int tid = threadIdx.x;
@@ -139,21 +140,22 @@ __global__ __launch_bounds__(256) void plan_kernel(const int32_t* __restrict__ c
   if (tid < nseq) s_len[tid] = tid < p.n_prefix ? p.prefix_len : cu[tid - p.n_prefix + 1] - cu[tid - p.n_prefix];
   __syncthreads();
   if (max_total > 0) {
-    // offsets a caller wrote: every length must be at least 1 and the total must fit;
-    // otherwise the lengths are cut to what fits and the error flag is raised
+    // offsets a caller wrote: every length must be at least min_len and the total must fit;
+    // otherwise the caller's sequences all get length 0 (nothing of them is computed or
+    // written) and the error flag is raised
     if (tid == 0) {
-      int pos = 0;
+      long long pos = 0;
       bool bad = false;
-      for (int i = 0; i < nseq; ++i) {
-        int len = s_len[i];
-        if (len < 1 || len > max_total - pos) {
-          bad = true;
-          len = max(0, min(len, max_total - pos));
-          s_len[i] = len;
-        }
-        pos += len;
+      for (int i = p.n_prefix; i < nseq; ++i) {
+        const int len = s_len[i];
+        if (len < min_len) bad = true;
+        pos += len > 0 ? len : 0;
       }
-      if (bad) *err_flag = 1;
+      if (pos > (long long)max_total) bad = true;
+      if (bad) {
+        for (int i = p.n_prefix; i < nseq; ++i) s_len[i] = 0;
+        *err_flag = 1;
+      }
     }
     __syncthreads();
   }
@@ -166,7 +168,7 @@ __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
     uint8_t* __restrict__ hit_next, int hit_bytes, int max_tokens,
     int32_t* __restrict__ tok_desc,
     int32_t* __restrict__ cu_seqlens, int32_t* __restrict__ level_counts,
-    int32_t* __restrict__ err_flag, PlanArgs plan) {
+    int32_t* __restrict__ err_flag, const int32_t* __restrict__ hard, PlanArgs plan) {
   __shared__ int s_split[kMaxBatch][kMaxLevels];   // hit cells per (frame, level)
   __shared__ int s_wave[kCompactThreads / kWave];
   // Workgroup B, if there is one (plan.items set), compacts nothing: the lengths that every
@@ -208,12 +210,13 @@ __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
     }
   }
   __syncthreads();
+  // A frame marked easy (hard given and 0 for it) has no fine stage: no token at all.
   long long total_tokens = 0;
   int base = 0;
   for (int j = 0; j < B; ++j) {
     int sj = 0;
     for (int l = 0; l + 1 < n; ++l) sj += s_split[j][l];
-    const int tj = pyr.rows[0] * pyr.cols[0] + 3 * sj;
+    const int tj = (hard != nullptr && hard[j] == 0) ? 0 : pyr.rows[0] * pyr.cols[0] + 3 * sj;
     if (j < frame) base += tj;
     total_tokens += tj;
   }
@@ -226,6 +229,7 @@ __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
         int sj = 0;
         for (int l = 0; l + 1 < n; ++l) sj += s_split[tid - plan.n_prefix][l];
         len = too_many ? 0 : pyr.rows[0] * pyr.cols[0] + 3 * sj;
+        if (hard != nullptr && hard[tid - plan.n_prefix] == 0) len = 0;
       }
       s_len[tid] = len;
     }
@@ -241,6 +245,7 @@ __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
     for (int i = lo + tid; i < hi; i += kCompactThreads) hit_next[i] = 0;
   }
   const bool overflow = total_tokens > (long long)max_tokens;
+  const bool skipped = hard != nullptr && hard[frame] == 0;
   if (tid == 0) {
     cu_seqlens[frame] = overflow ? 0 : base;
     if (frame == B - 1) cu_seqlens[B] = overflow ? 0 : (int)total_tokens;
@@ -249,9 +254,9 @@ __global__ __launch_bounds__(kCompactThreads) void select_compact_kernel(
   if (level_counts != nullptr && tid < n) {
     const int prev4 = tid == 0 ? pyr.rows[0] * pyr.cols[0] : 4 * s_split[frame][tid - 1];
     const int cur = (tid + 1 < n) ? s_split[frame][tid] : 0;
-    level_counts[frame * n + tid] = overflow ? 0 : prev4 - cur;
+    level_counts[frame * n + tid] = (overflow || skipped) ? 0 : prev4 - cur;
   }
-  if (overflow) return;
+  if (overflow || skipped) return;
 
   const uint8_t* fhit = hit + (size_t)frame * nonfinest;
   int running = base;
@@ -301,10 +306,12 @@ __global__ __launch_bounds__(256) void pad_tokens_kernel(const int32_t* __restri
   if (j == 0) {
     cu_pad[f] = f * t_pad;
     if (f == B - 1) cu_pad[B] = B * t_pad;
-    kv_len[f] = min(len, t_pad);
-    if (len > t_pad) *err_flag = 1;
+    // a frame without tokens cannot be padded (its keys would all be masked): it gets one
+    // key, the rows hold the first coarse cell, and the error flag is raised
+    kv_len[f] = max(min(len, t_pad), 1);
+    if (len > t_pad || len < 1) *err_flag = 1;
   }
-  if (j < t_pad) tok_pad[(size_t)f * t_pad + j] = tok_desc[t0 + min(j, len - 1)];
+  if (j < t_pad) tok_pad[(size_t)f * t_pad + j] = len > 0 ? tok_desc[t0 + min(j, len - 1)] : 0;
 }
 
 }  // namespace
@@ -321,7 +328,7 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
                          const int32_t* box_offsets, int B, int nonfinest, uint8_t* hit,
                          uint8_t* hit_next, int hit_bytes, int max_tokens, int32_t* tok_desc,
                          int32_t* cu_seqlens, int32_t* level_counts, int32_t* err_flag,
-                         hipStream_t s, const PlanArgs* plan) {
+                         hipStream_t s, const PlanArgs* plan, const int32_t* hard) {
   if (nonfinest > 0) {
     const int cells_per_block = kHitThreads / kBoxLanes;
     dim3 grid((nonfinest + cells_per_block - 1) / cells_per_block, B);
@@ -331,14 +338,14 @@ hipError_t launch_select(const Pyramid& pyr, const int32_t* boxes, const uint8_t
   PlanArgs none{};
   hipLaunchKernelGGL(select_compact_kernel, dim3(B + (plan ? 1 : 0)), dim3(kCompactThreads), 0, s,
                      pyr, B, nonfinest, hit, hit_next, hit_bytes, max_tokens, tok_desc, cu_seqlens,
-                     level_counts, err_flag, plan ? *plan : none);
+                     level_counts, err_flag, hard, plan ? *plan : none);
   return hipGetLastError();
 }
 
 hipError_t launch_plan(const int32_t* cu_seqlens, int B, const PlanArgs& plan, hipStream_t s,
-                       int max_total, int32_t* err_flag, const int32_t* gate) {
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, cu_seqlens, B, plan, max_total, err_flag,
-                     gate);
+                       int max_total, int min_len, int32_t* err_flag, const int32_t* gate) {
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, s, cu_seqlens, B, plan, max_total, min_len,
+                     err_flag, gate);
   return hipGetLastError();
 }
 

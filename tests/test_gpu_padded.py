@@ -102,3 +102,29 @@ def test_padded_form_errors(K):
                                enc.max_tokens // cfg.B + 1, y)
     assert e.value.status == K.CFDETR_ECAPACITY
     enc.close()
+
+
+def test_padded_form_reports_a_frame_without_tokens(K):
+    """A frame that skipped the fine stage has no token; the padded form has no place for an
+    empty frame (all of its keys would be masked): reported, and every row stays finite."""
+    import torch
+    cfg = synth.replace(synth.config(3), B=3, H=320, W=320, layers=1)
+    wl = synth.make_workload(cfg, seed=63)
+    enc = K.Encoder(cfg, wl["weights"], act_dtype="bf16")
+    img = enc.upload_images(wl["images"])
+    b, t, o = enc.upload_boxes(wl["boxes"], wl["tier"], wl["box_offsets"])
+    out = enc.alloc_outputs(cfg.B)
+    hard = torch.tensor([1, 0, 1], dtype=torch.int32, device="cuda")
+    enc.select_fine_hard(b, t, o, hard, cfg.B, out["tok_desc"], out["cu_seqlens"], None)
+    enc.sync_status()
+    cu = out["cu_seqlens"].cpu().numpy()
+    assert cu[2] == cu[1]
+    tp = int(np.diff(cu).max())
+    y = torch.zeros((cfg.B * tp, cfg.d), dtype=torch.float32, device="cuda")
+    _say(f"[case] padded form with an empty frame, lengths {np.diff(cu).tolist()} padded to {tp}")
+    enc.fine_encode_padded(img, cfg.B, out["tok_desc"], out["cu_seqlens"], None, tp, y)
+    with pytest.raises(K.CfdetrError) as e:
+        enc.sync_status()
+    assert e.value.status == K.CFDETR_ECAPACITY
+    assert np.isfinite(y.cpu().numpy()).all()
+    enc.close()

@@ -25,7 +25,15 @@ def _say(msg):
 
 
 def rel_err(g, r):
+    """The bar's metric: largest absolute deviation over the largest reference magnitude."""
     return float(np.abs(np.asarray(g, np.float64) - r).max() / np.abs(r).max())
+
+
+def rms_err(g, r):
+    """Root-mean-square deviation over the root-mean-square of the reference (reported beside
+    the bar's metric: it cannot be satisfied by a few large reference values)."""
+    g, r = np.asarray(g, np.float64), np.asarray(r, np.float64)
+    return float(np.sqrt(((g - r) ** 2).mean() / (r ** 2).mean()))
 
 
 @pytest.fixture(scope="module")
@@ -67,7 +75,9 @@ def check_all(got, ref, act, label):
     np.testing.assert_array_equal(got["tok_desc"][:T], ref["tok_desc"])
     ec = rel_err(got["y_coarse"], ref["y_coarse"])
     em = rel_err(got["y_mixed"][:T], ref["y_mixed"])
-    _say(f"[parity] {label} {act}: T={T} coarse {ec:.2e} mixed {em:.2e} (bar {TOL[act]:.0e})")
+    _say(f"[parity] {label} {act}: T={T} coarse {ec:.2e} mixed {em:.2e} (bar {TOL[act]:.0e}); "
+         f"rms-relative coarse {rms_err(got['y_coarse'], ref['y_coarse']):.2e} "
+         f"mixed {rms_err(got['y_mixed'][:T], ref['y_mixed']):.2e}")
     assert np.isfinite(got["y_mixed"][:T]).all()
     assert ec <= TOL[act], (label, act, ec)
     assert em <= TOL[act], (label, act, em)
@@ -440,4 +450,102 @@ def test_profile_interface_counts_launches(K):
     assert prof["select"]["launches"] == 1 and prof["gather"]["launches"] == 1
     assert prof["embed"]["launches"] == 2
     assert all(v["ms"] >= 0 for v in prof.values())
+    enc.close()
+
+
+# ------------------------------------------------------------------ offsets from the caller
+def test_fine_encode_rejects_offsets_beyond_the_capacity(K):
+    """cfdetr_fine_encode takes its offsets from the caller: a total above max_tokens_total, or
+    a negative length, must be reported by cfdetr_sync_status and must leave y untouched."""
+    import torch
+    cfg = synth.replace(synth.config(3), B=2, H=128, W=128, layers=1)
+    wl = synth.make_workload(cfg, seed=51)
+    for act in ("bf16", "fp32"):
+        enc = K.Encoder(cfg, wl["weights"], act_dtype=act, max_tokens_total=100)
+        img = enc.upload_images(wl["images"])
+        out = enc.alloc_outputs(cfg.B)
+        out["tok_desc"].zero_()                      # every entry a valid coarse cell
+        for bad in ([0, 60, 130], [0, 70, 60], [0, -5, 40]):
+            _say(f"[case] fine_encode with offsets {bad} on a context of 100 tokens, {act}")
+            out["y_mixed"].fill_(-7.0)
+            out["cu_seqlens"].copy_(torch.tensor(bad, dtype=torch.int32))
+            enc.fine_encode(img, cfg.B, out["tok_desc"], out["cu_seqlens"], None, out["y_mixed"])
+            with pytest.raises(K.CfdetrError) as ei:
+                enc.sync_status()
+            assert ei.value.status == K.CFDETR_ECAPACITY
+            assert (out["y_mixed"].cpu().numpy() == -7.0).all()
+        # the context keeps working: a total that just fits
+        out["cu_seqlens"].copy_(torch.tensor([0, 60, 100], dtype=torch.int32))
+        enc.fine_encode(img, cfg.B, out["tok_desc"], out["cu_seqlens"], None, out["y_mixed"])
+        enc.sync_status()
+        y = out["y_mixed"].cpu().numpy()
+        assert np.isfinite(y).all() and (y != -7.0).all()
+        enc.close()
+
+
+@pytest.mark.parametrize("act", ["fp32", "bf16"])
+def test_easy_frames_skip_the_fine_stage(K, act):
+    """Sec. III-B, A1: a frame found easy after the coarse stage has no fine stage.  With the
+    difficulty flags the selection gives such a frame no token and the fine pass computes
+    nothing for it; the other frames come out as without the flags."""
+    import torch
+    cfg = synth.replace(synth.config(3), B=4, H=320, W=320, layers=2)
+    wl = synth.make_workload(cfg, seed=53)
+    for hard in ([1, 0, 1, 0], [0, 1, 1, 1], [0, 0, 0, 0]):
+        _say(f"[case] easy-frame skip, hard = {hard}, {act}")
+        tok, cu, counts = O.select_fine(wl["boxes"], wl["tier"], wl["box_offsets"], cfg.B, cfg.H,
+                                        cfg.W, cfg.patch, hard=np.asarray(hard))
+        ref = O.fine_encode(wl["images"], tok, cu, cfg.patch, wl["weights"], cfg.heads)
+        enc = K.Encoder(cfg, wl["weights"], act_dtype=act)
+        img = enc.upload_images(wl["images"])
+        b, t, o = enc.upload_boxes(wl["boxes"], wl["tier"], wl["box_offsets"])
+        out = enc.alloc_outputs(cfg.B)
+        out["y_mixed"].fill_(-7.0)
+        h = torch.tensor(hard, dtype=torch.int32, device="cuda")
+        enc.coarse_encode(img, cfg.B, out["x0_cache"], out["y_coarse"])
+        enc.select_fine_hard(b, t, o, h, cfg.B, out["tok_desc"], out["cu_seqlens"],
+                             out["level_counts"])
+        enc.fine_encode(img, cfg.B, out["tok_desc"], out["cu_seqlens"], out["x0_cache"],
+                        out["y_mixed"])
+        enc.sync_status()
+        T = int(cu[-1])
+        np.testing.assert_array_equal(out["cu_seqlens"].cpu().numpy(), cu)
+        np.testing.assert_array_equal(out["level_counts"].cpu().numpy(), counts)
+        np.testing.assert_array_equal(out["tok_desc"].cpu().numpy()[:T], O.pack_tok_desc(tok))
+        y = out["y_mixed"].cpu().numpy()
+        assert (y[T:] == -7.0).all()
+        if T:
+            e = rel_err(y[:T], ref)
+            _say(f"[parity] easy-frame skip {hard} {act}: T={T} mixed {e:.2e} rms {rms_err(y[:T], ref):.2e}")
+            assert e <= TOL[act]
+        enc.close()
+
+
+def test_a_run_with_non_finite_values_does_not_poison_later_runs(K):
+    """The feature-major copy of V pads every sequence to a multiple of 64 positions, and the
+    padding moves with the sequence lengths.  Whatever a run leaves there (here: NaN from a
+    frame of NaN pixels) must not reach a later run on the same context."""
+    import torch
+    cfg = synth.replace(synth.config(3), B=3, H=320, W=320, layers=2)
+    wl = synth.make_workload(cfg, seed=57)
+    clean = gpu_multilevel(K, cfg, wl, "bf16")
+    enc = K.Encoder(cfg, wl["weights"], act_dtype="bf16")
+    b, t, o = enc.upload_boxes(wl["boxes"], wl["tier"], wl["box_offsets"])
+    # run 1: NaN frames, every cell refined (the longest sequences the context takes)
+    bad_img = enc.upload_images(np.full_like(wl["images"], np.nan))
+    everything = np.tile(np.asarray([[0, 0, cfg.W, cfg.H]], np.int32), (cfg.B, 1))
+    ab, at, ao = enc.upload_boxes(everything, np.ones(cfg.B, np.uint8), np.arange(cfg.B + 1))
+    out = enc.alloc_outputs(cfg.B)
+    enc.multilevel_batch(bad_img, cfg.B, ab, at, ao, out)
+    enc.sync_status()
+    assert not np.isfinite(out["y_mixed"].cpu().numpy()).any()
+    # run 2: the clean workload on the same context
+    img = enc.upload_images(wl["images"])
+    out = enc.alloc_outputs(cfg.B)
+    enc.multilevel_batch(img, cfg.B, b, t, o, out)
+    enc.sync_status()
+    T = int(clean["cu_seqlens"][-1])
+    assert (np.diff(clean["cu_seqlens"]) % 64 != 0).any()
+    np.testing.assert_array_equal(out["y_mixed"].cpu().numpy()[:T], clean["y_mixed"][:T])
+    np.testing.assert_array_equal(out["y_coarse"].cpu().numpy(), clean["y_coarse"])
     enc.close()

@@ -1,0 +1,179 @@
+"""GPU parity at the edges of the attention kernel's softmax (Sec. II-A: every token attends
+to every token of its frame): logits far from zero in either direction, a wide spread with
+the winning key in the last, ragged key tile, and sequence lengths around the tile size.
+
+The bf16 kernel keeps a reference exponent per query that moves only when a tile's
+probabilities get large, or when nothing has anchored it yet and the sums are vanishing;
+ordinary random weights reach neither case.  The weights here are built so that every query
+of a head sees the same logit vector (query matrix zero, query bias along one direction, key
+matrix of rank one): logits are then either all equal or separated by many units, so the
+bf16 rounding of q and k cannot move the result and the usual bar applies.
+
+The sequences are given to cfdetr_fine_encode directly (any token list is a valid input), so
+their lengths are free: 1, 63, 64, 65, 129, 200.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import cfdetr_oracle as O
+from paper_2505_23317_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+LENGTHS = (1, 63, 64, 65, 129, 200)
+LOG2E = 1.4426950408889634
+BAR = 2e-2
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def K():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2505_23317_amd import cfdetr
+    cfdetr.load_library()
+    return cfdetr
+
+
+def _model(d, heads):
+    return synth.Config(f"edge{d}h{heads}", len(LENGTHS), 128, 128, (16, 8), d, heads, 1,
+                        128 if d < 256 else 256, "bf16", box_rule="poisson", box_lambda=1.0,
+                        side_lo=8, side_hi=40)
+
+
+LEAD = 8.0   # base-2 units the winning key is ahead of every other key of its frame
+
+
+def _cells(cfg):
+    return np.asarray([(l, r, c) for l in range(cfg.n_levels) for r in range(cfg.grid(l)[0])
+                       for c in range(cfg.grid(l)[1])], np.int64)
+
+
+def _tokens(cfg, rng, images, w, winner):
+    """Arbitrary distinct cells of both levels, LENGTHS[i] of them for frame i.  With
+    `winner` ("first" / "last") the cell with the largest logit of the frame is one of them,
+    sits at that end, and no other chosen cell comes within LEAD of it: the result then does
+    not hinge on how q and k round to bf16."""
+    cells = _cells(cfg)
+    tok, cu, leads = [], [0], []
+    for f, n in enumerate(LENGTHS):
+        if winner is None or n == 1:
+            chosen = cells[rng.choice(len(cells), size=n, replace=False)]
+        else:
+            s = _logits_of_frame(O.embed_frame(images[f], cells, cfg.patch, w), w, cfg)
+            j = int(np.argmax(s))
+            pool = np.flatnonzero(s <= s[j] - LEAD)
+            assert len(pool) >= n - 1
+            rest = cells[rng.choice(pool, size=n - 1, replace=False)]
+            chosen = (np.concatenate([rest, cells[j:j + 1]]) if winner == "last"
+                      else np.concatenate([cells[j:j + 1], rest]))
+            leads.append(float(s[j] - s[pool].max()))
+        tok.append(chosen)
+        cu.append(cu[-1] + n)
+    return np.concatenate(tok), np.asarray(cu, np.int64), leads
+
+
+def _shared_logit_weights(cfg, seed, spread_log2, offset_log2):
+    """Weights whose base-2 logits are offset + spread * z_j for every query of every head,
+    z_j = w . LN1(x_j) with |w| = 1: query matrix 0, query bias beta along the all-ones
+    direction of each head, key matrix ones x w^T, key bias gamma along the same direction."""
+    w = synth.make_weights(cfg, seed)
+    d, dh = cfg.d, cfg.d_head
+    rng = np.random.default_rng(seed + 100)
+    wdir = rng.standard_normal(d)
+    wdir /= np.linalg.norm(wdir)
+    # base-e logit = (q . k) / sqrt(dh) = beta * sqrt(dh) * (z_j + gamma)
+    beta = max(spread_log2, 1.0) / (LOG2E * np.sqrt(dh))
+    scale = spread_log2 / max(spread_log2, 1.0)
+    gamma = offset_log2 / (LOG2E * np.sqrt(dh) * beta)
+    w["w_qkv"][0, :d, :] = 0.0
+    w["b_qkv"][0, :d] = np.float32(beta)
+    w["w_qkv"][0, d:2 * d, :] = synth.bf16_round(
+        np.broadcast_to(scale * wdir, (d, d)).astype(np.float32))
+    w["b_qkv"][0, d:2 * d] = np.float32(gamma)
+    # values and output projection of order one, so that what a query reads is a large part
+    # of its result and a wrong softmax weight shows in the output
+    w["w_qkv"][0, 2 * d:, :] = synth.bf16_round(
+        (rng.standard_normal((d, d)) / np.sqrt(d)).astype(np.float32))
+    w["w_o"][0] = synth.bf16_round((rng.standard_normal((d, d)) / np.sqrt(d)).astype(np.float32))
+    return w
+
+
+def _logits_of_frame(x, w, cfg):
+    """Base-2 logits every query of head 0 sees for the keys of one frame (oracle arithmetic)."""
+    d, dh = cfg.d, cfg.d_head
+    a = O.layer_norm(x, w["ln1_g"][0], w["ln1_b"][0])
+    qkv = a @ w["w_qkv"][0].astype(np.float64).T + w["b_qkv"][0].astype(np.float64)
+    return LOG2E * (qkv[:, :dh] @ qkv[:, d:d + dh].T / np.sqrt(dh))[0]
+
+
+CASES = {
+    # every logit the same, far below zero: nothing anchors the reference until the sums
+    # would vanish (2^-60 per key)
+    "flat_far_negative": dict(spread=0.0, offset=-60.0, winner=None),
+    # every logit the same, far above zero: the first tile's sum is 64 * 2^40
+    "flat_far_positive": dict(spread=0.0, offset=40.0, winner=None),
+    # spread of ~30 units, the winning key moved to the end of its frame (the last, ragged
+    # key tile where the length is no multiple of 64): the reference moves there once more
+    "wide_winner_last": dict(spread=30.0, offset=0.0, winner="last"),
+    # the same spread 80 units down: vanishing sums first, then keys far above the reference
+    "wide_low_winner_last": dict(spread=30.0, offset=-80.0, winner="last"),
+    # winner first: the reference moves in the first tile and never again
+    "wide_winner_first": dict(spread=30.0, offset=0.0, winner="first"),
+}
+
+
+@pytest.mark.parametrize("case", sorted(CASES))
+@pytest.mark.parametrize("shape", [(64, 2), (128, 2), (256, 8)])
+def test_softmax_edges(K, shape, case):
+    import torch
+    cfg = _model(*shape)
+    spec = CASES[case]
+    _say(f"[case] softmax edge d={cfg.d} dh={cfg.d_head} {case}")
+    rng = np.random.default_rng(7)
+    images, *_ = synth.make_frames(cfg, 11)
+    w = _shared_logit_weights(cfg, 13, spec["spread"], spec["offset"])
+    tok, cu, leads = _tokens(cfg, rng, images, w, spec["winner"])
+    if spec["spread"] == 0.0:
+        for f in range(cfg.B):
+            x = O.embed_frame(images[f], tok[cu[f]:cu[f + 1]], cfg.patch, w)
+            s = _logits_of_frame(x, w, cfg)
+            assert np.ptp(s) < 1e-6 and abs(s[0] - spec["offset"]) < 2.0
+    else:
+        _say(f"        winner's lead over the runner-up, base-2 units per frame: "
+             f"{[round(g, 1) for g in leads]}")
+        assert min(leads) >= LEAD
+    ref = O.fine_encode(images, tok, cu, cfg.patch, w, cfg.heads)
+    if spec["spread"] > 0.0:
+        # the case can see a wrong softmax: with uniform attention instead (same values,
+        # spread 0) the oracle's result is far outside the bar
+        flat = O.fine_encode(images, tok, cu, cfg.patch,
+                             _shared_logit_weights(cfg, 13, 0.0, spec["offset"]), cfg.heads)
+        assert np.abs(flat - ref).max() / np.abs(ref).max() > 10 * BAR
+
+    enc = K.Encoder(cfg, w, act_dtype="bf16", max_tokens_total=int(cu[-1]) + 64)
+    img = enc.upload_images(images)
+    out = enc.alloc_outputs(cfg.B)
+    T = int(cu[-1])
+    out["tok_desc"][:T] = torch.from_numpy(O.pack_tok_desc(tok).astype(np.int32)).cuda()
+    out["cu_seqlens"].copy_(torch.from_numpy(cu.astype(np.int32)).cuda())
+    enc.fine_encode(img, cfg.B, out["tok_desc"], out["cu_seqlens"], None, out["y_mixed"])
+    enc.sync_status()
+    got = out["y_mixed"].cpu().numpy()[:T].astype(np.float64)
+    enc.close()
+    assert np.isfinite(got).all()
+    worst = 0.0
+    for f in range(cfg.B):
+        lo, hi = int(cu[f]), int(cu[f + 1])
+        e = float(np.abs(got[lo:hi] - ref[lo:hi]).max() / np.abs(ref).max())
+        worst = max(worst, e)
+        assert e <= BAR, (case, shape, LENGTHS[f], e)
+    rms = float(np.sqrt(((got - ref) ** 2).mean() / (ref ** 2).mean()))
+    _say(f"[parity] softmax edge d={cfg.d} {case}: max {worst:.2e} rms {rms:.2e} (bar {BAR:.0e})")

@@ -171,3 +171,26 @@ def test_pack_tok_desc():
     tok = np.asarray([[0, 0, 0], [1, 3, 5], [2, 16383, 16383]])
     assert O.pack_tok_desc(tok).tolist() == [0, (1 << 28) | (3 << 14) | 5,
                                              (2 << 28) | (16383 << 14) | 16383]
+
+
+def test_easy_frames_contribute_no_token():
+    # Sec. III-B, A1: an easy frame skips the fine stage.  Hand-worked: three 128x128 frames,
+    # patches 32/16 (16 coarse cells); frame 0 has one box inside coarse cell (0, 0) -> 19
+    # tokens, frame 1 has a box over the whole frame -> 64, frame 2 has none -> 16.
+    boxes = np.asarray([(0, 0, 10, 10), (0, 0, 128, 128)], np.int32)
+    tier = np.asarray([1, 1], np.uint8)
+    offs = np.asarray([0, 1, 2, 2], np.int32)
+    full = O.select_fine(boxes, tier, offs, 3, 128, 128, (32, 16))
+    assert full[1].tolist() == [0, 19, 83, 99]
+    for hard, want_cu, want_counts in [
+            ([1, 1, 1], [0, 19, 83, 99], [[15, 4], [0, 64], [16, 0]]),
+            ([1, 0, 1], [0, 19, 19, 35], [[15, 4], [0, 0], [16, 0]]),
+            ([0, 1, 0], [0, 0, 64, 64], [[0, 0], [0, 64], [0, 0]]),
+            ([0, 0, 0], [0, 0, 0, 0], [[0, 0], [0, 0], [0, 0]])]:
+        tok, cu, counts = O.select_fine(boxes, tier, offs, 3, 128, 128, (32, 16),
+                                        hard=np.asarray(hard))
+        assert cu.tolist() == want_cu and counts.tolist() == want_counts
+        # the tokens of the frames that remain are exactly those of the unflagged selection
+        keep = np.concatenate([np.arange(full[1][f], full[1][f + 1]) for f in range(3) if hard[f]]
+                              or [np.zeros(0, np.int64)]).astype(np.int64)
+        assert tok.tolist() == full[0][keep].tolist()
