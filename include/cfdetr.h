@@ -271,6 +271,30 @@ CFDETR_API cfdetr_status cfdetr_select_fine_hard(cfdetr_ctx* ctx, const int32_t*
                                       void* hip_stream);
 
 /*
+ * cfdetr_select_fine for callers that cannot allocate device memory and have no context:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * call allocates nothing and needs no cfdetr_create: its scratch memory (one flag byte per
+ * frame and cell of the levels below the finest) is a static device array of 1 MiB that
+ * every GPU the library runs on holds until the process ends.
+ *   cfg       host pointer; the same structure cfdetr_create takes (its pyramid fields,
+ *             max_batch and max_tokens_total are used; all fields are validated)
+ *   overflow  [1] int32 (device) out: 0, or 1 if the token total exceeds
+ *             cfg->max_tokens_total; then cu_seqlens and level_counts are all 0 and
+ *             tok_desc is untouched (there is no context to hold a sticky flag)
+ *   other arguments and outputs exactly as in cfdetr_select_fine, bit for bit.
+ * Limits: B * (cells of all levels but the finest) <= 1048576, else CFDETR_ECAPACITY and
+ * nothing is enqueued.  The reason for a failure is cfdetr_last_error(NULL).
+ * All calls on one GPU share the one array, which keeps the last call's contents (each call
+ * clears what it uses, with a kernel): calls that overlap on one GPU, on whatever streams or
+ * threads, race.  Calls in stream order on one stream are safe.
+ */
+CFDETR_API cfdetr_status cfdetr_select_fine_static(const cfdetr_config* cfg, const int32_t* boxes,
+                                        const uint8_t* tier, const int32_t* box_offsets,
+                                        int32_t B, int32_t* tok_desc, int32_t* cu_seqlens,
+                                        int32_t* level_counts, int32_t* overflow,
+                                        void* hip_stream);
+
+/*
  * A2 + A3, encoder over the mixed-granularity token sets as one variable-length
  * batch (Sec. III-B, A2 "reuse the coarse-stage tokens", A3 patch-level batch).
  *   images, B    as in cfdetr_coarse_encode

@@ -31,7 +31,7 @@ STATUS_NAMES = ["OK", "EINVAL", "ESHAPE", "ECAPACITY", "ENOMEM", "EDEVICE"]
 EXPORTS = [
     "cfdetr_create", "cfdetr_destroy", "cfdetr_last_error", "cfdetr_workspace_bytes",
     "cfdetr_sync_status", "cfdetr_coarse_encode", "cfdetr_propose_rois", "cfdetr_select_fine",
-    "cfdetr_select_fine_hard",
+    "cfdetr_select_fine_hard", "cfdetr_select_fine_static",
     "cfdetr_fine_encode", "cfdetr_fine_encode_padded",
     "cfdetr_multilevel_batch", "cfdetr_profile_begin", "cfdetr_profile_end",
     "cfdetr_sched_response_times", "cfdetr_sched_coarse_batch", "cfdetr_sched_fine_batches",
@@ -121,6 +121,9 @@ def load_library() -> ctypes.CDLL:
     lib.cfdetr_select_fine.restype = ctypes.c_int
     lib.cfdetr_select_fine_hard.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.cfdetr_select_fine_hard.restype = ctypes.c_int
+    lib.cfdetr_select_fine_static.argtypes = [ctypes.POINTER(CfdetrConfig), vp, vp, vp, i32, vp, vp,
+                                              vp, vp, vp]
+    lib.cfdetr_select_fine_static.restype = ctypes.c_int
     lib.cfdetr_fine_encode.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp]
     lib.cfdetr_fine_encode.restype = ctypes.c_int
     lib.cfdetr_fine_encode_padded.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp, vp]
@@ -228,6 +231,13 @@ def cfdetr_select_fine_hard(ctx, boxes, tier, box_offsets, hard, B, tok_desc, cu
                             level_counts, stream=0) -> None:
     _check(load_library().cfdetr_select_fine_hard(ctx, boxes, tier, box_offsets, hard, B, tok_desc,
                                                   cu_seqlens, level_counts, stream), ctx)
+
+
+def cfdetr_select_fine_static(cfg: CfdetrConfig, boxes, tier, box_offsets, B, tok_desc, cu_seqlens,
+                              level_counts, overflow, stream=0) -> None:
+    _check(load_library().cfdetr_select_fine_static(ctypes.byref(cfg), boxes, tier, box_offsets, B,
+                                                    tok_desc, cu_seqlens, level_counts, overflow,
+                                                    stream), None)
 
 
 def cfdetr_fine_encode(ctx, images, B, tok_desc, cu_seqlens, x0_cache, y_mixed, stream=0) -> None:
@@ -472,6 +482,16 @@ class Encoder:
                                 hard.data_ptr(), B, tok_desc.data_ptr(), cu_seqlens.data_ptr(),
                                 level_counts.data_ptr() if level_counts is not None else None,
                                 self._stream())
+
+    def select_fine_static(self, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts,
+                           overflow):
+        """The selection through the entry point that allocates nothing and uses no context
+        (the configuration structure of this encoder is passed instead)."""
+        cfdetr_select_fine_static(self.c_cfg, boxes.data_ptr(), tier.data_ptr(),
+                                  box_offsets.data_ptr(), B, tok_desc.data_ptr(),
+                                  cu_seqlens.data_ptr(),
+                                  level_counts.data_ptr() if level_counts is not None else None,
+                                  overflow.data_ptr(), self._stream())
 
     def fine_encode(self, images, B, tok_desc, cu_seqlens, x0_cache, y_mixed):
         cfdetr_fine_encode(self.ctx, images.data_ptr(), B, tok_desc.data_ptr(),

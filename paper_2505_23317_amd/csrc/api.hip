@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -100,6 +101,52 @@ namespace {
 
 // Error text of the last failed cfdetr_create of this thread (no context exists then).
 thread_local std::string g_create_err;
+
+// Scratch memory of cfdetr_select_fine_static, the entry point for callers that cannot
+// allocate: the cell flags of one selection (B frames times the cells of all levels but the
+// finest, one byte each).  Every GPU the library runs
+// on holds its own copy until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; kernels get the device address that call returns.
+constexpr uint64_t kStaticFlagBytes = 1u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticFlagBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device, with that
+// device current); returns an error text, or null on success.
+const char* static_scratch(unsigned char** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return "cannot identify the current device";
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p)
+      return "hipGetSymbolAddress of the static scratch array failed";
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return nullptr;
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ p, uint64_t n16,
+                                                        int32_t* __restrict__ word) {
+  const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) p[i] = make_uint4(0, 0, 0, 0);
+  if (i == 0) *word = 0;
+}
+
+// Clears the first `bytes` bytes at p (rounded up to 16; p is 256-byte aligned and the
+// array is longer than any count this is called with) and *word.
+hipError_t launch_fill_zero(unsigned char* p, uint64_t bytes, int32_t* word, hipStream_t s) {
+  const uint64_t n16 = (bytes + 15) / 16;
+  const unsigned blocks = (unsigned)((n16 + 255) / 256);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks ? blocks : 1), dim3(256), 0, s,
+                     reinterpret_cast<uint4*>(p), n16, word);
+  return hipGetLastError();
+}
 
 cfdetr_status fail(cfdetr_ctx* c, cfdetr_status st, const std::string& msg) {
   if (c) c->err = msg;
@@ -885,6 +932,48 @@ CFDETR_API cfdetr_status cfdetr_select_fine_hard(cfdetr_ctx* ctx, const int32_t*
   if (!aligned16(boxes)) return fail(ctx, CFDETR_EINVAL, "boxes must be 16-byte aligned");
   return select_impl(ctx, boxes, tier, box_offsets, B, tok_desc, cu_seqlens, level_counts,
                      static_cast<hipStream_t>(hip_stream), nullptr, hard);
+}
+
+CFDETR_API cfdetr_status cfdetr_select_fine_static(const cfdetr_config* cfg, const int32_t* boxes,
+                                        const uint8_t* tier, const int32_t* box_offsets,
+                                        int32_t B, int32_t* tok_desc, int32_t* cu_seqlens,
+                                        int32_t* level_counts, int32_t* overflow,
+                                        void* hip_stream) {
+  if (!cfg || !boxes || !tier || !box_offsets || !tok_desc || !cu_seqlens || !overflow)
+    return fail_create(CFDETR_EINVAL, "null pointer");
+  if (const char* why = check_config(*cfg)) return fail_create(CFDETR_ESHAPE, why);
+  if (B < 1) return fail_create(CFDETR_EINVAL, "B must be >= 1");
+  if (B > cfg->max_batch) return fail_create(CFDETR_ECAPACITY, "B exceeds max_batch");
+  if (!aligned16(boxes)) return fail_create(CFDETR_EINVAL, "boxes must be 16-byte aligned");
+  Pyramid p;
+  p.n_levels = cfg->n_levels;
+  p.img_h = cfg->img_h;
+  p.img_w = cfg->img_w;
+  int nonfinest = 0;
+  for (int l = 0; l < kMaxLevels; ++l) {
+    p.patch[l] = l < cfg->n_levels ? cfg->patch[l] : 1;
+    p.rows[l] = l < cfg->n_levels ? cfg->img_h / cfg->patch[l] : 0;
+    p.cols[l] = l < cfg->n_levels ? cfg->img_w / cfg->patch[l] : 0;
+    if (l + 1 < cfg->n_levels) nonfinest += p.rows[l] * p.cols[l];
+  }
+  const uint64_t flag_bytes = (uint64_t)B * (uint64_t)nonfinest;
+  if (flag_bytes > kStaticFlagBytes)
+    return fail_create(CFDETR_ECAPACITY,
+                       "B times the cells of the non-finest levels exceeds the 1 MiB of static scratch");
+  unsigned char* scratch_dev = nullptr;
+  if (const char* why = static_scratch(&scratch_dev)) return fail_create(CFDETR_EDEVICE, why);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  uint8_t* flags = scratch_dev;
+  // The array keeps what the last call left: the flags of this call's cells, and the
+  // caller's overflow word, start from zero (a fill kernel, so that the call can be
+  // captured into a graph).
+  hipError_t e = launch_fill_zero(flags, flag_bytes, overflow, s);
+  if (e == hipSuccess)
+    e = launch_select(p, boxes, tier, box_offsets, B, nonfinest, flags, nullptr, 0,
+                      cfg->max_tokens_total, tok_desc, cu_seqlens, level_counts, overflow, s);
+  if (e != hipSuccess)
+    return fail_create(CFDETR_EDEVICE, std::string("selection launch: ") + hipGetErrorString(e));
+  return CFDETR_OK;
 }
 
 CFDETR_API cfdetr_status cfdetr_fine_encode(cfdetr_ctx* ctx, const void* images, int32_t B,
