@@ -8,6 +8,10 @@ on one synthetic multi-camera batch that is resident in HBM before the clock
 starts.  Prints one JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
+
+The headline workload is configs[3] (four 1280 x 1280 cameras: the largest of the
+configurations in work per step); configs[2] and configs[4] ride along as other_workloads,
+each with its own roofline object, kernel table and oracle timing.
 """
 from __future__ import annotations
 
@@ -49,34 +53,46 @@ def family_work(cfg, lens_coarse, lens_fine, level_counts):
     }
 
 
-def cpu_baseline(cfg, wl, cfg_id):
-    """The oracle as it stands, timed on this host's cores on a bounded sample."""
+# frames of a workload that the oracle is timed on (the whole batch where that takes seconds;
+# for the two largest configs a sample of whole frames that keeps it to 10-30 s)
+ORACLE_SAMPLE = {4: [1], 5: [0, 1, 2]}
+
+
+def cpu_baseline(cfg, wl, cfg_id, single_thread=False, budget_s=10.0):
+    """The oracle as it stands, timed on this host's cores on a bounded sample: whole frames
+    of the workload, all layers, coarse + mixed pass, repeated until budget_s have passed."""
     from oracle import cfdetr_oracle as O
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count() or 1
-    if cfg_id <= 3:
-        frames = list(range(cfg.B))
+    from threadpoolctl import threadpool_info, threadpool_limits
+    frames = ORACLE_SAMPLE.get(cfg_id, list(range(cfg.B)))
+    if len(frames) == cfg.B:
         sample = f"full {cfg.name} batch ({cfg.B} frames), coarse + mixed pass"
     else:
-        frames = [0]
-        sample = f"frame 0 of {cfg.name} (all layers, coarse + mixed pass)"
-    lo, hi = int(wl["box_offsets"][frames[0]]), int(wl["box_offsets"][frames[-1] + 1])
-    offs = wl["box_offsets"][frames[0]:frames[-1] + 2] - lo
-    # whole passes of the sample until about ten seconds of CPU work have been timed
-    t0 = time.perf_counter()
-    tokens, passes = 0, 0
-    while True:
-        yc, ym, tok, cu, counts = O.multilevel_batch(
-            wl["images"][frames], wl["boxes"][lo:hi], wl["tier"][lo:hi], offs, cfg.patch,
-            wl["weights"], cfg.heads)
-        tokens += len(yc) + len(ym)
-        passes += 1
-        dt = time.perf_counter() - t0
-        if dt >= 10.0:
-            break
+        sample = (f"frames {frames} of the {cfg.B} of {cfg.name} (all layers, coarse + mixed "
+                  f"pass)")
+    bo = wl["box_offsets"]
+    boxes = np.concatenate([wl["boxes"][bo[f]:bo[f + 1]] for f in frames]).reshape(-1, 4)
+    tier = np.concatenate([wl["tier"][bo[f]:bo[f + 1]] for f in frames])
+    offs = np.concatenate([[0], np.cumsum([bo[f + 1] - bo[f] for f in frames])]).astype(np.int32)
+
+    def run():
+        t0 = time.perf_counter()
+        tokens, passes = 0, 0
+        while True:
+            yc, ym, tok, cu, counts = O.multilevel_batch(wl["images"][frames], boxes, tier, offs,
+                                                         cfg.patch, wl["weights"], cfg.heads)
+            tokens += len(yc) + len(ym)
+            passes += 1
+            dt = time.perf_counter() - t0
+            if dt >= budget_s:
+                return tokens, passes, dt
+
+    if single_thread:
+        with threadpool_limits(limits=1):
+            tokens, passes, dt = run()
+        cores = 1
+    else:
+        tokens, passes, dt = run()
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     return {"value": tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"{sample}, repeated {passes} times", "seconds": dt, "tokens": int(tokens)}
 
@@ -106,6 +122,39 @@ def hbm_traffic(cfg_id, family):
         if name in found:
             return found[name]
     return None
+
+
+# kernel family -> pattern of its kernel names in the rocprofv3 kernel statistics
+STATS_FAMILY = {
+    "attention": r"attention_bf16_kernel",
+    "qkv": r"EpiQkv|layer_head_kernel",
+    "ffn1": r"EpiAct<unsigned short, (true|1)>",
+    "out_proj": r"EpiResidual",
+    "ffn2": r"layer_tail_kernel|EpiResidual",
+    "layernorm": r"layernorm",
+    "embed": r"EpiEmbed|gemm_bf16_gather_kernel",
+    "gather": r"gather_coarse_kernel",
+    "select": r"select_",
+}
+
+
+def rocprof_avg_us(cfg_id, family):
+    """Average launch duration (microseconds) of a kernel family from the committed rocprofv3
+    --kernel-trace --stats summary of this workload, or None when there is none.  (The two
+    residual contractions share a kernel name there; their average is over both.)"""
+    import re
+    path = os.path.join(ROOT, "profiles", f"multilevel_batch_cfg{cfg_id}_kernel_stats.md")
+    pat = STATS_FAMILY.get(family)
+    if pat is None or not os.path.exists(path):
+        return None
+    calls, total = 0, 0.0
+    with open(path) as f:
+        for line in f:
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) >= 5 and cells[1].startswith("`") and re.search(pat, cells[1]):
+                calls += int(cells[2])
+                total += float(cells[3])
+    return total / calls if calls else None
 
 
 def measure(cfg_id, steps, warmup, profile_steps):
@@ -153,6 +202,7 @@ def measure(cfg_id, steps, warmup, profile_steps):
         # everything after attention ran as one kernel per layer, counted under ffn2: it
         # does the output projection and both feed-forward products
         work["ffn2"] = ("flop", work["out_proj"][1] + work["ffn1"][1] + work["ffn2"][1])
+        del work["out_proj"], work["ffn1"]        # counted once, under the kernel that does them
         if prof["qkv"]["launches"] // profile_steps < cfg.layers:
             # ... and the next layer's q/k/v projection; only the first layer's is a launch
             per_layer = work["qkv"][1] / cfg.layers
@@ -192,6 +242,14 @@ def measure(cfg_id, steps, warmup, profile_steps):
                      "launches_per_step": launches,
                      "algorithmic_per_launch": round(amount / launches, 1),
                      "traffic": hbm_traffic(cfg_id, dom)})
+    # the same figure from the committed rocprofv3 kernel statistics of this workload (kernel
+    # durations without the event pair around them), as a cross-check
+    us = rocprof_avg_us(cfg_id, dom)
+    if us and dom != "out_proj" and not (dom == "ffn2" and "out_proj" in kernels):
+        per_s = amount / launches / (us * 1e-6)
+        peak = PEAK_BF16_TFLOPS * 1e12 if kind == "flop" else PEAK_HBM_GBPS * 1e9
+        roofline["rocprof"] = {"avg_launch_us": round(us, 2), "frac": round(per_s / peak, 5),
+                               "source": f"profiles/multilevel_batch_cfg{cfg_id}_kernel_stats.md"}
     total_flop = sum(a for k, a in work.values() if k == "flop")
     return {
         "cfg": cfg, "wl": wl, "elapsed": elapsed, "tokens_per_step": tokens_per_step,
@@ -399,7 +457,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3)")
+    ap.add_argument("--config", type=int, default=4,
+                    help="workload 1..5 (default 4: the largest configuration on one GPU)")
     ap.add_argument("--profile-steps", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--compare-padded", action="store_true",
@@ -451,19 +510,23 @@ def main() -> int:
         "kernels": m["kernels"],
     }
     if not args.no_others:
-        # context only: the same step on the two largest configs, a few steps each
+        # the same step on the other two configurations the throughput target names, a few
+        # steps each, with their own roofline object, kernel table and oracle timing
         others = []
-        for cid in (4, 5):
+        for cid in (3, 4, 5):
             if cid == args.config:
                 continue
             mo = measure(cid, 40, 8, 3)
             oc = mo["cfg"]
-            others.append({"workload": f"configs[{cid - 1}] {oc.name}",
-                           "tokens_per_s": mo["tokens_per_step"] * 40 / mo["elapsed"],
-                           "frames_per_s": oc.B * 40 / mo["elapsed"],
-                           "ms_per_step": mo["ms_per_step"],
-                           "whole_step_mfma_frac": mo["whole_step_mfma_frac"],
-                           "roofline": mo["roofline"]})
+            row = {"workload": f"configs[{cid - 1}] {oc.name}",
+                   "tokens_per_s": mo["tokens_per_step"] * 40 / mo["elapsed"],
+                   "frames_per_s": oc.B * 40 / mo["elapsed"],
+                   "ms_per_step": mo["ms_per_step"],
+                   "whole_step_mfma_frac": mo["whole_step_mfma_frac"],
+                   "roofline": mo["roofline"], "kernels": mo["kernels"]}
+            if not args.no_cpu_baseline:
+                row["cpu_baseline"] = cpu_baseline(oc, mo["wl"], cid)
+            others.append(row)
         result["other_workloads"] = others
     if args.compare_padded:
         result["padded_baseline"] = [padded_comparison(c, 20, 3)
@@ -474,6 +537,21 @@ def main() -> int:
         result["coarse_stage"] = coarse_stage_table(args.config)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, m["wl"], args.config)
+        if not args.no_others:
+            # the oracle on the three small configurations, all cores and one thread
+            from paper_2505_23317_amd import synth
+            small = []
+            for cid, budget in ((1, 1.0), (2, 3.0), (3, 8.0)):
+                sc, swl = synth.config(cid), synth.make_workload(cid)
+                one = cpu_baseline(sc, swl, cid, single_thread=True, budget_s=budget)
+                small.append({"workload": f"configs[{cid - 1}] {sc.name}",
+                              "single_thread_tokens_per_s": one["value"],
+                              "single_thread_seconds": one["seconds"]})
+                if cid < 3:
+                    allc = cpu_baseline(sc, swl, cid, budget_s=budget)
+                    small[-1].update({"all_cores_tokens_per_s": allc["value"],
+                                      "cores": allc["cores"]})
+            result["oracle_timing_small_configs"] = small
     print(json.dumps(result))
     return 0
 

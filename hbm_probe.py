@@ -3,10 +3,10 @@
 Two steps, both on the GPU machine:
 
   rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d OUT/fetch -o t -- \
-      python3 -m paper_2505_23317_amd.hbm_probe run --config 3
+      python3 hbm_probe.py run --config 3
   rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d OUT/write -o t -- \
-      python3 -m paper_2505_23317_amd.hbm_probe run --config 3
-  python3 -m paper_2505_23317_amd.hbm_probe report OUT/fetch/t_counter_collection.csv \
+      python3 hbm_probe.py run --config 3
+  python3 hbm_probe.py report OUT/fetch/t_counter_collection.csv \
       OUT/write/t_counter_collection.csv --config 3 > profiles/<name>.txt
 
 `run` first copies a buffer of known size with a plain device-to-device copy kernel
@@ -19,8 +19,11 @@ from __future__ import annotations
 import argparse
 import collections
 import csv
+import os
 import re
 import sys
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 COPY_BYTES = 1 << 30
 STEPS = 3
@@ -28,7 +31,7 @@ STEPS = 3
 FAMILIES = [
     ("attention", r"attention_bf16_kernel"),
     ("gemm_qkv", r"gemm_bf16_direct_kernel.*EpiQkv"),
-    ("gemm_ffn1_gelu", r"gemm_bf16_direct_kernel.*EpiAct<unsigned short, true>"),
+    ("gemm_ffn1_gelu", r"gemm_bf16_direct_kernel.*EpiAct<unsigned short, (true|1)>"),
     ("gemm_residual", r"gemm_bf16_direct_kernel.*EpiResidual|gemm_bf16_rowln_kernel"),
     ("layer_tail", r"layer_tail_kernel"),
     ("layer_head", r"layer_head_kernel"),
@@ -43,7 +46,7 @@ FAMILIES = [
 
 def run(cfg_id: int) -> None:
     import torch
-    from . import cfdetr, synth
+    from paper_2505_23317_amd import cfdetr, synth
     src = torch.empty(COPY_BYTES, dtype=torch.uint8, device="cuda")
     src.fill_(1)
     dst = torch.empty_like(src)
@@ -103,8 +106,8 @@ def report(fetch_csv: str, write_csv: str, cfg_id: int) -> None:
     print("# commands, from the repository root on the MI355X box (OUT = any scratch folder):")
     for c in ("FETCH_SIZE", "WRITE_SIZE"):
         print(f"#   rocprofv3 --pmc {c} --kernel-trace --output-format csv -d OUT/{c.lower()} -o t "
-              f"-- python3 -m paper_2505_23317_amd.hbm_probe run --config {cfg_id}")
-    print(f"#   python3 -m paper_2505_23317_amd.hbm_probe report OUT/fetch_size/t_counter_collection.csv "
+              f"-- python3 hbm_probe.py run --config {cfg_id}")
+    print(f"#   python3 hbm_probe.py report OUT/fetch_size/t_counter_collection.csv "
           f"OUT/write_size/t_counter_collection.csv --config {cfg_id}")
     print(f"# counters: {fname}, {wname}; calibration: a {COPY_BYTES} byte device copy read "
           f"{cf:.1f} / {cw:.1f} counter units -> {kf:.1f} / {kw:.1f} bytes per unit "
@@ -136,8 +139,8 @@ def counters(csvs, cfg_id: int, names) -> None:
     print(f"# Shader counters per launch, cfdetr_multilevel_batch, config {cfg_id}")
     print("# command, from the repository root on the MI355X box (OUT = any scratch folder):")
     print(f"#   rocprofv3 --pmc {' '.join(names)} --kernel-trace --output-format csv -d OUT -o t "
-          f"-- python3 -m paper_2505_23317_amd.hbm_probe run --config {cfg_id}")
-    print(f"#   python3 -m paper_2505_23317_amd.hbm_probe counters OUT/t_counter_collection.csv "
+          f"-- python3 hbm_probe.py run --config {cfg_id}")
+    print(f"#   python3 hbm_probe.py counters OUT/t_counter_collection.csv "
           f"--config {cfg_id}")
     print("# values are sums over the chip (SQ counters: over its 1024 SIMDs = 256 CUs x 4;")
     print("# GRBM_GUI_ACTIVE: over its 8 XCDs), averaged over the launches of a family.")

@@ -455,8 +455,8 @@ __device__ __forceinline__ int lds_row_key(int r) {
 #define CFDETR_GTL(i_)
 #endif
 
-template <int BM, int BN, int NWM, int NWN, int kStages, int BKT, typename AROWS, typename EP, int KS = 1>
-__global__ __launch_bounds__(64 * NWM * NWN * KS) void gemm_bf16_direct_kernel(
+template <int BM, int BN, int NWM, int NWN, int kStages, int BKT, typename AROWS, typename EP, int KS = 1, int WPE = 1>
+__global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_kernel(
     AROWS arows, const bf16_t* __restrict__ W, int N, int K, EP ep,
     const int32_t* __restrict__ m_ptr, int m_host) {
   constexpr int NW = NWM * NWN;
@@ -1984,10 +1984,10 @@ hipError_t allow_lds(Kern kern, size_t bytes, bool* configured) {
   return e;
 }
 
-template <int BM, int BN, int NWM, int NWN, int S, int BKT, int KS = 1, typename AROWS, typename EP>
+template <int BM, int BN, int NWM, int NWN, int S, int BKT, int KS = 1, int WPE = 1, typename AROWS, typename EP>
 hipError_t launch_direct_tile(const AROWS& a, const bf16_t* w, int N, int K, const EP& ep,
                               const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
-  auto kern = gemm_bf16_direct_kernel<BM, BN, NWM, NWN, S, BKT, AROWS, EP, KS>;
+  auto kern = gemm_bf16_direct_kernel<BM, BN, NWM, NWN, S, BKT, AROWS, EP, KS, WPE>;
   if (K % (BKT * KS) != 0) return hipErrorInvalidValue;
   // the kernel addresses the weights with 32-bit byte offsets (the rows: see the callers)
   if ((size_t)N * K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
