@@ -807,6 +807,234 @@ __global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_ker
   CFDETR_GTL(4);
 }
 
+// ---------------------------------------------------------------------------
+// The same contraction for the layer matrices at large row counts, as a kernel whose
+// workgroups stay: the grid is what the chip holds at once and workgroup w walks over the
+// tiles w, w + grid, w + 2 grid, ... of the XCD-grouped order.  What a tile costs besides
+// its main loop is thereby paid once per workgroup (the row count from device memory) or
+// hidden: right behind a tile's last slab the first slab of the next tile is requested
+// into ring buffer 0, and arrives while the epilogue of the finished tile runs, with its
+// staging area in ring buffer 1.  A staging row is 128 bytes (64 bf16 or 32 fp32 columns,
+// the latter in two passes per 64 columns), so the area of all wavefronts fits one buffer.
+// Every tile starts with vmcnt(0): the epilogue's stores are younger than the requested
+// slab and their number is not known to the wait.
+// K is contracted in ascending slabs of BKT by every tile shape, so a result does not
+// depend on the tile that produced it.
+// ---------------------------------------------------------------------------
+template <int BM, int BN, int NWM, int NWN, int BKT, typename EP>
+__global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_persist_kernel(
+    DenseRows arows, const bf16_t* __restrict__ W, int N, int K, EP ep,
+    const int32_t* __restrict__ m_ptr, int m_host) {
+  constexpr int kStages = 2;
+  constexpr int NW = NWM * NWN;
+  constexpr int WTM = BM / NWM, WTN = BN / NWN;
+  constexpr int MT = WTM / 32, NT = WTN / 32;
+  constexpr int ROWB = BKT * 2;
+  constexpr int CPR = ROWB / 16;
+  constexpr int RPI = 64 / CPR;
+  constexpr int A_INST = BM / (RPI * NW), B_INST = BN / (RPI * NW);
+  constexpr int STAGE = (BM + BN) * ROWB;
+  static_assert(BKT == 64, "slab width");
+  static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile / wavefront mismatch");
+  static_assert(EP::kStageElem == 2 || EP::kStageElem == 4, "staged epilogues only");
+  static_assert(WTN == 64, "a wavefront's tile is 64 columns wide");
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_persist[];
+
+  const int M = m_ptr ? *m_ptr : m_host;
+  const int n_blocks = N / BN;
+  const int total = ((M + BM - 1) / BM) * n_blocks;
+  int v = blockIdx.x;
+  if (v >= total) return;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / NWN, wn = wave % NWN;
+  const int lrow = lane / CPR, lpos = lane % CPR;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int nk = K / BKT;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem_persist;
+
+  uint32_t avo[A_INST], wvo[B_INST];
+  // loader offsets of the tile with first row m0_ and first column n0_
+#define CFDETR_SET_TILE(m0_, n0_)                                                              \
+  do {                                                                                         \
+    _Pragma("unroll") for (int j = 0; j < A_INST; ++j) {                                       \
+      const int rt = (wave * A_INST + j) * RPI + lrow;                                         \
+      bool ok;                                                                                 \
+      avo[j] = arows.row_off((m0_) + rt, M, ok) +                                              \
+               arows.lane_off((lpos ^ lds_row_key<ROWB>(rt)) * 8);                             \
+    }                                                                                          \
+    _Pragma("unroll") for (int j = 0; j < B_INST; ++j) {                                       \
+      const int rt = (wave * B_INST + j) * RPI + lrow;                                         \
+      wvo[j] = ((uint32_t)((n0_) + rt) * (uint32_t)K +                                         \
+                (uint32_t)((lpos ^ lds_row_key<ROWB>(rt)) * 8)) * 2u;                          \
+    }                                                                                          \
+  } while (0)
+#define CFDETR_ISSUE_SLAB(k0_, buf_)                                                          \
+  do {                                                                                        \
+    const unsigned char* ab_ = arows.base() + arows.slab_off(k0_);                            \
+    const unsigned char* wb_ = reinterpret_cast<const unsigned char*>(W) + (size_t)(k0_) * 2; \
+    const uint32_t st_ = lds0 + (buf_) * STAGE;                                               \
+    _Pragma("unroll") for (int j = 0; j < A_INST; ++j)                                        \
+        dma16_untracked_s(ab_, avo[j], st_ + (wave * A_INST + j) * 1024);                     \
+    _Pragma("unroll") for (int j = 0; j < B_INST; ++j)                                        \
+        dma16_untracked_s(wb_, wvo[j], st_ + BM * ROWB + (wave * B_INST + j) * 1024);         \
+  } while (0)
+
+  int pid = xcd_tile_order(v, total);
+  int m0 = (pid / n_blocks) * BM, n0 = (pid % n_blocks) * BN;
+  CFDETR_SET_TILE(m0, n0);
+  CFDETR_ISSUE_SLAB(0, 0);
+
+  for (;;) {
+    // what the epilogue needs per row and per column arrives while the main loop runs
+    int32_t info[MT];
+    float4 bias_r[NT][4];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) info[i] = ep.row_info(min(m0 + wm * WTM + i * 32 + l32, M - 1));
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) bias_r[j][q] = ep.bias4(n0 + wn * WTN + j * 32 + 8 * q + 4 * g);
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    int buf = 0;
+    for (int it = 0; it < nk; ++it) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __builtin_amdgcn_s_barrier();
+      if (it + 1 < nk) CFDETR_ISSUE_SLAB((it + 1) * BKT, buf ^ 1);
+      const unsigned char* pa = smem_persist + buf * STAGE;
+      const unsigned char* pb = pa + BM * ROWB;
+      buf ^= 1;
+      bf16x8 fa[2][MT], fb[2][NT];
+      auto read_ops = [&](int ks, bf16x8(&oa)[MT], bf16x8(&ob)[NT]) {
+        const int c = 2 * ks + g;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          const int r = wm * WTM + i * 32 + l32;
+          oa[i] = *reinterpret_cast<const bf16x8*>(pa + r * ROWB + ((c ^ lds_row_key<ROWB>(r)) << 4));
+        }
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          const int r = wn * WTN + j * 32 + l32;
+          ob[j] = *reinterpret_cast<const bf16x8*>(pb + r * ROWB + ((c ^ lds_row_key<ROWB>(r)) << 4));
+        }
+      };
+      read_ops(0, fa[0], fb[0]);
+      __builtin_amdgcn_sched_group_barrier(0x100, MT + NT, 0);
+#pragma unroll
+      for (int ks = 0; ks < BKT / 16; ++ks) {
+        if (ks + 1 < BKT / 16) read_ops(ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[ks & 1][i], acc[i][j], 0, 0, 0);
+        if (ks + 1 < BKT / 16) {
+#pragma unroll
+          for (int t = 0; t < MT + NT; ++t) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, MT * NT - (MT + NT), 0);
+        } else {
+          __builtin_amdgcn_sched_group_barrier(0x008, MT * NT, 0);
+        }
+      }
+    }
+    __builtin_amdgcn_s_barrier();   // every wavefront is done reading the ring
+
+    // the next tile's first slab goes into buffer 0 while this tile's epilogue runs
+    const int vn = v + (int)gridDim.x;
+    const bool more = vn < total;
+    const int m0_cur = m0, n0_cur = n0;
+    if (more) {
+      pid = xcd_tile_order(vn, total);
+      m0 = (pid / n_blocks) * BM;
+      n0 = (pid % n_blocks) * BN;
+      CFDETR_SET_TILE(m0, n0);
+      CFDETR_ISSUE_SLAB(0, 0);
+    }
+
+    // Epilogue of the finished tile, one 32-row block of the wavefront at a time; the
+    // finished values pass through the wavefront's staging rows in buffer 1, from which
+    // rows leave as 128-byte runs, 16 bytes per lane.
+    {
+      constexpr int ES = EP::kStageElem;
+      constexpr int CPP = 128 / ES;          // columns per staging pass: 64 bf16 or 32 fp32
+      constexpr int NPASS = WTN / CPP;
+      constexpr int STRIDE = 128 + 16;
+      constexpr int NCOPY = 4;               // 8 lanes copy a row, 8 rows per instruction
+      static_assert(NW * 32 * STRIDE <= STAGE, "staging area exceeds a ring buffer");
+      const int nw0 = n0_cur + wn * WTN;
+      if (ep.staged(nw0)) {
+        unsigned char* stg = smem_persist + STAGE + wave * (32 * STRIDE);
+        const int crow = lane >> 3, cchunk = lane & 7;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          const int mb = m0_cur + wm * WTM + i * 32;
+          if (mb >= M) break;
+#pragma unroll
+          for (int ps = 0; ps < NPASS; ++ps) {
+            const int nc0 = nw0 + ps * CPP;   // first column of this pass
+            float4 xin[NCOPY];
+            if (EP::kExtra) {
+#pragma unroll
+              for (int t = 0; t < NCOPY; ++t)
+                xin[t] = ep.extra4(min(mb + t * 8 + crow, M - 1), nc0 + cchunk * (16 / ES), info[i]);
+            }
+#pragma unroll
+            for (int jj = 0; jj < CPP / 32; ++jj) {
+              const int j = ps * (CPP / 32) + jj;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const int nl = jj * 32 + 8 * q + 4 * g;   // column inside the pass
+                const float v4[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                                     acc[i][j][4 * q + 3]};
+                ep.stage4(stg + l32 * STRIDE + nl * ES, nc0 + nl, v4, bias_r[j][q]);
+              }
+            }
+#pragma unroll
+            for (int t = 0; t < NCOPY; ++t) {
+              const int row = t * 8 + crow;
+              const uint4 dd = *reinterpret_cast<const uint4*>(stg + row * STRIDE + cchunk * 16);
+              if (mb + row < M) ep.copy16(mb + row, nc0 + cchunk * (16 / ES), dd, xin[t]);
+            }
+          }
+        }
+      } else {
+        // direct form (columns that do not leave as rows): per-element stores
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          const int m = m0_cur + wm * WTM + i * 32 + l32;
+          if (m >= M || !ep.row_ok(info[i])) continue;
+#pragma unroll
+          for (int j = 0; j < NT; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int n = nw0 + j * 32 + 8 * q + 4 * g;
+              const float v4[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                                   acc[i][j][4 * q + 3]};
+              ep.store4(m, n, v4, bias_r[j][q], ep.extra4(m, n, info[i]), info[i]);
+            }
+          }
+        }
+      }
+    }
+    if (!more) break;
+    v = vn;
+  }
+#undef CFDETR_SET_TILE
+#undef CFDETR_ISSUE_SLAB
+}
+
 // Sum over each group of 16 consecutive lanes, delivered to all 16 (quad swaps, then the
 // mirror of each half-row and of the row: a fixed order, no LDS).
 __device__ __forceinline__ float row16_sum(float v) {
@@ -2014,6 +2242,29 @@ int cu_count() {
   return cus;
 }
 
+// Launch of the staying-workgroup form: the grid is `per_cu` workgroups per CU (what the
+// tile's LDS ring allows), a multiple of 8, and no more than the tiles the capacity yields.
+template <int BM, int BN, int NWM, int NWN, typename EP>
+hipError_t launch_persist_tile(const DenseRows& a, const bf16_t* w, int N, int K, const EP& ep,
+                               const int32_t* m_ptr, int m_host, int m_capacity, int per_cu,
+                               hipStream_t s) {
+  auto kern = gemm_bf16_persist_kernel<BM, BN, NWM, NWN, 64, EP>;
+  if (K % 64 != 0 || N % BN != 0) return hipErrorInvalidValue;
+  if ((size_t)N * K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
+  constexpr size_t lds = (size_t)2 * (BM + BN) * 64 * 2;
+  static_assert(lds <= 160 * 1024, "ring exceeds the LDS");
+  static bool configured = false;
+  hipError_t e = allow_lds(kern, lds, &configured);
+  if (e != hipSuccess) return e;
+  const long tiles = (long)((m_capacity + BM - 1) / BM) * (N / BN);
+  long grid = ((long)cu_count() * per_cu) & ~7L;
+  if (grid < 8) grid = 8;
+  if (tiles < grid) grid = tiles;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NWM * NWN), lds, s, a, w, N, K, ep, m_ptr,
+                     m_host);
+  return hipSuccess;
+}
+
 // Tile choice by problem size: 256x256 (8 wavefronts, 128x64 each) or 192x256 (96x64
 // each) for wide outputs over many rows, 128x128 (4 wavefronts, 64x64 each) while that
 // still yields a workgroup per CU, else 64x64.  The rows that count are the likely ones:
@@ -2045,16 +2296,22 @@ hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& e
     return launch_direct_tile<192, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
   if (CFDETR_TILE_OVERRIDE == 128)
     return launch_direct_tile<128, 128, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+  if (CFDETR_TILE_OVERRIDE == 1256 && N % 256 == 0)
+    return launch_persist_tile<256, 256, 2, 4>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 1, s);
+  if (CFDETR_TILE_OVERRIDE == 1192 && N % 256 == 0)
+    return launch_persist_tile<192, 256, 2, 4>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 1, s);
+  if (CFDETR_TILE_OVERRIDE == 1128)
+    return launch_persist_tile<128, 128, 2, 2>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 2, s);
 #endif
   if (N % 256 == 0 && m >= 8192) {
     const long t256 = 180 * rounds256, t192 = 145 * rounds192, t128 = 100 * rounds128;
     if (t192 < t256 && t192 <= t128)
-      return launch_direct_tile<192, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+      return launch_persist_tile<192, 256, 2, 4>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 1, s);
     if (t256 <= t128)
-      return launch_direct_tile<256, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+      return launch_persist_tile<256, 256, 2, 4>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 1, s);
   }
   if (N % 128 == 0 && tiles128 >= cus)
-    return launch_direct_tile<128, 128, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+    return launch_persist_tile<128, 128, 2, 2>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 2, s);
   return launch_direct_tile<64, 64, 2, 2, 4, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
 }
 
