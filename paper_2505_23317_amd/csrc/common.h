@@ -46,11 +46,17 @@ __device__ __forceinline__ int tok_level(int32_t t) { return (t >> 28) & 0x7; }
 __device__ __forceinline__ int tok_row(int32_t t) { return (t >> 14) & 0x3FFF; }
 __device__ __forceinline__ int tok_col(int32_t t) { return t & 0x3FFF; }
 
-// Frame index of global token t: the i with cu[i] <= t < cu[i+1].
+// Frame index of global token t: the i with cu[i] <= t < cu[i+1] (cu[0] = 0, offsets
+// ascending; frames may be empty, and the last i with cu[i] <= t is the one that holds t).
+// A bisection: its loads depend on each other, and a walk from the front costs up to B of
+// those round trips in front of a tile's first instruction.
 __device__ __forceinline__ int frame_of_token(const int32_t* __restrict__ cu, int B, int t) {
-  int i = 0;
-  while (i + 1 < B && cu[i + 1] <= t) ++i;
-  return i;
+  int lo = 0, hi = B - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (cu[mid] <= t) lo = mid; else hi = mid - 1;
+  }
+  return lo;
 }
 
 template <typename T>

@@ -2288,21 +2288,6 @@ hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& e
   const long rounds192 = (tiles192 + cus - 1) / cus;
   // A deeper ring (3 or 4 buffers, also with slabs of 32) measured no faster for these
   // tiles: their main loops are bound by LDS traffic, not by the latency of the loads.
-#ifdef CFDETR_TILE_OVERRIDE
-  // a development harness sets the tile: 256, 192, 128 (0: the rule below)
-  if (CFDETR_TILE_OVERRIDE == 256 && N % 256 == 0)
-    return launch_direct_tile<256, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
-  if (CFDETR_TILE_OVERRIDE == 192 && N % 256 == 0)
-    return launch_direct_tile<192, 256, 2, 4, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
-  if (CFDETR_TILE_OVERRIDE == 128)
-    return launch_direct_tile<128, 128, 2, 2, 2, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
-  if (CFDETR_TILE_OVERRIDE == 1256 && N % 256 == 0)
-    return launch_persist_tile<256, 256, 2, 4>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 1, s);
-  if (CFDETR_TILE_OVERRIDE == 1192 && N % 256 == 0)
-    return launch_persist_tile<192, 256, 2, 4>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 1, s);
-  if (CFDETR_TILE_OVERRIDE == 1128)
-    return launch_persist_tile<128, 128, 2, 2>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 2, s);
-#endif
   if (N % 256 == 0 && m >= 8192) {
     const long t256 = 180 * rounds256, t192 = 145 * rounds192, t128 = 100 * rounds128;
     if (t192 < t256 && t192 <= t128)
