@@ -57,6 +57,7 @@ struct cfdetr_ctx {
   int32_t* kv_len = nullptr;
   int block_q = 0;
   int32_t* err_flag = nullptr;
+  int32_t* vt_pos = nullptr;     // position of every row of the run in vt (first LayerNorm writes it)
   void* tail_packed = nullptr;   // w_o, w_ff1, w_ff2 of every layer in the fused kernel's order
   uint64_t tail_packed_layer = 0;   // bytes per layer; 0: the shape has no fused kernel
   void* head_packed = nullptr;      // w_qkv of the first layer in the same layout
@@ -322,17 +323,22 @@ cfdetr_status run_encoder(cfdetr_ctx* ctx, const int32_t* cu, int B, int n_prefi
                 launch_layer_head(ctx->x, ctx->head_packed, w.ln1_g, w.ln1_b, eps, w.b_qkv,
                                   attention_q_scale(d / c.n_heads), ctx->qkv, ctx->vt, ctx->vt_ld,
                                   cu_all, ctx->pcu, nseq, d, m_ptr, 0, m_cap, s));
-    else if (!fused_ln || l == 0)
+    else if (!fused_ln || l == 0) {
+      // the first LayerNorm of a bf16 run also lists where every row goes in vt
+      const RowPositions rp{ctx->vt_pos, cu_all, ctx->pcu, nseq};
+      const bool list = bf && l == 0 && d % 4 == 0;
       CF_LAUNCH(CFDETR_K_LN,
                 launch_layernorm(ctx->x, w.ln1_g + (size_t)l * d, w.ln1_b + (size_t)l * d, ctx->a,
-                                 bf, d, eps, m_ptr, 0, m_cap, 0, nullptr, s));
+                                 bf, d, eps, m_ptr, 0, m_cap, 0, nullptr, s, list ? &rp : nullptr));
+    }
     if (fused_tail) {
       // q, k, v of this layer came out of the kernel before (the previous layer's last)
     } else if (bf)
       CF_LAUNCH(CFDETR_K_QKV,
                 launch_gemm_qkv(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, d,
                                 attention_q_scale(d / c.n_heads), ctx->qkv, ctx->vt,
-                                ctx->vt_ld, cu_all, ctx->pcu, nseq, m_ptr, m_hint, m_cap, s));
+                                ctx->vt_ld, cu_all, ctx->pcu, nseq, m_ptr, m_hint, m_cap, s,
+                                d % 4 == 0 ? ctx->vt_pos : nullptr));
     else
       CF_LAUNCH(CFDETR_K_QKV, launch_gemm(ctx->a, wqkv, w.b_qkv + (size_t)l * 3 * d, 3 * d, d,
                                           Epilogue::kBias, ctx->qkv, nullptr, bf, m_ptr, m_hint, m_cap,
@@ -735,6 +741,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   const uint64_t o_hit0 = cv.take(hit_bytes), o_hit1 = cv.take(hit_bytes);
   c->hit_bytes = (int)hit_bytes;
   const uint64_t o_items = cv.take((uint64_t)c->cap8 * 8 * 16), o_err = cv.take(4);
+  const uint64_t o_vtpos = cv.take(Tm * 4);
   const uint64_t o_qh = cv.take((uint64_t)cfg->n_layers * 8 * 4);
   const uint64_t o_nroi = cv.take((uint64_t)kMaxBatch * 4);
   const uint64_t o_tpad = cv.take((uint64_t)cfg->max_tokens_total * 4);
@@ -777,6 +784,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->hit[1] = reinterpret_cast<uint8_t*>(base + o_hit1);
   c->items = reinterpret_cast<int32_t*>(base + o_items);
   c->err_flag = reinterpret_cast<int32_t*>(base + o_err);
+  c->vt_pos = reinterpret_cast<int32_t*>(base + o_vtpos);
   c->queue_heads = reinterpret_cast<int32_t*>(base + o_qh);
   c->n_roi = reinterpret_cast<int32_t*>(base + o_nroi);
   c->tok_pad = reinterpret_cast<int32_t*>(base + o_tpad);

@@ -188,7 +188,9 @@ struct EpiQkv {
   const int32_t* cu;
   const int32_t* pcu;
   int B;
+  const int32_t* vt_pos;   // the positions of all rows, if a kernel before has listed them
   __device__ __forceinline__ int32_t row_info(int m) const {
+    if (vt_pos != nullptr) return vt_pos[m];
     const int f = frame_of_token(cu, B, m);
     return pcu[f] + (m - cu[f]);
   }
@@ -2500,9 +2502,9 @@ hipError_t launch_embed(const EmbedArgs& a, const void* w, const float* bias, in
 hipError_t launch_gemm_qkv(const void* A, const void* W, const float* bias, int d,
                            float q_scale, void* qk, void* vt, int vt_ld, const int32_t* cu_seqlens, const int32_t* pcu,
                            int B, const int32_t* m_ptr, int m_host, int m_capacity,
-                           hipStream_t s) {
+                           hipStream_t s, const int32_t* vt_pos) {
   EpiQkv ep{bias, static_cast<bf16_t*>(qk), 3 * d, 2 * d, d, q_scale, static_cast<bf16_t*>(vt),
-            vt_ld, cu_seqlens, pcu, B};
+            vt_ld, cu_seqlens, pcu, B, vt_pos};
   hipError_t e = launch_direct(A, W, 3 * d, d, ep, m_ptr, m_host, m_capacity, s);
   if (e != hipSuccess) return e;
   return hipGetLastError();

@@ -89,13 +89,23 @@ hipError_t launch_plan(const int32_t* cu_seqlens, int B, const PlanArgs& plan, h
 // Position tables of one level: pe_row [rows, d/2], pe_col [cols, d/2] (fp32).
 hipError_t launch_pe_tables(int patch, int rows, int cols, int img_h, int img_w, int d,
                             float* pe_row, float* pe_col, hipStream_t s);
+// Where the rows of a run sit in the feature-major copy of V: out[m] = pcu[f] + (m - cu[f])
+// for row m of sequence f (cu, pcu: nseq + 1 offsets from launch_plan).
+struct RowPositions {
+  int32_t* out;
+  const int32_t* cu;
+  const int32_t* pcu;
+  int nseq;
+};
 // out = LayerNorm(x) * g + b for rows < M, M = *m_ptr if m_ptr else m_host.
 // out_is_bf16 selects bf16 bit patterns or fp32 for `out`.  Rows >= split_row go to
-// out2 (row - split_row) instead, when out2 is given.
+// out2 (row - split_row) instead, when out2 is given.  With `positions` (widths that are
+// multiples of 4 only) the kernel also fills that table for its rows: every row's frame is
+// found once per run instead of once per projection.
 hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* out,
                             bool out_is_bf16, int d, float eps, const int32_t* m_ptr,
                             int m_host, int m_capacity, int split_row, void* out2,
-                            hipStream_t s);
+                            hipStream_t s, const RowPositions* positions = nullptr);
 // out (bf16 bit patterns) = in (fp32) for the first M * d elements, M = *m_ptr.
 hipError_t launch_cast_bf16(const float* in, void* out, int d, const int32_t* m_ptr,
                             int m_capacity, hipStream_t s);
@@ -228,11 +238,13 @@ hipError_t launch_layer_mid(const void* O, const void* packed, const float* b_o,
 // bf16 query/key/value projection: q and k go to qk [M, 3d] (columns 0..2d, bias added,
 // q multiplied by q_scale = attention_q_scale(d_head) so that the attention kernel gets
 // base-2 logits straight from its first MFMA); v goes feature-major to vt [d, vt_ld] at
-// position pcu[frame] + (token - cu[frame]).
+// position pcu[frame] + (token - cu[frame]); vt_pos (may be null) holds those positions
+// for all rows already (launch_layernorm with `positions`).
 hipError_t launch_gemm_qkv(const void* A, const void* W, const float* bias, int d,
                            float q_scale, void* qk, void* vt, int vt_ld,
                            const int32_t* cu_seqlens, const int32_t* pcu, int B,
-                           const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s);
+                           const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s,
+                           const int32_t* vt_pos = nullptr);
 // log2(e) / sqrt(d_head): the factor the bf16 attention kernel expects folded into q.
 float attention_q_scale(int d_head);
 

@@ -92,11 +92,16 @@ template <typename TOut>
 __global__ __launch_bounds__(256) void layernorm4_kernel(
     const float* __restrict__ x, const float* __restrict__ g, const float* __restrict__ b,
     TOut* __restrict__ out, int d, float eps, const int32_t* __restrict__ m_ptr, int m_host,
-    int split_row, TOut* __restrict__ out2) {
+    int split_row, TOut* __restrict__ out2, RowPositions rp) {
   const int M = m_ptr ? *m_ptr : m_host;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= M) return;
   const int lane = threadIdx.x & 63;
+  if (rp.out != nullptr && lane == 0) {
+    // position of the row in the feature-major copy of V, for the projections that follow
+    const int f = frame_of_token(rp.cu, rp.nseq, row);
+    rp.out[row] = rp.pcu[f] + (row - rp.cu[f]);
+  }
   const int quads = d >> 2;
   const float4* xr = reinterpret_cast<const float4*>(x + (size_t)row * d);
   float4 v[kLnMaxQuads];
@@ -233,19 +238,22 @@ hipError_t launch_pe_tables(int patch, int rows, int cols, int img_h, int img_w,
 hipError_t launch_layernorm(const float* x, const float* g, const float* b, void* out,
                             bool out_is_bf16, int d, float eps, const int32_t* m_ptr,
                             int m_host, int m_capacity, int split_row, void* out2,
-                            hipStream_t s) {
+                            hipStream_t s, const RowPositions* positions) {
   dim3 grid((m_capacity + 3) / 4);
+  const RowPositions none{nullptr, nullptr, nullptr, 0};
   if (d % 4 == 0) {
+    const RowPositions rp = positions ? *positions : none;
     if (out_is_bf16)
       hipLaunchKernelGGL(layernorm4_kernel<bf16_t>, grid, dim3(256), 0, s, x, g, b,
                          static_cast<bf16_t*>(out), d, eps, m_ptr, m_host, split_row,
-                         static_cast<bf16_t*>(out2));
+                         static_cast<bf16_t*>(out2), rp);
     else
       hipLaunchKernelGGL(layernorm4_kernel<float>, grid, dim3(256), 0, s, x, g, b,
                          static_cast<float*>(out), d, eps, m_ptr, m_host, split_row,
-                         static_cast<float*>(out2));
+                         static_cast<float*>(out2), rp);
     return hipGetLastError();
   }
+  if (positions) return hipErrorInvalidValue;
   if (out_is_bf16)
     hipLaunchKernelGGL(layernorm_kernel<bf16_t>, grid, dim3(256), 0, s, x, g, b,
                        static_cast<bf16_t*>(out), d, eps, m_ptr, m_host, split_row,
