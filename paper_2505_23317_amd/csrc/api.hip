@@ -704,8 +704,7 @@ CFDETR_API cfdetr_status cfdetr_create(const cfdetr_config* cfg, const cfdetr_we
   c->n0 = p.rows[0] * p.cols[0];
   c->nonfinest = 0;
   for (int l = 0; l + 1 < cfg->n_levels; ++l) c->nonfinest += p.rows[l] * p.cols[l];
-  c->block_q = attention_block_q(cfg->d_model / cfg->n_heads, c->bf16,
-                                 cfg->max_tokens_total / cfg->max_batch);
+  c->block_q = attention_block_q();
   // Activation buffers hold one merged run: max_batch coarse grids + the mixed sets.
   c->tok_cap = (uint64_t)cfg->max_tokens_total + (uint64_t)cfg->max_batch * c->n0;
   {

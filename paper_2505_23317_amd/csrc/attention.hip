@@ -44,13 +44,6 @@
 // The fp32 kernel (check mode) is the same online softmax with one query per thread.
 #include "kernels.h"
 
-// Phase time stamps of attention_bf16_kernel for a development harness that defines
-// these macros before including the file; nothing otherwise.
-#ifndef CFDETR_ATL
-#define CFDETR_ATL(i_)
-#define CFDETR_ATL_TILES(n_)
-#endif
-
 namespace cfdetr {
 
 namespace {
@@ -124,7 +117,6 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
   // first item: entry blockIdx/8 of the home queue; later ones through the counter, which
   // starts behind the entries handed out this way
   int entry = blockIdx.x >> 3;
-  CFDETR_ATL(0);
   // -1: the queue holds no more entries than were handed out by index (launch_plan)
   const bool drained = queue_heads[home] < 0;
 
@@ -146,7 +138,6 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     const int4 rec = items[home + 8 * entry];
     const int32_t item = rec.x;
     if (item < 0) break;   // entries are in use from the front: the queue is empty
-    CFDETR_ATL(1);
 
     const int frame = item >> 24, head = (item >> 19) & 31, qt = item & 0x7FFFF;
     const int seq0 = rec.y, T = rec.z;
@@ -212,7 +203,6 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
       // every wavefront's part and retires all reads of the other buffer.
       __builtin_amdgcn_s_waitcnt(0x0F70);
       __syncthreads();
-      if (it == 0) CFDETR_ATL(2);
       if (it + 1 < n_kv) CFDETR_ATTN_ISSUE(kv0 + kBlockKV, b ^ 1);
       const unsigned char* cK = b ? sK1 : sK0;
       const unsigned char* cV = b ? sV1 : sV0;
@@ -311,8 +301,6 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
 #undef CFDETR_ATTN_ISSUE
 #undef CFDETR_ATTN_LOGITS
 
-    CFDETR_ATL(3);
-    CFDETR_ATL_TILES(n_kv);
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     const float inv = 1.0f / l_tot;
     const int q_local = qt * BQ + wave * 32 + l32;
@@ -331,7 +319,6 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     }
     // the next entry; the barriers also keep the next item's first fill behind every
     // wavefront's last reads of this one's tiles
-    CFDETR_ATL(4);
     if (drained) break;
     __syncthreads();
     if (tid == 0) s_item = atomicAdd(&queue_heads[home], 1);
@@ -408,12 +395,7 @@ __global__ __launch_bounds__(256) void attention_f32_kernel(
 
 }  // namespace
 
-int attention_block_q(int d_head, bool use_bf16, int tokens_per_frame) {
-  (void)d_head;
-  (void)use_bf16;
-  (void)tokens_per_frame;
-  return 128;
-}
+int attention_block_q() { return 128; }
 
 float attention_q_scale(int d_head) {
   return 1.44269504088896340736f / sqrtf((float)d_head);

@@ -451,12 +451,6 @@ __device__ __forceinline__ int lds_row_key(int r) {
   return ROWB == 128 ? ((r >> 1) & 7) : ((r >> 2) & 3);
 }
 
-// Phase time stamps of gemm_bf16_direct_kernel for a development harness that defines this
-// macro before including the file; nothing otherwise.
-#ifndef CFDETR_GTL
-#define CFDETR_GTL(i_)
-#endif
-
 template <int BM, int BN, int NWM, int NWN, int kStages, int BKT, typename AROWS, typename EP, int KS = 1, int WPE = 1>
 __global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_kernel(
     AROWS arows, const bf16_t* __restrict__ W, int N, int K, EP ep,
@@ -480,7 +474,6 @@ __global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_ker
   static_assert(KS == 1 || (KS == 2 && MT * NT == 1 && kStages == 4 && BKT == 64 && EP::kStageElem == 0),
                 "K split: single-tile wavefronts, direct epilogue");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_direct[];
-  CFDETR_GTL(0);
 
   const int M = m_ptr ? *m_ptr : m_host;
   const int n_blocks = N / BN;
@@ -582,7 +575,6 @@ __global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_ker
   for (int s = 0; s < kStages - 1; ++s)
     if (s < nk) CFDETR_ISSUE_SLAB(s * BKT, s);
   int buf = 0;   // ring position of slab `it`
-  CFDETR_GTL(1);
   constexpr bool kChain = MT * NT == 1 && kStages == 4 && BKT == 64;
   if constexpr (kChain) {
     // A wavefront with a single 32x32 tile (small problems: a workgroup per CU, one
@@ -645,7 +637,6 @@ __global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_ker
     else
       __builtin_amdgcn_s_waitcnt(0x0F70);
     __builtin_amdgcn_s_barrier();
-    CFDETR_GTL(2);
     read_slab(0, fa0, fb0);
     for (int it = 0; it < nk; it += 2) {
       step(it, fa0, fb0, fa1, fb1);
@@ -675,7 +666,6 @@ __global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_ker
     else
       __builtin_amdgcn_s_waitcnt(0x0F70);
     __builtin_amdgcn_s_barrier();
-    if (it == 0) CFDETR_GTL(2);
     if (it + kStages - 1 < nk) {
       const int nb = buf == 0 ? kStages - 1 : buf - 1;   // (buf + kStages - 1) % kStages
       CFDETR_ISSUE_SLAB((it + kStages - 1) * BKT, nb);
@@ -733,7 +723,6 @@ __global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_ker
         for (int r = 0; r < 16; ++r)
           acc[i][j][r] = lo[kHalves ? i : 0][kHalves ? j : 0][r] + acc[i][j][r];
   }
-  CFDETR_GTL(3);
 
   // Epilogue, one 32-row tile of the wavefront at a time.  With a row per lane a store
   // instruction would touch 32 rows with 16 bytes each; instead the finished values
@@ -780,7 +769,6 @@ __global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_ker
           if (mb + row < M) ep.copy16(mb + row, nw0 + cchunk * (16 / ES), d, xin[t]);
         }
       }
-      CFDETR_GTL(4);
       return;
     }
   }
@@ -806,7 +794,6 @@ __global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_ker
       }
     }
   }
-  CFDETR_GTL(4);
 }
 
 // ---------------------------------------------------------------------------

@@ -275,7 +275,7 @@ hipError_t launch_cross_attention(const void* q, const void* k, const void* vt, 
 // Grid of launch_attention on the current device: a multiple of 8, at most 8*cap8;
 // 0 if the device cannot be queried.
 int attention_grid(int d_head, bool use_bf16, int cap8);
-// Queries per workgroup (128 or 256) for a given head width and typical frame length.
-int attention_block_q(int d_head, bool use_bf16, int tokens_per_frame);
+// Queries per work item of both attention kernels.
+int attention_block_q();
 
 }  // namespace cfdetr
