@@ -2256,7 +2256,8 @@ hipError_t launch_persist_tile(const DenseRows& a, const bf16_t* w, int N, int K
 
 // Tile choice by problem size: 256x256 (8 wavefronts, 128x64 each) or 192x256 (96x64
 // each) for wide outputs over many rows, 128x128 (4 wavefronts, 64x64 each) while that
-// still yields a workgroup per CU, else 64x64.  The rows that count are the likely ones:
+// still yields a workgroup per CU, else 64x64 (2 wavefronts, 32x64 each).  All are the
+// staying-workgroup kernel.  The rows that count are the likely ones:
 // with the row count on the device (m_ptr), m_host > 0 is the caller's estimate of it (the
 // kernels do not read it) and the capacity stands in otherwise.  A CU holds one large tile
 // or two 128-tiles; a 256-tile is four times the work of a 128-tile and takes about 1.8
@@ -2286,7 +2287,8 @@ hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& e
   }
   if (N % 128 == 0 && tiles128 >= cus)
     return launch_persist_tile<128, 128, 2, 2>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 2, s);
-  return launch_direct_tile<64, 64, 2, 2, 4, 64>(a, w, N, K, ep, m_ptr, m_host, m_capacity, s);
+  // small problems: 64 x 64 tiles of two wavefronts (32 x 64 each), several per CU
+  return launch_persist_tile<64, 64, 2, 1>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 4, s);
 }
 
 template <int BM, int BN, typename TPix>
