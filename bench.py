@@ -399,6 +399,12 @@ def coarse_stage_table(cfg_id, n_queries=300, dec_layers=6, runs=30):
         enc.select_fine(boxes, tier, offs, B, out["tok_desc"], out["cu_seqlens"], out["level_counts"])
         enc.fine_encode(img, B, out["tok_desc"], out["cu_seqlens"], out["x0_cache"], out["y_mixed"])
 
+    def fine_skipping_easy():
+        # Sec. III-B, A1: frames the difficulty test found easy have no fine stage
+        enc.select_fine_hard(boxes, tier, offs, hard, B, out["tok_desc"], out["cu_seqlens"],
+                             out["level_counts"])
+        enc.fine_encode(img, B, out["tok_desc"], out["cu_seqlens"], out["x0_cache"], out["y_mixed"])
+
     def decode_fine():
         enc.decode(out["y_mixed"], out["cu_seqlens"], B, fq)
 
@@ -434,6 +440,18 @@ def coarse_stage_table(cfg_id, n_queries=300, dec_layers=6, runs=30):
     enc.sync_status()
     res["tokens_per_frame_mixed"] = np.diff(out["cu_seqlens"].cpu().numpy()).tolist()
     res["select_and_fine_encode"] = timed(fine)
+    # the same with half of the frames marked easy by the synthetic queries (no region, and
+    # with the difficulty flags no token): kept in the batch as coarse-only sets, or skipped
+    half = list(range(0, B, 2))
+    sq_easy = torch.from_numpy(synth.make_queries(cfg, cfg_id, n_queries=Q, easy_frames=half)).cuda()
+    propose(sq_easy)
+    res["hard_frames_half_easy"] = int(hard.cpu().numpy().sum())
+    res["select_and_fine_encode_half_easy_kept"] = timed(fine)
+    res["select_and_fine_encode_half_easy_skipped"] = timed(fine_skipping_easy)
+    enc.sync_status()
+    res["tokens_per_frame_mixed_half_easy_skipped"] = np.diff(out["cu_seqlens"].cpu().numpy()).tolist()
+    propose(sq)
+    fine()
     res["decode_fine_stage"] = timed(decode_fine)
     res["merge_detections"] = timed(merge)
     res["whole_loop_decoded_queries"] = timed(loop)
