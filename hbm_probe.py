@@ -30,9 +30,9 @@ STEPS = 3
 
 FAMILIES = [
     ("attention", r"attention_bf16_kernel"),
-    ("gemm_qkv", r"gemm_bf16_direct_kernel.*EpiQkv"),
-    ("gemm_ffn1_gelu", r"gemm_bf16_direct_kernel.*EpiAct<unsigned short, (true|1)>"),
-    ("gemm_residual", r"gemm_bf16_direct_kernel.*EpiResidual|gemm_bf16_rowln_kernel"),
+    ("gemm_qkv", r"gemm_bf16_(direct|persist)_kernel.*EpiQkv"),
+    ("gemm_ffn1_gelu", r"gemm_bf16_(direct|persist)_kernel.*EpiAct<unsigned short, (true|1)>"),
+    ("gemm_residual", r"gemm_bf16_(direct|persist)_kernel.*EpiResidual|gemm_bf16_rowln_kernel"),
     ("layer_tail", r"layer_tail_kernel"),
     ("layer_head", r"layer_head_kernel"),
     ("embed", r"gemm_bf16_gather_kernel|gemm_bf16_direct_kernel.*EpiEmbed"),
