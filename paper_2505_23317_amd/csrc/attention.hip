@@ -87,6 +87,26 @@ __device__ __forceinline__ float exp_tile(const f32x16 (&s)[2], bf16x8 (&pf)[2][
   return psum;
 }
 
+// Clears, in a V^T tile in LDS (row = feature, 8 chunks of 8 keys), the keys from `nvalid`
+// on.  Not inlined on purpose: it runs once per work item, and inlined into the tile loop it
+// costs the kernel an occupancy step (the loop's register budget is what sets it).
+template <int DH>
+__device__ __attribute__((noinline)) void clear_v_padding(unsigned char* wV, int nvalid, int tid) {
+  for (int u = tid; u < DH * 8; u += 256) {
+    const int rho = u >> 3, c = u & 7;   // row (feature), logical chunk of 8 keys
+    const int n = nvalid - 8 * c;        // keys of this chunk inside the sequence
+    if (n < 8) {
+      uint4* q = reinterpret_cast<uint4*>(wV + rho * 128 + ((c ^ swz<128>(rho)) << 4));
+      uint4 w = *q;
+      uint32_t* e = reinterpret_cast<uint32_t*>(&w);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        e[j] &= (2 * j < n ? 0x0000FFFFu : 0u) | (2 * j + 1 < n ? 0xFFFF0000u : 0u);
+      *q = w;
+    }
+  }
+}
+
 template <int DH>
 __global__ __launch_bounds__(256) void attention_bf16_kernel(
     const bf16_t* __restrict__ qbuf, int q_ld, const bf16_t* __restrict__ kbuf, int k_ld,
@@ -211,21 +231,7 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
         // of the sequence are padding that nothing in this run wrote.  They only meet
         // probabilities that are exactly 0, but 0 * NaN is NaN, so they are cleared here:
         // whatever an earlier run left there cannot reach a result.
-        unsigned char* wV = b ? sV1 : sV0;
-        const int nvalid = TK - kv0;
-        for (int u = tid; u < DH * 8; u += 256) {
-          const int rho = u >> 3, c = u & 7;   // row (feature), logical chunk of 8 keys
-          const int n = nvalid - 8 * c;        // keys of this chunk inside the sequence
-          if (n < 8) {
-            uint4* q = reinterpret_cast<uint4*>(wV + rho * 128 + ((c ^ swz<128>(rho)) << 4));
-            uint4 w = *q;
-            uint32_t* e = reinterpret_cast<uint32_t*>(&w);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-              e[j] &= (2 * j < n ? 0x0000FFFFu : 0u) | (2 * j + 1 < n ? 0xFFFF0000u : 0u);
-            *q = w;
-          }
-        }
+        clear_v_padding<DH>(b ? sV1 : sV0, TK - kv0, tid);
         __syncthreads();
       }
 
