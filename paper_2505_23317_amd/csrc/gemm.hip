@@ -810,8 +810,8 @@ __global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_ker
 // K is contracted in ascending slabs of BKT by every tile shape, so a result does not
 // depend on the tile that produced it.
 // ---------------------------------------------------------------------------
-template <int BM, int BN, int NWM, int NWN, int BKT, typename EP>
-__global__ __launch_bounds__(64 * NWM * NWN) void gemm_bf16_persist_kernel(
+template <int BM, int BN, int NWM, int NWN, int BKT, typename EP, int WPE = 1>
+__global__ __launch_bounds__(64 * NWM * NWN, WPE) void gemm_bf16_persist_kernel(
     DenseRows arows, const bf16_t* __restrict__ W, int N, int K, EP ep,
     const int32_t* __restrict__ m_ptr, int m_host) {
   constexpr int kStages = 2;
@@ -2233,11 +2233,11 @@ int cu_count() {
 
 // Launch of the staying-workgroup form: the grid is `per_cu` workgroups per CU (what the
 // tile's LDS ring allows), a multiple of 8, and no more than the tiles the capacity yields.
-template <int BM, int BN, int NWM, int NWN, typename EP>
+template <int BM, int BN, int NWM, int NWN, int WPE = 1, typename EP>
 hipError_t launch_persist_tile(const DenseRows& a, const bf16_t* w, int N, int K, const EP& ep,
                                const int32_t* m_ptr, int m_host, int m_capacity, int per_cu,
                                hipStream_t s) {
-  auto kern = gemm_bf16_persist_kernel<BM, BN, NWM, NWN, 64, EP>;
+  auto kern = gemm_bf16_persist_kernel<BM, BN, NWM, NWN, 64, EP, WPE>;
   if (K % 64 != 0 || N % BN != 0) return hipErrorInvalidValue;
   if ((size_t)N * K * 2 >= ((size_t)1 << 32)) return hipErrorInvalidValue;
   constexpr size_t lds = (size_t)2 * (BM + BN) * 64 * 2;
@@ -2255,14 +2255,17 @@ hipError_t launch_persist_tile(const DenseRows& a, const bf16_t* w, int N, int K
 }
 
 // Tile choice by problem size: 256x256 (8 wavefronts, 128x64 each) or 192x256 (96x64
-// each) for wide outputs over many rows, 128x128 (4 wavefronts, 64x64 each) while that
-// still yields a workgroup per CU, else 64x64 (2 wavefronts, 32x64 each).  All are the
-// staying-workgroup kernel.  The rows that count are the likely ones:
-// with the row count on the device (m_ptr), m_host > 0 is the caller's estimate of it (the
-// kernels do not read it) and the capacity stands in otherwise.  A CU holds one large tile
-// or two 128-tiles; a 256-tile is four times the work of a 128-tile and takes about 1.8
-// times as long as a pair of them, a 192x256 tile 1.45 times, so what decides at a few
-// rounds is how full the last round is: the estimate is rounds x time per round.
+// each) for wide outputs over many rows, 192x128 or 128x128 (4 wavefronts, 96x64 or 64x64
+// each, two workgroups per CU) while that still yields a workgroup per CU, else 64x64
+// (2 wavefronts, 32x64 each).  All are the staying-workgroup kernel.  The rows that count
+// are the likely ones: with the row count on the device (m_ptr), m_host > 0 is the caller's
+// estimate of it (the kernels do not read it) and the capacity stands in otherwise.  A CU
+// holds one large tile or two of the four-wavefront tiles; against a pair of 128-tiles a
+// 256-tile is twice the work per CU and takes about 1.8 times as long, a 192x256 tile or a
+// pair of 192x128 tiles 1.5 times the work in about 1.45 to 1.5 times as long, so what
+// decides at a few rounds is how full the last round is: the estimate is rounds x time per
+// round.  (24 470 rows x 384 columns are 576 tiles of 128x128 for 512 places, two rounds
+// of which the second is an eighth full, and 384 tiles of 192x128, one round.)
 template <typename EP>
 hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& ep,
                          const int32_t* m_ptr, int m_host, int m_capacity, hipStream_t s) {
@@ -2274,18 +2277,24 @@ hipError_t launch_direct(const void* A, const void* W, int N, int K, const EP& e
   const long tiles128 = (long)((m + 127) / 128) * (N / 128);
   const long tiles256 = (long)((m + 255) / 256) * (N / 256);
   const long tiles192 = (long)((m + 191) / 192) * (N / 256);
+  const long tiles192n = (long)((m + 191) / 192) * (N / 128);
   const long rounds128 = (tiles128 + 2 * cus - 1) / (2 * cus), rounds256 = (tiles256 + cus - 1) / cus;
-  const long rounds192 = (tiles192 + cus - 1) / cus;
+  const long rounds192 = (tiles192 + cus - 1) / cus, rounds192n = (tiles192n + 2 * cus - 1) / (2 * cus);
+  const long t128 = 100 * rounds128, t192n = 150 * rounds192n;
+  const bool narrow_ok = N % 128 == 0 && tiles128 >= cus;
   // A deeper ring (3 or 4 buffers, also with slabs of 32) measured no faster for these
   // tiles: their main loops are bound by LDS traffic, not by the latency of the loads.
   if (N % 256 == 0 && m >= 8192) {
-    const long t256 = 180 * rounds256, t192 = 145 * rounds192, t128 = 100 * rounds128;
-    if (t192 < t256 && t192 <= t128)
+    const long t256 = 180 * rounds256, t192 = 145 * rounds192;
+    const long tn = t192n < t128 ? t192n : t128;
+    if (t192 < t256 && t192 <= tn)
       return launch_persist_tile<192, 256, 2, 4>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 1, s);
-    if (t256 <= t128)
+    if (t256 <= tn)
       return launch_persist_tile<256, 256, 2, 4>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 1, s);
   }
-  if (N % 128 == 0 && tiles128 >= cus)
+  if (narrow_ok && m >= 8192 && t192n < t128)
+    return launch_persist_tile<192, 128, 2, 2, 2>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 2, s);
+  if (narrow_ok)
     return launch_persist_tile<128, 128, 2, 2>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 2, s);
   // small problems: 64 x 64 tiles of two wavefronts (32 x 64 each), several per CU
   return launch_persist_tile<64, 64, 2, 1>(a, w, N, K, ep, m_ptr, m_host, m_capacity, 4, s);
