@@ -389,9 +389,14 @@ def test_no_roi_gives_the_coarse_result(K):
     np.testing.assert_array_equal(got["y_mixed"][:2 * n0], got["y_coarse"])
 
 
-def test_batched_equals_frame_by_frame(K):
-    cfg = synth.replace(synth.config(3), B=3, layers=2)
+@pytest.mark.parametrize("cfg_id", [3, 4])
+def test_batched_equals_frame_by_frame(K, cfg_id):
+    """A frame's result does not depend on its batch, bit for bit.  At cfg 4's size the batch
+    and the single frames also get different contraction tiles (192 x 128 and 128 x 128 against
+    smaller ones), which must not show either."""
+    cfg = synth.replace(synth.config(cfg_id), B=3 if cfg_id == 3 else 4, layers=2)
     wl = synth.make_workload(cfg, seed=41, sharp=True)
+    _say(f"[case] batched vs frame by frame, {cfg.name} with {cfg.B} frames, 2 layers")
     full = gpu_multilevel(K, cfg, wl, "bf16")
     cu = full["cu_seqlens"]
     n0 = cfg.n_cells(0)
