@@ -105,3 +105,36 @@ def test_decoder_invariants():
     dw1 = dict(dw); dw1["b_cls"] = dw["b_cls"] - 1.0
     low = O.decode_frame(mem, dw1, cfg.heads)
     assert (low[:, 4] < out[:, 4]).all() and np.array_equal(low[:, :4], out[:, :4])
+
+
+def test_detection_heads_hand_worked():
+    """The confidence and box heads against values worked by hand (closed-form sigmoids of
+    logarithms; tests/golden/decoder_heads_worked_example.txt): no decoder layer, width 2, so
+    the heads see the final LayerNorm of the query vectors.  A transposed matrix, a missing
+    ReLU, a swapped output or a sign error in either head changes at least one value."""
+    import os
+    from fractions import Fraction
+    want = {}
+    path = os.path.join(os.path.dirname(__file__), "golden", "decoder_heads_worked_example.txt")
+    with open(path) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, *vals = line.split()
+            want[name] = [float(Fraction(v)) for v in vals]
+    ln = math.log
+    e = lambda *shape: np.zeros(shape)
+    dw = {
+        "query_embed": np.array([[1000.0, -1000.0], [-3000.0, 3000.0]]),
+        "w_qkv": e(0, 6, 2),   # no layers: nothing else of a layer is read
+        "lnf_g": np.array([1.0, 2.0]), "lnf_b": e(2),
+        "w_cls": np.array([[ln(3), 0.0]]), "b_cls": e(1),
+        "w_box1": np.array([[1.0, 1.0], [0.0, -1.0]]), "b_box1": np.array([2.0, -1.0]),
+        "w_box2": np.array([[1.0, -1.0], [2.0, 0.0]]), "b_box2": np.array([0.0, -1.0]),
+        "w_box3": np.array([[ln(3), 0.0], [0.0, ln(3)], [ln(2), -ln(2)], [0.0, 0.0]]),
+        "b_box3": np.array([0.0, 0.0, 0.0, -ln(9)]),
+    }
+    got = O.decode_frame(np.ones((3, 2)), dw, 1)
+    assert got.shape == (2, 5)
+    assert np.abs(got[0] - want["A"]).max() < 1e-9
+    assert np.abs(got[1] - want["B"]).max() < 1e-9
