@@ -52,9 +52,6 @@ constexpr int kBlockKV = 64;
 constexpr float kLazyLimit = 4096.0f;   // tile sum above which the reference maximum moves
 constexpr float kTinySum = 0x1p-20f;    // running sum below which an unanchored reference moves
 
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef const __attribute__((address_space(1))) void* global_void_ptr;
-
 __device__ __forceinline__ int swap_bits_2_3(int i) {
   return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
 }
@@ -85,6 +82,17 @@ __device__ __forceinline__ float exp_tile(const f32x16 (&s)[2], bf16x8 (&pf)[2][
       pf[sub][t] = *reinterpret_cast<bf16x8*>(&packed);
     }
   return psum;
+}
+
+// One 16-byte piece per lane from global memory straight into LDS (1 KB per wavefront at
+// lds_addr, lane order): the address is a base in scalar registers plus the lane's 32-bit
+// byte offset, so a tile that lies inside its sequence costs no vector arithmetic.  The
+// compiler does not count these loads; the tile loop waits with vmcnt(0) itself.
+__device__ __forceinline__ void attn_dma16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(sbase)
+               : "memory");
 }
 
 // Clears, in a V^T tile in LDS (row = feature, 8 chunks of 8 keys), the keys from `nvalid`
@@ -131,7 +139,8 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
   __shared__ __attribute__((aligned(1024))) unsigned char sV1[VBYTES];
   __shared__ int32_t s_item;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, g = lane >> 5;
   const int home = blockIdx.x & 7;   // queue of this workgroup; w mod 8 is also its XCD
   // first item: entry blockIdx/8 of the home queue; later ones through the counter, which
@@ -140,15 +149,23 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
   // -1: the queue holds no more entries than were handed out by index (launch_plan)
   const bool drained = queue_heads[home] < 0;
 
-  // Loader roles.  K: LDS row rho <- key (rho & 32) | swap23(rho & 31), chunk swizzled.
-  int k_key[KI];
-  int k_chunk[KI];
+  // Loader roles, as byte offsets of the lane's piece from the tile's first key (K) or
+  // first position (V^T).  K: LDS row rho <- key (rho & 32) | swap23(rho & 31), chunk
+  // swizzled.  V^T: LDS row rho = dh index; 64 keys = 8 chunks of 8.
+  uint32_t k_off[KI], v_off[VI];
 #pragma unroll
   for (int j = 0; j < KI; ++j) {
     const int rho = (wave * KI + j) * KRPI + lane / KCPR;
-    k_key[j] = (rho & 32) | swap_bits_2_3(rho & 31);
-    k_chunk[j] = (lane % KCPR) ^ swz<KROWB>(rho);
+    const int key = (rho & 32) | swap_bits_2_3(rho & 31);
+    k_off[j] = (uint32_t)key * (uint32_t)(k_ld * 2) + (uint32_t)(((lane % KCPR) ^ swz<KROWB>(rho)) * 16);
   }
+#pragma unroll
+  for (int j = 0; j < VI; ++j) {
+    const int rho = (wave * VI + j) * 8 + (lane >> 3);
+    v_off[j] = ((uint32_t)rho * (uint32_t)vt_ld + (uint32_t)(((lane & 7) ^ swz<128>(rho)) * 8)) * 2u;
+  }
+  const uint32_t lds_k0 = (uint32_t)(uintptr_t)sK0, lds_k1 = (uint32_t)(uintptr_t)sK1;
+  const uint32_t lds_v0 = (uint32_t)(uintptr_t)sV0, lds_v1 = (uint32_t)(uintptr_t)sV1;
 
   for (;;) {
     // An entry is four words: the item, then offset, length and padded offset of its
@@ -178,26 +195,28 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
       for (int ks = 0; ks < KS; ++ks)
         qf[ks] = *reinterpret_cast<const bf16x8*>(qbase + (size_t)q_load * q_ld + ks * 16 + g * 8);
     }
-    // V^T: LDS row rho = dh index; 64 keys = 8 chunks of 8.
-    const bf16_t* v_src[VI];
-#pragma unroll
-    for (int j = 0; j < VI; ++j) {
-      const int rho = (wave * VI + j) * 8 + (lane >> 3);
-      const int chunk = (lane & 7) ^ swz<128>(rho);
-      v_src[j] = vt + (size_t)(head * DH + rho) * vt_ld + kpad0 + chunk * 8;
-    }
+    const bf16_t* vbase = vt + (size_t)(head * DH) * vt_ld + kpad0;
 
+    // Fill of the tile that starts at key kv0_: inside the sequence the lane offsets are the
+    // constants above; the last, ragged tile clamps its keys to the sequence (the lanes that
+    // would read past it fetch the last key again; their logits are masked).
 #define CFDETR_ATTN_ISSUE(kv0_, buf_)                                                        \
   do {                                                                                       \
-    _Pragma("unroll") for (int j = 0; j < KI; ++j) {                                         \
-      const int key = min((kv0_) + k_key[j], TK - 1);                                        \
-      __builtin_amdgcn_global_load_lds(                                                      \
-          (global_void_ptr)(kbase + (size_t)key * k_ld + k_chunk[j] * 8),                    \
-          (lds_void_ptr)(((buf_) ? sK1 : sK0) + (wave * KI + j) * 1024), 16, 0, 0);          \
+    const bf16_t* kb_ = kbase + (size_t)(kv0_) * k_ld;                                       \
+    const uint32_t lk_ = ((buf_) ? lds_k1 : lds_k0) + wave * (KI * 1024);                    \
+    if ((kv0_) + kBlockKV <= TK) {                                                           \
+      _Pragma("unroll") for (int j = 0; j < KI; ++j) attn_dma16(kb_, k_off[j], lk_ + j * 1024); \
+    } else {                                                                                 \
+      _Pragma("unroll") for (int j = 0; j < KI; ++j) {                                       \
+        const int rho = (wave * KI + j) * KRPI + lane / KCPR;                                \
+        const int key = min((rho & 32) | swap_bits_2_3(rho & 31), TK - 1 - (kv0_));          \
+        attn_dma16(kb_, (uint32_t)key * (uint32_t)(k_ld * 2) +                               \
+                            (uint32_t)(((lane % KCPR) ^ swz<KROWB>(rho)) * 16), lk_ + j * 1024); \
+      }                                                                                      \
     }                                                                                        \
-    _Pragma("unroll") for (int j = 0; j < VI; ++j) __builtin_amdgcn_global_load_lds(         \
-        (global_void_ptr)(v_src[j] + (kv0_)),                                                \
-        (lds_void_ptr)(((buf_) ? sV1 : sV0) + (wave * VI + j) * 1024), 16, 0, 0);            \
+    const bf16_t* vb_ = vbase + (kv0_);                                                      \
+    const uint32_t lv_ = ((buf_) ? lds_v1 : lds_v0) + wave * (VI * 1024);                    \
+    _Pragma("unroll") for (int j = 0; j < VI; ++j) attn_dma16(vb_, v_off[j], lv_ + j * 1024); \
   } while (0)
 
     f32x16 acc_o[MO];
