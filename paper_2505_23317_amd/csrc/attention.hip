@@ -9,10 +9,10 @@
 // a query is a LANE:
 //   S^T[key, q] = K . Q^T          (MFMA A = K rows from LDS, B = Q rows in registers)
 //   O^T[dh, q] += V^T . P^T        (MFMA A = V^T rows from LDS, B = P from registers)
-// In the MFMA result layout a lane then holds 16 keys of ONE query, so the running
-// max, the running sum and the rescale factor are per-lane scalars, the only
-// cross-lane step is one exchange between lane l and l^32, and the probabilities
-// feed the second MFMA straight from registers.  For that to work the 8 keys a
+// In the MFMA result layout a lane then holds 16 keys of ONE query, so the sum of its
+// probabilities is a per-lane scalar, the only cross-lane step is one exchange between
+// lane l and l^32 at the end, and the probabilities feed the second MFMA straight from
+// registers.  For that to work the 8 keys a
 // lane contributes to one k-step must sit in 8 consecutive result registers: LDS row
 // rho of a 32-key sub-tile therefore holds the key whose index is rho with bits 2
 // and 3 swapped (result register r of lane group g holds row 8*(r/4)+4*g+r%4, which
@@ -23,15 +23,17 @@
 // unpadded; 16-byte chunks are XOR-swizzled by row so that operand reads of 16
 // consecutive rows hit disjoint banks.
 //
-// Softmax arithmetic per element is one exp2, one add and half a convert:
-//  * q arrives multiplied by log2(e)/sqrt(dh), so S is a base-2 logit;
-//  * the first MFMA of S starts from an accumulator that holds -m (m: the reference
-//    maximum of the query) in all registers, so S leaves the matrix unit already shifted;
-//  * m is only a reference point, not the exact running maximum.  It starts at 0 and
-//    moves when a tile's probabilities sum above 2^12, or when it has never moved and
-//    the running sum is below 2^-20; the tile is then redone against the largest logit
-//    so far and the accumulators are rescaled.  Any reference gives the same quotient
-//    O / l; a bounded lag only shifts the fp32 exponents in use.
+// Softmax arithmetic per element is one exp2, one add and half a convert: q arrives
+// multiplied by log2(e)/sqrt(dh), so S is a base-2 logit, and the probabilities are taken as
+// 2^S, relative to the reference 0 and not to a running maximum: O / l is the same quotient
+// for any reference, floating point keeps the same relative precision at any magnitude, and
+// no maximum has to be tracked, compared or applied.  What a fixed reference cannot do is
+// stay inside the exponent range: when a query's sum of probabilities ends outside
+// [2^-64, 2^100] (or is no number), some probability that matters may have been flushed to
+// zero or have overflowed; the workgroup then walks the item's keys again, once for the
+// largest logit of every query and once with the probabilities relative to it, which is
+// exact for any logits.  Trained or randomly initialised weights do not get there (|S| of
+// a few tens); the parity tests force it.
 //
 // Work distribution: sequences differ in length by 2-3x, so a fixed item -> workgroup
 // map leaves CUs idle while the longest items finish.  The grid is sized to what the
@@ -41,7 +43,10 @@
 // placement; with the usual round-robin placement those all sit on one XCD and share
 // its L2.
 //
-// The fp32 kernel (check mode) is the same online softmax with one query per thread.
+// The fp32 kernel (check mode) is an online softmax (running maximum) with one query per
+// thread.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace cfdetr {
@@ -49,8 +54,12 @@ namespace cfdetr {
 namespace {
 
 constexpr int kBlockKV = 64;
-constexpr float kLazyLimit = 4096.0f;   // tile sum above which the reference maximum moves
-constexpr float kTinySum = 0x1p-20f;    // running sum below which an unanchored reference moves
+// sums of probabilities (relative to the reference 0) outside this range send an item
+// through the exact walk: below, probabilities that matter may have been flushed to zero
+// (normal numbers end at 2^-126; 2^24 flushed ones add up to less than 2^-100); above, one
+// may have overflowed
+constexpr float kSumLow = 0x1p-64f, kSumHigh = 0x1p+100f;
+constexpr int kFast = 0, kScan = 1, kExact = 2;
 
 __device__ __forceinline__ int swap_bits_2_3(int i) {
   return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
@@ -219,114 +228,119 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(
     _Pragma("unroll") for (int j = 0; j < VI; ++j) attn_dma16(vb_, v_off[j], lv_ + j * 1024); \
   } while (0)
 
+    // One walk over the key tiles of the item.  kFast: probabilities relative to the
+    // reference 0.  kScan: only the largest logit of every query.  kExact: probabilities
+    // relative to m_ref (that largest logit).  All wavefronts of the workgroup take the same
+    // walks (the tiles and the barriers are shared).
     f32x16 acc_o[MO];
-    f32x16 negm;        // -m in every register: the start value of S
-    float l_run = 0.f;
-    bool anchored = false;   // wave-uniform: the reference has been moved at least once
-#pragma unroll
-    for (int r = 0; r < 16; ++r) negm[r] = 0.f;
-#pragma unroll
-    for (int i = 0; i < MO; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
-
+    float l_run = 0.f;    // sum of the probabilities of this lane's keys
+    float m_ref = 0.f;
     const int n_kv = (TK + kBlockKV - 1) / kBlockKV;
-    CFDETR_ATTN_ISSUE(0, 0);
-    for (int it0 = 0; it0 < n_kv; it0 += 2) {
-#pragma unroll
-     for (int b = 0; b < 2; ++b) {   // buffer index: a constant after unrolling
-      const int it = it0 + b;
-      if (it >= n_kv) break;
-      const int kv0 = it * kBlockKV;
-      // vmcnt(0): this wavefront's part of tile `it` is in LDS; the barrier publishes
-      // every wavefront's part and retires all reads of the other buffer.
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      __syncthreads();
-      if (it + 1 < n_kv) CFDETR_ATTN_ISSUE(kv0 + kBlockKV, b ^ 1);
-      const unsigned char* cK = b ? sK1 : sK0;
-      const unsigned char* cV = b ? sV1 : sV0;
-      if (kv0 + kBlockKV > TK) {
-        // Last, ragged tile (no fill is in flight any more): the V^T positions past the end
-        // of the sequence are padding that nothing in this run wrote.  They only meet
-        // probabilities that are exactly 0, but 0 * NaN is NaN, so they are cleared here:
-        // whatever an earlier run left there cannot reach a result.
-        clear_v_padding<DH>(b ? sV1 : sV0, TK - kv0, tid);
-        __syncthreads();
-      }
-
-      // S^T - m for the two 32-key sub-tiles; keys past the end of the frame (last tile
-      // only) get -inf.
-      f32x16 s[2];
-#define CFDETR_ATTN_LOGITS()                                                                  \
-  do {                                                                                        \
-    _Pragma("unroll") for (int sub = 0; sub < 2; ++sub) {                                     \
-      const int rho = sub * 32 + l32;                                                         \
-      _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                     \
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(                                   \
-            cK + rho * KROWB + (((2 * ks + g) ^ swz<KROWB>(rho)) << 4));                      \
-        s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? negm : s[sub], \
-                                                         0, 0, 0);                            \
-      }                                                                                       \
-    }                                                                                         \
-    if (kv0 + kBlockKV > TK) {                                                                \
-      _Pragma("unroll") for (int sub = 0; sub < 2; ++sub)                                     \
-      _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                        \
-        const int key = kv0 + sub * 32 + 16 * (r >> 3) + 8 * g + (r & 7);                     \
-        if (key >= TK) s[sub][r] = -INFINITY;                                                 \
-      }                                                                                       \
-    }                                                                                         \
-  } while (0)
-      CFDETR_ATTN_LOGITS();
-      bf16x8 pf[2][2];
-      float psum = exp_tile(s, pf);
-      // Rare: some probability is far above 1, or nothing has anchored the reference yet
-      // and the sums are vanishing.  Move the reference to the largest logit so far
-      // (max of this tile's logits and log2 of the running sum) and redo the tile.
-      if (__any(!(psum <= kLazyLimit) || (!anchored && !(l_run + psum >= kTinySum)))) {
-        anchored = true;
-        CFDETR_ATTN_LOGITS();   // not kept across the exponentials
-        float mx = -INFINITY;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
-        const float delta = fmaxf(mx, __builtin_amdgcn_logf(l_tot));   // log2; -inf for 0
-        const float alpha = fminf(__builtin_amdgcn_exp2f(-delta), 0x1p126f);
-        l_run *= alpha;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) negm[r] -= delta;
+    auto walk = [&](auto mode_tag) {
+      constexpr int kMode = decltype(mode_tag)::value;
+      float smax = -INFINITY;
+      if (kMode != kScan) {
+        l_run = 0.f;
 #pragma unroll
         for (int i = 0; i < MO; ++i)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) s[sub][r] -= delta;
-        psum = exp_tile(s, pf);
+          for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
       }
-      l_run += psum;
-      // O^T += V^T . P^T
+      CFDETR_ATTN_ISSUE(0, 0);
+      for (int it0 = 0; it0 < n_kv; it0 += 2) {
 #pragma unroll
-      for (int i = 0; i < MO; ++i) {
-        const int rho = i * 32 + l32;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            const bf16x8 vf = *reinterpret_cast<const bf16x8*>(
-                cV + rho * 128 + (((4 * sub + 2 * t + g) ^ swz<128>(rho)) << 4));
-            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sub][t], acc_o[i], 0, 0, 0);
+        for (int b = 0; b < 2; ++b) {   // buffer index: a constant after unrolling
+          const int it = it0 + b;
+          if (it >= n_kv) break;
+          const int kv0 = it * kBlockKV;
+          // vmcnt(0): this wavefront's part of tile `it` is in LDS; the barrier publishes
+          // every wavefront's part and retires all reads of the other buffer.
+          __builtin_amdgcn_s_waitcnt(0x0F70);
+          __syncthreads();
+          if (it + 1 < n_kv) CFDETR_ATTN_ISSUE(kv0 + kBlockKV, b ^ 1);
+          const unsigned char* cK = b ? sK1 : sK0;
+          const unsigned char* cV = b ? sV1 : sV0;
+          if (kMode != kScan && kv0 + kBlockKV > TK) {
+            // Last, ragged tile (no fill is in flight any more): the V^T positions past the
+            // end of the sequence are padding that nothing in this run wrote.  They only
+            // meet probabilities that are exactly 0, but 0 * NaN is NaN, so they are cleared
+            // here: whatever an earlier run left there cannot reach a result.
+            clear_v_padding<DH>(b ? sV1 : sV0, TK - kv0, tid);
+            __syncthreads();
           }
+
+          // S^T for the two 32-key sub-tiles; keys past the end of the frame (last tile
+          // only) get -inf.
+          f32x16 s[2];
+#pragma unroll
+          for (int sub = 0; sub < 2; ++sub) {
+            const int rho = sub * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+              const bf16x8 kf = *reinterpret_cast<const bf16x8*>(
+                  cK + rho * KROWB + (((2 * ks + g) ^ swz<KROWB>(rho)) << 4));
+              s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[sub], 0, 0, 0);
+            }
+          }
+          if (kv0 + kBlockKV > TK) {
+            asm volatile("" ::: "memory");   // keeps this a branch: one tile per item comes here
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int key = kv0 + sub * 32 + 16 * (r >> 3) + 8 * g + (r & 7);
+                if (key >= TK) s[sub][r] = -INFINITY;
+              }
+          }
+          if (kMode == kScan) {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) smax = fmaxf(smax, s[sub][r]);
+            continue;
+          }
+          if (kMode == kExact) {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) s[sub][r] -= m_ref;
+          }
+          bf16x8 pf[2][2];
+          l_run += exp_tile(s, pf);
+          // O^T += V^T . P^T
+#pragma unroll
+          for (int i = 0; i < MO; ++i) {
+            const int rho = i * 32 + l32;
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+              for (int t = 0; t < 2; ++t) {
+                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(
+                    cV + rho * 128 + (((4 * sub + 2 * t + g) ^ swz<128>(rho)) << 4));
+                acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sub][t], acc_o[i], 0, 0, 0);
+              }
+          }
+        }
       }
-     }
+      return smax;
+    };
+
+    walk(std::integral_constant<int, kFast>{});
+    float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+    // A sum that left the range in which every probability that matters is a normal number
+    // (some logit beyond +-100 or so in base 2; also inf and NaN): find every query's
+    // largest logit first and take the probabilities relative to it.
+    if (__syncthreads_or(!(l_tot >= kSumLow && l_tot <= kSumHigh))) {
+      const float smax = walk(std::integral_constant<int, kScan>{});
+      m_ref = fmaxf(smax, __shfl_xor(smax, 32, kWave));
+      __syncthreads();   // every wavefront is done with the last tile of the scan
+      walk(std::integral_constant<int, kExact>{});
+      l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     }
 #undef CFDETR_ATTN_ISSUE
-#undef CFDETR_ATTN_LOGITS
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     const float inv = 1.0f / l_tot;
     const int q_local = qt * BQ + wave * 32 + l32;
     if (q_local < T) {

@@ -2,10 +2,10 @@
 to every token of its frame): logits far from zero in either direction, a wide spread with
 the winning key in the last, ragged key tile, and sequence lengths around the tile size.
 
-The bf16 kernel keeps a reference exponent per query that moves only when a tile's
-probabilities get large, or when nothing has anchored it yet and the sums are vanishing;
-ordinary random weights reach neither case.  The weights here are built so that every query
-of a head sees the same logit vector (query matrix zero, query bias along one direction, key
+The bf16 kernel takes probabilities as powers of two of the logits themselves and walks an
+item a second time, relative to every query's largest logit, only when a sum of probabilities
+leaves the range in which that is exact; ordinary random weights never get there.  The
+weights here are built so that every query of a head sees the same logit vector (query matrix zero, query bias along one direction, key
 matrix of rank one): logits are then either all equal or separated by many units, so the
 bf16 rounding of q and k cannot move the result and the usual bar applies.
 
@@ -115,18 +115,22 @@ def _logits_of_frame(x, w, cfg):
 
 
 CASES = {
-    # every logit the same, far below zero: nothing anchors the reference until the sums
-    # would vanish (2^-60 per key)
+    # every logit the same, far below zero (2^-60 per key: small, still exact)
     "flat_far_negative": dict(spread=0.0, offset=-60.0, winner=None),
-    # every logit the same, far above zero: the first tile's sum is 64 * 2^40
+    # every logit the same, far above zero: a tile's sum is 64 * 2^40
     "flat_far_positive": dict(spread=0.0, offset=40.0, winner=None),
     # spread of ~30 units, the winning key moved to the end of its frame (the last, ragged
-    # key tile where the length is no multiple of 64): the reference moves there once more
+    # key tile where the length is no multiple of 64)
     "wide_winner_last": dict(spread=30.0, offset=0.0, winner="last"),
-    # the same spread 80 units down: vanishing sums first, then keys far above the reference
+    # the same spread 80 units down: sums near the lower end of the exact range
     "wide_low_winner_last": dict(spread=30.0, offset=-80.0, winner="last"),
-    # winner first: the reference moves in the first tile and never again
+    # winner first
     "wide_winner_first": dict(spread=30.0, offset=0.0, winner="first"),
+    # logits beyond what a power of two of them can hold in fp32 (2^-200 is flushed to zero,
+    # 2^180 is infinite): only probabilities relative to the largest logit exist
+    "flat_below_the_exponent_range": dict(spread=0.0, offset=-200.0, winner=None),
+    "flat_above_the_exponent_range": dict(spread=0.0, offset=180.0, winner=None),
+    "wide_above_the_exponent_range": dict(spread=30.0, offset=150.0, winner="last"),
 }
 
 
