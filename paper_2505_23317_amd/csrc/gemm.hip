@@ -801,12 +801,13 @@ __global__ __launch_bounds__(64 * NWM * NWN * KS, WPE) void gemm_bf16_direct_ker
 // workgroups stay: the grid is what the chip holds at once and workgroup w walks over the
 // tiles w, w + grid, w + 2 grid, ... of the XCD-grouped order.  What a tile costs besides
 // its main loop is thereby paid once per workgroup (the row count from device memory) or
-// hidden: right behind a tile's last slab the first slab of the next tile is requested
-// into ring buffer 0, and arrives while the epilogue of the finished tile runs, with its
-// staging area in ring buffer 1.  A staging row is 128 bytes (64 bf16 or 32 fp32 columns,
-// the latter in two passes per 64 columns), so the area of all wavefronts fits one buffer.
-// Every tile starts with vmcnt(0): the epilogue's stores are younger than the requested
-// slab and their number is not known to the wait.
+// hidden: together with a tile's last slab being worked on, the first slab of the next tile
+// is requested into the free ring buffer; it is waited for before the epilogue's stores are
+// issued (the wait counter is in order: behind them the wait would last until they are
+// done), so the next tile starts computing at once and its second slab comes in behind the
+// stores.  The epilogue's staging area is the other ring buffer.  A staging row is 128
+// bytes (64 bf16 or 32 fp32 columns, the latter in two passes per 64 columns), so the area
+// of all wavefronts fits one buffer.
 // K is contracted in ascending slabs of BKT by every tile shape, so a result does not
 // depend on the tile that produced it.
 // ---------------------------------------------------------------------------
@@ -874,6 +875,8 @@ __global__ __launch_bounds__(64 * NWM * NWN, WPE) void gemm_bf16_persist_kernel(
   int m0 = (pid / n_blocks) * BM, n0 = (pid % n_blocks) * BN;
   CFDETR_SET_TILE(m0, n0);
   CFDETR_ISSUE_SLAB(0, 0);
+  int buf = 0;                // ring buffer of the slab that is computed next
+  bool first_ready = false;   // that slab is the tile's first and is in LDS already (below)
 
   for (;;) {
     // what the epilogue needs per row and per column arrives while the main loop runs
@@ -894,11 +897,24 @@ __global__ __launch_bounds__(64 * NWM * NWN, WPE) void gemm_bf16_persist_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    int buf = 0;
+    // the tile after this one: its first slab is requested behind this tile's last one
+    const int vn = v + (int)gridDim.x;
+    const bool more = vn < total;
+    const int m0_cur = m0, n0_cur = n0;
     for (int it = 0; it < nk; ++it) {
-      __builtin_amdgcn_s_waitcnt(0x0F70);
+      // a tile's first slab that came in under the previous epilogue needs no wait; the
+      // barrier then only retires that epilogue's reads of its staging rows
+      if (!(it == 0 && first_ready)) __builtin_amdgcn_s_waitcnt(0x0F70);
       __builtin_amdgcn_s_barrier();
-      if (it + 1 < nk) CFDETR_ISSUE_SLAB((it + 1) * BKT, buf ^ 1);
+      if (it + 1 < nk) {
+        CFDETR_ISSUE_SLAB((it + 1) * BKT, buf ^ 1);
+      } else if (more) {
+        pid = xcd_tile_order(vn, total);
+        m0 = (pid / n_blocks) * BM;
+        n0 = (pid % n_blocks) * BN;
+        CFDETR_SET_TILE(m0, n0);
+        CFDETR_ISSUE_SLAB(0, buf ^ 1);
+      }
       const unsigned char* pa = smem_persist + buf * STAGE;
       const unsigned char* pb = pa + BM * ROWB;
       buf ^= 1;
@@ -938,19 +954,13 @@ __global__ __launch_bounds__(64 * NWM * NWN, WPE) void gemm_bf16_persist_kernel(
         }
       }
     }
-    __builtin_amdgcn_s_barrier();   // every wavefront is done reading the ring
-
-    // the next tile's first slab goes into buffer 0 while this tile's epilogue runs
-    const int vn = v + (int)gridDim.x;
-    const bool more = vn < total;
-    const int m0_cur = m0, n0_cur = n0;
-    if (more) {
-      pid = xcd_tile_order(vn, total);
-      m0 = (pid / n_blocks) * BM;
-      n0 = (pid % n_blocks) * BN;
-      CFDETR_SET_TILE(m0, n0);
-      CFDETR_ISSUE_SLAB(0, 0);
-    }
+    // The next tile's first slab was requested one slab ago into the buffer `buf`; it has to
+    // be in LDS before the epilogue's stores are issued: the wait counter is in order, and a
+    // wait for it behind them would last until they are done.  The barrier also tells that
+    // every wavefront is done reading the ring; the staging rows are in the other buffer.
+    if (more) __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+    const int stage_buf = buf ^ 1;
 
     // Epilogue of the finished tile, one 32-row block of the wavefront at a time; the
     // finished values pass through the wavefront's staging rows in buffer 1, from which
@@ -964,7 +974,7 @@ __global__ __launch_bounds__(64 * NWM * NWN, WPE) void gemm_bf16_persist_kernel(
       static_assert(NW * 32 * STRIDE <= STAGE, "staging area exceeds a ring buffer");
       const int nw0 = n0_cur + wn * WTN;
       if (ep.staged(nw0)) {
-        unsigned char* stg = smem_persist + STAGE + wave * (32 * STRIDE);
+        unsigned char* stg = smem_persist + stage_buf * STAGE + wave * (32 * STRIDE);
         const int crow = lane >> 3, cchunk = lane & 7;
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
@@ -1019,6 +1029,7 @@ __global__ __launch_bounds__(64 * NWM * NWN, WPE) void gemm_bf16_persist_kernel(
     }
     if (!more) break;
     v = vn;
+    first_ready = true;
   }
 #undef CFDETR_SET_TILE
 #undef CFDETR_ISSUE_SLAB
